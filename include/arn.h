@@ -1,0 +1,138 @@
+/*
+ * arn -- Accelerated-RL Network: the neural-network hot path of Stooke & Abbeel,
+ * "Accelerated Methods for Deep Reinforcement Learning", as hand-written gfx950
+ * (MI355X) kernels behind a C ABI.
+ *
+ * The network is the Atari "Nature" CNN that the paper's appendix "Atari Frame
+ * Processing" calls the standard 3-convolutional-layer network:
+ *   uint8 [4,84,84] -> /255 -> conv 8x8/4 x32 -> conv 4x4/2 x64 -> conv 3x3/1 x64
+ *   -> fc 3136->512 (ReLU after every hidden layer) -> heads.
+ * Heads: policy logits [A] + value [1]   (head_kind ARN_HEAD_PV), or
+ *        categorical atom logits [A,51]   (head_kind ARN_HEAD_C51).
+ *
+ * Two operations follow the paper's problem statement:
+ *   - batched action-selection inference: one forward over all simulators'
+ *     observations per environment step (section "Synchronized Sampling");
+ *   - the local gradient of a training batch, step 1 of the synchronous
+ *     data-parallel update (section "Synchronous Multi-GPU Optimization"), for
+ *     the advantage actor-critic, PPO clipped-surrogate and Categorical-DQN
+ *     objectives (section "RL Algorithm Background").
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller and must be
+ *     16-byte aligned (256-byte for workspace and packed weights).  `arn_config`
+ *     and `arn_batch` structs themselves live in HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they never synchronise, allocate or free.
+ *   - Return value: ARN_OK (0) or a negative arn_status.  Argument errors are
+ *     detected on the host before anything is launched.
+ *   - Arithmetic: bf16 MFMA operands, fp32 accumulation, fp32 epilogues and
+ *     losses.  Gradients are reduced over the batch in a fixed order, so
+ *     repeated calls on the same inputs give bit-identical results.
+ *
+ * Flat fp32 parameter / gradient vector, canonical order (row-major tensors):
+ *   conv1.W[32,4,8,8] conv1.b[32] conv2.W[64,32,4,4] conv2.b[64]
+ *   conv3.W[64,64,3,3] conv3.b[64] fc.W[512,3136] fc.b[512]
+ *   (fc input index = c*49 + y*7 + x), then
+ *   PV : pi.W[A,512] pi.b[A] v.W[1,512] v.b[1]
+ *   C51: c51.W[A*atoms,512] (row a*atoms+j) c51.b[A*atoms]
+ */
+#ifndef ARN_H
+#define ARN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ARN_OK = 0,
+    ARN_EINVAL = -1,     /* null or misaligned pointer, B <= 0 */
+    ARN_ESHAPE = -2,     /* unsupported num_actions / num_atoms / head for this call */
+    ARN_EKIND = -3,      /* unknown head_kind / loss_kind / mode */
+    ARN_EWORKSPACE = -4, /* workspace smaller than arn_workspace_bytes() */
+    ARN_EARCH = -5,      /* current device is not gfx950 */
+    ARN_EHIP = -6        /* a HIP runtime call or launch failed */
+} arn_status;
+
+enum { ARN_HEAD_PV = 0, ARN_HEAD_C51 = 1 };
+enum { ARN_LOSS_A2C = 0, ARN_LOSS_PPO = 1, ARN_LOSS_C51 = 2 };
+enum { ARN_MODE_FORWARD = 0, ARN_MODE_TRAIN = 1 };
+
+typedef struct {
+    int32_t num_actions;   /* 1..32 for PV; 1..18 for C51 */
+    int32_t head_kind;     /* ARN_HEAD_PV or ARN_HEAD_C51 */
+    int32_t num_atoms;     /* C51 only: 2..64 (51 in the paper's Categorical DQN) */
+    float v_min, v_max;    /* C51 support end points (-10, 10) */
+    float gamma;           /* C51 discount (0.99) */
+    float clip_eps;        /* PPO clip range (0.1) */
+    float value_coef;      /* weight of mean((V-ret)^2) (0.5) */
+    float entropy_coef;    /* weight of the mean-entropy bonus (0.01) */
+} arn_config;
+
+/* Number of fp32 entries of the flat parameter vector; 0 on a bad config. */
+size_t arn_param_count(const arn_config *cfg);
+
+/* Bytes of the packed (bf16, kernel-layout) copy of the parameters that
+ * arn_weights_prepare writes; 0 on a bad config.  It holds forward-layout and
+ * input-gradient-layout copies of every weight matrix plus fp32 biases. */
+size_t arn_packed_bytes(const arn_config *cfg);
+
+/* Bytes of scratch device memory that a call with batch size B needs.
+ * mode = ARN_MODE_FORWARD (arn_policy_forward) or ARN_MODE_TRAIN
+ * (arn_train_step_grads).  0 on bad arguments. */
+size_t arn_workspace_bytes(const arn_config *cfg, int B, int mode);
+
+/* Convert the flat fp32 parameters to the packed form.  Belongs to the
+ * parameter update (step 3 of the synchronous procedure), not to the gradient
+ * step; call it once per update.  w_fp32: [arn_param_count], device.
+ * w_packed: [arn_packed_bytes], device, overwritten. */
+int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_packed, void *stream);
+
+/* Batched action-selection inference (section "Synchronized Sampling").
+ *   obs    : uint8 [B,4,84,84] (NCHW), read only
+ *   logits : PV: fp32 [B,A]; C51: fp32 [B,A,atoms].  Required.
+ *   value  : PV: fp32 [B], required.  C51: expected action values Q [B,A], or NULL.
+ *   probs  : PV: softmax over actions [B,A]; C51: softmax over atoms [B,A,atoms]; or NULL
+ *   greedy : int32 [B] -- lowest-index argmax of the logits (PV) or of Q (C51); or NULL
+ * Outputs are overwritten.  Workspace contents are undefined afterwards. */
+int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B,
+                       float *logits, float *value, float *probs, int32_t *greedy,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+typedef struct {
+    const uint8_t *obs;        /* [B,4,84,84] */
+    const int32_t *action;     /* [B], 0 <= a < A */
+    const float *adv;          /* [B]  a2c, ppo: advantage estimates (constants) */
+    const float *ret;          /* [B]  a2c, ppo: value regression targets */
+    const float *old_logp;     /* [B]  ppo: log pi_old(a|s) */
+    const uint8_t *next_obs;   /* [B,4,84,84]  c51 */
+    const float *reward;       /* [B]  c51 */
+    const uint8_t *done;       /* [B]  c51: 1 = terminal transition */
+    const void *w_target_packed; /* c51: packed target-network parameters */
+} arn_batch;
+
+/* Local gradient of one training batch (step 1 of section "Synchronous
+ * Multi-GPU Optimization").  Every loss term is a mean over the batch:
+ *   a2c: -mean(log pi(a) adv) + value_coef mean((V-ret)^2) - entropy_coef mean(H)
+ *   ppo: -mean(min(rho adv, clip(rho,1-eps,1+eps) adv)) + same value/entropy terms,
+ *        rho = exp(log pi(a) - old_logp)
+ *   c51: -mean(sum_i m_i log p_i(s,a)), m = projection onto the support of the
+ *        target network's distribution for its greedy next action, shifted by
+ *        reward and gamma (1-done).
+ *   dW   : fp32 [arn_param_count], overwritten with dLoss/dW in canonical order
+ *   loss : fp32 [4], overwritten: {total, policy (or cross-entropy), value mse, entropy}
+ * loss_kind a2c/ppo need head PV; c51 needs head C51. */
+int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_batch *batch, int B,
+                         int loss_kind, float *dW, float *loss,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Human-readable name of a status code (static storage). */
+const char *arn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARN_H */

@@ -1,0 +1,367 @@
+// C ABI of the library (declared in include/arn.h): argument checks on the host,
+// then a fixed sequence of kernel launches on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <string.h>
+
+#include "arn_gemm.h"
+#include "arn_layout.h"
+#include "arn_problems.h"
+#include "arn_small_kernels.h"
+
+using namespace arn;
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// gfx950 check, cached per device
+int check_arch() {
+    static int cached[64];   // 0 unknown, 1 ok, -1 wrong arch, -2 hip error
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ARN_EHIP;
+    if (dev < 0 || dev >= 64) return ARN_EHIP;
+    if (cached[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) cached[dev] = -2;
+        else cached[dev] = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+    }
+    return cached[dev] == 1 ? ARN_OK : (cached[dev] == -1 ? ARN_EARCH : ARN_EHIP);
+}
+
+inline int launched() { return hipGetLastError() == hipSuccess ? ARN_OK : ARN_EHIP; }
+
+inline unsigned cdiv(long a, long b) { return (unsigned)((a + b - 1) / b); }
+
+template <class P>
+void launch_nt(const P &p, long M, int n_tiles, int z, hipStream_t s) {
+    hipLaunchKernelGGL((gemm_nt_kernel<P, false>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(256), 0, s, p);
+}
+template <class P>
+void launch_nt_split(const P &p, long M, int n_tiles, int z, hipStream_t s) {
+    hipLaunchKernelGGL((gemm_nt_kernel<P, true>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(256), 0, s, p);
+}
+
+template <class P>
+void launch_tn(const P &p, float *part, long M, int N1, int KP, int splits, hipStream_t s) {
+    long rows = (M + splits - 1) / splits;
+    rows = (rows + 63) / 64 * 64;
+    hipLaunchKernelGGL(gemm_tn_kernel<P>, dim3(KP / P::BK2, N1 / P::BN1, splits), dim3(256), 0, s, p, part,
+                       (int)rows);
+}
+
+template <class F>
+void launch_reduce(const F &f, const float *part, float *dW, long wcount, long bcount, int splits, float wscale,
+                   hipStream_t s) {
+    const long block = wcount + bcount;
+    hipLaunchKernelGGL(reduce_partials_kernel<F>, dim3(cdiv(block, 256)), dim3(256), 0, s, f, part, dW, block, wcount,
+                       splits, wscale);
+}
+
+template <class F>
+void launch_pack(const F &f, const float *w, void *out, void *out_lo, long n, hipStream_t s) {
+    hipLaunchKernelGGL(pack_bf16_kernel<F>, dim3(cdiv(n, 256)), dim3(256), 0, s, f, w, (__bf16 *)out,
+                       (__bf16 *)out_lo, n);
+}
+template <class F>
+void launch_pack_f32(const F &f, const float *w, void *out, long n, hipStream_t s) {
+    hipLaunchKernelGGL(pack_f32_kernel<F>, dim3(cdiv(n, 256)), dim3(256), 0, s, f, w, (float *)out, n);
+}
+
+struct Packed {   // typed views of the packed blob
+    const __bf16 *w1, *w2, *w3, *wfc, *wh, *whd, *wfcd, *w3d, *w2d;
+    const __bf16 *w1l, *w2l, *w3l, *wfcl, *whl;
+    const float *b1, *b2, *b3, *bfc, *bh;
+};
+Packed view_packed(const void *blob, const Dims &d) {
+    const PackedOffsets o = packed_offsets(d);
+    const char *b = (const char *)blob;
+    Packed p;
+    p.w1 = (const __bf16 *)(b + o.w1);
+    p.w2 = (const __bf16 *)(b + o.w2);
+    p.w3 = (const __bf16 *)(b + o.w3);
+    p.wfc = (const __bf16 *)(b + o.wfc);
+    p.wh = (const __bf16 *)(b + o.wh);
+    p.b1 = (const float *)(b + o.b1);
+    p.b2 = (const float *)(b + o.b2);
+    p.b3 = (const float *)(b + o.b3);
+    p.bfc = (const float *)(b + o.bfc);
+    p.bh = (const float *)(b + o.bh);
+    p.whd = (const __bf16 *)(b + o.whd);
+    p.wfcd = (const __bf16 *)(b + o.wfcd);
+    p.w3d = (const __bf16 *)(b + o.w3d);
+    p.w2d = (const __bf16 *)(b + o.w2d);
+    p.w1l = (const __bf16 *)(b + o.w1l);
+    p.w2l = (const __bf16 *)(b + o.w2l);
+    p.w3l = (const __bf16 *)(b + o.w3l);
+    p.wfcl = (const __bf16 *)(b + o.wfcl);
+    p.whl = (const __bf16 *)(b + o.whl);
+    return p;
+}
+
+// trunk + heads forward.  z_out: logits [B][A] (PV) or atom logits [B][NH]; v_out: value [B] (PV) or null.
+// split = three-product bf16 (inference: fp32-class accuracy); otherwise plain bf16 operands (training).
+void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                      float *z_out, float *v_out, bool split, hipStream_t s) {
+    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
+    __bf16 *h = (__bf16 *)(ws + o.h);
+    __bf16 *a1l = split ? (__bf16 *)(ws + o.a1l) : nullptr, *a2l = split ? (__bf16 *)(ws + o.a2l) : nullptr;
+    __bf16 *a3l = split ? (__bf16 *)(ws + o.a3l) : nullptr, *hl = split ? (__bf16 *)(ws + o.hl) : nullptr;
+    {
+        Conv1Fwd p;
+        p.obs = obs; p.M = B * P1; p.w = w.w1; p.w_lo = w.w1l; p.bias = w.b1; p.out = a1; p.out_lo = a1l;
+        split ? launch_nt_split(p, p.M, 1, 1, s) : launch_nt(p, p.M, 1, 1, s);
+    }
+    {
+        Conv2Fwd p;
+        p.in = a1; p.lo_off = a1l - a1; p.M = B * P2; p.w = w.w2; p.w_lo = w.w2l; p.bias = w.b2;
+        p.out = a2; p.out_lo = a2l;
+        split ? launch_nt_split(p, p.M, 1, 1, s) : launch_nt(p, p.M, 1, 1, s);
+    }
+    {
+        Conv3Fwd p;
+        p.in = a2; p.lo_off = a2l - a2; p.M = B * P3; p.w = w.w3; p.w_lo = w.w3l; p.bias = w.b3;
+        p.out = a3; p.out_lo = a3l;
+        split ? launch_nt_split(p, p.M, 1, 1, s) : launch_nt(p, p.M, 1, 1, s);
+    }
+    {
+        FcFwd p;
+        p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
+        p.out = h; p.out_lo = hl;
+        split ? launch_nt_split(p, B, HID / FcFwd::BN, 1, s) : launch_nt(p, B, HID / FcFwd::BN, 1, s);
+    }
+    if (d.head == ARN_HEAD_PV) {
+        HeadFwd<32> p;
+        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
+        p.z = z_out; p.value = v_out; p.ZW = d.A;
+        split ? launch_nt_split(p, B, 1, 1, s) : launch_nt(p, B, 1, 1, s);
+    } else {
+        HeadFwd<64> p;
+        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
+        p.z = z_out; p.value = nullptr; p.ZW = d.NH;
+        split ? launch_nt_split(p, B, d.NHP / 64, 1, s) : launch_nt(p, B, d.NHP / 64, 1, s);
+    }
+}
+
+MapHeadRow head_rows(const Dims &d, const ParamOffsets &po) {
+    MapHeadRow h;
+    h.wh = (long)po.wh; h.wv = (long)po.wv; h.bh = (long)po.bh; h.bv = (long)po.bv;
+    h.A = d.A; h.NH = d.NH; h.pv = d.head == ARN_HEAD_PV;
+    return h;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *arn_status_string(int status) {
+    switch (status) {
+        case ARN_OK: return "ok";
+        case ARN_EINVAL: return "invalid argument (null or misaligned pointer, or B <= 0)";
+        case ARN_ESHAPE: return "unsupported shape (num_actions, num_atoms or head for this call)";
+        case ARN_EKIND: return "unknown head_kind, loss_kind or mode";
+        case ARN_EWORKSPACE: return "workspace too small";
+        case ARN_EARCH: return "device is not gfx950";
+        case ARN_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+size_t arn_param_count(const arn_config *cfg) {
+    const Dims d = make_dims(cfg);
+    return d.ok ? param_offsets(d).total : 0;
+}
+
+size_t arn_packed_bytes(const arn_config *cfg) {
+    const Dims d = make_dims(cfg);
+    return d.ok ? packed_offsets(d).total : 0;
+}
+
+size_t arn_workspace_bytes(const arn_config *cfg, int B, int mode) {
+    const Dims d = make_dims(cfg);
+    if (!d.ok || B <= 0 || B > (1 << 20) || (mode != ARN_MODE_FORWARD && mode != ARN_MODE_TRAIN)) return 0;
+    return make_workspace(d, B, mode).total;
+}
+
+int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_packed, void *stream) {
+    if (!cfg) return ARN_EINVAL;
+    if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+    const Dims d = make_dims(cfg);
+    if (!d.ok) return ARN_ESHAPE;
+    if (!aligned(w_fp32, 16) || !aligned(w_packed, 256)) return ARN_EINVAL;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    const ParamOffsets po = param_offsets(d);
+    const PackedOffsets o = packed_offsets(d);
+    char *b = (char *)w_packed;
+    const MapHeadRow hr = head_rows(d, po);
+    launch_pack(MapIdentity{(long)po.w1}, w_fp32, b + o.w1, b + o.w1l, (long)C1 * KW1, s);
+    launch_pack(MapConvFwd<C1, K2>{(long)po.w2}, w_fp32, b + o.w2, b + o.w2l, (long)C2 * KW2, s);
+    launch_pack(MapConvFwd<C2, K3>{(long)po.w3}, w_fp32, b + o.w3, b + o.w3l, (long)C3 * KW3, s);
+    launch_pack(MapFcFwd{(long)po.wfc}, w_fp32, b + o.wfc, b + o.wfcl, (long)HID * FEAT, s);
+    launch_pack(MapHeadFwd{hr}, w_fp32, b + o.wh, b + o.whl, (long)d.NHP * HID, s);
+    launch_pack_f32(MapIdentity{(long)po.b1}, w_fp32, b + o.b1, C1, s);
+    launch_pack_f32(MapIdentity{(long)po.b2}, w_fp32, b + o.b2, C2, s);
+    launch_pack_f32(MapIdentity{(long)po.b3}, w_fp32, b + o.b3, C3, s);
+    launch_pack_f32(MapIdentity{(long)po.bfc}, w_fp32, b + o.bfc, HID, s);
+    launch_pack_f32(MapHeadBias{hr}, w_fp32, b + o.bh, d.NHP, s);
+    launch_pack(MapHeadDgrad{hr, d.NHP}, w_fp32, b + o.whd, nullptr, (long)HID * d.NHP, s);
+    launch_pack(MapFcDgrad{(long)po.wfc}, w_fp32, b + o.wfcd, nullptr, (long)FEAT * HID, s);
+    launch_pack(MapConv3Dgrad{(long)po.w3}, w_fp32, b + o.w3d, nullptr, (long)C2 * KW3, s);
+    launch_pack(MapConv2Dgrad{(long)po.w2}, w_fp32, b + o.w2d, nullptr, (long)4 * C1 * 256, s);
+    return launched();
+}
+
+int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, float *logits,
+                       float *value, float *probs, int32_t *greedy, void *workspace, size_t workspace_bytes,
+                       void *stream) {
+    if (!cfg || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
+    if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+    const Dims d = make_dims(cfg);
+    if (!d.ok) return ARN_ESHAPE;
+    if (!aligned(w_packed, 256) || !aligned(obs, 16) || !aligned(logits, 16) || !aligned(workspace, 256))
+        return ARN_EINVAL;
+    if (d.head == ARN_HEAD_PV && !aligned(value, 16)) return ARN_EINVAL;
+    if ((value && !aligned(value, 16)) || (probs && !aligned(probs, 16)) || (greedy && !aligned(greedy, 16)))
+        return ARN_EINVAL;
+    const Workspace o = make_workspace(d, B, ARN_MODE_FORWARD);
+    if (workspace_bytes < o.total) return ARN_EWORKSPACE;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    const Packed w = view_packed(w_packed, d);
+    forward_launches(d, w, obs, B, (char *)workspace, o, logits, d.head == ARN_HEAD_PV ? value : nullptr, true, s);
+    if (d.head == ARN_HEAD_PV) {
+        if (probs || greedy)
+            hipLaunchKernelGGL(policy_epilogue_kernel, dim3(cdiv(B, 256)), dim3(256), 0, s, logits, B, d.A, probs,
+                               greedy);
+    } else if (value || probs || greedy) {
+        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, B, d.A,
+                           d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, (const float *)nullptr,
+                           (const uint8_t *)nullptr, probs, value, greedy, (float *)nullptr);
+    }
+    return launched();
+}
+
+int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_batch *batch, int B, int loss_kind,
+                         float *dW, float *loss, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!cfg || !batch || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
+    if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+    if (loss_kind != ARN_LOSS_A2C && loss_kind != ARN_LOSS_PPO && loss_kind != ARN_LOSS_C51) return ARN_EKIND;
+    const Dims d = make_dims(cfg);
+    if (!d.ok) return ARN_ESHAPE;
+    if ((loss_kind == ARN_LOSS_C51) != (d.head == ARN_HEAD_C51)) return ARN_ESHAPE;
+    if (!aligned(w_packed, 256) || !aligned(batch->obs, 16) || !aligned(batch->action, 16) || !aligned(dW, 16) ||
+        !aligned(loss, 16) || !aligned(workspace, 256))
+        return ARN_EINVAL;
+    if (loss_kind != ARN_LOSS_C51) {
+        if (!aligned(batch->adv, 16) || !aligned(batch->ret, 16)) return ARN_EINVAL;
+        if (loss_kind == ARN_LOSS_PPO && !aligned(batch->old_logp, 16)) return ARN_EINVAL;
+    } else {
+        if (!aligned(batch->next_obs, 16) || !aligned(batch->reward, 16) || !aligned(batch->done, 16) ||
+            !aligned(batch->w_target_packed, 256))
+            return ARN_EINVAL;
+    }
+    const Workspace o = make_workspace(d, B, ARN_MODE_TRAIN);
+    if (workspace_bytes < o.total) return ARN_EWORKSPACE;
+    if (int e = check_arch()) return e;
+
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const Packed w = view_packed(w_packed, d);
+    const ParamOffsets po = param_offsets(d);
+    const Splits sp = make_splits(d, B);
+    float *z = (float *)(ws + o.z), *zv = (float *)(ws + o.zv);
+    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
+    __bf16 *h = (__bf16 *)(ws + o.h);
+    __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
+    __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
+    float *lossp = (float *)(ws + o.lossp);
+    const int lblocks = loss_blocks(d, B);
+
+    // ---- forward and objective ----
+    if (loss_kind == ARN_LOSS_C51) {
+        // target network on next states -> projected target m; its activations are then overwritten
+        const Packed wt = view_packed(batch->w_target_packed, d);
+        float *ztgt = (float *)(ws + o.ztgt), *m = (float *)(ws + o.m);
+        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, nullptr, true, s);
+        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, B, d.A,
+                           d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
+                           (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
+        forward_launches(d, w, batch->obs, B, ws, o, z, nullptr, true, s);
+        hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
+                           d.atoms, d.NHP, dz, lossp);
+        hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, 0.f, 0.f, loss);
+    } else {
+        forward_launches(d, w, batch->obs, B, ws, o, z, zv, true, s);
+        hipLaunchKernelGGL(ac_loss_kernel, dim3(lblocks), dim3(LOSS_BLOCK), 0, s, z, zv, batch->action, batch->adv,
+                           batch->ret, batch->old_logp, loss_kind == ARN_LOSS_PPO ? 1 : 0, cfg->clip_eps,
+                           cfg->value_coef, cfg->entropy_coef, B, d.A, d.NHP, dz, lossp);
+        hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, cfg->value_coef,
+                           cfg->entropy_coef, loss);
+    }
+
+    // ---- backward: heads ----
+    {
+        HeadWgrad p;
+        p.in = h; p.M = B; p.N1 = d.NHP; p.dy = dz;
+        float *part = (float *)(ws + o.pwh);
+        launch_tn(p, part, B, d.NHP, HID, sp.hd, s);
+        launch_reduce(UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s);
+    }
+    {
+        HeadDgrad p;
+        p.in = dz; p.M = B; p.K = d.NHP; p.w = w.whd; p.h = h; p.out = dph;
+        launch_nt(p, B, HID / HeadDgrad::BN, 1, s);
+    }
+    // ---- fc ----
+    {
+        FcWgrad p;
+        p.in = a3; p.M = B; p.dy = dph;
+        float *part = (float *)(ws + o.pwfc);
+        launch_tn(p, part, B, HID, FEAT, sp.fc, s);
+        launch_reduce(UnmapFc{(long)po.wfc, (long)po.bfc}, part, dW, (long)HID * FEAT, HID, sp.fc, 1.f, s);
+    }
+    {
+        FcDgrad p;
+        p.in = dph; p.M = B; p.w = w.wfcd; p.act = a3; p.out = dp3;
+        launch_nt(p, B, FEAT / FcDgrad::BN, 1, s);
+    }
+    // ---- conv3 ----
+    {
+        Conv3Wgrad p;
+        p.in = a2; p.M = B * P3; p.dy = dp3;
+        float *part = (float *)(ws + o.pw3);
+        launch_tn(p, part, p.M, C3, KW3, sp.c3, s);
+        launch_reduce(UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s);
+    }
+    {
+        Conv3Dgrad p;
+        p.dpre = dp3; p.w = w.w3d; p.act = a2; p.out = dp2; p.M = B * P2;
+        launch_nt(p, p.M, 1, 1, s);
+    }
+    // ---- conv2 ----
+    {
+        Conv2Wgrad p;
+        p.in = a1; p.M = B * P2; p.dy = dp2;
+        float *part = (float *)(ws + o.pw2);
+        launch_tn(p, part, p.M, C2, KW2, sp.c2, s);
+        launch_reduce(UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s);
+    }
+    {
+        Conv2Dgrad p;
+        p.dpre = dp2; p.w = w.w2d; p.act = a1; p.out = dp1; p.M = B * 100;
+        launch_nt(p, p.M, 1, 4, s);
+    }
+    // ---- conv1 (weight gradient only: the input is data) ----
+    {
+        Conv1Wgrad p;
+        p.obs = batch->obs; p.M = B * P1; p.dy = dp1;
+        float *part = (float *)(ws + o.pw1);
+        launch_tn(p, part, p.M, C1, KW1, sp.c1, s);
+        // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
+        launch_reduce(UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
+    }
+    return launched();
+}
+
+}  // extern "C"

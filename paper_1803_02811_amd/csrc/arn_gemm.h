@@ -1,0 +1,351 @@
+// MFMA building blocks for gfx950: two workgroup-level contraction kernels that
+// every layer of the network is an instance of.
+//
+//   gemm_nt_kernel : out[m][n] = sum_k act(m,k) * W[n][k]
+//       forward layers and input gradients.  `act` is gathered on the fly
+//       (implicit im2col); W is a packed bf16 matrix with k contiguous.
+//   gemm_tn_kernel : out[n][k] = sum_m dY[m][n] * act(m,k)
+//       weight gradients: the contraction runs over the batch/position index,
+//       which is the slow index of both operands in memory, so fragments are
+//       taken from LDS with the transposing read ds_read_b64_tr_b16.
+//
+// Both use v_mfma_f32_32x32x16_bf16 (fp32 accumulate), 256 threads = 4
+// wavefronts of 64 lanes, and 64-element k-tiles staged through LDS with a
+// register prefetch of the next tile.
+//
+// MFMA operand layout used throughout (checked on hardware):
+//   A (32 x 16): lane l holds row l%32,  k = 8*(l/32) .. +7
+//   B (16 x 32): lane l holds col l%32,  k = 8*(l/32) .. +7
+//   D (32 x 32): lane l holds col l%32,  rows 8*(r/4) + 4*(l/32) + r%4, r = 0..15
+// The weights (or dY) go in as A and the activations as B, so a lane ends up
+// with 4 consecutive channels of one position: one 8-byte NHWC store.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace arn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int LDS_ROW = 9;   // uint4 per staged row: 8 of data (64 bf16) + 1 of padding
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d) {
+    bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    return __builtin_bit_cast(uint2, v);
+}
+
+// v -> (hi, lo) with hi = bf16(v), lo = bf16(v - hi)
+__device__ __forceinline__ void store_bf16x4_split(__bf16 *hi, __bf16 *lo, size_t at, float a, float b, float c,
+                                                   float d) {
+    const bf16x4 h = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+    *reinterpret_cast<uint2 *>(hi + at) = __builtin_bit_cast(uint2, h);
+    if (lo) {
+        const bf16x4 l = {(__bf16)(a - (float)h[0]), (__bf16)(b - (float)h[1]), (__bf16)(c - (float)h[2]),
+                          (__bf16)(d - (float)h[3])};
+        *reinterpret_cast<uint2 *>(lo + at) = __builtin_bit_cast(uint2, l);
+    }
+}
+
+__device__ __forceinline__ f32x4 unpack_bf16x4(uint2 u) {
+    bf16x4 v = __builtin_bit_cast(bf16x4, u);
+    f32x4 r = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+    return r;
+}
+
+// eight uint8 (two little-endian words) -> eight bf16, exact
+__device__ __forceinline__ uint4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+    auto two = [](uint32_t b0, uint32_t b1) -> uint32_t {
+        return (__float_as_uint((float)b0) >> 16) | (__float_as_uint((float)b1) & 0xffff0000u);
+    };
+    uint4 r;
+    r.x = two(lo & 0xff, (lo >> 8) & 0xff);
+    r.y = two((lo >> 16) & 0xff, lo >> 24);
+    r.z = two(hi & 0xff, (hi >> 8) & 0xff);
+    r.w = two((hi >> 16) & 0xff, hi >> 24);
+    return r;
+}
+
+__device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
+
+// ---------------------------------------------------------------------------
+// out[m][n] = sum_k act(m,k) W[n][k]
+//
+// Problem P supplies
+//   BM, BN           workgroup tile (positions x channels), multiples of 32
+//   WAVES_N          wavefronts along channels (1, 2 or 4)
+//   K                contraction length, multiple of 64 (static or a data member)
+//   Row row(m, z)    per-row gather state for position m (z = blockIdx.z)
+//   uint4 load(row, k)   eight bf16 of act(m, k..k+7); zeros where out of range
+//   const __bf16* weights(z)   W, at least gridDim.y*BN rows of K
+//   store(m, n, v, z)    epilogue for channels n..n+3 of position m
+// Grid: x = position tiles, y = channel tiles, z = problem-defined.
+//
+// SPLIT = true is the three-product bf16 scheme used for action-selection
+// inference: each operand is a pair (hi, lo) of bf16 with hi + lo carrying ~16
+// mantissa bits, and the product is accumulated as hi*hi + lo_w*hi_a + hi_w*lo_a
+// in fp32.  P then also supplies weights_lo(z), load_lo(row, k) and the flag
+// ACT_LO (false when the activation operand is exact in one bf16, as for uint8
+// pixels, which drops the third product).
+// ---------------------------------------------------------------------------
+template <class P, bool SPLIT>
+struct ActLo {
+    static constexpr bool value = false;
+};
+template <class P>
+struct ActLo<P, true> {
+    static constexpr bool value = P::ACT_LO;
+};
+
+template <class P, bool SPLIT = false>
+__global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
+    constexpr int BM = P::BM, BN = P::BN, WN = P::WAVES_N, WM = 4 / WN;
+    constexpr int TN = BN / (32 * WN), TM = BM / (32 * WM);
+    constexpr int A_CH = BM / 32, W_CH = BN / 32;     // 16-byte chunks staged per thread and k-tile
+    constexpr bool ALO = ActLo<P, SPLIT>::value;
+    const int KT = p.K / 64;
+    static_assert(TN >= 1 && TM >= 1, "tile shape");
+
+    __shared__ uint4 sA[BM * LDS_ROW];
+    __shared__ uint4 sW[BN * LDS_ROW];
+    __shared__ uint4 sA2[ALO ? BM * LDS_ROW : 1];
+    __shared__ uint4 sW2[SPLIT ? BN * LDS_ROW : 1];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave % WN, wm = wave / WN;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN, z = blockIdx.z;
+    const int kc = tid & 7;      // which 16-byte chunk of the 128-byte k-tile row
+    const int r0 = tid >> 3;     // first staged row; this thread also stages r0+32, r0+64, ...
+
+    typename P::Row rows[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) rows[i] = p.row(m0 + r0 + 32 * i, z);
+    const uint4 *wsrc[W_CH];
+    const uint4 *wsrc2[W_CH];
+#pragma unroll
+    for (int i = 0; i < W_CH; ++i) {
+        const size_t at = (size_t)(n0 + r0 + 32 * i) * p.K;
+        wsrc[i] = reinterpret_cast<const uint4 *>(p.weights(z) + at) + kc;
+        if constexpr (SPLIT) wsrc2[i] = reinterpret_cast<const uint4 *>(p.weights_lo(z) + at) + kc;
+    }
+
+    uint4 ra[A_CH], rw[W_CH], ra2[ALO ? A_CH : 1], rw2[SPLIT ? W_CH : 1];
+    auto gload = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            ra[i] = p.load(rows[i], kt * 64 + kc * 8);
+            if constexpr (ALO) ra2[i] = p.load_lo(rows[i], kt * 64 + kc * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < W_CH; ++i) {
+            rw[i] = wsrc[i][kt * 8];
+            if constexpr (SPLIT) rw2[i] = wsrc2[i][kt * 8];
+        }
+    };
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    gload(0);
+    const int fr = lane & 31, fg = lane >> 5;
+    for (int kt = 0; kt < KT; ++kt) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            sA[(r0 + 32 * i) * LDS_ROW + kc] = ra[i];
+            if constexpr (ALO) sA2[(r0 + 32 * i) * LDS_ROW + kc] = ra2[i];
+        }
+#pragma unroll
+        for (int i = 0; i < W_CH; ++i) {
+            sW[(r0 + 32 * i) * LDS_ROW + kc] = rw[i];
+            if constexpr (SPLIT) sW2[(r0 + 32 * i) * LDS_ROW + kc] = rw2[i];
+        }
+        __syncthreads();
+        if (kt + 1 < KT) gload(kt + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 fw[TN], fa[TM], fw2[SPLIT ? TN : 1], fa2[ALO ? TM : 1];
+#pragma unroll
+            for (int a = 0; a < TN; ++a) {
+                const int at = ((wn * TN + a) * 32 + fr) * LDS_ROW + kk * 2 + fg;
+                fw[a] = as_bf16x8(sW[at]);
+                if constexpr (SPLIT) fw2[a] = as_bf16x8(sW2[at]);
+            }
+#pragma unroll
+            for (int b = 0; b < TM; ++b) {
+                const int at = ((wm * TM + b) * 32 + fr) * LDS_ROW + kk * 2 + fg;
+                fa[b] = as_bf16x8(sA[at]);
+                if constexpr (ALO) fa2[b] = as_bf16x8(sA2[at]);
+            }
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    if constexpr (SPLIT)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw2[a], fa[b], acc[a][b], 0, 0, 0);
+                    if constexpr (ALO)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fa2[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fa[b], acc[a][b], 0, 0, 0);
+                }
+        }
+    }
+
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int m = m0 + (wm * TM + b) * 32 + fr;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + (wn * TN + a) * 32 + 8 * q + 4 * fg;
+                f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                p.store(m, n, v, z);
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------
+// Transposing LDS fragment read.
+//
+// `tile` holds 64 rows (contraction index m) of `row_u4` uint4 each, columns
+// contiguous.  Returns, for MFMA lane l, the eight values
+//   tile[mbase + 8*(l/32) + e][col0 + l%32],  e = 0..7
+// i.e. an A- or B-operand fragment whose k index is the tile's row index.
+// ds_read_b64_tr_b16 works on groups of 16 lanes: lane 4q+e of a group receives
+// element e of the four 8-byte rows addressed by lanes q, q+4, q+8, q+12.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8 tr_fragment(const uint4 *tile, int row_u4, int mbase, int col0, int lane) {
+    const int o = lane & 15, G = lane >> 4;
+    const int row = mbase + 8 * (G >> 1) + (o >> 2);
+    const int col = col0 + 16 * (G & 1) + 4 * (o & 3);
+    const char *addr = reinterpret_cast<const char *>(tile) + (size_t)row * row_u4 * 16 + col * 2;
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(addr));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(addr + (size_t)4 * row_u4 * 16));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// ---------------------------------------------------------------------------
+// part[split][n][k] = sum_{m in split} dY[m][n] * act(m,k)       (fp32)
+// part[split][N1*KP + n] = sum_{m in split} dY[m][n]             (bias gradient)
+//
+// Problem P supplies
+//   BN1, BK2         output tile (dY channels x act columns), multiples of 32
+//   WAVES_X          wavefronts along act columns (1, 2 or 4)
+//   N1, KP           full output shape (rows, columns; static or data members)
+//   XRow xrow(m), uint4 loadx(xrow, k)    gather of act(m, k..k+7)
+//   uint4 loady(m, n)                     eight bf16 of dY[m][n..n+7]
+//   int M                                  number of contraction rows
+// Grid: x = column tiles, y = row tiles, z = batch split.  Each split covers
+// `rows_per_split` (a multiple of 64) consecutive m; partials are summed by
+// reduce_partials_kernel in split order, which fixes the rounding order.
+// ---------------------------------------------------------------------------
+template <class P>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restrict__ part, int rows_per_split) {
+    constexpr int BN1 = P::BN1, BK2 = P::BK2, WX = P::WAVES_X, WY = 4 / WX;
+    constexpr int TY = BN1 / (32 * WY), TX = BK2 / (32 * WX);
+    constexpr int YC = BN1 / 8, XC = BK2 / 8;          // 16-byte chunks per staged row
+    constexpr int YROW = YC + 1, XROW = XC + 1;        // padded LDS row, in uint4
+    constexpr int Y_CH = 64 * YC / 256, X_CH = 64 * XC / 256;
+    static_assert(TY >= 1 && TX >= 1 && Y_CH >= 1 && X_CH >= 1, "tile shape");
+
+    __shared__ uint4 sY[64 * YROW];
+    __shared__ uint4 sX[64 * XROW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wx = wave % WX, wy = wave / WX;
+    const int x0 = blockIdx.x * BK2, y0 = blockIdx.y * BN1, split = blockIdx.z;
+    const long m_begin = (long)split * rows_per_split;
+    long m_end = m_begin + rows_per_split;
+    if (m_end > p.M) m_end = p.M;
+
+    uint4 ry[Y_CH], rx[X_CH];
+    auto gload = [&](long mt) {
+#pragma unroll
+        for (int i = 0; i < Y_CH; ++i) {
+            const int c = tid + 256 * i, r = c / YC, cc = c % YC;
+            const long m = mt + r;
+            ry[i] = m < m_end ? p.loady(m, y0 + cc * 8) : zero_u4();
+        }
+#pragma unroll
+        for (int i = 0; i < X_CH; ++i) {
+            const int c = tid + 256 * i, r = c / XC, cc = c % XC;
+            const long m = mt + r;
+            rx[i] = m < m_end ? p.loadx(p.xrow(m), x0 + cc * 8) : zero_u4();
+        }
+    };
+
+    f32x16 acc[TY][TX];
+#pragma unroll
+    for (int a = 0; a < TY; ++a)
+#pragma unroll
+        for (int b = 0; b < TX; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    float bsum = 0.f;
+
+    if (m_begin < m_end) gload(m_begin);
+    for (long mt = m_begin; mt < m_end; mt += 64) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < Y_CH; ++i) {
+            const int c = tid + 256 * i;
+            sY[(c / YC) * YROW + c % YC] = ry[i];
+        }
+#pragma unroll
+        for (int i = 0; i < X_CH; ++i) {
+            const int c = tid + 256 * i;
+            sX[(c / XC) * XROW + c % XC] = rx[i];
+        }
+        __syncthreads();
+        if (mt + 64 < m_end) gload(mt + 64);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 fy[TY], fx[TX];
+#pragma unroll
+            for (int a = 0; a < TY; ++a) fy[a] = tr_fragment(sY, YROW, kk * 16, (wy * TY + a) * 32, lane);
+#pragma unroll
+            for (int b = 0; b < TX; ++b) fx[b] = tr_fragment(sX, XROW, kk * 16, (wx * TX + b) * 32, lane);
+#pragma unroll
+            for (int a = 0; a < TY; ++a)
+#pragma unroll
+                for (int b = 0; b < TX; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[a], fx[b], acc[a][b], 0, 0, 0);
+        }
+        if (blockIdx.x == 0 && tid < BN1) {
+            // column sums of the staged dY rows: bias gradient, summed in row order
+            const __bf16 *col = reinterpret_cast<const __bf16 *>(sY) + tid;
+#pragma unroll 8
+            for (int r = 0; r < 64; ++r) bsum += (float)col[r * YROW * 8];
+        }
+    }
+
+    float *out = part + (size_t)split * ((size_t)p.N1 * p.KP + p.N1);
+    const int fr = lane & 31, fg = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < TY; ++a)
+#pragma unroll
+        for (int b = 0; b < TX; ++b) {
+            const int k = x0 + (wx * TX + b) * 32 + fr;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int n = y0 + (wy * TY + a) * 32 + 8 * (r >> 2) + 4 * fg + (r & 3);
+                out[(size_t)n * p.KP + k] = acc[a][b][r];
+            }
+        }
+    if (blockIdx.x == 0 && tid < BN1) out[(size_t)p.N1 * p.KP + y0 + tid] = bsum;
+}
+
+}  // namespace arn

@@ -1,0 +1,197 @@
+// Shapes of the Nature CNN, the packed-weight blob and the workspace carve-up.
+// Host-side arithmetic only; shared by the API layer and the kernel launchers.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/arn.h"
+
+namespace arn {
+
+// network geometry (appendix "Atari Frame Processing": the standard
+// 3-convolutional-layer network; 84x84 frames, no padding)
+constexpr int IN_C = 4, IN_H = 84, IN_W = 84;
+constexpr int OBS_BYTES = IN_C * IN_H * IN_W;            // 28224
+constexpr int C1 = 32, K1 = 8, S1 = 4, H1 = 20;          // conv1 out 20x20
+constexpr int C2 = 64, K2 = 4, S2 = 2, H2 = 9;           // conv2 out 9x9
+constexpr int C3 = 64, K3 = 3, S3 = 1, H3 = 7;           // conv3 out 7x7
+constexpr int P1 = H1 * H1, P2 = H2 * H2, P3 = H3 * H3;  // 400, 81, 49
+constexpr int KW1 = IN_C * K1 * K1;                      // 256
+constexpr int KW2 = C1 * K2 * K2;                        // 512
+constexpr int KW3 = C2 * K3 * K3;                        // 576
+constexpr int FEAT = C3 * P3;                            // 3136
+constexpr int HID = 512;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Dims {
+    int A = 0, head = 0, atoms = 0;
+    int NH = 0;    // real head rows: A+1 (PV) or A*atoms (C51)
+    int NHP = 0;   // head rows padded to a multiple of 64 (MFMA k-tile of the head dgrad)
+    bool ok = false;
+};
+
+inline Dims make_dims(const arn_config *c) {
+    Dims d;
+    if (!c) return d;
+    d.A = c->num_actions;
+    d.head = c->head_kind;
+    if (d.head == ARN_HEAD_PV) {
+        if (d.A < 1 || d.A > 31) return d;
+        d.atoms = 1;
+        d.NH = d.A + 1;
+    } else if (d.head == ARN_HEAD_C51) {
+        d.atoms = c->num_atoms;
+        if (d.A < 1 || d.A > 18 || d.atoms < 2 || d.atoms > 64) return d;
+        if (!(c->v_max > c->v_min)) return d;
+        d.NH = d.A * d.atoms;
+    } else {
+        return d;
+    }
+    d.NHP = (int)align_up((size_t)d.NH, 64);
+    d.ok = true;
+    return d;
+}
+
+// offsets (in fp32 entries) into the canonical flat parameter vector
+struct ParamOffsets {
+    size_t w1, b1, w2, b2, w3, b3, wfc, bfc, wh, bh, wv, bv, total;
+};
+inline ParamOffsets param_offsets(const Dims &d) {
+    ParamOffsets o{};
+    size_t p = 0;
+    o.w1 = p; p += (size_t)C1 * KW1;
+    o.b1 = p; p += C1;
+    o.w2 = p; p += (size_t)C2 * KW2;
+    o.b2 = p; p += C2;
+    o.w3 = p; p += (size_t)C3 * KW3;
+    o.b3 = p; p += C3;
+    o.wfc = p; p += (size_t)HID * FEAT;
+    o.bfc = p; p += HID;
+    if (d.head == ARN_HEAD_PV) {
+        o.wh = p; p += (size_t)d.A * HID;
+        o.bh = p; p += d.A;
+        o.wv = p; p += HID;
+        o.bv = p; p += 1;
+    } else {
+        o.wh = p; p += (size_t)d.NH * HID;
+        o.bh = p; p += d.NH;
+        o.wv = o.bv = p;
+    }
+    o.total = p;
+    return o;
+}
+
+// byte offsets into the packed blob
+struct PackedOffsets {
+    size_t w1, w2, w3, wfc, wh;          // forward layouts  [N][K'] bf16 (high parts)
+    size_t b1, b2, b3, bfc, bh;          // fp32 biases
+    size_t w1l, w2l, w3l, wfcl, whl;     // low parts (w - hi) for the three-product inference path
+    size_t whd, wfcd, w3d, w2d;          // input-gradient layouts
+    size_t fwd_bytes, total;
+};
+inline PackedOffsets packed_offsets(const Dims &d) {
+    PackedOffsets o{};
+    size_t p = 0;
+    auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes, 256); return at; };
+    o.w1 = take((size_t)C1 * KW1 * 2);
+    o.w2 = take((size_t)C2 * KW2 * 2);
+    o.w3 = take((size_t)C3 * KW3 * 2);
+    o.wfc = take((size_t)HID * FEAT * 2);
+    o.wh = take((size_t)d.NHP * HID * 2);
+    o.b1 = take(C1 * 4);
+    o.b2 = take(C2 * 4);
+    o.b3 = take(C3 * 4);
+    o.bfc = take(HID * 4);
+    o.bh = take((size_t)d.NHP * 4);
+    o.fwd_bytes = p;
+    o.w1l = take((size_t)C1 * KW1 * 2);
+    o.w2l = take((size_t)C2 * KW2 * 2);
+    o.w3l = take((size_t)C3 * KW3 * 2);
+    o.wfcl = take((size_t)HID * FEAT * 2);
+    o.whl = take((size_t)d.NHP * HID * 2);
+    o.whd = take((size_t)HID * d.NHP * 2);
+    o.wfcd = take((size_t)FEAT * HID * 2);
+    o.w3d = take((size_t)C2 * KW3 * 2);
+    o.w2d = take((size_t)4 * C1 * 4 * C2 * 2);
+    o.total = p;
+    return o;
+}
+
+// how many batch slices each weight-gradient GEMM is cut into (fixed function
+// of B only, so the summation order -- and the bits of dW -- never change)
+struct Splits {
+    int c1, c2, c3, fc, hd;
+};
+inline int pick_split(long rows, int tiles, int target_wgs) {
+    long iters = (rows + 63) / 64;
+    long s = target_wgs / tiles;
+    if (s < 1) s = 1;
+    if (s > iters) s = iters;
+    return (int)s;
+}
+inline Splits make_splits(const Dims &d, int B) {
+    Splits s;
+    s.c1 = pick_split((long)B * P1, 2, 1024);
+    s.c2 = pick_split((long)B * P2, 4, 1024);
+    s.c3 = pick_split((long)B * P3, 9, 1024);
+    s.fc = pick_split(B, 49 * 4, 512);
+    s.hd = pick_split(B, 4 * (d.NHP / 64), 512);
+    return s;
+}
+
+constexpr int LOSS_BLOCK = 256;   // samples per block in the actor-critic loss kernel
+constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
+
+// byte offsets into the workspace
+struct Workspace {
+    size_t a1, a2, a3, h;               // bf16 NHWC activations
+    size_t a1l, a2l, a3l, hl;           // their low parts (written and read by the forward pass only)
+    size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
+    size_t ztgt, m;                     // C51: target-net atom logits, projected target
+    size_t dz, dph, dp3, dp2, dp1;      // bf16 gradients at pre-activations
+    size_t lossp;                       // fp32 [blocks][4] partial loss sums
+    size_t pw1, pw2, pw3, pwfc, pwh;    // fp32 weight-gradient partials [split][N*K' + N]
+    size_t total;
+};
+inline int loss_blocks(const Dims &d, int B) {
+    return d.head == ARN_HEAD_PV ? (B + LOSS_BLOCK - 1) / LOSS_BLOCK : (B + C51_WAVES - 1) / C51_WAVES;
+}
+inline Workspace make_workspace(const Dims &d, int B, int mode) {
+    Workspace w{};
+    size_t p = 0;
+    auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes, 256); return at; };
+    const size_t b = (size_t)B;
+    w.a1 = take(b * P1 * C1 * 2);
+    w.a2 = take(b * P2 * C2 * 2);
+    w.a3 = take(b * FEAT * 2);
+    w.h = take(b * HID * 2);
+    w.a1l = take(b * P1 * C1 * 2);
+    w.a2l = take(b * P2 * C2 * 2);
+    w.a3l = take(b * FEAT * 2);
+    w.hl = take(b * HID * 2);
+    if (mode == ARN_MODE_TRAIN) {
+        w.z = take(b * (size_t)(d.head == ARN_HEAD_PV ? d.A : d.NH) * 4);
+        w.zv = take(b * 4);
+        if (d.head == ARN_HEAD_C51) {
+            w.ztgt = take(b * (size_t)d.NH * 4);
+            w.m = take(b * (size_t)d.atoms * 4);
+        }
+        w.dz = take(b * (size_t)d.NHP * 2);
+        w.dph = take(b * HID * 2);
+        w.dp3 = take(b * FEAT * 2);
+        w.dp2 = take(b * P2 * C2 * 2);
+        w.dp1 = take(b * P1 * C1 * 2);
+        w.lossp = take((size_t)loss_blocks(d, B) * 4 * 4);
+        const Splits s = make_splits(d, B);
+        w.pw1 = take((size_t)s.c1 * ((size_t)C1 * KW1 + C1) * 4);
+        w.pw2 = take((size_t)s.c2 * ((size_t)C2 * KW2 + C2) * 4);
+        w.pw3 = take((size_t)s.c3 * ((size_t)C3 * KW3 + C3) * 4);
+        w.pwfc = take((size_t)s.fc * ((size_t)HID * FEAT + HID) * 4);
+        w.pwh = take((size_t)s.hd * ((size_t)d.NHP * HID + d.NHP) * 4);
+    }
+    w.total = p;
+    return w;
+}
+
+}  // namespace arn

@@ -1,0 +1,374 @@
+// Everything that is not a contraction: weight packing, the softmax / loss /
+// categorical-projection kernels (plain fp32 ALU work with wavefront and block
+// reductions in a fixed order), and the ordered reduction of weight-gradient
+// partials into the canonical flat gradient vector.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "arn_layout.h"
+
+namespace arn {
+
+// ----------------------------- weight packing ------------------------------
+// One launch per packed region; F maps a packed element index to the index of
+// its source in the flat fp32 vector (or -1 for padding).
+// With `out_lo`, also writes the residual lo = bf16(w - hi) used by the
+// three-product inference path.
+template <class F>
+__global__ void pack_bf16_kernel(F f, const float *__restrict__ w, __bf16 *__restrict__ out,
+                                 __bf16 *__restrict__ out_lo, long n) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const long s = f(i);
+    const float v = s >= 0 ? w[s] : 0.f;
+    const __bf16 hi = (__bf16)v;
+    out[i] = hi;
+    if (out_lo) out_lo[i] = (__bf16)(v - (float)hi);
+}
+template <class F>
+__global__ void pack_f32_kernel(F f, const float *__restrict__ w, float *__restrict__ out, long n) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const long s = f(i);
+    out[i] = s >= 0 ? w[s] : 0.f;
+}
+
+struct MapIdentity {   // conv1: canonical order is already [co][ci*64+ky*8+kx]
+    long off;
+    __device__ long operator()(long i) const { return off + i; }
+};
+template <int CIN, int KS>
+struct MapConvFwd {    // packed [co][(ky*KS+kx)*CIN+ci]  <-  W[co][ci][ky][kx]
+    long off;
+    __device__ long operator()(long i) const {
+        constexpr int KW = CIN * KS * KS;
+        const int co = (int)(i / KW), k = (int)(i % KW);
+        const int tap = k / CIN, ci = k % CIN, ky = tap / KS, kx = tap % KS;
+        return off + (((long)co * CIN + ci) * KS + ky) * KS + kx;
+    }
+};
+struct MapFcFwd {      // packed [n][pos*64+c]  <-  Wfc[n][c*49+pos]
+    long off;
+    __device__ long operator()(long i) const {
+        const int n = (int)(i / FEAT), k = (int)(i % FEAT), pos = k >> 6, c = k & 63;
+        return off + (long)n * FEAT + c * P3 + pos;
+    }
+};
+struct MapHeadRow {    // head row r of the packed head -> offset of its weight row / bias, or -1
+    long wh, wv, bh, bv;
+    int A, NH, pv;
+    __device__ long wrow(int r) const {
+        if (pv) return r < A ? wh + (long)r * HID : (r == A ? wv : -1);
+        return r < NH ? wh + (long)r * HID : -1;
+    }
+    __device__ long brow(int r) const {
+        if (pv) return r < A ? bh + r : (r == A ? bv : -1);
+        return r < NH ? bh + r : -1;
+    }
+};
+struct MapHeadFwd {    // packed [r][j]
+    MapHeadRow h;
+    __device__ long operator()(long i) const {
+        const long b = h.wrow((int)(i / HID));
+        return b < 0 ? -1 : b + i % HID;
+    }
+};
+struct MapHeadBias {
+    MapHeadRow h;
+    __device__ long operator()(long i) const { return h.brow((int)i); }
+};
+struct MapHeadDgrad {  // packed [j][r]  (NHP columns)
+    MapHeadRow h;
+    int NHP;
+    __device__ long operator()(long i) const {
+        const long b = h.wrow((int)(i % NHP));
+        return b < 0 ? -1 : b + i / NHP;
+    }
+};
+struct MapFcDgrad {    // packed [pos*64+c][n]  <-  Wfc[n][c*49+pos]
+    long off;
+    __device__ long operator()(long i) const {
+        const int k = (int)(i / HID), n = (int)(i % HID), pos = k >> 6, c = k & 63;
+        return off + (long)n * FEAT + c * P3 + pos;
+    }
+};
+struct MapConv3Dgrad { // packed [ci][(ty*3+tx)*64+co]  <-  W3[co][ci][2-ty][2-tx]
+    long off;
+    __device__ long operator()(long i) const {
+        const int ci = (int)(i / KW3), k = (int)(i % KW3), tap = k >> 6, co = k & 63, ty = tap / 3, tx = tap % 3;
+        return off + (((long)co * C2 + ci) * K3 + (2 - ty)) * K3 + (2 - tx);
+    }
+};
+struct MapConv2Dgrad { // packed [z][ci][(ty*2+tx)*64+co]  <-  W2[co][ci][py+2(1-ty)][px+2(1-tx)]
+    long off;
+    __device__ long operator()(long i) const {
+        const int z = (int)(i / (C1 * 256)), rem = (int)(i % (C1 * 256));
+        const int ci = rem / 256, k = rem % 256, tap = k >> 6, co = k & 63, ty = tap >> 1, tx = tap & 1;
+        const int ky = (z >> 1) + 2 * (1 - ty), kx = (z & 1) + 2 * (1 - tx);
+        return off + (((long)co * C1 + ci) * K2 + ky) * K2 + kx;
+    }
+};
+
+// --------------------- ordered reduction of wgrad partials ------------------
+// dW[map(n,k)] = wscale * sum_s part[s][n*KP + k];  db[bmap(n)] = sum_s part[s][N1*KP + n]
+// F maps an index of the [N1*KP + N1] partial block to the flat gradient index (or -1);
+// the first `wcount` entries of the block are weights, the rest biases.
+template <class F>
+__global__ void reduce_partials_kernel(F f, const float *__restrict__ part, float *__restrict__ dW, long block,
+                                       long wcount, int splits, float wscale) {
+    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= block) return;
+    const long dst = f(i);
+    if (dst < 0) return;
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[(size_t)k * block + i];
+    dW[dst] = i < wcount ? s * wscale : s;
+}
+template <int CIN, int KS, int COUT>
+struct UnmapConv {     // partial [co][(ky*KS+kx)*CIN+ci] then [co] bias
+    long woff, boff;
+    __device__ long operator()(long i) const {
+        constexpr int KW = CIN * KS * KS;
+        if (i >= (long)COUT * KW) return boff + (i - (long)COUT * KW);
+        const int co = (int)(i / KW), k = (int)(i % KW);
+        const int tap = k / CIN, ci = k % CIN, ky = tap / KS, kx = tap % KS;
+        return woff + (((long)co * CIN + ci) * KS + ky) * KS + kx;
+    }
+};
+struct UnmapConv1 {
+    long woff, boff;
+    __device__ long operator()(long i) const { return i >= C1 * KW1 ? boff + (i - C1 * KW1) : woff + i; }
+};
+struct UnmapFc {
+    long woff, boff;
+    __device__ long operator()(long i) const {
+        if (i >= (long)HID * FEAT) return boff + (i - (long)HID * FEAT);
+        const int n = (int)(i / FEAT), k = (int)(i % FEAT), pos = k >> 6, c = k & 63;
+        return woff + (long)n * FEAT + c * P3 + pos;
+    }
+};
+struct UnmapHead {
+    MapHeadRow h;
+    int NHP;
+    __device__ long operator()(long i) const {
+        if (i >= (long)NHP * HID) return h.brow((int)(i - (long)NHP * HID));
+        const long b = h.wrow((int)(i / HID));
+        return b < 0 ? -1 : b + i % HID;
+    }
+};
+
+// ------------------------------ reductions ---------------------------------
+__device__ __forceinline__ float wave_sum(float v) {     // result valid in every lane, same bits
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_down(v, o, 64);
+    return __shfl(v, 0, 64);
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_down(v, o, 64));
+    return __shfl(v, 0, 64);
+}
+
+// ----------------------- policy outputs (inference) -------------------------
+// probs = softmax(logits), greedy = lowest-index argmax; one thread per sample.
+__global__ void policy_epilogue_kernel(const float *__restrict__ logits, int B, int A, float *__restrict__ probs,
+                                       int32_t *__restrict__ greedy) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= B) return;
+    const float *z = logits + (size_t)n * A;
+    float mx = z[0];
+    int arg = 0;
+    for (int k = 1; k < A; ++k)
+        if (z[k] > mx) { mx = z[k]; arg = k; }
+    if (greedy) greedy[n] = arg;
+    if (probs) {
+        float s = 0.f;
+        for (int k = 0; k < A; ++k) s += __expf(z[k] - mx);
+        const float inv = 1.f / s;
+        for (int k = 0; k < A; ++k) probs[(size_t)n * A + k] = __expf(z[k] - mx) * inv;
+    }
+}
+
+// ------------------- actor-critic objectives (A2C, PPO) ---------------------
+// Section "RL Algorithm Background": advantage actor-critic gradient and the PPO
+// clipped surrogate; value regression and entropy bonus as batch means.
+// One thread per sample.  Writes the gradient at the head outputs as one bf16
+// row [NHP] per sample (columns 0..A-1 logits, column A value, rest 0) and one
+// partial sum {policy, value, entropy} per block.
+__global__ __launch_bounds__(LOSS_BLOCK) void ac_loss_kernel(
+    const float *__restrict__ logits, const float *__restrict__ value, const int32_t *__restrict__ action,
+    const float *__restrict__ adv, const float *__restrict__ ret, const float *__restrict__ old_logp, int ppo,
+    float clip_eps, float value_coef, float entropy_coef, int B, int A, int NHP, __bf16 *__restrict__ dz,
+    float *__restrict__ lossp) {
+    __shared__ float red[3][LOSS_BLOCK];
+    const int tid = threadIdx.x, n = blockIdx.x * LOSS_BLOCK + tid;
+    float pol = 0.f, val = 0.f, ent = 0.f;
+    if (n < B) {
+        float z[32];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            z[k] = k < A ? logits[(size_t)n * A + k] : -INFINITY;
+            mx = fmaxf(mx, z[k]);
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) s += k < A ? expf(z[k] - mx) : 0.f;
+        const float lse = mx + logf(s);
+        float H = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const float lp = z[k] - lse;
+            z[k] = lp;                                   // z now holds log-probabilities
+            H -= k < A ? expf(lp) * lp : 0.f;
+        }
+        const int a = action[n];
+        float lpa = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) lpa = k == a ? z[k] : lpa;
+        const float ad = adv[n];
+        float w;   // d(surrogate)/d(log pi(a))
+        if (ppo) {
+            const float rho = expf(lpa - old_logp[n]);
+            const float clipped = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
+            pol = -fminf(rho * ad, clipped * ad);
+            const bool active = (ad >= 0.f && rho <= 1.f + clip_eps) || (ad < 0.f && rho >= 1.f - clip_eps);
+            w = active ? ad * rho : 0.f;
+        } else {
+            pol = -lpa * ad;
+            w = ad;
+        }
+        const float v = value[n], dv = v - ret[n];
+        val = dv * dv;
+        ent = H;
+        const float invB = 1.f / (float)B;
+        __bf16 *row = dz + (size_t)n * NHP;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            if (k < A) {
+                const float p = expf(z[k]);
+                const float g = (-w * ((k == a ? 1.f : 0.f) - p) + entropy_coef * p * (z[k] + H)) * invB;
+                row[k] = (__bf16)g;
+            }
+        }
+        row[A] = (__bf16)(value_coef * 2.f * dv * invB);
+        for (int k = A + 1; k < NHP; ++k) row[k] = (__bf16)0.f;
+    }
+    red[0][tid] = pol;
+    red[1][tid] = val;
+    red[2][tid] = ent;
+    __syncthreads();
+    for (int o = LOSS_BLOCK / 2; o >= 1; o >>= 1) {
+        if (tid < o) {
+            red[0][tid] += red[0][tid + o];
+            red[1][tid] += red[1][tid + o];
+            red[2][tid] += red[2][tid + o];
+        }
+        __syncthreads();
+    }
+    if (tid < 3) lossp[blockIdx.x * 4 + tid] = red[tid][0];
+}
+
+// loss[0..3] = {total, policy|cross-entropy, value mse, entropy}: block partials
+// are added in block order by one thread.
+__global__ void loss_finalize_kernel(const float *__restrict__ lossp, int blocks, int B, float value_coef,
+                                     float entropy_coef, float *__restrict__ loss) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f;
+    for (int b = 0; b < blocks; ++b) {
+        s0 += lossp[b * 4 + 0];
+        s1 += lossp[b * 4 + 1];
+        s2 += lossp[b * 4 + 2];
+    }
+    const float inv = 1.f / (float)B;
+    s0 *= inv; s1 *= inv; s2 *= inv;
+    loss[0] = s0 + value_coef * s1 - entropy_coef * s2;
+    loss[1] = s0;
+    loss[2] = s1;
+    loss[3] = s2;
+}
+
+// ------------------------- Categorical DQN target ---------------------------
+// One wavefront per sample, lane j = atom j.  From atom logits [A][atoms] of
+// one network: per-action softmax, expected values Q, lowest-index argmax.
+// With `m_out`, also the projection of the greedy action's distribution onto
+// the support after the shift T_j = clip(r + gamma (1-done) z_j):
+//     m_i = sum_j p_j max(0, 1 - |T_j - z_i| / delta).
+__global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
+    const float *__restrict__ zin, int B, int A, int atoms, float v_min, float v_max, float gamma,
+    const float *__restrict__ reward, const uint8_t *__restrict__ done, float *__restrict__ probs,
+    float *__restrict__ q_out, int32_t *__restrict__ greedy, float *__restrict__ m_out) {
+    const int lane = threadIdx.x & 63, n = blockIdx.x * C51_WAVES + (threadIdx.x >> 6);
+    if (n >= B) return;
+    const float delta = (v_max - v_min) / (float)(atoms - 1);
+    const float zj = v_min + delta * (float)lane;
+    const bool on = lane < atoms;
+    float best_q = -INFINITY, best_p = 0.f;
+    int best_a = 0;
+    for (int a = 0; a < A; ++a) {
+        const size_t at = ((size_t)n * A + a) * atoms + lane;
+        const float x = on ? zin[at] : -INFINITY;
+        const float mx = wave_max(x);
+        const float e = on ? expf(x - mx) : 0.f;
+        const float p = e / wave_sum(e);
+        const float q = wave_sum(p * (on ? zj : 0.f));
+        if (probs && on) probs[at] = p;
+        if (q_out && lane == 0) q_out[(size_t)n * A + a] = q;
+        if (q > best_q) { best_q = q; best_a = a; best_p = p; }
+    }
+    if (greedy && lane == 0) greedy[n] = best_a;
+    if (m_out) {
+        const float shrink = done[n] ? 0.f : gamma;
+        const float T = fminf(fmaxf(reward[n] + shrink * zj, v_min), v_max);
+        const float inv_delta = 1.f / delta;
+        float m = 0.f;
+        for (int j = 0; j < atoms; ++j) {
+            const float pj = __shfl(best_p, j, 64), Tj = __shfl(T, j, 64);
+            m += pj * fmaxf(0.f, 1.f - fabsf(Tj - zj) * inv_delta);
+        }
+        if (on) m_out[(size_t)n * atoms + lane] = m;
+    }
+}
+
+// Categorical cross-entropy against the projected target and its gradient:
+// L_n = -sum_i m_i log p_i(s_n, a_n);  d/dlogit[a_n][i] = (p_i sum(m) - m_i)/B, other rows 0.
+// One wavefront per sample writes the whole bf16 gradient row [NHP].
+__global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
+    const float *__restrict__ z, const float *__restrict__ m_in, const int32_t *__restrict__ action, int B, int A,
+    int atoms, int NHP, __bf16 *__restrict__ dz, float *__restrict__ lossp) {
+    __shared__ float red[C51_WAVES];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, n = blockIdx.x * C51_WAVES + wv;
+    float ce = 0.f;
+    if (n < B) {
+        const int a = action[n];
+        const bool on = lane < atoms;
+        const float x = on ? z[((size_t)n * A + a) * atoms + lane] : -INFINITY;
+        const float mx = wave_max(x);
+        const float e = on ? expf(x - mx) : 0.f;
+        const float s = wave_sum(e);
+        const float lp = x - mx - logf(s);
+        const float m = on ? m_in[(size_t)n * atoms + lane] : 0.f;
+        ce = -wave_sum(on ? m * lp : 0.f);
+        const float msum = wave_sum(m);
+        const float g = on ? (e / s * msum - m) / (float)B : 0.f;
+        const int lo = a * atoms;
+        __bf16 *row = dz + (size_t)n * NHP;
+        for (int c0 = 0; c0 < NHP; c0 += 64) {
+            const int c = c0 + lane, src = c - lo;
+            const float gv = __shfl(g, src & 63, 64);
+            row[c] = (__bf16)((src >= 0 && src < atoms) ? gv : 0.f);
+        }
+    }
+    if (lane == 0) red[wv] = ce;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int i = 0; i < C51_WAVES; ++i) s += red[i];
+        lossp[blockIdx.x * 4 + 0] = s;
+        lossp[blockIdx.x * 4 + 1] = 0.f;
+        lossp[blockIdx.x * 4 + 2] = 0.f;
+    }
+}
+
+}  // namespace arn

@@ -1,0 +1,91 @@
+"""Helpers for the GPU parity tests: device buffers around the C-ABI binding."""
+import numpy as np
+import torch
+
+import paper_1803_02811_amd as arn
+import workloads as wl
+
+DEV = "cuda:0"
+
+
+def tol_check(got, ref, name, rel=1e-2, abs_=1e-3):
+    """max|err| <= rel * max|ref| + abs_ (the bar stated for this build)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    assert np.isfinite(got).all(), name
+    err = float(np.abs(got - ref).max()) if got.size else 0.0
+    bound = rel * float(np.abs(ref).max() if ref.size else 0.0) + abs_
+    assert err <= bound, f"{name}: max|err| {err:.3e} > {bound:.3e} (max|ref| {np.abs(ref).max():.3e})"
+    return err, bound
+
+
+class GpuNet:
+    """Packed weights + workspace for one config; thin wrapper over the binding."""
+
+    def __init__(self, num_actions, head, flat_params, num_atoms=51, **hyper):
+        self.head = head
+        self.cfg = arn.Config(num_actions, arn.ARN_HEAD_PV if head == "pv" else arn.ARN_HEAD_C51, num_atoms, **hyper)
+        self.A, self.atoms = num_actions, num_atoms
+        self.nparam = arn.param_count(self.cfg)
+        assert self.nparam == flat_params.size
+        self.packed = self.pack(flat_params)
+        self._ws = {}
+
+    def pack(self, flat_params):
+        w = torch.from_numpy(np.ascontiguousarray(flat_params, dtype=np.float32)).to(DEV)
+        packed = torch.empty(arn.packed_bytes(self.cfg), dtype=torch.uint8, device=DEV)
+        arn.weights_prepare(self.cfg, w, packed)
+        torch.cuda.synchronize()
+        return packed
+
+    def workspace(self, B, mode):
+        key = (B, mode)
+        if key not in self._ws:
+            self._ws[key] = torch.empty(arn.workspace_bytes(self.cfg, B, mode), dtype=torch.uint8, device=DEV)
+        return self._ws[key]
+
+    def forward(self, obs_np):
+        B = obs_np.shape[0]
+        obs = torch.from_numpy(obs_np).to(DEV)
+        ws = self.workspace(B, arn.ARN_MODE_FORWARD)
+        greedy = torch.empty(B, dtype=torch.int32, device=DEV)
+        if self.head == "pv":
+            logits = torch.empty(B, self.A, dtype=torch.float32, device=DEV)
+            value = torch.empty(B, dtype=torch.float32, device=DEV)
+            probs = torch.empty(B, self.A, dtype=torch.float32, device=DEV)
+        else:
+            logits = torch.empty(B, self.A, self.atoms, dtype=torch.float32, device=DEV)
+            value = torch.empty(B, self.A, dtype=torch.float32, device=DEV)
+            probs = torch.empty(B, self.A, self.atoms, dtype=torch.float32, device=DEV)
+        arn.policy_forward(self.cfg, self.packed, obs, logits, value, probs, greedy, workspace=ws)
+        torch.cuda.synchronize()
+        return dict(logits=logits.cpu().numpy(), value=value.cpu().numpy(), probs=probs.cpu().numpy(),
+                    greedy=greedy.cpu().numpy())
+
+    def device_batch(self, batch_np, target_packed=None):
+        out = {}
+        for k, v in batch_np.items():
+            v = np.ascontiguousarray(v)
+            if k in ("adv", "ret", "old_logp", "reward"):
+                v = v.astype(np.float32)
+            if k == "action":
+                v = v.astype(np.int32)
+            out[k] = torch.from_numpy(v).to(DEV)
+        if target_packed is not None:
+            out["w_target_packed"] = target_packed
+        return out
+
+    def train(self, batch_np, kind, target_packed=None, dev_batch=None):
+        b = dev_batch if dev_batch is not None else self.device_batch(batch_np, target_packed)
+        B = b["obs"].shape[0]
+        ws = self.workspace(B, arn.ARN_MODE_TRAIN)
+        dW = torch.full((self.nparam,), float("nan"), dtype=torch.float32, device=DEV)
+        loss = torch.empty(4, dtype=torch.float32, device=DEV)
+        arn.train_step_grads(self.cfg, self.packed, b, kind, dW, loss, workspace=ws)
+        torch.cuda.synchronize()
+        return dW.cpu().numpy(), loss.cpu().numpy()
+
+
+def per_tensor(flat, A, head, atoms=51):
+    return wl.split_params(np.asarray(flat), A, head, atoms)

@@ -1,0 +1,136 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element
+by element on the same seeded inputs.  Bar: max|err| <= 1e-2 max|ref| + 1e-3
+per output tensor; greedy actions equal wherever the top-2 gap exceeds 1e-2."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import nature_cnn as orc
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from tests import gpu_util
+    return gpu_util
+
+
+def _oracle_forward(flat, obs, A, head):
+    spec = orc.NetSpec(A, head)
+    return orc.forward(orc.unflatten(flat, spec), obs, spec), spec
+
+
+@pytest.mark.parametrize("B", [1, 16, 37, 130])
+def test_forward_uniform_frames(gu, B):
+    """Workload 1 (B=16, A=6, uniform frames) plus ragged and single-sample batches."""
+    flat = wl.he_normal_params(6, "pv", 2001, bias_std=0.0 if B == 16 else 0.1)
+    obs = wl.uniform_frames(B, 1001)
+    ref, _ = _oracle_forward(flat, obs, 6, "pv")
+    out = gu.GpuNet(6, "pv", flat).forward(obs)
+    gu.tol_check(out["logits"], ref["logits"], "logits")
+    gu.tol_check(out["value"], ref["value"], "value")
+
+
+def test_inference_structured_frames_b256(gu):
+    """Workload 2: probabilities, greedy action and value for 256 simulators."""
+    flat = wl.he_normal_params(18, "pv", 2002)
+    obs = wl.frames_for(2)
+    ref, _ = _oracle_forward(flat, obs, 18, "pv")
+    out = gu.GpuNet(18, "pv", flat).forward(obs)
+    pol = orc.policy_outputs(ref)
+    gu.tol_check(out["logits"], ref["logits"], "logits")
+    gu.tol_check(out["probs"], pol["probs"], "probs")
+    gu.tol_check(out["value"], ref["value"], "value")
+    np.testing.assert_allclose(out["probs"].sum(axis=1), 1.0, atol=1e-5)
+    decided = orc.top2_gap(ref["logits"]) > 1e-2
+    assert decided.sum() > 200
+    np.testing.assert_array_equal(out["greedy"][decided], pol["greedy"][decided])
+    # the kernel's own argmax is the lowest-index maximum of its own logits
+    np.testing.assert_array_equal(out["greedy"], np.argmax(out["logits"], axis=1))
+
+
+def _compare_grads(gu, dW, ref_flat, A, head, loss, ref_loss, keys):
+    got, ref = gu.per_tensor(dW, A, head), gu.per_tensor(ref_flat, A, head)
+    report = {}
+    for name in ref:
+        err, bound = gu.tol_check(got[name], ref[name], name)
+        report[name] = (err, float(np.abs(ref[name]).max()))
+    for i, k in enumerate(keys):
+        if k is not None:
+            gu.tol_check(loss[i:i + 1], np.array([ref_loss[k]]), f"loss.{k}")
+    return report
+
+
+@pytest.mark.parametrize("kind,B", [("a2c", 200), ("ppo", 200), ("a2c", 3)])
+def test_actor_critic_gradients(gu, kind, B):
+    """A2C / PPO loss and every parameter gradient, ragged batch over several tiles."""
+    A = 18
+    flat = wl.he_normal_params(A, "pv", 2003, bias_std=0.1)
+    batch = wl.actor_critic_batch(3 if kind == "a2c" else 4, B=B, normalise_adv=(kind == "ppo"))
+    spec = orc.NetSpec(A, "pv")
+    if kind == "ppo":
+        ref_fwd = orc.forward(orc.unflatten(flat, spec), batch["obs"], spec)
+        noisy = ref_fwd["logits"] + wl.logit_noise(4, B, A)
+        batch["old_logp"] = orc.log_softmax(noisy)[np.arange(B), batch["action"]].astype(np.float32)
+    ref = orc.train_step_grads(flat, batch, kind, spec)
+    dW, loss = gu.GpuNet(A, "pv", flat).train(batch, kind)
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+
+
+@pytest.mark.parametrize("B", [150, 2])
+def test_c51_gradients(gu, B):
+    """Categorical DQN step: target forward, projection, cross-entropy, all gradients."""
+    A = 18
+    flat = wl.he_normal_params(A, "c51", 2005, bias_std=0.1)
+    tflat = wl.he_normal_params(A, "c51", 3005, bias_std=0.1)
+    batch = wl.c51_batch(5, B=B)
+    batch["done"][: min(B, 3)] = 1            # terminal transitions present (reward 0 hits an atom exactly)
+    batch["reward"][0] = 0.0
+    spec = orc.NetSpec(A, "c51")
+    ref = orc.train_step_grads(flat, batch, "c51", spec, flat_target_params=tflat)
+    net = gu.GpuNet(A, "c51", flat)
+    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    _compare_grads(gu, dW, ref["flat"], A, "c51", loss, ref["loss"], ["total", "ce", None, None])
+
+
+def test_c51_inference_outputs(gu):
+    """Atom probabilities, expected values and greedy action of the categorical head."""
+    A, B = 18, 40
+    flat = wl.he_normal_params(A, "c51", 2005)
+    obs = wl.frames_for(5, B)
+    ref, _ = _oracle_forward(flat, obs, A, "c51")
+    out = gu.GpuNet(A, "c51", flat).forward(obs)
+    gu.tol_check(out["logits"], ref["atom_logits"], "atom_logits")
+    p = np.exp(orc.log_softmax(ref["atom_logits"]))
+    q = p @ orc.c51_support()
+    gu.tol_check(out["probs"], p, "atom_probs")
+    gu.tol_check(out["value"], q, "q")
+    decided = orc.top2_gap(q) > 1e-2
+    np.testing.assert_array_equal(out["greedy"][decided], orc.greedy(q)[decided])
+
+
+def test_gradients_bit_reproducible(gu):
+    A, B = 18, 300
+    flat = wl.he_normal_params(A, "pv", 2003)
+    batch = wl.actor_critic_batch(3, B=B)
+    net = gu.GpuNet(A, "pv", flat)
+    d1, l1 = net.train(batch, "a2c")
+    d2, l2 = net.train(batch, "a2c")
+    assert d1.tobytes() == d2.tobytes() and l1.tobytes() == l2.tobytes()
+
+
+def test_full_batch_gradient_is_mean_of_shards(gu):
+    """Data-parallel rule (section "Synchronous Multi-GPU Optimization") on the GPU path."""
+    A, B = 18, 512
+    flat = wl.he_normal_params(A, "pv", 2003)
+    batch = wl.actor_critic_batch(3, B=B)
+    net = gu.GpuNet(A, "pv", flat)
+    full, lf = net.train(batch, "a2c")
+    halves = [net.train({k: v[s] for k, v in batch.items()}, "a2c") for s in (slice(0, 256), slice(256, 512))]
+    mean = 0.5 * (halves[0][0] + halves[1][0])
+    scale = np.abs(mean).max()
+    assert np.abs(full - mean).max() <= 2e-3 * scale + 1e-6
+    assert abs(lf[0] - 0.5 * (halves[0][1][0] + halves[1][1][0])) < 1e-5
