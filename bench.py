@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the Nature-CNN hot path on one MI355X.
+
+A step is one pass of the whole training hot path (forward, objective,
+backward, ordered gradient reduction) over one synthetic batch that is already
+resident in HBM: the A2C gradient step at B=2048 (256 envs x 8-step rollouts).
+Prints ONE JSON line; see the design doc for how each field is derived.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# algorithmic multiply-accumulates per sample (dense, nothing avoided), A = 18 heads
+MACS = {"conv1": 3_276_800, "conv2": 2_654_208, "conv3": 1_806_336, "fc": 1_605_632, "head_pv": 19 * 512}
+FWD_FLOPS = 2 * sum(MACS.values())                                  # 18,705,408
+FWDBWD_FLOPS = 3 * FWD_FLOPS - 2 * 2 * MACS["conv1"]                # no conv1 input gradient: 49,562,624
+KERNEL_FLOPS = {  # per sample, by instrumented kernel name
+    "conv1_fwd": 2 * MACS["conv1"], "conv2_fwd": 2 * MACS["conv2"], "conv3_fwd": 2 * MACS["conv3"],
+    "fc_fwd": 2 * MACS["fc"], "head_fwd": 2 * MACS["head_pv"],
+    "conv1_wgrad": 2 * MACS["conv1"], "conv2_wgrad": 2 * MACS["conv2"], "conv3_wgrad": 2 * MACS["conv3"],
+    "fc_wgrad": 2 * MACS["fc"], "head_wgrad": 2 * MACS["head_pv"],
+    "conv2_dgrad": 2 * MACS["conv2"], "conv3_dgrad": 2 * MACS["conv3"], "fc_dgrad": 2 * MACS["fc"],
+    "head_dgrad": 2 * MACS["head_pv"],
+}
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-samples", type=int, default=0, help="oracle sample size (0 = auto, ~10-30 s)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (see DESIGN.md, sharding)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1803_02811_amd as arn
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    A, B, k = 18, args.batch, 3
+    cfg = arn.Config(A, arn.ARN_HEAD_PV)
+    flat = wl.he_normal_params(A, "pv", 2000 + k)
+    w = torch.from_numpy(flat).to(dev)
+    packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+    arn.weights_prepare(cfg, w, packed)
+    batch_np = wl.actor_critic_batch(k, B=B)
+    batch = {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for n, v in batch_np.items()}
+    ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
+    dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        arn.train_step_grads(cfg, packed, batch, "a2c", dW, loss, workspace=ws, stream=stream)
+
+    def timed(fn, steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    for _ in range(args.warmup):
+        step()
+    sec = timed(step, args.steps)
+    value = B / sec
+
+    # forward-only (action-selection inference) rate on the same batch, for the report
+    wsf = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
+    logits = torch.empty(B, A, dtype=torch.float32, device=dev)
+    val = torch.empty(B, dtype=torch.float32, device=dev)
+
+    def fwd():
+        arn.policy_forward(cfg, packed, batch["obs"], logits, val, workspace=wsf, stream=stream)
+
+    for _ in range(args.warmup):
+        fwd()
+    sec_fwd = timed(fwd, args.steps)
+
+    # per-kernel durations: the same K steps again with a HIP event pair around every launch
+    arn.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    recs = arn.profile_collect(cap=64 * args.steps + 64)
+    arn.profile_enable(False)
+    per = {}
+    for name, ms in recs:
+        tot, cnt = per.get(name, (0.0, 0))
+        per[name] = (tot + ms, cnt + 1)
+    avg_ms = {n: t / c for n, (t, c) in per.items()}
+    dominant = max(avg_ms, key=avg_ms.get)
+    dom_flops = KERNEL_FLOPS.get(dominant, 0) * B
+    achieved = dom_flops / (avg_ms[dominant] * 1e-3) / 1e12 if dom_flops else 0.0
+    roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(avg_ms[dominant] * 1e3, 2)}
+
+    out = {
+        "metric": "Nature-CNN samples/sec (fwd+bwd) at B=%d on 1 GPU" % B,
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "a2c_grad_step_B%d_A18 (256 envs x 8 steps, rectangle frames)" % B,
+                   "global_batch": B, "parallelism": "single-gpu"},
+        "mfma_frac_whole_step": round(value * FWDBWD_FLOPS / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "forward_samples_per_s": round(B / sec_fwd, 1),
+        "forward_ms": round(sec_fwd * 1e3, 4),
+        "kernel_us": {n: round(v * 1e3, 2) for n, v in sorted(avg_ms.items(), key=lambda kv: -kv[1])},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import nature_cnn as orc
+        spec = orc.NetSpec(A, "pv")
+        n = args.cpu_samples or 64
+        sub = {kk: v[:n] for kk, v in batch_np.items()}
+        t0 = time.perf_counter()
+        orc.train_step_grads(flat, sub, "a2c", spec)
+        dt = time.perf_counter() - t0
+        if not args.cpu_samples and dt < 8.0:       # grow the sample towards ~15 s of CPU work
+            n = int(min(B, max(64, n * 15.0 / max(dt, 1e-3)) // 32 * 32))
+            sub = {kk: v[:n] for kk, v in batch_np.items()}
+            t0 = time.perf_counter()
+            orc.train_step_grads(flat, sub, "a2c", spec)
+            dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n / dt, 1), "unit": "samples/s", "cores": orc.num_threads(),
+                               "kind": "oracle", "sample": "first %d samples of the same batch, fwd+loss+bwd, %.1f s" % (n, dt)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

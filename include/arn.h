@@ -62,7 +62,7 @@ enum { ARN_LOSS_A2C = 0, ARN_LOSS_PPO = 1, ARN_LOSS_C51 = 2 };
 enum { ARN_MODE_FORWARD = 0, ARN_MODE_TRAIN = 1 };
 
 typedef struct {
-    int32_t num_actions;   /* 1..32 for PV; 1..18 for C51 */
+    int32_t num_actions;   /* 1..31 for PV; 1..18 for C51 */
     int32_t head_kind;     /* ARN_HEAD_PV or ARN_HEAD_C51 */
     int32_t num_atoms;     /* C51 only: 2..64 (51 in the paper's Categorical DQN) */
     float v_min, v_max;    /* C51 support end points (-10, 10) */
@@ -128,6 +128,16 @@ typedef struct {
 int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_batch *batch, int B,
                          int loss_kind, float *dW, float *loss,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Optional instrumentation for benchmarks (not part of the paper's method).
+ * While enabled, every kernel launch made by the calls above is bracketed by a
+ * pair of HIP events on the caller's stream.  arn_profile_collect waits for the
+ * recorded events (it DOES synchronise), writes up to `cap` records in launch
+ * order -- names as HOST char[cap][32], durations in milliseconds as HOST
+ * float[cap] -- frees the events and returns the number written.  Process-wide
+ * state; not thread-safe. */
+int arn_profile_enable(int on);
+int arn_profile_collect(char *names, float *ms, int cap);
 
 /* Human-readable name of a status code (static storage). */
 const char *arn_status_string(int status);

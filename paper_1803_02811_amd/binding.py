@@ -65,6 +65,10 @@ def load_library():
         lib.arn_train_step_grads.restype = ctypes.c_int
         lib.arn_train_step_grads.argtypes = [cp, vp, ctypes.POINTER(_Batch), ctypes.c_int, ctypes.c_int, vp, vp, vp,
                                              ctypes.c_size_t, vp]
+        lib.arn_profile_enable.restype = ctypes.c_int
+        lib.arn_profile_enable.argtypes = [ctypes.c_int]
+        lib.arn_profile_collect.restype = ctypes.c_int
+        lib.arn_profile_collect.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         _LIB = lib
     return _LIB
 
@@ -122,3 +126,15 @@ def train_step_grads(cfg: Config, w_packed, batch: dict, loss_kind, dW, loss, *,
     _check(load_library().arn_train_step_grads(
         ctypes.byref(cfg), _ptr(w_packed), ctypes.byref(b), B, kind, _ptr(dW), _ptr(loss), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)), "arn_train_step_grads")
+
+
+def profile_enable(on: bool) -> None:
+    load_library().arn_profile_enable(1 if on else 0)
+
+
+def profile_collect(cap: int = 4096):
+    """[(kernel name, milliseconds)] in launch order for the launches recorded since enabling."""
+    names = ctypes.create_string_buffer(cap * 32)
+    ms = (ctypes.c_float * cap)()
+    n = load_library().arn_profile_collect(names, ms, cap)
+    return [(names.raw[i * 32:(i + 1) * 32].split(b"\0", 1)[0].decode(), float(ms[i])) for i in range(n)]

@@ -4,6 +4,8 @@
 
 #include <string.h>
 
+#include <vector>
+
 #include "arn_gemm.h"
 #include "arn_layout.h"
 #include "arn_problems.h"
@@ -31,19 +33,44 @@ int check_arch() {
 
 inline int launched() { return hipGetLastError() == hipSuccess ? ARN_OK : ARN_EHIP; }
 
+// Optional instrumentation (arn_profile_enable): a pair of HIP events around every launch.
+struct ProfRecord {
+    const char *name;
+    hipEvent_t start, stop;
+};
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof;
+struct ProfScope {
+    hipStream_t s;
+    bool on;
+    ProfScope(const char *name, hipStream_t stream) : s(stream), on(g_prof_on) {
+        if (!on) return;
+        ProfRecord r{name, nullptr, nullptr};
+        if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) { on = false; return; }
+        hipEventRecord(r.start, s);
+        g_prof.push_back(r);
+    }
+    ~ProfScope() {
+        if (on) hipEventRecord(g_prof.back().stop, s);
+    }
+};
+
 inline unsigned cdiv(long a, long b) { return (unsigned)((a + b - 1) / b); }
 
 template <class P>
-void launch_nt(const P &p, long M, int n_tiles, int z, hipStream_t s) {
+void launch_nt(const char *name, const P &p, long M, int n_tiles, int z, hipStream_t s) {
+    ProfScope ps(name, s);
     hipLaunchKernelGGL((gemm_nt_kernel<P, false>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(256), 0, s, p);
 }
 template <class P>
-void launch_nt_split(const P &p, long M, int n_tiles, int z, hipStream_t s) {
+void launch_nt_split(const char *name, const P &p, long M, int n_tiles, int z, hipStream_t s) {
+    ProfScope ps(name, s);
     hipLaunchKernelGGL((gemm_nt_kernel<P, true>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(256), 0, s, p);
 }
 
 template <class P>
-void launch_tn(const P &p, float *part, long M, int N1, int KP, int splits, hipStream_t s) {
+void launch_tn(const char *name, const P &p, float *part, long M, int N1, int KP, int splits, hipStream_t s) {
+    ProfScope ps(name, s);
     long rows = (M + splits - 1) / splits;
     rows = (rows + 63) / 64 * 64;
     hipLaunchKernelGGL(gemm_tn_kernel<P>, dim3(KP / P::BK2, N1 / P::BN1, splits), dim3(256), 0, s, p, part,
@@ -51,8 +78,9 @@ void launch_tn(const P &p, float *part, long M, int N1, int KP, int splits, hipS
 }
 
 template <class F>
-void launch_reduce(const F &f, const float *part, float *dW, long wcount, long bcount, int splits, float wscale,
-                   hipStream_t s) {
+void launch_reduce(const char *name, const F &f, const float *part, float *dW, long wcount, long bcount, int splits,
+                   float wscale, hipStream_t s) {
+    ProfScope ps(name, s);
     const long block = wcount + bcount;
     hipLaunchKernelGGL(reduce_partials_kernel<F>, dim3(cdiv(block, 256)), dim3(256), 0, s, f, part, dW, block, wcount,
                        splits, wscale);
@@ -110,36 +138,36 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
     {
         Conv1Fwd p;
         p.obs = obs; p.M = B * P1; p.w = w.w1; p.w_lo = w.w1l; p.bias = w.b1; p.out = a1; p.out_lo = a1l;
-        split ? launch_nt_split(p, p.M, 1, 1, s) : launch_nt(p, p.M, 1, 1, s);
+        split ? launch_nt_split("conv1_fwd", p, p.M, 1, 1, s) : launch_nt("conv1_fwd", p, p.M, 1, 1, s);
     }
     {
         Conv2Fwd p;
         p.in = a1; p.lo_off = a1l - a1; p.M = B * P2; p.w = w.w2; p.w_lo = w.w2l; p.bias = w.b2;
         p.out = a2; p.out_lo = a2l;
-        split ? launch_nt_split(p, p.M, 1, 1, s) : launch_nt(p, p.M, 1, 1, s);
+        split ? launch_nt_split("conv2_fwd", p, p.M, 1, 1, s) : launch_nt("conv2_fwd", p, p.M, 1, 1, s);
     }
     {
         Conv3Fwd p;
         p.in = a2; p.lo_off = a2l - a2; p.M = B * P3; p.w = w.w3; p.w_lo = w.w3l; p.bias = w.b3;
         p.out = a3; p.out_lo = a3l;
-        split ? launch_nt_split(p, p.M, 1, 1, s) : launch_nt(p, p.M, 1, 1, s);
+        split ? launch_nt_split("conv3_fwd", p, p.M, 1, 1, s) : launch_nt("conv3_fwd", p, p.M, 1, 1, s);
     }
     {
         FcFwd p;
         p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
         p.out = h; p.out_lo = hl;
-        split ? launch_nt_split(p, B, HID / FcFwd::BN, 1, s) : launch_nt(p, B, HID / FcFwd::BN, 1, s);
+        split ? launch_nt_split("fc_fwd", p, B, HID / FcFwd::BN, 1, s) : launch_nt("fc_fwd", p, B, HID / FcFwd::BN, 1, s);
     }
     if (d.head == ARN_HEAD_PV) {
         HeadFwd<32> p;
         p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
         p.z = z_out; p.value = v_out; p.ZW = d.A;
-        split ? launch_nt_split(p, B, 1, 1, s) : launch_nt(p, B, 1, 1, s);
+        split ? launch_nt_split("head_fwd", p, B, 1, 1, s) : launch_nt("head_fwd", p, B, 1, 1, s);
     } else {
         HeadFwd<64> p;
         p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
         p.z = z_out; p.value = nullptr; p.ZW = d.NH;
-        split ? launch_nt_split(p, B, d.NHP / 64, 1, s) : launch_nt(p, B, d.NHP / 64, 1, s);
+        split ? launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s) : launch_nt("head_fwd", p, B, d.NHP / 64, 1, s);
     }
 }
 
@@ -231,10 +259,12 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     const Packed w = view_packed(w_packed, d);
     forward_launches(d, w, obs, B, (char *)workspace, o, logits, d.head == ARN_HEAD_PV ? value : nullptr, true, s);
     if (d.head == ARN_HEAD_PV) {
+        ProfScope ps("policy_epilogue", s);
         if (probs || greedy)
             hipLaunchKernelGGL(policy_epilogue_kernel, dim3(cdiv(B, 256)), dim3(256), 0, s, logits, B, d.A, probs,
                                greedy);
     } else if (value || probs || greedy) {
+        ProfScope ps("c51_dist", s);
         hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, B, d.A,
                            d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, (const float *)nullptr,
                            (const uint8_t *)nullptr, probs, value, greedy, (float *)nullptr);
@@ -284,15 +314,20 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         const Packed wt = view_packed(batch->w_target_packed, d);
         float *ztgt = (float *)(ws + o.ztgt), *m = (float *)(ws + o.m);
         forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, nullptr, true, s);
-        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, B, d.A,
-                           d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
-                           (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
+        {
+            ProfScope ps("c51_target", s);
+                hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, B, d.A,
+                               d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
+                               (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
+        }
         forward_launches(d, w, batch->obs, B, ws, o, z, nullptr, true, s);
+        ProfScope ps("loss", s);
         hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
                            d.atoms, d.NHP, dz, lossp);
         hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, 0.f, 0.f, loss);
     } else {
         forward_launches(d, w, batch->obs, B, ws, o, z, zv, true, s);
+        ProfScope ps("loss", s);
         hipLaunchKernelGGL(ac_loss_kernel, dim3(lblocks), dim3(LOSS_BLOCK), 0, s, z, zv, batch->action, batch->adv,
                            batch->ret, batch->old_logp, loss_kind == ARN_LOSS_PPO ? 1 : 0, cfg->clip_eps,
                            cfg->value_coef, cfg->entropy_coef, B, d.A, d.NHP, dz, lossp);
@@ -305,63 +340,86 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         HeadWgrad p;
         p.in = h; p.M = B; p.N1 = d.NHP; p.dy = dz;
         float *part = (float *)(ws + o.pwh);
-        launch_tn(p, part, B, d.NHP, HID, sp.hd, s);
-        launch_reduce(UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s);
+        launch_tn("head_wgrad", p, part, B, d.NHP, HID, sp.hd, s);
+        launch_reduce("head_reduce", UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s);
     }
     {
         HeadDgrad p;
         p.in = dz; p.M = B; p.K = d.NHP; p.w = w.whd; p.h = h; p.out = dph;
-        launch_nt(p, B, HID / HeadDgrad::BN, 1, s);
+        launch_nt("head_dgrad", p, B, HID / HeadDgrad::BN, 1, s);
     }
     // ---- fc ----
     {
         FcWgrad p;
         p.in = a3; p.M = B; p.dy = dph;
         float *part = (float *)(ws + o.pwfc);
-        launch_tn(p, part, B, HID, FEAT, sp.fc, s);
-        launch_reduce(UnmapFc{(long)po.wfc, (long)po.bfc}, part, dW, (long)HID * FEAT, HID, sp.fc, 1.f, s);
+        launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s);
+        launch_reduce("fc_reduce", UnmapFc{(long)po.wfc, (long)po.bfc}, part, dW, (long)HID * FEAT, HID, sp.fc, 1.f, s);
     }
     {
         FcDgrad p;
         p.in = dph; p.M = B; p.w = w.wfcd; p.act = a3; p.out = dp3;
-        launch_nt(p, B, FEAT / FcDgrad::BN, 1, s);
+        launch_nt("fc_dgrad", p, B, FEAT / FcDgrad::BN, 1, s);
     }
     // ---- conv3 ----
     {
         Conv3Wgrad p;
         p.in = a2; p.M = B * P3; p.dy = dp3;
         float *part = (float *)(ws + o.pw3);
-        launch_tn(p, part, p.M, C3, KW3, sp.c3, s);
-        launch_reduce(UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s);
+        launch_tn("conv3_wgrad", p, part, p.M, C3, KW3, sp.c3, s);
+        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s);
     }
     {
         Conv3Dgrad p;
         p.dpre = dp3; p.w = w.w3d; p.act = a2; p.out = dp2; p.M = B * P2;
-        launch_nt(p, p.M, 1, 1, s);
+        launch_nt("conv3_dgrad", p, p.M, 1, 1, s);
     }
     // ---- conv2 ----
     {
         Conv2Wgrad p;
         p.in = a1; p.M = B * P2; p.dy = dp2;
         float *part = (float *)(ws + o.pw2);
-        launch_tn(p, part, p.M, C2, KW2, sp.c2, s);
-        launch_reduce(UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s);
+        launch_tn("conv2_wgrad", p, part, p.M, C2, KW2, sp.c2, s);
+        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s);
     }
     {
         Conv2Dgrad p;
         p.dpre = dp2; p.w = w.w2d; p.act = a1; p.out = dp1; p.M = B * 100;
-        launch_nt(p, p.M, 1, 4, s);
+        launch_nt("conv2_dgrad", p, p.M, 1, 4, s);
     }
     // ---- conv1 (weight gradient only: the input is data) ----
     {
         Conv1Wgrad p;
         p.obs = batch->obs; p.M = B * P1; p.dy = dp1;
         float *part = (float *)(ws + o.pw1);
-        launch_tn(p, part, p.M, C1, KW1, sp.c1, s);
+        launch_tn("conv1_wgrad", p, part, p.M, C1, KW1, sp.c1, s);
         // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
-        launch_reduce(UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
+        launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
     }
     return launched();
+}
+
+int arn_profile_enable(int on) {
+    g_prof_on = on != 0;
+    return ARN_OK;
+}
+
+int arn_profile_collect(char *names, float *ms, int cap) {
+    int n = 0;
+    for (const ProfRecord &r : g_prof) {
+        float t = 0.f;
+        if (r.stop && hipEventSynchronize(r.stop) == hipSuccess) hipEventElapsedTime(&t, r.start, r.stop);
+        if (n < cap && names && ms) {
+            strncpy(names + (size_t)n * 32, r.name, 31);
+            names[(size_t)n * 32 + 31] = 0;
+            ms[n] = t;
+            ++n;
+        }
+        if (r.start) hipEventDestroy(r.start);
+        if (r.stop) hipEventDestroy(r.stop);
+    }
+    g_prof.clear();
+    return n;
 }
 
 }  // extern "C"
