@@ -39,7 +39,8 @@ _LIB = None
 
 
 def lib_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libarn.so")
+    """In-tree libarn.so, or the library named by the ARN_LIBRARY environment variable."""
+    return os.environ.get("ARN_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libarn.so")
 
 
 def load_library():

@@ -9,6 +9,7 @@
 #include "arn_gemm.h"
 #include "arn_layout.h"
 #include "arn_problems.h"
+#include "arn_resident.h"
 #include "arn_small_kernels.h"
 
 using namespace arn;
@@ -152,12 +153,12 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         p.out = a3; p.out_lo = a3l;
         split ? launch_nt_split("conv3_fwd", p, p.M, 1, 1, s) : launch_nt("conv3_fwd", p, p.M, 1, 1, s);
     }
-    {
-        FcFwd p;
+    auto fc = [&](auto p) {
         p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
         p.out = h; p.out_lo = hl;
-        split ? launch_nt_split("fc_fwd", p, B, HID / FcFwd::BN, 1, s) : launch_nt("fc_fwd", p, B, HID / FcFwd::BN, 1, s);
-    }
+        split ? launch_nt_split("fc_fwd", p, B, HID / p.BN, 1, s) : launch_nt("fc_fwd", p, B, HID / p.BN, 1, s);
+    };
+    if (B >= 8192) fc(FcFwdT<128>{}); else fc(FcFwdT<64>{});
     if (d.head == ARN_HEAD_PV) {
         HeadFwd<32> p;
         p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
@@ -389,10 +390,12 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     }
     // ---- conv1 (weight gradient only: the input is data) ----
     {
-        Conv1Wgrad p;
-        p.obs = batch->obs; p.M = B * P1; p.dy = dp1;
         float *part = (float *)(ws + o.pw1);
-        launch_tn("conv1_wgrad", p, part, p.M, C1, KW1, sp.c1, s);
+        {
+            ProfScope ps("conv1_wgrad", s);
+            hipLaunchKernelGGL(conv1_wgrad_resident_kernel, dim3(sp.c1), dim3(256), 0, s, batch->obs, dp1, part, B,
+                               resident_spw(B, 256));
+        }
         // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
         launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
     }

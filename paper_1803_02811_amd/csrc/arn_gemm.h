@@ -20,6 +20,9 @@
 // The weights (or dY) go in as A and the activations as B, so a lane ends up
 // with 4 consecutive channels of one position: one 8-byte NHWC store.
 #pragma once
+#ifndef ARN_EXP
+#define ARN_EXP 0
+#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -73,6 +76,16 @@ __device__ __forceinline__ uint4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
 }
 
 __device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
+
+// v if keep else 0, through a mask the optimiser cannot see through: a gather
+// written as `ok ? *p : 0` is compiled to a branch around the load with a wait
+// right behind it, which serialises the loads of one k-tile.  With the mask the
+// (always in-bounds, clamped) loads are issued back to back.
+__device__ __forceinline__ uint4 keep_or_zero(uint4 v, bool keep) {
+    uint32_t mask = keep ? 0xffffffffu : 0u;
+    asm volatile("" : "+v"(mask));
+    return make_uint4(v.x & mask, v.y & mask, v.z & mask, v.w & mask);
+}
 
 // ---------------------------------------------------------------------------
 // out[m][n] = sum_k act(m,k) W[n][k]
@@ -172,7 +185,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
             if constexpr (SPLIT) sW2[(r0 + 32 * i) * LDS_ROW + kc] = rw2[i];
         }
         __syncthreads();
+#if ARN_EXP != 1
         if (kt + 1 < KT) gload(kt + 1);
+#endif
+#if ARN_EXP != 2
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             bf16x8 fw[TN], fa[TM], fw2[SPLIT ? TN : 1], fa2[ALO ? TM : 1];
@@ -199,6 +215,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fa[b], acc[a][b], 0, 0, 0);
                 }
         }
+#endif
     }
 
 #pragma unroll
@@ -277,13 +294,15 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
         for (int i = 0; i < Y_CH; ++i) {
             const int c = tid + 256 * i, r = c / YC, cc = c % YC;
             const long m = mt + r;
-            ry[i] = m < m_end ? p.loady(m, y0 + cc * 8) : zero_u4();
+            const uint4 v = p.loady(m < m_end ? m : m_begin, y0 + cc * 8);   // clamp, load, then zero
+            ry[i] = keep_or_zero(v, m < m_end);
         }
 #pragma unroll
         for (int i = 0; i < X_CH; ++i) {
             const int c = tid + 256 * i, r = c / XC, cc = c % XC;
             const long m = mt + r;
-            rx[i] = m < m_end ? p.loadx(p.xrow(m), x0 + cc * 8) : zero_u4();
+            const uint4 v = p.loadx(p.xrow(m < m_end ? m : m_begin), x0 + cc * 8);
+            rx[i] = keep_or_zero(v, m < m_end);
         }
     };
 

@@ -130,13 +130,19 @@ inline int pick_split(long rows, int tiles, int target_wgs) {
     if (s > iters) s = iters;
     return (int)s;
 }
+// sample-resident weight-gradient kernels: samples per workgroup and number of workgroups
+inline int resident_spw(int B, int target_wgs) { return (B + target_wgs - 1) / target_wgs; }
+inline int resident_groups(int B, int target_wgs) {
+    const int spw = resident_spw(B, target_wgs);
+    return (B + spw - 1) / spw;
+}
 inline Splits make_splits(const Dims &d, int B) {
     Splits s;
-    s.c1 = pick_split((long)B * P1, 2, 1024);
-    s.c2 = pick_split((long)B * P2, 4, 1024);
-    s.c3 = pick_split((long)B * P3, 9, 1024);
-    s.fc = pick_split(B, 49 * 4, 512);
-    s.hd = pick_split(B, 4 * (d.NHP / 64), 512);
+    s.c1 = resident_groups(B, 256);
+    s.c2 = pick_split((long)B * P2, 4, 256);
+    s.c3 = pick_split((long)B * P3, 9, 288);
+    s.fc = pick_split(B, 49 * 4, 392);
+    s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
     return s;
 }
 

@@ -30,11 +30,13 @@ struct ObsGather {
         r.base = obs + (size_t)n * OBS_BYTES + oy * (S1 * IN_W) + ox * S1;
         return r;
     }
+    // Loads are unconditional (out-of-range rows read sample 0 and are zeroed
+    // afterwards) so that several can be in flight at once.
     __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
-        if (!r.ok) return zero_u4();
         const int ci = k >> 6, ky = (k >> 3) & 7;
         const uint32_t *q = reinterpret_cast<const uint32_t *>(r.base + ci * (IN_H * IN_W) + ky * IN_W);
-        return u8x8_to_bf16x8(q[0], q[1]);
+        const uint32_t lo = q[0], hi = q[1];
+        return keep_or_zero(u8x8_to_bf16x8(lo, hi), r.ok);
     }
 };
 
@@ -58,16 +60,16 @@ struct ConvGather {
         return r;
     }
     __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
-        if (!r.ok) return zero_u4();
         constexpr int SEG = KS * CIN;
         const int ky = k / SEG, within = k - ky * SEG;
-        return *reinterpret_cast<const uint4 *>(r.base + ky * (HIN * CIN) + within);
+        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + ky * (HIN * CIN) + within);
+        return keep_or_zero(v, r.ok);
     }
     __device__ __forceinline__ uint4 load_lo_at(const Row &r, int k) const {
-        if (!r.ok) return zero_u4();
         constexpr int SEG = KS * CIN;
         const int ky = k / SEG, within = k - ky * SEG;
-        return *reinterpret_cast<const uint4 *>(r.base + lo_off + ky * (HIN * CIN) + within);
+        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + lo_off + ky * (HIN * CIN) + within);
+        return keep_or_zero(v, r.ok);
     }
 };
 typedef ConvGather<C1, H1, K2, S2, H2> Conv2Gather;
@@ -90,10 +92,12 @@ struct DenseGather {
         return r;
     }
     __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
-        return r.ok ? *reinterpret_cast<const uint4 *>(r.base + k) : zero_u4();
+        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + k);
+        return keep_or_zero(v, r.ok);
     }
     __device__ __forceinline__ uint4 load_lo_at(const Row &r, int k) const {
-        return r.ok ? *reinterpret_cast<const uint4 *>(r.base + lo_off + k) : zero_u4();
+        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + lo_off + k);
+        return keep_or_zero(v, r.ok);
     }
 };
 // dense rows with a run-time row length (head gradients: K = padded head width)
@@ -111,7 +115,8 @@ struct DenseGatherRt {
         return r;
     }
     __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
-        return r.ok ? *reinterpret_cast<const uint4 *>(r.base + k) : zero_u4();
+        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + k);
+        return keep_or_zero(v, r.ok);
     }
 };
 
@@ -160,8 +165,9 @@ struct ConvFwd : Gather {
 typedef ConvFwd<Conv2Gather, C2, KW2> Conv2Fwd;
 typedef ConvFwd<Conv3Gather, C3, KW3> Conv3Fwd;
 
-struct FcFwd : DenseGather<FEAT> {
-    static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT;
+template <int BT>   // square workgroup tile: 64 fills the chip at B = 2048, 128 reuses operands better at large B
+struct FcFwdT : DenseGather<FEAT> {
+    static constexpr int BM = BT, BN = BT, WAVES_N = 2, K = FEAT;
     static constexpr bool ACT_LO = true;
     const __bf16 *w, *w_lo = nullptr;
     const float *bias;
@@ -178,6 +184,7 @@ struct FcFwd : DenseGather<FEAT> {
                            fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
     }
 };
+typedef FcFwdT<128> FcFwd;
 
 // heads: rows of the packed head matrix are the A policy rows then the value
 // row (PV), or the A*atoms categorical rows (C51); outputs are fp32.
@@ -210,7 +217,7 @@ struct HeadFwd : DenseGather<HID> {
 // --------------------------- input gradients ------------------------------
 // d(pre_fc) = (dz W_head) * [h > 0]; the contraction length is the padded head width
 struct HeadDgrad : DenseGatherRt {
-    static constexpr int BM = 128, BN = 128, WAVES_N = 2;
+    static constexpr int BM = 64, BN = 64, WAVES_N = 2;
     const __bf16 *w;     // [512][K]
     const __bf16 *h;
     __bf16 *out;         // [M][512]
@@ -272,8 +279,10 @@ struct Conv3Dgrad {
     __device__ __forceinline__ uint4 load(const Row &r, int k) const {
         const int tap = k >> 6, ty = tap / 3, tx = tap - ty * 3;
         const int sy = r.y - 2 + ty, sx = r.x - 2 + tx;
-        if (!r.ok || sy < 0 || sy >= H3 || sx < 0 || sx >= H3) return zero_u4();
-        return *reinterpret_cast<const uint4 *>(dpre + r.base + ((ty - 2) * H3 + (tx - 2)) * C3 + (k & 63));
+        const bool ok = r.ok && sy >= 0 && sy < H3 && sx >= 0 && sx < H3;
+        const long at = ok ? r.base + ((ty - 2) * H3 + (tx - 2)) * C3 + (k & 63) : 0;   // clamp, load, then zero
+        const uint4 v = *reinterpret_cast<const uint4 *>(dpre + at);
+        return keep_or_zero(v, ok);
     }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
@@ -313,8 +322,10 @@ struct Conv2Dgrad {
     __device__ __forceinline__ uint4 load(const Row &r, int k) const {
         const int tap = k >> 6, ty = tap >> 1, tx = tap & 1;
         const int sy = r.u - 1 + ty, sx = r.v - 1 + tx;
-        if (!r.ok || sy < 0 || sy >= H2 || sx < 0 || sx >= H2) return zero_u4();
-        return *reinterpret_cast<const uint4 *>(dpre + r.base + ((ty - 1) * H2 + (tx - 1)) * C2 + (k & 63));
+        const bool ok = r.ok && sy >= 0 && sy < H2 && sx >= 0 && sx < H2;
+        const long at = ok ? r.base + ((ty - 1) * H2 + (tx - 1)) * C2 + (k & 63) : 0;
+        const uint4 v = *reinterpret_cast<const uint4 *>(dpre + at);
+        return keep_or_zero(v, ok);
     }
     __device__ __forceinline__ const __bf16 *weights(int z) const { return w + (size_t)z * C1 * K; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {

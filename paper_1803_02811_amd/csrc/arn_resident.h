@@ -1,0 +1,141 @@
+// Weight-gradient kernels that keep one sample's operands resident in LDS.
+//
+// dW[co][k'] = sum over samples and output positions m of dY[m][co] * x(m,k').
+// The contraction index m is the slow index of both operands in memory, so both
+// MFMA fragments are taken with the transposing LDS read.  Unlike the generic
+// gemm_tn_kernel no im2col tile is built: a sample's input (converted to bf16
+// once) and its dY rows are copied to LDS with contiguous 16-byte loads, and the
+// transposing reads address the overlapping windows inside that image directly.
+// Each workgroup owns a fixed, contiguous range of samples and accumulates in
+// registers; partial results go to part[workgroup][...] and are summed in
+// workgroup order by reduce_partials_kernel, so dW is bit-reproducible.
+#pragma once
+#include "arn_gemm.h"
+#include "arn_layout.h"
+
+namespace arn {
+
+// two transposing 8-byte reads -> one MFMA fragment (k = rows a..a+3, b..b+3)
+__device__ __forceinline__ bf16x8 tr_pair(const char *lds_base, int off_a, int off_b) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + off_a));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + off_b));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// conv1: x = uint8 observation [4][84][84] (k' = ci*64 + ky*8 + kx, window at
+// (4oy, 4ox)), dY = d(pre1) [400][32].  part[wg] = [32][256] then [32] bias sums.
+// The 1/255 pixel scale is applied by the reduction.
+__global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t *__restrict__ obs,
+                                                                   const __bf16 *__restrict__ dy,
+                                                                   float *__restrict__ part, int B, int spw) {
+    constexpr int IMG_U4 = OBS_BYTES / 16;        // 1764 sixteen-pixel groups per sample
+    constexpr int DY_U4 = P1 * C1 * 2 / 16;       // 1600
+    constexpr int NI = (IMG_U4 + 255) / 256, ND = (DY_U4 + 255) / 256;   // 7, 7
+    __shared__ uint4 s_img[2 * IMG_U4];           // bf16 [4][84][84]
+    __shared__ uint4 s_dy[DY_U4];                 // bf16 [400][32]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s_begin = blockIdx.x * spw;
+    const int s_end = s_begin + spw < B ? s_begin + spw : B;
+
+    uint4 rimg[NI], rdy[ND];
+    auto gload = [&](int s) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(obs + (size_t)s * OBS_BYTES);
+        const uint4 *dsrc = reinterpret_cast<const uint4 *>(dy + (size_t)s * P1 * C1);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = tid + 256 * i;
+            rimg[i] = src[idx < IMG_U4 ? idx : IMG_U4 - 1];
+        }
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int idx = tid + 256 * i;
+            rdy[i] = dsrc[idx < DY_U4 ? idx : DY_U4 - 1];
+        }
+    };
+
+    f32x16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    float bsum = 0.f;
+
+    // per-lane constants of the transposing reads
+    const int o = lane & 15, G = lane >> 4;
+    const int row_in_step = 8 * (G >> 1) + (o >> 2);          // + 4 for the second read
+    const int ycol_off = (16 * (G & 1) + 4 * (o & 3)) * 2;    // byte offset inside a dY row
+    const int ky_lane = 2 * (G & 1) + ((o & 3) >> 1), kx0 = 4 * (o & 1);
+    int xoff[2];                                               // byte offset of (ci, ky, kx0) for the wave's two column tiles
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int t = 2 * wave + j, ci = t >> 1, ky = (t & 1) * 4 + ky_lane;
+        xoff[j] = ((ci * IN_H + ky) * IN_W + kx0) * 2;
+    }
+    const int bco = tid & 31, bpart = tid >> 5;
+
+    if (s_begin < s_end) gload(s_begin);
+    for (int s = s_begin; s < s_end; ++s) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = tid + 256 * i;
+            if (idx < IMG_U4) {
+                s_img[2 * idx] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
+                s_img[2 * idx + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int idx = tid + 256 * i;
+            if (idx < DY_U4) s_dy[idx] = rdy[i];
+        }
+        __syncthreads();
+        if (s + 1 < s_end) gload(s + 1);
+
+        const char *img = reinterpret_cast<const char *>(s_img);
+        const char *dyl = reinterpret_cast<const char *>(s_dy);
+#pragma unroll 5
+        for (int ks = 0; ks < P1 / 16; ++ks) {
+            const int ma = 16 * ks + row_in_step, mb = ma + 4;
+            const int oya = ma / H1, oxa = ma - oya * H1, oyb = mb / H1, oxb = mb - oyb * H1;
+            const int pa = (S1 * oya * IN_W + S1 * oxa) * 2, pb = (S1 * oyb * IN_W + S1 * oxb) * 2;
+            const bf16x8 fy = tr_pair(dyl, ma * (C1 * 2) + ycol_off, mb * (C1 * 2) + ycol_off);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x8 fx = tr_pair(img, pa + xoff[j], pb + xoff[j]);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc[j], 0, 0, 0);
+            }
+        }
+        // bias gradient: eight threads per channel, 50 rows each, in row order
+        const __bf16 *col = reinterpret_cast<const __bf16 *>(s_dy) + bco;
+#pragma unroll 10
+        for (int r = 0; r < P1 / 8; ++r) bsum += (float)col[(bpart * (P1 / 8) + r) * C1];
+    }
+
+    float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
+    const int fr = lane & 31, fg = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int k = (2 * wave + j) * 32 + fr;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int n = 8 * (r >> 2) + 4 * fg + (r & 3);
+            out[n * KW1 + k] = acc[j][r];
+        }
+    }
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(s_dy);
+    red[tid] = bsum;
+    __syncthreads();
+    if (tid < C1) {
+        float t = 0.f;
+#pragma unroll
+        for (int p8 = 0; p8 < 8; ++p8) t += red[p8 * 32 + tid];
+        out[C1 * KW1 + tid] = t;
+    }
+}
+
+}  // namespace arn

@@ -122,7 +122,15 @@ __global__ void reduce_partials_kernel(F f, const float *__restrict__ part, floa
     const long dst = f(i);
     if (dst < 0) return;
     float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += part[(size_t)k * block + i];
+    int k = 0;
+    for (; k + 8 <= splits; k += 8) {     // eight independent loads in flight, added in split order
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = part[(size_t)(k + j) * block + i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += v[j];
+    }
+    for (; k < splits; ++k) s += part[(size_t)k * block + i];
     dW[dst] = i < wcount ? s * wscale : s;
 }
 template <int CIN, int KS, int COUT>
