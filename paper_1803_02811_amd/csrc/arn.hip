@@ -364,10 +364,13 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     }
     // ---- conv3 ----
     {
-        Conv3Wgrad p;
-        p.in = a2; p.M = B * P3; p.dy = dp3;
         float *part = (float *)(ws + o.pw3);
-        launch_tn("conv3_wgrad", p, part, p.M, C3, KW3, sp.c3, s);
+        {
+            ProfScope ps("conv3_wgrad", s);
+            const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
+                               dim3(256), 0, s, a2, dp3, part, B, resident_spw(groups, 256) * CONV3_WG_G);
+        }
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s);
     }
     {
@@ -377,10 +380,13 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     }
     // ---- conv2 ----
     {
-        Conv2Wgrad p;
-        p.in = a1; p.M = B * P2; p.dy = dp2;
         float *part = (float *)(ws + o.pw2);
-        launch_tn("conv2_wgrad", p, part, p.M, C2, KW2, sp.c2, s);
+        {
+            ProfScope ps("conv2_wgrad", s);
+            const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 1>), dim3(sp.c2),
+                               dim3(256), 0, s, a1, dp2, part, B, resident_spw(groups, 256) * CONV2_WG_G);
+        }
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s);
     }
     {

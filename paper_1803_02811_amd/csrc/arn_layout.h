@@ -130,6 +130,7 @@ inline int pick_split(long rows, int tiles, int target_wgs) {
     if (s > iters) s = iters;
     return (int)s;
 }
+constexpr int CONV2_WG_G = 2, CONV3_WG_G = 4;   // samples staged per iteration by the conv2 / conv3 weight-gradient kernels
 // sample-resident weight-gradient kernels: samples per workgroup and number of workgroups
 inline int resident_spw(int B, int target_wgs) { return (B + target_wgs - 1) / target_wgs; }
 inline int resident_groups(int B, int target_wgs) {
@@ -139,8 +140,8 @@ inline int resident_groups(int B, int target_wgs) {
 inline Splits make_splits(const Dims &d, int B) {
     Splits s;
     s.c1 = resident_groups(B, 256);
-    s.c2 = pick_split((long)B * P2, 4, 256);
-    s.c3 = pick_split((long)B * P3, 9, 288);
+    s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, 256);
+    s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, 256);
     s.fc = pick_split(B, 49 * 4, 392);
     s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
     return s;

@@ -138,4 +138,156 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
     }
 }
 
+// conv2 / conv3: x = NHWC bf16 activations [HIN][HIN][CIN] of G samples per
+// iteration (k' = (ky*KS + kx)*CIN + ci), dY = d(pre) rows [G*HOUT*HOUT][COUT].
+// LDS pixels and dY rows are padded (PS, YS bytes) so that the four rows touched
+// by one transposing read fall into different banks.  WAVES_Y wavefronts split
+// the COUT/32 row tiles, the others split the column tiles.
+template <int CIN, int HIN, int KS, int STRIDE, int HOUT, int COUT, int G, int WAVES_Y>
+__global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *__restrict__ x,
+                                                                  const __bf16 *__restrict__ dy,
+                                                                  float *__restrict__ part, int B, int spw) {
+    constexpr int PIX = HIN * HIN, P = HOUT * HOUT, KP = KS * KS * CIN;
+    constexpr int PS = CIN * 2 + 16, YS = COUT * 2 + 16;            // padded strides in bytes
+    constexpr int R = G * P, KSTEPS = (R + 15) / 16, RPAD = KSTEPS * 16;
+    constexpr int XCH = CIN / 8, YCH = COUT / 8;                     // 16-byte chunks per pixel / per dY row
+    constexpr int NXC = G * PIX * XCH, NYC = G * P * YCH;
+    constexpr int NI = (NXC + 255) / 256, ND = (NYC + 255) / 256;
+    constexpr int NY = COUT / 32, NX = KP / 32, WAVES_X = 4 / WAVES_Y;
+    constexpr int TY = NY / WAVES_Y, TX = NX / WAVES_X;
+    static_assert(NY % WAVES_Y == 0 && NX % WAVES_X == 0, "tile split");
+    constexpr int BPARTS = 256 / COUT, BROWS = (R + BPARTS - 1) / BPARTS;
+
+    __shared__ uint4 s_x[G * PIX * PS / 16];
+    __shared__ uint4 s_dy[RPAD * YS / 16];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wy = wave % WAVES_Y, wx = wave / WAVES_Y;
+    const int s_begin = blockIdx.x * spw;
+    const int s_end = s_begin + spw < B ? s_begin + spw : B;
+
+    // rows R..RPAD of dY stay zero for the whole kernel
+    for (int i = tid; i < (RPAD - R) * YS / 16; i += 256) s_dy[R * YS / 16 + i] = zero_u4();
+
+    uint4 rx[NI], ry[ND];
+    auto gload = [&](int s) {   // samples s .. s+G-1; those at or beyond s_end are read from s_end-1 and zeroed on store
+        const int last = s_end - 1;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            int idx = tid + 256 * i;
+            idx = idx < NXC ? idx : NXC - 1;
+            const int g = idx / (PIX * XCH), rem = idx - g * (PIX * XCH);
+            const int sg = s + g < s_end ? s + g : last;
+            rx[i] = reinterpret_cast<const uint4 *>(x + (size_t)sg * PIX * CIN)[rem];
+        }
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            int idx = tid + 256 * i;
+            idx = idx < NYC ? idx : NYC - 1;
+            const int g = idx / (P * YCH), rem = idx - g * (P * YCH);
+            const int sg = s + g < s_end ? s + g : last;
+            ry[i] = reinterpret_cast<const uint4 *>(dy + (size_t)sg * P * COUT)[rem];
+        }
+    };
+
+    f32x16 acc[TY][TX];
+#pragma unroll
+    for (int a = 0; a < TY; ++a)
+#pragma unroll
+        for (int b = 0; b < TX; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    float bsum = 0.f;
+
+    const int o = lane & 15, Gq = lane >> 4;
+    const int row_in_step = 8 * (Gq >> 1) + (o >> 2);
+    const int col_lane = (16 * (Gq & 1) + 4 * (o & 3)) * 2;         // byte offset of the lane's 4 columns in a 32-column tile
+    const int bco = tid % COUT, bpart = tid / COUT;
+
+    if (s_begin < s_end) gload(s_begin);
+    for (int s = s_begin; s < s_end; s += G) {
+        __syncthreads();
+        char *xl = reinterpret_cast<char *>(s_x);
+        char *yl = reinterpret_cast<char *>(s_dy);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = tid + 256 * i;
+            if (idx < NXC) {
+                const int pix = idx / XCH, c = idx - pix * XCH;
+                const bool live = s + pix / PIX < s_end;
+                *reinterpret_cast<uint4 *>(xl + pix * PS + c * 16) = live ? rx[i] : zero_u4();
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int idx = tid + 256 * i;
+            if (idx < NYC) {
+                const int row = idx / YCH, c = idx - row * YCH;
+                const bool live = s + row / P < s_end;
+                *reinterpret_cast<uint4 *>(yl + row * YS + c * 16) = live ? ry[i] : zero_u4();
+            }
+        }
+        __syncthreads();
+        if (s + G < s_end) gload(s + G);
+
+#pragma unroll 1
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const int ma = 16 * ks + row_in_step, mb = ma + 4;
+            int base[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int m = h ? mb : ma;
+                m = m < R ? m : R - 1;                       // padded rows: any in-range window (their dY is zero)
+                const int g = m / P, rem = m - g * P, oy = rem / HOUT, ox = rem - oy * HOUT;
+                base[h] = (g * PIX + STRIDE * oy * HIN + STRIDE * ox) * PS + col_lane;
+            }
+            bf16x8 fy[TY];
+#pragma unroll
+            for (int a = 0; a < TY; ++a) {
+                const int c0 = (wy * TY + a) * 64 + col_lane;
+                fy[a] = tr_pair(yl, ma * YS + c0, mb * YS + c0);
+            }
+#pragma unroll
+            for (int b = 0; b < TX; ++b) {
+                const int k0 = (wx * TX + b) * 32, tap = k0 / CIN, ci0 = k0 - tap * CIN;
+                const int ky = tap / KS, kx = tap - ky * KS;
+                const int toff = (ky * HIN + kx) * PS + ci0 * 2;
+                const bf16x8 fx = tr_pair(xl, base[0] + toff, base[1] + toff);
+#pragma unroll
+                for (int a = 0; a < TY; ++a)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[a], fx, acc[a][b], 0, 0, 0);
+            }
+        }
+        // bias gradient: 256/COUT threads per channel, consecutive row blocks, in row order
+        if (bpart < BPARTS) {
+            const int r0 = bpart * BROWS, r1 = r0 + BROWS < R ? r0 + BROWS : R;
+            for (int r = r0; r < r1; ++r) bsum += (float)*reinterpret_cast<const __bf16 *>(yl + r * YS + bco * 2);
+        }
+    }
+
+    float *out = part + (size_t)blockIdx.x * (COUT * KP + COUT);
+    const int fr = lane & 31, fg = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < TY; ++a)
+#pragma unroll
+        for (int b = 0; b < TX; ++b) {
+            const int k = (wx * TX + b) * 32 + fr;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int n = (wy * TY + a) * 32 + 8 * (r >> 2) + 4 * fg + (r & 3);
+                out[(size_t)n * KP + k] = acc[a][b][r];
+            }
+        }
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(s_dy);
+    red[tid] = bsum;
+    __syncthreads();
+    if (tid < COUT) {
+        float t = 0.f;
+#pragma unroll
+        for (int p8 = 0; p8 < BPARTS; ++p8) t += red[p8 * COUT + tid];
+        out[COUT * KP + tid] = t;
+    }
+}
+
 }  // namespace arn
