@@ -83,8 +83,9 @@ void launch_reduce(const char *name, const F &f, const float *part, float *dW, l
                    float wscale, hipStream_t s) {
     ProfScope ps(name, s);
     const long block = wcount + bcount;
-    hipLaunchKernelGGL(reduce_partials_kernel<F>, dim3(cdiv(block, 256)), dim3(256), 0, s, f, part, dW, block, wcount,
-                       splits, wscale);
+    const int ng = splits >= 64 ? 8 : splits >= 16 ? 4 : splits >= 4 ? 2 : 1;
+    hipLaunchKernelGGL(reduce_partials_kernel<F>, dim3(cdiv(block, 256 / ng)), dim3(256), 0, s, f, part, dW, block,
+                       wcount, splits, wscale, ng);
 }
 
 template <class F>
@@ -153,12 +154,19 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         p.out = a3; p.out_lo = a3l;
         split ? launch_nt_split("conv3_fwd", p, p.M, 1, 1, s) : launch_nt("conv3_fwd", p, p.M, 1, 1, s);
     }
-    auto fc = [&](auto p) {
+    {
+        FcFwd p;
         p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
-        p.out = h; p.out_lo = hl;
-        split ? launch_nt_split("fc_fwd", p, B, HID / p.BN, 1, s) : launch_nt("fc_fwd", p, B, HID / p.BN, 1, s);
-    };
-    if (B >= 8192) fc(FcFwdT<128>{}); else fc(FcFwdT<64>{});
+        p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
+        split ? launch_nt_split("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s)
+              : launch_nt("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s);
+        if (p.ksplit > 1) {
+            ProfScope ps("fc_finish", s);
+            const long total = (long)B * HID;
+            hipLaunchKernelGGL(fc_finish_kernel, dim3(cdiv(total / 4, 256)), dim3(256), 0, s, p.partial, p.ksplit,
+                               w.bfc, h, hl, total);
+        }
+    }
     if (d.head == ARN_HEAD_PV) {
         HeadFwd<32> p;
         p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;

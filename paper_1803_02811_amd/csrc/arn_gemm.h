@@ -10,8 +10,8 @@
 //       taken from LDS with the transposing read ds_read_b64_tr_b16.
 //
 // Both use v_mfma_f32_32x32x16_bf16 (fp32 accumulate), 256 threads = 4
-// wavefronts of 64 lanes, and 64-element k-tiles staged through LDS with a
-// register prefetch of the next tile.
+// wavefronts of 64 lanes, and 64-element k-tiles staged through LDS (two stages
+// in the NT kernel) with a register prefetch of the tile after next.
 //
 // MFMA operand layout used throughout (checked on hardware):
 //   A (32 x 16): lane l holds row l%32,  k = 8*(l/32) .. +7
@@ -20,9 +20,6 @@
 // The weights (or dY) go in as A and the activations as B, so a lane ends up
 // with 4 consecutive channels of one position: one 8-byte NHWC store.
 #pragma once
-#ifndef ARN_EXP
-#define ARN_EXP 0
-#endif
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -116,19 +113,52 @@ struct ActLo<P, true> {
     static constexpr bool value = P::ACT_LO;
 };
 
+// Problems with a data member `ksplit` cut the contraction into that many
+// ranges of k-tiles, one per blockIdx.z; their store() receives z and writes a
+// partial sum that a later kernel adds up in z order.
+template <class P, class = void>
+struct HasKSplit {
+    static constexpr bool value = false;
+};
+template <class P>
+struct HasKSplit<P, decltype((void)P::ksplit)> {
+    static constexpr bool value = true;
+};
+
+// Problems with a static member STAGES = 2 double-buffer their LDS tiles (one
+// barrier per k-tile, staging of the next tile overlaps the MFMAs); the default
+// of one stage halves the LDS footprint, which matters more when several
+// workgroups can share a CU.
+template <class P, class = void>
+struct StagesOf {
+    static constexpr int value = 1;
+};
+template <class P>
+struct StagesOf<P, decltype((void)P::STAGES)> {
+    static constexpr int value = P::STAGES;
+};
+
 template <class P, bool SPLIT = false>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
     constexpr int BM = P::BM, BN = P::BN, WN = P::WAVES_N, WM = 4 / WN;
     constexpr int TN = BN / (32 * WN), TM = BM / (32 * WM);
     constexpr int A_CH = BM / 32, W_CH = BN / 32;     // 16-byte chunks staged per thread and k-tile
     constexpr bool ALO = ActLo<P, SPLIT>::value;
-    const int KT = p.K / 64;
+    int kt_begin = 0, KT = p.K / 64;
+    if constexpr (HasKSplit<P>::value) {
+        const int total = KT;
+        kt_begin = (int)blockIdx.z * total / p.ksplit;
+        KT = ((int)blockIdx.z + 1) * total / p.ksplit;
+    }
     static_assert(TN >= 1 && TM >= 1, "tile shape");
 
-    __shared__ uint4 sA[BM * LDS_ROW];
-    __shared__ uint4 sW[BN * LDS_ROW];
-    __shared__ uint4 sA2[ALO ? BM * LDS_ROW : 1];
-    __shared__ uint4 sW2[SPLIT ? BN * LDS_ROW : 1];
+    // with two LDS stages tile kt is consumed from stage kt&1 while tile kt+1 is written to the other
+    constexpr int NST = StagesOf<P>::value;
+    constexpr int SA = BM * LDS_ROW, SW = BN * LDS_ROW;
+    __shared__ uint4 sA[NST * SA];
+    __shared__ uint4 sW[NST * SW];
+    __shared__ uint4 sA2[ALO ? NST * SA : 1];
+    __shared__ uint4 sW2[SPLIT ? NST * SW : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave % WN, wm = wave / WN;
@@ -170,37 +200,44 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    gload(0);
-    const int fr = lane & 31, fg = lane >> 5;
-    for (int kt = 0; kt < KT; ++kt) {
-        __syncthreads();
+    auto stage = [&](int st) {   // registers -> LDS stage st
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
-            sA[(r0 + 32 * i) * LDS_ROW + kc] = ra[i];
-            if constexpr (ALO) sA2[(r0 + 32 * i) * LDS_ROW + kc] = ra2[i];
+            sA[st * SA + (r0 + 32 * i) * LDS_ROW + kc] = ra[i];
+            if constexpr (ALO) sA2[st * SA + (r0 + 32 * i) * LDS_ROW + kc] = ra2[i];
         }
 #pragma unroll
         for (int i = 0; i < W_CH; ++i) {
-            sW[(r0 + 32 * i) * LDS_ROW + kc] = rw[i];
-            if constexpr (SPLIT) sW2[(r0 + 32 * i) * LDS_ROW + kc] = rw2[i];
+            sW[st * SW + (r0 + 32 * i) * LDS_ROW + kc] = rw[i];
+            if constexpr (SPLIT) sW2[st * SW + (r0 + 32 * i) * LDS_ROW + kc] = rw2[i];
         }
-        __syncthreads();
-#if ARN_EXP != 1
-        if (kt + 1 < KT) gload(kt + 1);
-#endif
-#if ARN_EXP != 2
+    };
+
+    const int fr = lane & 31, fg = lane >> 5;
+    gload(kt_begin);
+    stage(0);
+    if (kt_begin + 1 < KT) gload(kt_begin + 1);
+    __syncthreads();
+    for (int kt = kt_begin; kt < KT; ++kt) {
+        const int st = NST == 2 ? (kt - kt_begin) & 1 : 0;
+        if constexpr (NST == 2) {
+            // tile kt+1 (in registers since the previous iteration) goes to the free stage,
+            // then the loads of tile kt+2 are issued; both overlap the MFMAs on tile kt
+            if (kt + 1 < KT) stage(st ^ 1);
+            if (kt + 2 < KT) gload(kt + 2);
+        }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             bf16x8 fw[TN], fa[TM], fw2[SPLIT ? TN : 1], fa2[ALO ? TM : 1];
 #pragma unroll
             for (int a = 0; a < TN; ++a) {
-                const int at = ((wn * TN + a) * 32 + fr) * LDS_ROW + kk * 2 + fg;
+                const int at = st * SW + ((wn * TN + a) * 32 + fr) * LDS_ROW + kk * 2 + fg;
                 fw[a] = as_bf16x8(sW[at]);
                 if constexpr (SPLIT) fw2[a] = as_bf16x8(sW2[at]);
             }
 #pragma unroll
             for (int b = 0; b < TM; ++b) {
-                const int at = ((wm * TM + b) * 32 + fr) * LDS_ROW + kk * 2 + fg;
+                const int at = st * SA + ((wm * TM + b) * 32 + fr) * LDS_ROW + kk * 2 + fg;
                 fa[b] = as_bf16x8(sA[at]);
                 if constexpr (ALO) fa2[b] = as_bf16x8(sA2[at]);
             }
@@ -215,7 +252,14 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fa[b], acc[a][b], 0, 0, 0);
                 }
         }
-#endif
+        __syncthreads();
+        if constexpr (NST == 1) {
+            if (kt + 1 < KT) {
+                stage(0);
+                if (kt + 2 < KT) gload(kt + 2);
+                __syncthreads();
+            }
+        }
     }
 
 #pragma unroll

@@ -147,6 +147,15 @@ inline Splits make_splits(const Dims &d, int B) {
     return s;
 }
 
+// number of k ranges the fc forward GEMM is cut into (fills the chip when B/128 * 4 tiles are too few)
+inline int fc_ksplit(int B) {
+    const int tiles = ((B + 127) / 128) * 4;
+    int ks = 256 / tiles;
+    if (ks < 1) ks = 1;
+    if (ks > 49) ks = 49;
+    return ks;
+}
+
 constexpr int LOSS_BLOCK = 256;   // samples per block in the actor-critic loss kernel
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
@@ -154,6 +163,7 @@ constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in th
 struct Workspace {
     size_t a1, a2, a3, h;               // bf16 NHWC activations
     size_t a1l, a2l, a3l, hl;           // their low parts (written and read by the forward pass only)
+    size_t fcp;                         // fp32 [ksplit][B][512] partial sums of the fc forward GEMM
     size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
     size_t dz, dph, dp3, dp2, dp1;      // bf16 gradients at pre-activations
@@ -177,6 +187,7 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     w.a2l = take(b * P2 * C2 * 2);
     w.a3l = take(b * FEAT * 2);
     w.hl = take(b * HID * 2);
+    w.fcp = take((size_t)(fc_ksplit(B) > 1 ? fc_ksplit(B) : 0) * b * HID * 4);
     if (mode == ARN_MODE_TRAIN) {
         w.z = take(b * (size_t)(d.head == ARN_HEAD_PV ? d.A : d.NH) * 4);
         w.zv = take(b * 4);

@@ -165,26 +165,34 @@ struct ConvFwd : Gather {
 typedef ConvFwd<Conv2Gather, C2, KW2> Conv2Fwd;
 typedef ConvFwd<Conv3Gather, C3, KW3> Conv3Fwd;
 
-template <int BT>   // square workgroup tile: 64 fills the chip at B = 2048, 128 reuses operands better at large B
-struct FcFwdT : DenseGather<FEAT> {
-    static constexpr int BM = BT, BN = BT, WAVES_N = 2, K = FEAT;
+// fc: h = relu(act3 Wfc^T + b).  With ksplit > 1 each blockIdx.z covers a range
+// of k-tiles and writes an fp32 partial [z][M][512]; fc_finish_kernel adds the
+// partials in z order and applies bias, ReLU and the hi/lo split.  With
+// ksplit == 1 the epilogue does that directly.
+struct FcFwd : DenseGather<FEAT> {
+    static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT, STAGES = 2;
     static constexpr bool ACT_LO = true;
+    int ksplit;
     const __bf16 *w, *w_lo = nullptr;
     const float *bias;
     __bf16 *out, *out_lo = nullptr;
+    float *partial;
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
     __device__ __forceinline__ uint4 load(const Row &r, int k) const { return load_at(r, k); }
     __device__ __forceinline__ uint4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
-    __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
+    __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {
         if (m >= M) return;
+        if (ksplit > 1) {
+            *reinterpret_cast<float4 *>(partial + ((size_t)z * M + m) * HID + n) = make_float4(v[0], v[1], v[2], v[3]);
+            return;
+        }
         const float4 b = *reinterpret_cast<const float4 *>(bias + n);
         store_bf16x4_split(out, out_lo, (size_t)m * HID + n, fmaxf(v[0] + b.x, 0.f), fmaxf(v[1] + b.y, 0.f),
                            fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
     }
 };
-typedef FcFwdT<128> FcFwd;
 
 // heads: rows of the packed head matrix are the A policy rows then the value
 // row (PV), or the A*atoms categorical rows (C51); outputs are fp32.
@@ -235,7 +243,7 @@ struct HeadDgrad : DenseGatherRt {
 
 // d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][3136], NHWC index
 struct FcDgrad : DenseGather<HID> {
-    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID;
+    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 2;
     const __bf16 *w;     // [3136][512]
     const __bf16 *act;   // act3
     __bf16 *out;

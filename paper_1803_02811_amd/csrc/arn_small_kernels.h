@@ -114,24 +114,40 @@ struct MapConv2Dgrad { // packed [z][ci][(ty*2+tx)*64+co]  <-  W2[co][ci][py+2(1
 // dW[map(n,k)] = wscale * sum_s part[s][n*KP + k];  db[bmap(n)] = sum_s part[s][N1*KP + n]
 // F maps an index of the [N1*KP + N1] partial block to the flat gradient index (or -1);
 // the first `wcount` entries of the block are weights, the rest biases.
+// A block of 256 threads reduces 256/ng outputs: ng thread groups (1, 2, 4 or 8)
+// each add a contiguous share of the splits in split order, then the group sums
+// are added in group order -- a fixed association, so the result is bit-reproducible.
 template <class F>
-__global__ void reduce_partials_kernel(F f, const float *__restrict__ part, float *__restrict__ dW, long block,
-                                       long wcount, int splits, float wscale) {
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= block) return;
-    const long dst = f(i);
-    if (dst < 0) return;
+__global__ __launch_bounds__(256) void reduce_partials_kernel(F f, const float *__restrict__ part,
+                                                              float *__restrict__ dW, long block, long wcount,
+                                                              int splits, float wscale, int ng) {
+    __shared__ float red[256];
+    const int opb = 256 / ng;
+    const int o = threadIdx.x % opb, q = threadIdx.x / opb;
+    const long i = (long)blockIdx.x * opb + o;
+    const int per = (splits + ng - 1) / ng;
+    const int k0 = q * per, k1 = k0 + per < splits ? k0 + per : splits;
     float s = 0.f;
-    int k = 0;
-    for (; k + 8 <= splits; k += 8) {     // eight independent loads in flight, added in split order
-        float v[8];
+    if (i < block) {
+        int k = k0;
+        for (; k + 8 <= k1; k += 8) {     // eight independent loads in flight, added in split order
+            float v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = part[(size_t)(k + j) * block + i];
+            for (int j = 0; j < 8; ++j) v[j] = part[(size_t)(k + j) * block + i];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) s += v[j];
+            for (int j = 0; j < 8; ++j) s += v[j];
+        }
+        for (; k < k1; ++k) s += part[(size_t)k * block + i];
     }
-    for (; k < splits; ++k) s += part[(size_t)k * block + i];
-    dW[dst] = i < wcount ? s * wscale : s;
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (q == 0 && i < block) {
+        const long dst = f(i);
+        if (dst < 0) return;
+        float t = red[o];
+        for (int g = 1; g < ng; ++g) t += red[g * opb + o];
+        dW[dst] = i < wcount ? t * wscale : t;
+    }
 }
 template <int CIN, int KS, int COUT>
 struct UnmapConv {     // partial [co][(ky*KS+kx)*CIN+ci] then [co] bias
@@ -165,6 +181,30 @@ struct UnmapHead {
         return b < 0 ? -1 : b + i % HID;
     }
 };
+
+// h = relu(sum_z partial[z] + bias), written as bf16 hi (and lo = residual) -- the
+// second half of the split-k fc layer.  One thread per four outputs.
+__global__ void fc_finish_kernel(const float *__restrict__ partial, int ksplit, const float *__restrict__ bias,
+                                 __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo, long total) {
+    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= total) return;
+    float4 s = *reinterpret_cast<const float4 *>(partial + i);
+    for (int z = 1; z < ksplit; ++z) {
+        const float4 v = *reinterpret_cast<const float4 *>(partial + (size_t)z * total + i);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    const float4 b = *reinterpret_cast<const float4 *>(bias + (i & (HID - 1)));
+    const float r0 = fmaxf(s.x + b.x, 0.f), r1 = fmaxf(s.y + b.y, 0.f), r2 = fmaxf(s.z + b.z, 0.f),
+                r3 = fmaxf(s.w + b.w, 0.f);
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    const bf16x4_t h = {(__bf16)r0, (__bf16)r1, (__bf16)r2, (__bf16)r3};
+    *reinterpret_cast<uint2 *>(out + i) = __builtin_bit_cast(uint2, h);
+    if (out_lo) {
+        const bf16x4_t l = {(__bf16)(r0 - (float)h[0]), (__bf16)(r1 - (float)h[1]), (__bf16)(r2 - (float)h[2]),
+                            (__bf16)(r3 - (float)h[3])};
+        *reinterpret_cast<uint2 *>(out_lo + i) = __builtin_bit_cast(uint2, l);
+    }
+}
 
 // ------------------------------ reductions ---------------------------------
 __device__ __forceinline__ float wave_sum(float v) {     // result valid in every lane, same bits
