@@ -10,6 +10,7 @@
 #include "arn_layout.h"
 #include "arn_problems.h"
 #include "arn_resident.h"
+#include "arn_resident_conv.h"
 #include "arn_small_kernels.h"
 
 using namespace arn;
@@ -78,6 +79,15 @@ void launch_tn(const char *name, const P &p, float *part, long M, int N1, int KP
                        (int)rows);
 }
 
+// sample-resident convolution: a fixed, contiguous range of samples per workgroup
+template <class C>
+void launch_resident(const char *name, const typename C::Args &a, int B, hipStream_t s) {
+    ProfScope ps(name, s);
+    const int groups = (B + C::G - 1) / C::G;
+    const int spw = resident_spw(groups, 256) * C::G;
+    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(cdiv(B, spw)), dim3(RES_THREADS), 0, s, a, B, spw);
+}
+
 template <class F>
 void launch_reduce(const char *name, const F &f, const float *part, float *dW, long wcount, long bcount, int splits,
                    float wscale, hipStream_t s) {
@@ -143,16 +153,14 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         split ? launch_nt_split("conv1_fwd", p, p.M, 1, 1, s) : launch_nt("conv1_fwd", p, p.M, 1, 1, s);
     }
     {
-        Conv2Fwd p;
-        p.in = a1; p.lo_off = a1l - a1; p.M = B * P2; p.w = w.w2; p.w_lo = w.w2l; p.bias = w.b2;
-        p.out = a2; p.out_lo = a2l;
-        split ? launch_nt_split("conv2_fwd", p, p.M, 1, 1, s) : launch_nt("conv2_fwd", p, p.M, 1, 1, s);
+        ResConv2Fwd::Args p;
+        p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
+        launch_resident<ResConv2Fwd>("conv2_fwd", p, B, s);
     }
     {
-        Conv3Fwd p;
-        p.in = a2; p.lo_off = a2l - a2; p.M = B * P3; p.w = w.w3; p.w_lo = w.w3l; p.bias = w.b3;
-        p.out = a3; p.out_lo = a3l;
-        split ? launch_nt_split("conv3_fwd", p, p.M, 1, 1, s) : launch_nt("conv3_fwd", p, p.M, 1, 1, s);
+        ResConv3Fwd::Args p;
+        p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
+        launch_resident<ResConv3Fwd>("conv3_fwd", p, B, s);
     }
     {
         FcFwd p;
@@ -382,9 +390,9 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s);
     }
     {
-        Conv3Dgrad p;
-        p.dpre = dp3; p.w = w.w3d; p.act = a2; p.out = dp2; p.M = B * P2;
-        launch_nt("conv3_dgrad", p, p.M, 1, 1, s);
+        ResConv3Dgrad::Args p;
+        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = a2; p.out = dp2;
+        launch_resident<ResConv3Dgrad>("conv3_dgrad", p, B, s);
     }
     // ---- conv2 ----
     {
@@ -398,9 +406,9 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s);
     }
     {
-        Conv2Dgrad p;
-        p.dpre = dp2; p.w = w.w2d; p.act = a1; p.out = dp1; p.M = B * 100;
-        launch_nt("conv2_dgrad", p, p.M, 1, 4, s);
+        ResConv2Dgrad::Args p;
+        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = a1; p.out = dp1;
+        launch_resident<ResConv2Dgrad>("conv2_dgrad", p, B, s);
     }
     // ---- conv1 (weight gradient only: the input is data) ----
     {

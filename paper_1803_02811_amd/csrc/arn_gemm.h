@@ -30,41 +30,44 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+// 16- and 8-byte register/LDS words as native vectors (plain loads and stores, kept in registers)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int LDS_ROW = 9;   // uint4 per staged row: 8 of data (64 bf16) + 1 of padding
+constexpr int LDS_ROW = 9;   // u32x4 per staged row: 8 of data (64 bf16) + 1 of padding
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d) {
+__device__ __forceinline__ u32x2 pack_bf16x4(float a, float b, float c, float d) {
     bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
-    return __builtin_bit_cast(uint2, v);
+    return __builtin_bit_cast(u32x2, v);
 }
 
 // v -> (hi, lo) with hi = bf16(v), lo = bf16(v - hi)
 __device__ __forceinline__ void store_bf16x4_split(__bf16 *hi, __bf16 *lo, size_t at, float a, float b, float c,
                                                    float d) {
     const bf16x4 h = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
-    *reinterpret_cast<uint2 *>(hi + at) = __builtin_bit_cast(uint2, h);
+    *reinterpret_cast<u32x2 *>(hi + at) = __builtin_bit_cast(u32x2, h);
     if (lo) {
         const bf16x4 l = {(__bf16)(a - (float)h[0]), (__bf16)(b - (float)h[1]), (__bf16)(c - (float)h[2]),
                           (__bf16)(d - (float)h[3])};
-        *reinterpret_cast<uint2 *>(lo + at) = __builtin_bit_cast(uint2, l);
+        *reinterpret_cast<u32x2 *>(lo + at) = __builtin_bit_cast(u32x2, l);
     }
 }
 
-__device__ __forceinline__ f32x4 unpack_bf16x4(uint2 u) {
+__device__ __forceinline__ f32x4 unpack_bf16x4(u32x2 u) {
     bf16x4 v = __builtin_bit_cast(bf16x4, u);
     f32x4 r = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
     return r;
 }
 
 // eight uint8 (two little-endian words) -> eight bf16, exact
-__device__ __forceinline__ uint4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+__device__ __forceinline__ u32x4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
     auto two = [](uint32_t b0, uint32_t b1) -> uint32_t {
         return (__float_as_uint((float)b0) >> 16) | (__float_as_uint((float)b1) & 0xffff0000u);
     };
-    uint4 r;
+    u32x4 r;
     r.x = two(lo & 0xff, (lo >> 8) & 0xff);
     r.y = two((lo >> 16) & 0xff, lo >> 24);
     r.z = two(hi & 0xff, (hi >> 8) & 0xff);
@@ -72,16 +75,16 @@ __device__ __forceinline__ uint4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
     return r;
 }
 
-__device__ __forceinline__ uint4 zero_u4() { return make_uint4(0u, 0u, 0u, 0u); }
+__device__ __forceinline__ u32x4 zero_u4() { return u32x4{0u, 0u, 0u, 0u}; }
 
 // v if keep else 0, through a mask the optimiser cannot see through: a gather
 // written as `ok ? *p : 0` is compiled to a branch around the load with a wait
 // right behind it, which serialises the loads of one k-tile.  With the mask the
 // (always in-bounds, clamped) loads are issued back to back.
-__device__ __forceinline__ uint4 keep_or_zero(uint4 v, bool keep) {
+__device__ __forceinline__ u32x4 keep_or_zero(u32x4 v, bool keep) {
     uint32_t mask = keep ? 0xffffffffu : 0u;
     asm volatile("" : "+v"(mask));
-    return make_uint4(v.x & mask, v.y & mask, v.z & mask, v.w & mask);
+    return u32x4{v.x & mask, v.y & mask, v.z & mask, v.w & mask};
 }
 
 // ---------------------------------------------------------------------------
@@ -92,7 +95,7 @@ __device__ __forceinline__ uint4 keep_or_zero(uint4 v, bool keep) {
 //   WAVES_N          wavefronts along channels (1, 2 or 4)
 //   K                contraction length, multiple of 64 (static or a data member)
 //   Row row(m, z)    per-row gather state for position m (z = blockIdx.z)
-//   uint4 load(row, k)   eight bf16 of act(m, k..k+7); zeros where out of range
+//   u32x4 load(row, k)   eight bf16 of act(m, k..k+7); zeros where out of range
 //   const __bf16* weights(z)   W, at least gridDim.y*BN rows of K
 //   store(m, n, v, z)    epilogue for channels n..n+3 of position m
 // Grid: x = position tiles, y = channel tiles, z = problem-defined.
@@ -155,10 +158,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
     // with two LDS stages tile kt is consumed from stage kt&1 while tile kt+1 is written to the other
     constexpr int NST = StagesOf<P>::value;
     constexpr int SA = BM * LDS_ROW, SW = BN * LDS_ROW;
-    __shared__ uint4 sA[NST * SA];
-    __shared__ uint4 sW[NST * SW];
-    __shared__ uint4 sA2[ALO ? NST * SA : 1];
-    __shared__ uint4 sW2[SPLIT ? NST * SW : 1];
+    __shared__ u32x4 sA[NST * SA];
+    __shared__ u32x4 sW[NST * SW];
+    __shared__ u32x4 sA2[ALO ? NST * SA : 1];
+    __shared__ u32x4 sW2[SPLIT ? NST * SW : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave % WN, wm = wave / WN;
@@ -169,17 +172,17 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
     typename P::Row rows[A_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) rows[i] = p.row(m0 + r0 + 32 * i, z);
-    const uint4 *wsrc[W_CH];
-    const uint4 *wsrc2[W_CH];
+    const u32x4 *wsrc[W_CH];
+    const u32x4 *wsrc2[W_CH];
 #pragma unroll
     for (int i = 0; i < W_CH; ++i) {
         const size_t at = (size_t)(n0 + r0 + 32 * i) * p.K;
-        wsrc[i] = reinterpret_cast<const uint4 *>(p.weights(z) + at) + kc;
-        if constexpr (SPLIT) wsrc2[i] = reinterpret_cast<const uint4 *>(p.weights_lo(z) + at) + kc;
+        wsrc[i] = reinterpret_cast<const u32x4 *>(p.weights(z) + at) + kc;
+        if constexpr (SPLIT) wsrc2[i] = reinterpret_cast<const u32x4 *>(p.weights_lo(z) + at) + kc;
     }
 
-    uint4 ra[A_CH], rw[W_CH], ra2[ALO ? A_CH : 1], rw2[SPLIT ? W_CH : 1];
-    auto gload = [&](int kt) {
+    u32x4 ra[A_CH], rw[W_CH], ra2[ALO ? A_CH : 1], rw2[SPLIT ? W_CH : 1];
+    auto gload = [&](int kt) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             ra[i] = p.load(rows[i], kt * 64 + kc * 8);
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    auto stage = [&](int st) {   // registers -> LDS stage st
+    auto stage = [&](int st) __attribute__((always_inline)) {   // registers -> LDS stage st
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             sA[st * SA + (r0 + 32 * i) * LDS_ROW + kc] = ra[i];
@@ -279,14 +282,14 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
 // ---------------------------------------------------------------------------
 // Transposing LDS fragment read.
 //
-// `tile` holds 64 rows (contraction index m) of `row_u4` uint4 each, columns
+// `tile` holds 64 rows (contraction index m) of `row_u4` u32x4 each, columns
 // contiguous.  Returns, for MFMA lane l, the eight values
 //   tile[mbase + 8*(l/32) + e][col0 + l%32],  e = 0..7
 // i.e. an A- or B-operand fragment whose k index is the tile's row index.
 // ds_read_b64_tr_b16 works on groups of 16 lanes: lane 4q+e of a group receives
 // element e of the four 8-byte rows addressed by lanes q, q+4, q+8, q+12.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ bf16x8 tr_fragment(const uint4 *tile, int row_u4, int mbase, int col0, int lane) {
+__device__ __forceinline__ bf16x8 tr_fragment(const u32x4 *tile, int row_u4, int mbase, int col0, int lane) {
     const int o = lane & 15, G = lane >> 4;
     const int row = mbase + 8 * (G >> 1) + (o >> 2);
     const int col = col0 + 16 * (G & 1) + 4 * (o & 3);
@@ -306,8 +309,8 @@ __device__ __forceinline__ bf16x8 tr_fragment(const uint4 *tile, int row_u4, int
 //   BN1, BK2         output tile (dY channels x act columns), multiples of 32
 //   WAVES_X          wavefronts along act columns (1, 2 or 4)
 //   N1, KP           full output shape (rows, columns; static or data members)
-//   XRow xrow(m), uint4 loadx(xrow, k)    gather of act(m, k..k+7)
-//   uint4 loady(m, n)                     eight bf16 of dY[m][n..n+7]
+//   XRow xrow(m), u32x4 loadx(xrow, k)    gather of act(m, k..k+7)
+//   u32x4 loady(m, n)                     eight bf16 of dY[m][n..n+7]
 //   int M                                  number of contraction rows
 // Grid: x = column tiles, y = row tiles, z = batch split.  Each split covers
 // `rows_per_split` (a multiple of 64) consecutive m; partials are summed by
@@ -318,12 +321,12 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
     constexpr int BN1 = P::BN1, BK2 = P::BK2, WX = P::WAVES_X, WY = 4 / WX;
     constexpr int TY = BN1 / (32 * WY), TX = BK2 / (32 * WX);
     constexpr int YC = BN1 / 8, XC = BK2 / 8;          // 16-byte chunks per staged row
-    constexpr int YROW = YC + 1, XROW = XC + 1;        // padded LDS row, in uint4
+    constexpr int YROW = YC + 1, XROW = XC + 1;        // padded LDS row, in u32x4
     constexpr int Y_CH = 64 * YC / 256, X_CH = 64 * XC / 256;
     static_assert(TY >= 1 && TX >= 1 && Y_CH >= 1 && X_CH >= 1, "tile shape");
 
-    __shared__ uint4 sY[64 * YROW];
-    __shared__ uint4 sX[64 * XROW];
+    __shared__ u32x4 sY[64 * YROW];
+    __shared__ u32x4 sX[64 * XROW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wx = wave % WX, wy = wave / WX;
@@ -332,20 +335,20 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
     long m_end = m_begin + rows_per_split;
     if (m_end > p.M) m_end = p.M;
 
-    uint4 ry[Y_CH], rx[X_CH];
-    auto gload = [&](long mt) {
+    u32x4 ry[Y_CH], rx[X_CH];
+    auto gload = [&](long mt) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < Y_CH; ++i) {
             const int c = tid + 256 * i, r = c / YC, cc = c % YC;
             const long m = mt + r;
-            const uint4 v = p.loady(m < m_end ? m : m_begin, y0 + cc * 8);   // clamp, load, then zero
+            const u32x4 v = p.loady(m < m_end ? m : m_begin, y0 + cc * 8);   // clamp, load, then zero
             ry[i] = keep_or_zero(v, m < m_end);
         }
 #pragma unroll
         for (int i = 0; i < X_CH; ++i) {
             const int c = tid + 256 * i, r = c / XC, cc = c % XC;
             const long m = mt + r;
-            const uint4 v = p.loadx(p.xrow(m < m_end ? m : m_begin), x0 + cc * 8);
+            const u32x4 v = p.loadx(p.xrow(m < m_end ? m : m_begin), x0 + cc * 8);
             rx[i] = keep_or_zero(v, m < m_end);
         }
     };

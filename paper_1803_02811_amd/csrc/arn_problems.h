@@ -32,7 +32,7 @@ struct ObsGather {
     }
     // Loads are unconditional (out-of-range rows read sample 0 and are zeroed
     // afterwards) so that several can be in flight at once.
-    __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
+    __device__ __forceinline__ u32x4 load_at(const Row &r, int k) const {
         const int ci = k >> 6, ky = (k >> 3) & 7;
         const uint32_t *q = reinterpret_cast<const uint32_t *>(r.base + ci * (IN_H * IN_W) + ky * IN_W);
         const uint32_t lo = q[0], hi = q[1];
@@ -59,16 +59,16 @@ struct ConvGather {
         r.base = in + ((size_t)(n * HIN + oy * STRIDE) * HIN + ox * STRIDE) * CIN;
         return r;
     }
-    __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
+    __device__ __forceinline__ u32x4 load_at(const Row &r, int k) const {
         constexpr int SEG = KS * CIN;
         const int ky = k / SEG, within = k - ky * SEG;
-        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + ky * (HIN * CIN) + within);
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + ky * (HIN * CIN) + within);
         return keep_or_zero(v, r.ok);
     }
-    __device__ __forceinline__ uint4 load_lo_at(const Row &r, int k) const {
+    __device__ __forceinline__ u32x4 load_lo_at(const Row &r, int k) const {
         constexpr int SEG = KS * CIN;
         const int ky = k / SEG, within = k - ky * SEG;
-        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + lo_off + ky * (HIN * CIN) + within);
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + lo_off + ky * (HIN * CIN) + within);
         return keep_or_zero(v, r.ok);
     }
 };
@@ -91,12 +91,12 @@ struct DenseGather {
         r.base = in + (size_t)(r.ok ? m : 0) * K_;
         return r;
     }
-    __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
-        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + k);
+    __device__ __forceinline__ u32x4 load_at(const Row &r, int k) const {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + k);
         return keep_or_zero(v, r.ok);
     }
-    __device__ __forceinline__ uint4 load_lo_at(const Row &r, int k) const {
-        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + lo_off + k);
+    __device__ __forceinline__ u32x4 load_lo_at(const Row &r, int k) const {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + lo_off + k);
         return keep_or_zero(v, r.ok);
     }
 };
@@ -114,8 +114,8 @@ struct DenseGatherRt {
         r.base = in + (size_t)(r.ok ? m : 0) * K;
         return r;
     }
-    __device__ __forceinline__ uint4 load_at(const Row &r, int k) const {
-        const uint4 v = *reinterpret_cast<const uint4 *>(r.base + k);
+    __device__ __forceinline__ u32x4 load_at(const Row &r, int k) const {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + k);
         return keep_or_zero(v, r.ok);
     }
 };
@@ -128,8 +128,8 @@ struct Conv1Fwd : ObsGather {
     const float *bias;
     __bf16 *out, *out_lo = nullptr;
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const { return load_at(r, k); }
-    __device__ __forceinline__ uint4 load_lo(const Row &, int) const { return zero_u4(); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 load_lo(const Row &, int) const { return zero_u4(); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
@@ -149,8 +149,8 @@ struct ConvFwd : Gather {
     const float *bias;
     __bf16 *out, *out_lo = nullptr;
     __device__ __forceinline__ typename Gather::Row row(int m, int) const { return this->row_at(m); }
-    __device__ __forceinline__ uint4 load(const typename Gather::Row &r, int k) const { return this->load_at(r, k); }
-    __device__ __forceinline__ uint4 load_lo(const typename Gather::Row &r, int k) const {
+    __device__ __forceinline__ u32x4 load(const typename Gather::Row &r, int k) const { return this->load_at(r, k); }
+    __device__ __forceinline__ u32x4 load_lo(const typename Gather::Row &r, int k) const {
         return this->load_lo_at(r, k);
     }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
@@ -178,8 +178,8 @@ struct FcFwd : DenseGather<FEAT> {
     __bf16 *out, *out_lo = nullptr;
     float *partial;
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const { return load_at(r, k); }
-    __device__ __forceinline__ uint4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {
@@ -206,8 +206,8 @@ struct HeadFwd : DenseGather<HID> {
     float *value;   // [M] (PV) or null
     int ZW;         // A (PV) or A*atoms (C51)
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const { return load_at(r, k); }
-    __device__ __forceinline__ uint4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
@@ -230,13 +230,13 @@ struct HeadDgrad : DenseGatherRt {
     const __bf16 *h;
     __bf16 *out;         // [M][512]
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
         if (m >= M) return;
         const size_t at = (size_t)m * HID + n;
-        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const uint2 *>(h + at));
-        *reinterpret_cast<uint2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
+        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(h + at));
+        *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
                                                           a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
     }
 };
@@ -248,13 +248,13 @@ struct FcDgrad : DenseGather<HID> {
     const __bf16 *act;   // act3
     __bf16 *out;
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
         if (m >= M) return;
         const size_t at = (size_t)m * FEAT + n;
-        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const uint2 *>(act + at));
-        *reinterpret_cast<uint2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
+        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+        *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
                                                           a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
     }
 };
@@ -284,20 +284,20 @@ struct Conv3Dgrad {
         r.base = ((long)(n * H3 + r.y) * H3 + r.x) * C3;
         return r;
     }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const {
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const {
         const int tap = k >> 6, ty = tap / 3, tx = tap - ty * 3;
         const int sy = r.y - 2 + ty, sx = r.x - 2 + tx;
         const bool ok = r.ok && sy >= 0 && sy < H3 && sx >= 0 && sx < H3;
         const long at = ok ? r.base + ((ty - 2) * H3 + (tx - 2)) * C3 + (k & 63) : 0;   // clamp, load, then zero
-        const uint4 v = *reinterpret_cast<const uint4 *>(dpre + at);
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(dpre + at);
         return keep_or_zero(v, ok);
     }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
         if (m >= M) return;
         const size_t at = (size_t)m * C2 + n;
-        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const uint2 *>(act + at));
-        *reinterpret_cast<uint2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
+        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+        *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
                                                           a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
     }
 };
@@ -327,12 +327,12 @@ struct Conv2Dgrad {
         r.base = ((long)(n * H2 + r.u) * H2 + r.v) * C2;
         return r;
     }
-    __device__ __forceinline__ uint4 load(const Row &r, int k) const {
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const {
         const int tap = k >> 6, ty = tap >> 1, tx = tap & 1;
         const int sy = r.u - 1 + ty, sx = r.v - 1 + tx;
         const bool ok = r.ok && sy >= 0 && sy < H2 && sx >= 0 && sx < H2;
         const long at = ok ? r.base + ((ty - 1) * H2 + (tx - 1)) * C2 + (k & 63) : 0;
-        const uint4 v = *reinterpret_cast<const uint4 *>(dpre + at);
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(dpre + at);
         return keep_or_zero(v, ok);
     }
     __device__ __forceinline__ const __bf16 *weights(int z) const { return w + (size_t)z * C1 * K; }
@@ -341,8 +341,8 @@ struct Conv2Dgrad {
         const int s = m / 100, rem = m - s * 100, u = rem / 10, vv = rem - u * 10;
         const int y = 2 * u + (z >> 1), x = 2 * vv + (z & 1);
         const size_t at = ((size_t)(s * H1 + y) * H1 + x) * C1 + n;
-        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const uint2 *>(act + at));
-        *reinterpret_cast<uint2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
+        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+        *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
                                                           a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
     }
 };
@@ -354,9 +354,9 @@ struct Wgrad : Gather {
     static constexpr int BN1 = BN1_, BK2 = BK2_, WAVES_X = WAVES_X_, N1 = N1_, KP = KP_;
     const __bf16 *dy;
     __device__ __forceinline__ typename Gather::Row xrow(long m) const { return this->row_at(m); }
-    __device__ __forceinline__ uint4 loadx(const typename Gather::Row &r, int k) const { return this->load_at(r, k); }
-    __device__ __forceinline__ uint4 loady(long m, int n) const {
-        return *reinterpret_cast<const uint4 *>(dy + (size_t)m * N1 + n);
+    __device__ __forceinline__ u32x4 loadx(const typename Gather::Row &r, int k) const { return this->load_at(r, k); }
+    __device__ __forceinline__ u32x4 loady(long m, int n) const {
+        return *reinterpret_cast<const u32x4 *>(dy + (size_t)m * N1 + n);
     }
 };
 typedef Wgrad<ObsGather, 32, 128, 4, C1, KW1> Conv1Wgrad;
@@ -369,9 +369,9 @@ struct HeadWgrad : DenseGather<HID> {
     int N1;
     const __bf16 *dy;
     __device__ __forceinline__ Row xrow(long m) const { return row_at(m); }
-    __device__ __forceinline__ uint4 loadx(const Row &r, int k) const { return load_at(r, k); }
-    __device__ __forceinline__ uint4 loady(long m, int n) const {
-        return *reinterpret_cast<const uint4 *>(dy + (size_t)m * N1 + n);
+    __device__ __forceinline__ u32x4 loadx(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 loady(long m, int n) const {
+        return *reinterpret_cast<const u32x4 *>(dy + (size_t)m * N1 + n);
     }
 };
 

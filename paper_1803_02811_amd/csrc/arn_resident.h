@@ -33,17 +33,17 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
     constexpr int IMG_U4 = OBS_BYTES / 16;        // 1764 sixteen-pixel groups per sample
     constexpr int DY_U4 = P1 * C1 * 2 / 16;       // 1600
     constexpr int NI = (IMG_U4 + 255) / 256, ND = (DY_U4 + 255) / 256;   // 7, 7
-    __shared__ uint4 s_img[2 * IMG_U4];           // bf16 [4][84][84]
-    __shared__ uint4 s_dy[DY_U4];                 // bf16 [400][32]
+    __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][84][84]
+    __shared__ u32x4 s_dy[DY_U4];                 // bf16 [400][32]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
 
-    uint4 rimg[NI], rdy[ND];
-    auto gload = [&](int s) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(obs + (size_t)s * OBS_BYTES);
-        const uint4 *dsrc = reinterpret_cast<const uint4 *>(dy + (size_t)s * P1 * C1);
+    u32x4 rimg[NI], rdy[ND];
+    auto gload = [&](int s) __attribute__((always_inline)) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(obs + (size_t)s * OBS_BYTES);
+        const u32x4 *dsrc = reinterpret_cast<const u32x4 *>(dy + (size_t)s * P1 * C1);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int idx = tid + 256 * i;
@@ -158,8 +158,8 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     static_assert(NY % WAVES_Y == 0 && NX % WAVES_X == 0, "tile split");
     constexpr int BPARTS = 256 / COUT, BROWS = (R + BPARTS - 1) / BPARTS;
 
-    __shared__ uint4 s_x[G * PIX * PS / 16];
-    __shared__ uint4 s_dy[RPAD * YS / 16];
+    __shared__ u32x4 s_x[G * PIX * PS / 16];
+    __shared__ u32x4 s_dy[RPAD * YS / 16];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wy = wave % WAVES_Y, wx = wave / WAVES_Y;
@@ -169,8 +169,8 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     // rows R..RPAD of dY stay zero for the whole kernel
     for (int i = tid; i < (RPAD - R) * YS / 16; i += 256) s_dy[R * YS / 16 + i] = zero_u4();
 
-    uint4 rx[NI], ry[ND];
-    auto gload = [&](int s) {   // samples s .. s+G-1; those at or beyond s_end are read from s_end-1 and zeroed on store
+    u32x4 rx[NI], ry[ND];
+    auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1; those at or beyond s_end are read from s_end-1 and zeroed on store
         const int last = s_end - 1;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
             idx = idx < NXC ? idx : NXC - 1;
             const int g = idx / (PIX * XCH), rem = idx - g * (PIX * XCH);
             const int sg = s + g < s_end ? s + g : last;
-            rx[i] = reinterpret_cast<const uint4 *>(x + (size_t)sg * PIX * CIN)[rem];
+            rx[i] = reinterpret_cast<const u32x4 *>(x + (size_t)sg * PIX * CIN)[rem];
         }
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
             idx = idx < NYC ? idx : NYC - 1;
             const int g = idx / (P * YCH), rem = idx - g * (P * YCH);
             const int sg = s + g < s_end ? s + g : last;
-            ry[i] = reinterpret_cast<const uint4 *>(dy + (size_t)sg * P * COUT)[rem];
+            ry[i] = reinterpret_cast<const u32x4 *>(dy + (size_t)sg * P * COUT)[rem];
         }
     };
 
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
             if (idx < NXC) {
                 const int pix = idx / XCH, c = idx - pix * XCH;
                 const bool live = s + pix / PIX < s_end;
-                *reinterpret_cast<uint4 *>(xl + pix * PS + c * 16) = live ? rx[i] : zero_u4();
+                *reinterpret_cast<u32x4 *>(xl + pix * PS + c * 16) = live ? rx[i] : zero_u4();
             }
         }
 #pragma unroll
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
             if (idx < NYC) {
                 const int row = idx / YCH, c = idx - row * YCH;
                 const bool live = s + row / P < s_end;
-                *reinterpret_cast<uint4 *>(yl + row * YS + c * 16) = live ? ry[i] : zero_u4();
+                *reinterpret_cast<u32x4 *>(yl + row * YS + c * 16) = live ? ry[i] : zero_u4();
             }
         }
         __syncthreads();

@@ -1,0 +1,313 @@
+// Convolutions (forward and input-gradient) with the input of a few samples
+// resident in LDS and the layer's weights resident in registers.
+//
+// One workgroup (4 wavefronts) walks over a fixed range of samples.  For each
+// group of G samples the input image (bf16, plus its low part in the
+// three-product inference/forward precision) is copied once, contiguously, into
+// a padded LDS image; the MFMA activation fragments are then read straight from
+// that image at (position, tap) addresses -- no im2col tile is ever built, so
+// each input element crosses the global-memory/LDS boundary once instead of once
+// per overlapping window.  Every wavefront owns CO/4 output channels and keeps
+// all K of their weights in registers for the whole kernel, so the only LDS
+// traffic in the inner loop is one activation fragment per MFMA group.
+// v_mfma_f32_16x16x32_bf16 is used because the 16-row position tile wastes
+// least on the odd spatial sizes (81, 49, 100 positions per sample).
+//
+// LDS images are double buffered by sample group and the next group is
+// prefetched into registers while the current one is multiplied.
+//
+// MFMA 16x16x32 layout (checked on hardware):
+//   A (16 x 32): lane l holds row l%16, k = 8*(l/16) .. +7     -> weights, row = channel
+//   B (32 x 16): lane l holds col l%16, k = 8*(l/16) .. +7     -> activations, col = position
+//   D (16 x 16): lane l holds col l%16, rows 4*(l/16) + r, r = 0..3
+#pragma once
+#include "arn_gemm.h"
+#include "arn_layout.h"
+
+namespace arn {
+
+// Conv description C supplies (all static):
+//   CI           input channels (32 or 64); a pixel is CI bf16, padded by 16 bytes in LDS
+//   SRC_PIX      pixels per sample in global memory;  LDS_PIX  pixels per sample in LDS
+//   P, HO        output positions per sample (HO x HO)
+//   CO, K        output channels (64 or 128) and contraction length (taps * CI)
+//   G            samples per iteration;  SPLIT  three-product precision
+//   ZERO_FILL    LDS image has a zero border (input-gradient problems)
+//   dst_pix(p)   LDS pixel of source pixel p
+//   base_pix(pos) LDS pixel of tap (0,0) of output position pos
+//   tap_pix(t)   LDS pixel offset of tap t
+//   MASK_ELEMS   0, or elements per sample of the tensor whose sign masks the output
+//                (ReLU derivative); its sign bits are staged to LDS with the image so
+//                that the epilogue needs no dependent global load
+// and an Args struct with in, in_lo (SPLIT), w, w_lo (SPLIT), mask (MASK_ELEMS > 0),
+//   Lane lane(n)                      per-lane constants for channels n..n+3 (e.g. the bias)
+//   store(sample, pos, n, v, lane, maskbits)   epilogue for channels n..n+3 of one position;
+//                                     maskbits = LDS bytes, bit e&7 of byte e>>3 for element e
+//                                     of the G samples' mask tensors.
+// bit i = 1 where bf16 element i of the 16-byte word is > 0
+__device__ __forceinline__ uint8_t positive_bits(u32x4 v) {
+    auto two = [](uint32_t w) -> uint32_t {
+        const uint32_t lo = w & 0xffffu, hi = w >> 16;
+        return ((lo - 1u) < 0x7fffu ? 1u : 0u) | ((hi - 1u) < 0x7fffu ? 2u : 0u);   // 0x0001..0x7fff: positive
+    };
+    return (uint8_t)(two(v.x) | (two(v.y) << 2) | (two(v.z) << 4) | (two(v.w) << 6));
+}
+
+// Eight wavefronts per workgroup: wavefront w and w+4 share a channel slice and
+// take alternate position tiles, so every SIMD has two wavefronts to overlap the
+// LDS-read latency of one with the MFMAs of the other.
+constexpr int RES_THREADS = 512;
+
+template <class C>
+__global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
+    constexpr int CI = C::CI, PS = CI * 2 + 16, NCH = CI / 8;
+    constexpr int IMG = C::LDS_PIX * PS;                 // bytes of one sample's image
+    constexpr int PARTS = C::SPLIT ? 2 : 1;              // hi (+ lo)
+    constexpr int BUF = C::G * IMG * PARTS;              // one buffer: G samples, hi then lo
+    constexpr int NQ = C::G * C::SRC_PIX * NCH;          // 16-byte chunks per part per iteration
+    constexpr int NL = (NQ + RES_THREADS - 1) / RES_THREADS;
+    constexpr int R = C::G * C::P, NT = (R + 15) / 16;
+    constexpr int CT = C::CO / 64;                       // 16-channel tiles per wavefront
+    constexpr int KS = C::K / 32;
+    constexpr int NMQ = C::G * C::MASK_ELEMS / 8;        // mask chunks (8 elements -> 1 byte) per iteration
+    constexpr int NML = (NMQ + RES_THREADS - 1) / RES_THREADS;
+    constexpr int MBUF = (NMQ + 15) / 16 * 16;
+    static_assert(BUF * 2 + MBUF * 2 <= 160 * 1024, "LDS budget");
+
+    __shared__ u32x4 lds[2 * BUF / 16];
+    __shared__ uint8_t lds_mask[NMQ ? 2 * MBUF : 16];
+    char *const lds_b = reinterpret_cast<char *>(lds);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, thalf = tid >> 8;
+    const int li = lane & 15, lg = lane >> 4;
+    const int s_begin = blockIdx.x * spw;
+    const int s_end = s_begin + spw < B ? s_begin + spw : B;
+    if (s_begin >= s_end) return;
+
+    // weights of this wavefront's channels, all k, as A-operand fragments
+    bf16x8 wh[CT][KS], wl[C::SPLIT ? CT : 1][C::SPLIT ? KS : 1];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const size_t row = (size_t)(wave * (16 * CT) + ct * 16 + li) * C::K + 8 * lg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w + row + 32 * ks));
+            if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + 32 * ks));
+        }
+    }
+
+    if constexpr (C::ZERO_FILL) {
+        for (int i = tid; i < 2 * BUF / 16; i += RES_THREADS) lds[i] = zero_u4();
+        __syncthreads();
+    }
+
+    typename C::Args::Lane lane_state[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) lane_state[ct] = a.lane(wave * (16 * CT) + ct * 16 + 4 * lg);
+
+    u32x4 rh[NL], rl[C::SPLIT ? NL : 1], rm[NML ? NML : 1];
+    auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1 (clamped to the last valid one)
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            int q = tid + RES_THREADS * i;
+            q = q < NQ ? q : NQ - 1;
+            const int g = q / (C::SRC_PIX * NCH), rem = q - g * (C::SRC_PIX * NCH);
+            const int sg = s + g < s_end ? s + g : s_end - 1;
+            const size_t at = (size_t)sg * C::SRC_PIX * CI + (size_t)rem * 8;
+            rh[i] = *reinterpret_cast<const u32x4 *>(a.in + at);
+            if constexpr (C::SPLIT) rl[i] = *reinterpret_cast<const u32x4 *>(a.in_lo + at);
+        }
+        if constexpr (NMQ > 0) {
+#pragma unroll
+            for (int i = 0; i < NML; ++i) {
+                int q = tid + RES_THREADS * i;
+                q = q < NMQ ? q : NMQ - 1;
+                const int g = q / (C::MASK_ELEMS / 8), rem = q - g * (C::MASK_ELEMS / 8);
+                const int sg = s + g < s_end ? s + g : s_end - 1;
+                rm[i] = *reinterpret_cast<const u32x4 *>(a.mask + (size_t)sg * C::MASK_ELEMS + (size_t)rem * 8);
+            }
+        }
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
+        char *dst = lds_b + buf * BUF;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int q = tid + RES_THREADS * i;
+            if (q < NQ) {
+                const int p = q / NCH, c = q - p * NCH;          // p = g * SRC_PIX + source pixel
+                const int g = p / C::SRC_PIX, sp = p - g * C::SRC_PIX;
+                const int off = (g * C::LDS_PIX + C::dst_pix(sp)) * PS + c * 16;
+                *reinterpret_cast<u32x4 *>(dst + off) = rh[i];
+                if constexpr (C::SPLIT) *reinterpret_cast<u32x4 *>(dst + C::G * IMG + off) = rl[i];
+            }
+        }
+        if constexpr (NMQ > 0) {
+#pragma unroll
+            for (int i = 0; i < NML; ++i) {
+                const int q = tid + RES_THREADS * i;
+                if (q < NMQ) lds_mask[buf * MBUF + q] = positive_bits(rm[i]);
+            }
+        }
+    };
+
+    gload(s_begin);
+    int buf = 0;
+    for (int s = s_begin; s < s_end; s += C::G) {
+        stage(buf);
+        __syncthreads();
+        if (s + C::G < s_end) gload(s + C::G);
+        const char *img = lds_b + buf * BUF;
+        const uint8_t *mbits = lds_mask + buf * MBUF;
+#pragma unroll 1
+        for (int t = thalf; t < NT; t += 2) {
+            int row = t * 16 + li;
+            row = row < R ? row : R - 1;                 // padded rows recompute the last one; never stored
+            const int g = row / C::P, pos = row - g * C::P;
+            const int base = (g * C::LDS_PIX + C::base_pix(pos)) * PS + 16 * lg;
+            f32x4 acc[CT];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int tap = (32 * ks) / CI, ci0 = (32 * ks) % CI;
+                const int off = base + C::tap_pix(tap) * PS + ci0 * 2;
+                const bf16x8 bh = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + off));
+                bf16x8 bl;
+                if constexpr (C::SPLIT) bl = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + C::G * IMG + off));
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    if constexpr (C::SPLIT) {
+                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ct][ks], bh, acc[ct], 0, 0, 0);
+                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], bl, acc[ct], 0, 0, 0);
+                    }
+                    acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], bh, acc[ct], 0, 0, 0);
+                }
+            }
+            const int orow = t * 16 + li;
+            if (orow < R && s + g < s_end) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    a.store(s + g, g, pos, wave * (16 * CT) + ct * 16 + 4 * lg, acc[ct], lane_state[ct], mbits);
+            }
+        }
+        buf ^= 1;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// conv2 forward: act1 [20][20][32] -> act2 [9][9][64], 4x4 stride 2.  The LDS
+// image keeps even and odd columns in separate planes so that the stride-2
+// windows of neighbouring positions are neighbouring LDS pixels.
+struct ResConv2Fwd {
+    static constexpr int CI = C1, SRC_PIX = P1, LDS_PIX = P1, P = P2, HO = H2, CO = C2, K = KW2, G = 1;
+    static constexpr bool SPLIT = true, ZERO_FILL = false;
+    static constexpr int MASK_ELEMS = 0;
+    __device__ static constexpr int dst_pix(int p) {
+        const int y = p / H1, x = p - y * H1;
+        return (y * 2 + (x & 1)) * (H1 / 2) + (x >> 1);
+    }
+    __device__ static constexpr int base_pix(int pos) {
+        const int oy = pos / H2, ox = pos - oy * H2;
+        return oy * (2 * H1) + ox;            // pixel (2oy, 2ox): row 2oy, even plane, column ox
+    }
+    __device__ static constexpr int tap_pix(int t) {
+        const int ky = t / K2, kx = t - ky * K2;
+        return (ky * 2 + (kx & 1)) * (H1 / 2) + (kx >> 1);
+    }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo, *mask;
+        const float *bias;
+        __bf16 *out, *out_lo;
+        typedef float4 Lane;
+        __device__ __forceinline__ Lane lane(int n) const { return *reinterpret_cast<const float4 *>(bias + n); }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &b,
+                                              const uint8_t *) const {
+            store_bf16x4_split(out, out_lo, ((size_t)s * P2 + pos) * C2 + n, fmaxf(v[0] + b.x, 0.f),
+                               fmaxf(v[1] + b.y, 0.f), fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
+        }
+    };
+};
+
+// conv3 forward: act2 [9][9][64] -> act3 [7][7][64], 3x3 stride 1
+struct ResConv3Fwd {
+    static constexpr int CI = C2, SRC_PIX = P2, LDS_PIX = P2, P = P3, HO = H3, CO = C3, K = KW3, G = 2;
+    static constexpr bool SPLIT = true, ZERO_FILL = false;
+    static constexpr int MASK_ELEMS = 0;
+    __device__ static constexpr int dst_pix(int p) { return p; }
+    __device__ static constexpr int base_pix(int pos) {
+        const int oy = pos / H3, ox = pos - oy * H3;
+        return oy * H2 + ox;
+    }
+    __device__ static constexpr int tap_pix(int t) { return (t / K3) * H2 + t % K3; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo, *mask;
+        const float *bias;
+        __bf16 *out, *out_lo;
+        typedef float4 Lane;
+        __device__ __forceinline__ Lane lane(int n) const { return *reinterpret_cast<const float4 *>(bias + n); }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &b,
+                                              const uint8_t *) const {
+            store_bf16x4_split(out, out_lo, ((size_t)s * P3 + pos) * C3 + n, fmaxf(v[0] + b.x, 0.f),
+                               fmaxf(v[1] + b.y, 0.f), fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
+        }
+    };
+};
+
+// conv3 input gradient: d(pre3) [7][7][64] zero-padded by 2 to 11x11, 3x3 taps
+// (ty,tx) reading padded (y+ty, x+tx) against W3[co][ci][2-ty][2-tx]; output
+// d(pre2) [9][9][64] masked by act2 > 0.
+struct ResConv3Dgrad {
+    static constexpr int PADW = H3 + 4;   // 11
+    static constexpr int CI = C3, SRC_PIX = P3, LDS_PIX = PADW * PADW, P = P2, HO = H2, CO = C2, K = 9 * C3, G = 2;
+    static constexpr bool SPLIT = false, ZERO_FILL = true;
+    static constexpr int MASK_ELEMS = P2 * C2;
+    __device__ static constexpr int dst_pix(int p) { return (p / H3 + 2) * PADW + p % H3 + 2; }
+    __device__ static constexpr int base_pix(int pos) { return (pos / H2) * PADW + pos % H2; }
+    __device__ static constexpr int tap_pix(int t) { return (t / 3) * PADW + t % 3; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo, *mask;   // mask = act2
+        __bf16 *out;
+        struct Lane {};
+        __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
+        __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
+                                              const uint8_t *mbits) const {
+            const int e = (g * P2 + pos) * C2 + n;
+            const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
+            *reinterpret_cast<u32x2 *>(out + ((size_t)s * P2 + pos) * C2 + n) =
+                pack_bf16x4(m & 1 ? v[0] : 0.f, m & 2 ? v[1] : 0.f, m & 4 ? v[2] : 0.f, m & 8 ? v[3] : 0.f);
+        }
+    };
+};
+
+// conv2 input gradient (stride 2): d(pre2) [9][9][64] zero-padded by 1 to 11x11.
+// The four output phases (y%2, x%2) share their activation fragments, so they
+// are the 4 x 32 "channels" of one 2x2 stride-1 convolution over the padded
+// image with 10x10 positions (u,v); channel n = phase*32 + ci lands at act1
+// pixel (2u + phase/2, 2v + phase%2).  Output d(pre1) masked by act1 > 0.
+struct ResConv2Dgrad {
+    static constexpr int PADW = H2 + 2;   // 11
+    static constexpr int CI = C2, SRC_PIX = P2, LDS_PIX = PADW * PADW, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 2;
+    static constexpr bool SPLIT = false, ZERO_FILL = true;
+    static constexpr int MASK_ELEMS = P1 * C1;
+    __device__ static constexpr int dst_pix(int p) { return (p / H2 + 1) * PADW + p % H2 + 1; }
+    __device__ static constexpr int base_pix(int pos) { return (pos / 10) * PADW + pos % 10; }
+    __device__ static constexpr int tap_pix(int t) { return (t / 2) * PADW + t % 2; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo, *mask;   // mask = act1
+        __bf16 *out;
+        struct Lane {};
+        __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
+        __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
+                                              const uint8_t *mbits) const {
+            const int phase = n >> 5, ci = n & 31, u = pos / 10, vv = pos - u * 10;
+            const int y = 2 * u + (phase >> 1), x = 2 * vv + (phase & 1);
+            const int pix = y * H1 + x;
+            const int e = (g * P1 + pix) * C1 + ci;
+            const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
+            *reinterpret_cast<u32x2 *>(out + ((size_t)s * P1 + pix) * C1 + ci) =
+                pack_bf16x4(m & 1 ? v[0] : 0.f, m & 2 ? v[1] : 0.f, m & 4 ? v[2] : 0.f, m & 8 ? v[3] : 0.f);
+        }
+    };
+};
+
+}  // namespace arn

@@ -198,11 +198,11 @@ __global__ void fc_finish_kernel(const float *__restrict__ partial, int ksplit, 
                 r3 = fmaxf(s.w + b.w, 0.f);
     typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
     const bf16x4_t h = {(__bf16)r0, (__bf16)r1, (__bf16)r2, (__bf16)r3};
-    *reinterpret_cast<uint2 *>(out + i) = __builtin_bit_cast(uint2, h);
+    *reinterpret_cast<u32x2 *>(out + i) = __builtin_bit_cast(u32x2, h);
     if (out_lo) {
         const bf16x4_t l = {(__bf16)(r0 - (float)h[0]), (__bf16)(r1 - (float)h[1]), (__bf16)(r2 - (float)h[2]),
                             (__bf16)(r3 - (float)h[3])};
-        *reinterpret_cast<uint2 *>(out_lo + i) = __builtin_bit_cast(uint2, l);
+        *reinterpret_cast<u32x2 *>(out_lo + i) = __builtin_bit_cast(u32x2, l);
     }
 }
 

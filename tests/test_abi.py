@@ -1,0 +1,101 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the
+header declares, sizes agree with the oracle's layout, and argument errors are
+caught on the host before anything touches a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1803_02811_amd as arn
+from oracle import nature_cnn as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(arn.lib_path()):
+        from paper_1803_02811_amd import build
+        build.build()
+    return arn.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "arn.h")).read()
+    declared = set(re.findall(r"\b(arn_[a-z_]+)\s*\(", header))
+    assert {"arn_policy_forward", "arn_train_step_grads", "arn_weights_prepare", "arn_param_count",
+            "arn_packed_bytes", "arn_workspace_bytes", "arn_status_string"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_param_counts_match_the_oracle_layout(lib):
+    for A, head, okind in [(6, arn.ARN_HEAD_PV, "pv"), (18, arn.ARN_HEAD_PV, "pv"), (18, arn.ARN_HEAD_C51, "c51")]:
+        assert arn.param_count(arn.Config(A, head)) == orc.param_count(orc.NetSpec(A, okind))
+    assert arn.param_count(arn.Config(18, arn.ARN_HEAD_PV)) == 1_693_875
+    assert arn.param_count(arn.Config(18, arn.ARN_HEAD_C51)) == 2_155_062
+
+
+def test_sizes_and_bad_configs(lib):
+    cfg = arn.Config(18, arn.ARN_HEAD_PV)
+    assert arn.packed_bytes(cfg) > 2 * 1_693_875          # bf16 copies of every matrix
+    f16, f256 = arn.workspace_bytes(cfg, 16, arn.ARN_MODE_FORWARD), arn.workspace_bytes(cfg, 256, arn.ARN_MODE_FORWARD)
+    assert 0 < f16 < f256
+    assert arn.workspace_bytes(cfg, 256, arn.ARN_MODE_TRAIN) > f256
+    assert arn.workspace_bytes(cfg, 0, arn.ARN_MODE_FORWARD) == 0
+    assert arn.workspace_bytes(cfg, 16, 7) == 0
+    for bad in [arn.Config(0, arn.ARN_HEAD_PV), arn.Config(32, arn.ARN_HEAD_PV), arn.Config(19, arn.ARN_HEAD_C51),
+                arn.Config(18, arn.ARN_HEAD_C51, num_atoms=1), arn.Config(18, 5),
+                arn.Config(18, arn.ARN_HEAD_C51, v_min=1.0, v_max=1.0)]:
+        assert arn.param_count(bad) == 0 and arn.packed_bytes(bad) == 0
+    # the gradient workspace is a fixed function of B (fixed split counts => reproducible sums)
+    assert arn.workspace_bytes(cfg, 2048, arn.ARN_MODE_TRAIN) == arn.workspace_bytes(cfg, 2048, arn.ARN_MODE_TRAIN)
+
+
+def test_argument_errors_are_reported_on_the_host(lib):
+    """Null / misaligned pointers, bad kinds and short workspaces return error codes without any launch."""
+    cfg = arn.Config(18, arn.ARN_HEAD_PV)
+    c = ctypes.byref(cfg)
+    fake = ctypes.c_void_p(0x1000)                 # aligned, never dereferenced on these paths
+    odd = ctypes.c_void_p(0x1001)
+    EINVAL, ESHAPE, EKIND, EWORKSPACE = -1, -2, -3, -4
+    assert lib.arn_weights_prepare(None, fake, fake, None) == EINVAL
+    assert lib.arn_weights_prepare(c, None, fake, None) == EINVAL
+    assert lib.arn_weights_prepare(c, fake, odd, None) == EINVAL
+    assert lib.arn_weights_prepare(ctypes.byref(arn.Config(18, 9)), fake, fake, None) == EKIND
+    assert lib.arn_weights_prepare(ctypes.byref(arn.Config(40, arn.ARN_HEAD_PV)), fake, fake, None) == ESHAPE
+    big = 1 << 40
+    assert lib.arn_policy_forward(c, fake, fake, 0, fake, fake, None, None, fake, big, None) == EINVAL
+    assert lib.arn_policy_forward(c, fake, None, 4, fake, fake, None, None, fake, big, None) == EINVAL
+    assert lib.arn_policy_forward(c, fake, fake, 4, fake, None, None, None, fake, big, None) == EINVAL   # PV needs value
+    assert lib.arn_policy_forward(c, fake, fake, 4, fake, fake, None, None, fake, 16, None) == EWORKSPACE
+    batch = arn.binding._Batch(*([0x1000] * 9))
+    b = ctypes.byref(batch)
+    assert lib.arn_train_step_grads(c, fake, b, 4, 9, fake, fake, fake, big, None) == EKIND
+    assert lib.arn_train_step_grads(c, fake, b, 4, arn.ARN_LOSS_C51, fake, fake, fake, big, None) == ESHAPE
+    assert lib.arn_train_step_grads(c, fake, b, 4, arn.ARN_LOSS_A2C, fake, fake, fake, 64, None) == EWORKSPACE
+    assert lib.arn_train_step_grads(c, fake, None, 4, arn.ARN_LOSS_A2C, fake, fake, fake, big, None) == EINVAL
+    nob = arn.binding._Batch(*([0x1000] * 2 + [None] * 7))
+    assert lib.arn_train_step_grads(c, fake, ctypes.byref(nob), 4, arn.ARN_LOSS_A2C, fake, fake, fake, big,
+                                    None) == EINVAL
+    assert "workspace" in arn.status_string(EWORKSPACE)
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    """No CPU fallback: a missing libarn.so is an error, not a silent detour."""
+    monkeypatch.setenv("ARN_LIBRARY", str(tmp_path / "nope.so"))
+    monkeypatch.setattr(arn.binding, "_LIB", None)
+    with pytest.raises(RuntimeError):
+        arn.load_library()
+    monkeypatch.delenv("ARN_LIBRARY")
+    monkeypatch.setattr(arn.binding, "_LIB", None)
+
+
+def test_product_path_does_not_import_the_oracle():
+    for root, _, files in os.walk(os.path.join(ROOT, "paper_1803_02811_amd")):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(root, f)).read()
+                assert "oracle" not in text, f
