@@ -148,9 +148,10 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
     __bf16 *a1l = split ? (__bf16 *)(ws + o.a1l) : nullptr, *a2l = split ? (__bf16 *)(ws + o.a2l) : nullptr;
     __bf16 *a3l = split ? (__bf16 *)(ws + o.a3l) : nullptr, *hl = split ? (__bf16 *)(ws + o.hl) : nullptr;
     {
-        Conv1Fwd p;
-        p.obs = obs; p.M = B * P1; p.w = w.w1; p.w_lo = w.w1l; p.bias = w.b1; p.out = a1; p.out_lo = a1l;
-        split ? launch_nt_split("conv1_fwd", p, p.M, 1, 1, s) : launch_nt("conv1_fwd", p, p.M, 1, 1, s);
+        ProfScope ps("conv1_fwd", s);
+        const int spw = resident_spw(B, 256);
+        hipLaunchKernelGGL(conv1_fwd_resident_kernel, dim3(cdiv(B, spw)), dim3(RES_THREADS), 0, s, obs, w.w1, w.w1l,
+                           w.b1, a1, a1l, B, spw);
     }
     {
         ResConv2Fwd::Args p;

@@ -195,6 +195,95 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
 }
 
 // ---------------------------------------------------------------------------
+// conv1 forward: uint8 observation [4][84][84] -> act1 [20][20][32], 8x8 stride 4,
+// fused with the uint8 -> bf16 unpack (exact) and the 1/255 scale (fp32 epilogue).
+// The sample is converted to a bf16 image in LDS once (each pixel is used by up
+// to four windows); a 32-wide k-step is four rows (ky) of eight pixels (kx) of
+// one input channel, so an activation fragment is 16 contiguous bytes of the
+// image.  Every wavefront keeps all of W1 (hi and lo parts) in registers; the 25
+// position tiles x 2 channel tiles of a sample are dealt round-robin to the eight
+// wavefronts.  Three-product precision with an exact activation operand needs
+// two MFMAs per fragment (W_hi x, W_lo x).
+__global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
+    const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w, const __bf16 *__restrict__ w_lo,
+    const float *__restrict__ bias, __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo, int B, int spw) {
+    constexpr int IMG_U4 = OBS_BYTES / 16;                           // 1764 sixteen-pixel groups
+    constexpr int NL = (IMG_U4 + RES_THREADS - 1) / RES_THREADS;     // 4
+    constexpr int KS = KW1 / 32;                                     // 8
+    constexpr int NT = P1 / 16;                                      // 25 position tiles, no remainder
+    __shared__ u32x4 s_img[2][2 * IMG_U4];                           // bf16 [4][84][84], double buffered
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, lg = lane >> 4;
+    const int s_begin = blockIdx.x * spw;
+    const int s_end = s_begin + spw < B ? s_begin + spw : B;
+    if (s_begin >= s_end) return;
+
+    bf16x8 wh[2][KS], wl[2][KS];
+    float4 bs[2];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+        const size_t row = (size_t)(ct * 16 + li) * KW1 + 8 * lg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + row + 32 * ks));
+            wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + row + 32 * ks));
+        }
+        bs[ct] = *reinterpret_cast<const float4 *>(bias + ct * 16 + 4 * lg);
+    }
+
+    u32x4 rimg[NL];
+    auto gload = [&](int s) __attribute__((always_inline)) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(obs + (size_t)s * OBS_BYTES);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int idx = tid + RES_THREADS * i;
+            rimg[i] = src[idx < IMG_U4 ? idx : IMG_U4 - 1];
+        }
+    };
+
+    gload(s_begin);
+    int buf = 0;
+    for (int s = s_begin; s < s_end; ++s) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int idx = tid + RES_THREADS * i;
+            if (idx < IMG_U4) {
+                s_img[buf][2 * idx] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
+                s_img[buf][2 * idx + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
+            }
+        }
+        __syncthreads();
+        if (s + 1 < s_end) gload(s + 1);
+        const char *img = reinterpret_cast<const char *>(s_img[buf]);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+            // channel tile 0 starts at tile `wave`, channel tile 1 at tile (wave+4)%8: 6 or 7 units per wavefront
+#pragma unroll 1
+            for (int t = (wave + 4 * ct) & 7; t < NT; t += 8) {
+                const int pos = t * 16 + li, oy = pos / H1, ox = pos - oy * H1;
+                const int base = ((S1 * oy + lg) * IN_W + S1 * ox) * 2;
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int off = base + ((ks >> 1) * (IN_H * IN_W) + (ks & 1) * 4 * IN_W) * 2;
+                    const u32x2 f0 = *reinterpret_cast<const u32x2 *>(img + off);
+                    const u32x2 f1 = *reinterpret_cast<const u32x2 *>(img + off + 8);
+                    const bf16x8 b = as_bf16x8(u32x4{f0.x, f0.y, f1.x, f1.y});
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ct][ks], b, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], b, acc, 0, 0, 0);
+                }
+                constexpr float sc = 1.0f / 255.0f;
+                store_bf16x4_split(out, out_lo, ((size_t)s * P1 + pos) * C1 + ct * 16 + 4 * lg,
+                                   fmaxf(acc[0] * sc + bs[ct].x, 0.f), fmaxf(acc[1] * sc + bs[ct].y, 0.f),
+                                   fmaxf(acc[2] * sc + bs[ct].z, 0.f), fmaxf(acc[3] * sc + bs[ct].w, 0.f));
+            }
+        }
+        buf ^= 1;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // conv2 forward: act1 [20][20][32] -> act2 [9][9][64], 4x4 stride 2.  The LDS
 // image keeps even and odd columns in separate planes so that the stride-2
 // windows of neighbouring positions are neighbouring LDS pixels.
