@@ -139,14 +139,15 @@ Packed view_packed(const void *blob, const Dims &d) {
     return p;
 }
 
-// trunk + heads forward.  z_out: logits [B][A] (PV) or atom logits [B][NH]; v_out: value [B] (PV) or null.
-// split = three-product bf16 (inference: fp32-class accuracy); otherwise plain bf16 operands (training).
+// trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits [B][NH].
+// PV: the head leaves fp32 partial sums in the workspace (o.hp) for the consumer to finish.
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                      float *z_out, float *v_out, bool split, hipStream_t s) {
+                      float *z_out, hipStream_t s) {
+    constexpr bool split = true;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *h = (__bf16 *)(ws + o.h);
-    __bf16 *a1l = split ? (__bf16 *)(ws + o.a1l) : nullptr, *a2l = split ? (__bf16 *)(ws + o.a2l) : nullptr;
-    __bf16 *a3l = split ? (__bf16 *)(ws + o.a3l) : nullptr, *hl = split ? (__bf16 *)(ws + o.hl) : nullptr;
+    __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l);
+    __bf16 *a3l = (__bf16 *)(ws + o.a3l), *hl = (__bf16 *)(ws + o.hl);
     {
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
@@ -177,15 +178,15 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         }
     }
     if (d.head == ARN_HEAD_PV) {
-        HeadFwd<32> p;
-        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
-        p.z = z_out; p.value = v_out; p.ZW = d.A;
-        split ? launch_nt_split("head_fwd", p, B, 1, 1, s) : launch_nt("head_fwd", p, B, 1, 1, s);
+        // partial sums only; policy_epilogue_kernel / ac_loss_kernel finish the rows
+        HeadFwdPV p;
+        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.ksplit = HEAD_KSPLIT;
+        p.partial = (float *)(ws + o.hp);
+        launch_nt_split("head_fwd", p, B, 1, HEAD_KSPLIT, s);
     } else {
-        HeadFwd<64> p;
-        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh;
-        p.z = z_out; p.value = nullptr; p.ZW = d.NH;
-        split ? launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s) : launch_nt("head_fwd", p, B, d.NHP / 64, 1, s);
+        HeadFwdC51 p;
+        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh; p.z = z_out; p.ZW = d.NH;
+        launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s);
     }
 }
 
@@ -275,12 +276,11 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     if (int e = check_arch()) return e;
     hipStream_t s = (hipStream_t)stream;
     const Packed w = view_packed(w_packed, d);
-    forward_launches(d, w, obs, B, (char *)workspace, o, logits, d.head == ARN_HEAD_PV ? value : nullptr, true, s);
+    forward_launches(d, w, obs, B, (char *)workspace, o, logits, s);
     if (d.head == ARN_HEAD_PV) {
         ProfScope ps("policy_epilogue", s);
-        if (probs || greedy)
-            hipLaunchKernelGGL(policy_epilogue_kernel, dim3(cdiv(B, 256)), dim3(256), 0, s, logits, B, d.A, probs,
-                               greedy);
+        hipLaunchKernelGGL(policy_epilogue_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s,
+                           (const float *)((char *)workspace + o.hp), w.bh, B, d.A, logits, value, probs, greedy);
     } else if (value || probs || greedy) {
         ProfScope ps("c51_dist", s);
         hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, B, d.A,
@@ -318,7 +318,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     const Packed w = view_packed(w_packed, d);
     const ParamOffsets po = param_offsets(d);
     const Splits sp = make_splits(d, B);
-    float *z = (float *)(ws + o.z), *zv = (float *)(ws + o.zv);
+    float *z = (float *)(ws + o.z);
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *h = (__bf16 *)(ws + o.h);
     __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
@@ -331,24 +331,25 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         // target network on next states -> projected target m; its activations are then overwritten
         const Packed wt = view_packed(batch->w_target_packed, d);
         float *ztgt = (float *)(ws + o.ztgt), *m = (float *)(ws + o.m);
-        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, nullptr, true, s);
+        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, s);
         {
             ProfScope ps("c51_target", s);
                 hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, B, d.A,
                                d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
                                (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
         }
-        forward_launches(d, w, batch->obs, B, ws, o, z, nullptr, true, s);
+        forward_launches(d, w, batch->obs, B, ws, o, z, s);
         ProfScope ps("loss", s);
         hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
                            d.atoms, d.NHP, dz, lossp);
         hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, 0.f, 0.f, loss);
     } else {
-        forward_launches(d, w, batch->obs, B, ws, o, z, zv, true, s);
+        forward_launches(d, w, batch->obs, B, ws, o, nullptr, s);
         ProfScope ps("loss", s);
-        hipLaunchKernelGGL(ac_loss_kernel, dim3(lblocks), dim3(LOSS_BLOCK), 0, s, z, zv, batch->action, batch->adv,
-                           batch->ret, batch->old_logp, loss_kind == ARN_LOSS_PPO ? 1 : 0, cfg->clip_eps,
-                           cfg->value_coef, cfg->entropy_coef, B, d.A, d.NHP, dz, lossp);
+        hipLaunchKernelGGL(ac_loss_kernel, dim3(lblocks), dim3(LOSS_BLOCK), 0, s, (const float *)(ws + o.hp), w.bh,
+                           batch->action, batch->adv, batch->ret, batch->old_logp,
+                           loss_kind == ARN_LOSS_PPO ? 1 : 0, cfg->clip_eps, cfg->value_coef, cfg->entropy_coef, B,
+                           d.A, dz, lossp);
         hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, cfg->value_coef,
                            cfg->entropy_coef, loss);
     }

@@ -156,7 +156,8 @@ inline int fc_ksplit(int B) {
     return ks;
 }
 
-constexpr int LOSS_BLOCK = 256;   // samples per block in the actor-critic loss kernel
+constexpr int LOSS_BLOCK = 64;    // samples per block in the actor-critic loss kernel
+constexpr int HEAD_KSPLIT = 8;    // k ranges of the policy/value head GEMM (one 64-element k-tile each)
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
 // byte offsets into the workspace
@@ -164,6 +165,7 @@ struct Workspace {
     size_t a1, a2, a3, h;               // bf16 NHWC activations
     size_t a1l, a2l, a3l, hl;           // their low parts (written and read by the forward pass only)
     size_t fcp;                         // fp32 [ksplit][B][512] partial sums of the fc forward GEMM
+    size_t hp;                          // fp32 [HEAD_KSPLIT][B][32] partial sums of the policy/value head GEMM
     size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
     size_t dz, dph, dp3, dp2, dp1;      // bf16 gradients at pre-activations
@@ -188,9 +190,10 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     w.a3l = take(b * FEAT * 2);
     w.hl = take(b * HID * 2);
     w.fcp = take((size_t)(fc_ksplit(B) > 1 ? fc_ksplit(B) : 0) * b * HID * 4);
+    w.hp = take(d.head == ARN_HEAD_PV ? (size_t)HEAD_KSPLIT * b * 32 * 4 : 0);
     if (mode == ARN_MODE_TRAIN) {
-        w.z = take(b * (size_t)(d.head == ARN_HEAD_PV ? d.A : d.NH) * 4);
-        w.zv = take(b * 4);
+        w.z = take(d.head == ARN_HEAD_PV ? 0 : b * (size_t)d.NH * 4);
+        w.zv = 0;
         if (d.head == ARN_HEAD_C51) {
             w.ztgt = take(b * (size_t)d.NH * 4);
             w.m = take(b * (size_t)d.atoms * 4);

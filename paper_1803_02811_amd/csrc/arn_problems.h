@@ -195,16 +195,33 @@ struct FcFwd : DenseGather<FEAT> {
 };
 
 // heads: rows of the packed head matrix are the A policy rows then the value
-// row (PV), or the A*atoms categorical rows (C51); outputs are fp32.
-template <int BN_>
-struct HeadFwd : DenseGather<HID> {
-    static constexpr int BM = 128, BN = BN_, WAVES_N = 1, K = HID;
+// row (PV), or the A*atoms categorical rows (C51).
+// PV: N = 32 columns, k cut into HEAD_KSPLIT ranges; fp32 partials [z][M][32]
+// (bias and the split into logits / value are applied by the consumer).
+struct HeadFwdPV : DenseGather<HID> {
+    static constexpr int BM = 128, BN = 32, WAVES_N = 1, K = HID;
+    static constexpr bool ACT_LO = true;
+    int ksplit;
+    const __bf16 *w, *w_lo = nullptr;
+    float *partial;
+    __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
+    __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
+    __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
+    __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
+    __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {
+        if (m >= M) return;
+        *reinterpret_cast<float4 *>(partial + ((size_t)z * M + m) * 32 + n) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+// C51: atom logits fp32 [M][A*atoms] with bias.
+struct HeadFwdC51 : DenseGather<HID> {
+    static constexpr int BM = 128, BN = 64, WAVES_N = 1, K = HID;
     static constexpr bool ACT_LO = true;
     const __bf16 *w, *w_lo = nullptr;
     const float *bias;
     float *z;       // [M][ZW]
-    float *value;   // [M] (PV) or null
-    int ZW;         // A (PV) or A*atoms (C51)
+    int ZW;         // A*atoms
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
     __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
     __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
@@ -215,9 +232,7 @@ struct HeadFwd : DenseGather<HID> {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int c = n + e;
-            const float x = v[e] + bias[c];
-            if (c < ZW) z[(size_t)m * ZW + c] = x;
-            else if (value && c == ZW) value[m] = x;
+            if (c < ZW) z[(size_t)m * ZW + c] = v[e] + bias[c];
         }
     }
 };

@@ -27,7 +27,7 @@
 namespace arn {
 
 // Conv description C supplies (all static):
-//   CI           input channels (32 or 64); a pixel is CI bf16, padded by 16 bytes in LDS
+//   CI           input channels (32 or 64); a pixel is CI bf16, padded by 32 bytes in LDS
 //   SRC_PIX      pixels per sample in global memory;  LDS_PIX  pixels per sample in LDS
 //   P, HO        output positions per sample (HO x HO)
 //   CO, K        output channels (64 or 128) and contraction length (taps * CI)
@@ -60,7 +60,7 @@ constexpr int RES_THREADS = 512;
 
 template <class C>
 __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
-    constexpr int CI = C::CI, PS = CI * 2 + 16, NCH = CI / 8;
+    constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
     constexpr int IMG = C::LDS_PIX * PS;                 // bytes of one sample's image
     constexpr int PARTS = C::SPLIT ? 2 : 1;              // hi (+ lo)
     constexpr int BUF = C::G * IMG * PARTS;              // one buffer: G samples, hi then lo

@@ -218,23 +218,53 @@ __device__ __forceinline__ float wave_max(float v) {
     return __shfl(v, 0, 64);
 }
 
-// ----------------------- policy outputs (inference) -------------------------
-// probs = softmax(logits), greedy = lowest-index argmax; one thread per sample.
-__global__ void policy_epilogue_kernel(const float *__restrict__ logits, int B, int A, float *__restrict__ probs,
-                                       int32_t *__restrict__ greedy) {
+// ------------------- policy / value head outputs (PV) -----------------------
+// The PV head GEMM (N = A+1 <= 32) is cut into HEAD_KSPLIT ranges of k so that it
+// fills more than a handful of CUs; it leaves fp32 partial sums part[z][B][32].
+// head_row adds them in z order and the bias: z[0..A-1] logits, z[A] value.
+__device__ __forceinline__ void head_row(const float *__restrict__ part, const float *__restrict__ bias, int B,
+                                         int n, float (&z)[32]) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        float4 s = *reinterpret_cast<const float4 *>(part + (size_t)n * 32 + 4 * q);
+        for (int k = 1; k < HEAD_KSPLIT; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(part + ((size_t)k * B + n) * 32 + 4 * q);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        const float4 b = *reinterpret_cast<const float4 *>(bias + 4 * q);
+        z[4 * q] = s.x + b.x; z[4 * q + 1] = s.y + b.y; z[4 * q + 2] = s.z + b.z; z[4 * q + 3] = s.w + b.w;
+    }
+}
+
+// Inference epilogue: logits, value, softmax probabilities and the lowest-index
+// greedy action; one thread per sample.
+__global__ void policy_epilogue_kernel(const float *__restrict__ part, const float *__restrict__ bias, int B, int A,
+                                       float *__restrict__ logits, float *__restrict__ value,
+                                       float *__restrict__ probs, int32_t *__restrict__ greedy) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= B) return;
-    const float *z = logits + (size_t)n * A;
-    float mx = z[0];
+    float z[32];
+    head_row(part, bias, B, n, z);
+    float mx = -INFINITY, val = 0.f;
     int arg = 0;
-    for (int k = 1; k < A; ++k)
-        if (z[k] > mx) { mx = z[k]; arg = k; }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+        if (k < A) {
+            logits[(size_t)n * A + k] = z[k];
+            if (z[k] > mx) { mx = z[k]; arg = k; }
+        }
+        val = k == A ? z[k] : val;
+    }
+    value[n] = val;
     if (greedy) greedy[n] = arg;
     if (probs) {
         float s = 0.f;
-        for (int k = 0; k < A; ++k) s += __expf(z[k] - mx);
+#pragma unroll
+        for (int k = 0; k < 32; ++k) s += k < A ? expf(z[k] - mx) : 0.f;
         const float inv = 1.f / s;
-        for (int k = 0; k < A; ++k) probs[(size_t)n * A + k] = __expf(z[k] - mx) * inv;
+#pragma unroll
+        for (int k = 0; k < 32; ++k)
+            if (k < A) probs[(size_t)n * A + k] = expf(z[k] - mx) * inv;
     }
 }
 
@@ -242,22 +272,24 @@ __global__ void policy_epilogue_kernel(const float *__restrict__ logits, int B, 
 // Section "RL Algorithm Background": advantage actor-critic gradient and the PPO
 // clipped surrogate; value regression and entropy bonus as batch means.
 // One thread per sample.  Writes the gradient at the head outputs as one bf16
-// row [NHP] per sample (columns 0..A-1 logits, column A value, rest 0) and one
-// partial sum {policy, value, entropy} per block.
+// row [NHP = 64] per sample (columns 0..A-1 logits, column A value, rest 0) and
+// one partial sum {policy, value, entropy} per block.
 __global__ __launch_bounds__(LOSS_BLOCK) void ac_loss_kernel(
-    const float *__restrict__ logits, const float *__restrict__ value, const int32_t *__restrict__ action,
+    const float *__restrict__ part, const float *__restrict__ bias, const int32_t *__restrict__ action,
     const float *__restrict__ adv, const float *__restrict__ ret, const float *__restrict__ old_logp, int ppo,
-    float clip_eps, float value_coef, float entropy_coef, int B, int A, int NHP, __bf16 *__restrict__ dz,
+    float clip_eps, float value_coef, float entropy_coef, int B, int A, __bf16 *__restrict__ dz,
     float *__restrict__ lossp) {
     __shared__ float red[3][LOSS_BLOCK];
     const int tid = threadIdx.x, n = blockIdx.x * LOSS_BLOCK + tid;
     float pol = 0.f, val = 0.f, ent = 0.f;
     if (n < B) {
         float z[32];
-        float mx = -INFINITY;
+        head_row(part, bias, B, n, z);
+        float v = 0.f, mx = -INFINITY;
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
-            z[k] = k < A ? logits[(size_t)n * A + k] : -INFINITY;
+            v = k == A ? z[k] : v;
+            z[k] = k < A ? z[k] : -INFINITY;
             mx = fmaxf(mx, z[k]);
         }
         float s = 0.f;
@@ -287,21 +319,28 @@ __global__ __launch_bounds__(LOSS_BLOCK) void ac_loss_kernel(
             pol = -lpa * ad;
             w = ad;
         }
-        const float v = value[n], dv = v - ret[n];
+        const float dv = v - ret[n];
         val = dv * dv;
         ent = H;
         const float invB = 1.f / (float)B;
-        __bf16 *row = dz + (size_t)n * NHP;
+        float g[32];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
-            if (k < A) {
-                const float p = expf(z[k]);
-                const float g = (-w * ((k == a ? 1.f : 0.f) - p) + entropy_coef * p * (z[k] + H)) * invB;
-                row[k] = (__bf16)g;
-            }
+            const float p = expf(z[k]);
+            const float gk = (-w * ((k == a ? 1.f : 0.f) - p) + entropy_coef * p * (z[k] + H)) * invB;
+            g[k] = k < A ? gk : (k == A ? value_coef * 2.f * dv * invB : 0.f);
         }
-        row[A] = (__bf16)(value_coef * 2.f * dv * invB);
-        for (int k = A + 1; k < NHP; ++k) row[k] = (__bf16)0.f;
+        typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+        u32x4_t *row = reinterpret_cast<u32x4_t *>(dz + (size_t)n * 64);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bf16x8_t h = {(__bf16)g[8 * q],     (__bf16)g[8 * q + 1], (__bf16)g[8 * q + 2], (__bf16)g[8 * q + 3],
+                                (__bf16)g[8 * q + 4], (__bf16)g[8 * q + 5], (__bf16)g[8 * q + 6], (__bf16)g[8 * q + 7]};
+            row[q] = __builtin_bit_cast(u32x4_t, h);
+        }
+#pragma unroll
+        for (int q = 4; q < 8; ++q) row[q] = u32x4_t{0u, 0u, 0u, 0u};
     }
     red[0][tid] = pol;
     red[1][tid] = val;
