@@ -85,7 +85,7 @@ void launch_resident(const char *name, const typename C::Args &a, int B, hipStre
     ProfScope ps(name, s);
     const int groups = (B + C::G - 1) / C::G;
     const int spw = resident_spw(groups, 256) * C::G;
-    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(cdiv(B, spw)), dim3(RES_THREADS), 0, s, a, B, spw);
+    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(cdiv(B, spw)), dim3(RESC_THREADS), 0, s, a, B, spw);
 }
 
 template <class F>

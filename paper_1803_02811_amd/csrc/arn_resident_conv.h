@@ -53,32 +53,36 @@ __device__ __forceinline__ uint8_t positive_bits(u32x4 v) {
     return (uint8_t)(two(v.x) | (two(v.y) << 2) | (two(v.z) << 4) | (two(v.w) << 6));
 }
 
-// Eight wavefronts per workgroup: wavefront w and w+4 share a channel slice and
-// take alternate position tiles, so every SIMD has two wavefronts to overlap the
-// LDS-read latency of one with the MFMAs of the other.
-constexpr int RES_THREADS = 512;
+// Threads per workgroup of the sample-resident kernels.  resident_conv_kernel runs
+// one wavefront per SIMD with up to 512 VGPRs each: the weights (up to 144
+// registers) and two half-tiles of activation fragments stay in registers, and
+// the LDS reads of one half-tile are issued while the MFMAs of the previous one
+// run, which hides the LDS latency that a single wavefront would otherwise expose.
+constexpr int RES_THREADS = 512;    // conv1 forward
+constexpr int RESC_THREADS = 256;   // resident_conv_kernel
 
 template <class C>
-__global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
+__global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
     constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
     constexpr int IMG = C::LDS_PIX * PS;                 // bytes of one sample's image
     constexpr int PARTS = C::SPLIT ? 2 : 1;              // hi (+ lo)
     constexpr int BUF = C::G * IMG * PARTS;              // one buffer: G samples, hi then lo
     constexpr int NQ = C::G * C::SRC_PIX * NCH;          // 16-byte chunks per part per iteration
-    constexpr int NL = (NQ + RES_THREADS - 1) / RES_THREADS;
+    constexpr int NL = (NQ + RESC_THREADS - 1) / RESC_THREADS;
     constexpr int R = C::G * C::P, NT = (R + 15) / 16;
     constexpr int CT = C::CO / 64;                       // 16-channel tiles per wavefront
-    constexpr int KS = C::K / 32;
+    constexpr int KS = C::K / 32, KH = KS / 2;           // k-steps per tile and per half-tile
     constexpr int NMQ = C::G * C::MASK_ELEMS / 8;        // mask chunks (8 elements -> 1 byte) per iteration
-    constexpr int NML = (NMQ + RES_THREADS - 1) / RES_THREADS;
+    constexpr int NML = (NMQ + RESC_THREADS - 1) / RESC_THREADS;
     constexpr int MBUF = (NMQ + 15) / 16 * 16;
+    static_assert(KS % 2 == 0, "k-steps split into two halves");
     static_assert(BUF * 2 + MBUF * 2 <= 160 * 1024, "LDS budget");
 
     __shared__ u32x4 lds[2 * BUF / 16];
     __shared__ uint8_t lds_mask[NMQ ? 2 * MBUF : 16];
     char *const lds_b = reinterpret_cast<char *>(lds);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, thalf = tid >> 8;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
@@ -97,7 +101,7 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
     }
 
     if constexpr (C::ZERO_FILL) {
-        for (int i = tid; i < 2 * BUF / 16; i += RES_THREADS) lds[i] = zero_u4();
+        for (int i = tid; i < 2 * BUF / 16; i += RESC_THREADS) lds[i] = zero_u4();
         __syncthreads();
     }
 
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
     auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1 (clamped to the last valid one)
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            int q = tid + RES_THREADS * i;
+            int q = tid + RESC_THREADS * i;
             q = q < NQ ? q : NQ - 1;
             const int g = q / (C::SRC_PIX * NCH), rem = q - g * (C::SRC_PIX * NCH);
             const int sg = s + g < s_end ? s + g : s_end - 1;
@@ -120,7 +124,7 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
         if constexpr (NMQ > 0) {
 #pragma unroll
             for (int i = 0; i < NML; ++i) {
-                int q = tid + RES_THREADS * i;
+                int q = tid + RESC_THREADS * i;
                 q = q < NMQ ? q : NMQ - 1;
                 const int g = q / (C::MASK_ELEMS / 8), rem = q - g * (C::MASK_ELEMS / 8);
                 const int sg = s + g < s_end ? s + g : s_end - 1;
@@ -132,7 +136,7 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
         char *dst = lds_b + buf * BUF;
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int q = tid + RES_THREADS * i;
+            const int q = tid + RESC_THREADS * i;
             if (q < NQ) {
                 const int p = q / NCH, c = q - p * NCH;          // p = g * SRC_PIX + source pixel
                 const int g = p / C::SRC_PIX, sp = p - g * C::SRC_PIX;
@@ -144,8 +148,47 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
         if constexpr (NMQ > 0) {
 #pragma unroll
             for (int i = 0; i < NML; ++i) {
-                const int q = tid + RES_THREADS * i;
+                const int q = tid + RESC_THREADS * i;
                 if (q < NMQ) lds_mask[buf * MBUF + q] = positive_bits(rm[i]);
+            }
+        }
+    };
+
+    // activation fragments of one half-tile (k-steps half*KH .. +KH-1) of position tile t
+    auto load_half = [&](const char *img, int t, int half, bf16x8 (&fh)[KH], bf16x8 (&fl)[C::SPLIT ? KH : 1])
+                         __attribute__((always_inline)) {
+        int row = t * 16 + li;
+        row = row < R ? row : R - 1;                     // padded rows recompute the last one; never stored
+        const int g = row / C::P, pos = row - g * C::P;
+        const int base = (g * C::LDS_PIX + C::base_pix(pos)) * PS + 16 * lg;
+#pragma unroll
+        for (int j = 0; j < KH; ++j) {
+            const int ks = half * KH + j;
+            const int tap = (32 * ks) / CI, ci0 = (32 * ks) % CI;
+            const int off = base + C::tap_pix(tap) * PS + ci0 * 2;
+            fh[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + off));
+            if constexpr (C::SPLIT) fl[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + C::G * IMG + off));
+        }
+    };
+    auto mfma_half = [&](int half, const bf16x8 (&fh)[KH], const bf16x8 (&fl)[C::SPLIT ? KH : 1], f32x4 (&acc)[CT])
+                         __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < KH; ++j) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                if (half == 0) {
+                    if constexpr (C::SPLIT) {
+                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ct][j], fh[j], acc[ct], 0, 0, 0);
+                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][j], fl[j], acc[ct], 0, 0, 0);
+                    }
+                    acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][j], fh[j], acc[ct], 0, 0, 0);
+                } else {
+                    if constexpr (C::SPLIT) {
+                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ct][KH + j], fh[j], acc[ct], 0, 0, 0);
+                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][KH + j], fl[j], acc[ct], 0, 0, 0);
+                    }
+                    acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][KH + j], fh[j], acc[ct], 0, 0, 0);
+                }
             }
         }
     };
@@ -158,32 +201,26 @@ __global__ __launch_bounds__(RES_THREADS) void resident_conv_kernel(const typena
         if (s + C::G < s_end) gload(s + C::G);
         const char *img = lds_b + buf * BUF;
         const uint8_t *mbits = lds_mask + buf * MBUF;
+
+        bf16x8 fa_h[KH], fa_l[C::SPLIT ? KH : 1], fb_h[KH], fb_l[C::SPLIT ? KH : 1];
+        load_half(img, 0, 0, fa_h, fa_l);
 #pragma unroll 1
-        for (int t = thalf; t < NT; t += 2) {
-            int row = t * 16 + li;
-            row = row < R ? row : R - 1;                 // padded rows recompute the last one; never stored
-            const int g = row / C::P, pos = row - g * C::P;
-            const int base = (g * C::LDS_PIX + C::base_pix(pos)) * PS + 16 * lg;
+        for (int t = 0; t < NT; ++t) {
             f32x4 acc[CT];
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int tap = (32 * ks) / CI, ci0 = (32 * ks) % CI;
-                const int off = base + C::tap_pix(tap) * PS + ci0 * 2;
-                const bf16x8 bh = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + off));
-                bf16x8 bl;
-                if constexpr (C::SPLIT) bl = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + C::G * IMG + off));
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    if constexpr (C::SPLIT) {
-                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ct][ks], bh, acc[ct], 0, 0, 0);
-                        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], bl, acc[ct], 0, 0, 0);
-                    }
-                    acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], bh, acc[ct], 0, 0, 0);
-                }
-            }
+            load_half(img, t, 1, fb_h, fb_l);            // in flight during the first half's MFMAs
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_half(0, fa_h, fa_l, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            load_half(img, t + 1 < NT ? t + 1 : t, 0, fa_h, fa_l);   // next tile's first half
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_half(1, fb_h, fb_l, acc);
+            __builtin_amdgcn_sched_barrier(0);
+
             const int orow = t * 16 + li;
+            const int rowc = orow < R ? orow : R - 1;
+            const int g = rowc / C::P, pos = rowc - g * C::P;
             if (orow < R && s + g < s_end) {
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
