@@ -23,7 +23,12 @@
  *     16-byte aligned (256-byte for workspace and packed weights).  `arn_config`
  *     and `arn_batch` structs themselves live in HOST memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Calls enqueue work and return; they never synchronise, allocate or free.
+ *     Calls enqueue work and return; they never synchronise, allocate or free
+ *     device memory.  arn_train_step_grads also uses one library-owned stream
+ *     per device (created on first use, default priority) for work that can run
+ *     next to the caller's stream; it is forked from and joined back to `stream`
+ *     with events inside the call, so to the caller the call behaves as if all
+ *     of its work were on `stream`.  Set ARN_SINGLE_STREAM=1 to disable it.
  *   - Return value: ARN_OK (0) or a negative arn_status.  Argument errors are
  *     detected on the host before anything is launched.
  *   - Arithmetic: bf16 MFMA operands, fp32 accumulation, fp32 epilogues and

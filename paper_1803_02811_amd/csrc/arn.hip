@@ -2,6 +2,7 @@
 // then a fixed sequence of kernel launches on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -59,6 +60,30 @@ struct ProfScope {
 
 inline unsigned cdiv(long a, long b) { return (unsigned)((a + b - 1) / b); }
 
+// A second, library-owned stream (default priority) on which the weight-gradient kernels and their
+// reductions run next to the input-gradient chain of the caller's stream; joined back with events
+// before the call returns.  Created once per device on first use.  ARN_SINGLE_STREAM=1 disables it.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork[5] = {}, join = nullptr;
+    int state = 0;   // 0 unknown, 1 ready, -1 unavailable
+};
+SideStream *side_stream() {
+    static SideStream per_dev[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    SideStream &ss = per_dev[dev];
+    if (ss.state == 0) {
+        const char *off = getenv("ARN_SINGLE_STREAM");
+        bool ok = !(off && off[0] == '1');
+        ok = ok && hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess;
+        for (int i = 0; ok && i < 5; ++i) ok = hipEventCreateWithFlags(&ss.fork[i], hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
+        ss.state = ok ? 1 : -1;
+    }
+    return ss.state == 1 ? &ss : nullptr;
+}
+
 template <class P>
 void launch_nt(const char *name, const P &p, long M, int n_tiles, int z, hipStream_t s) {
     ProfScope ps(name, s);
@@ -84,7 +109,7 @@ template <class C>
 void launch_resident(const char *name, const typename C::Args &a, int B, hipStream_t s) {
     ProfScope ps(name, s);
     const int groups = (B + C::G - 1) / C::G;
-    const int spw = resident_spw(groups, 256) * C::G;
+    const int spw = resident_spw(groups, C::NBUF == 1 ? 512 : 256) * C::G;   // single-buffered kernels share a CU
     hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(cdiv(B, spw)), dim3(RESC_THREADS), 0, s, a, B, spw);
 }
 
@@ -354,65 +379,78 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                            cfg->entropy_coef, loss);
     }
 
-    // ---- backward: heads ----
+    // ---- backward ----
+    // The input-gradient chain (head -> fc -> conv3 -> conv2, then conv1's weight gradient) runs on the
+    // caller's stream; every other weight gradient and its reduction runs on the side stream as soon as
+    // the gradient it consumes exists.
+    SideStream *ss = side_stream();
+    hipStream_t s2 = ss ? ss->stream : s;
+    int nfork = 0;
+    auto fork = [&]() {   // work queued on s2 from here on sees everything queued on s so far
+        if (!ss) return;
+        hipEventRecord(ss->fork[nfork], s);
+        hipStreamWaitEvent(s2, ss->fork[nfork], 0);
+        ++nfork;
+    };
+    fork();   // dz
     {
         HeadWgrad p;
         p.in = h; p.M = B; p.N1 = d.NHP; p.dy = dz;
         float *part = (float *)(ws + o.pwh);
-        launch_tn("head_wgrad", p, part, B, d.NHP, HID, sp.hd, s);
-        launch_reduce("head_reduce", UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s);
+        launch_tn("head_wgrad", p, part, B, d.NHP, HID, sp.hd, s2);
+        launch_reduce("head_reduce", UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s2);
     }
     {
         HeadDgrad p;
         p.in = dz; p.M = B; p.K = d.NHP; p.w = w.whd; p.h = h; p.out = dph;
         launch_nt("head_dgrad", p, B, HID / HeadDgrad::BN, 1, s);
     }
-    // ---- fc ----
+    fork();   // d(pre_fc)
     {
         FcWgrad p;
         p.in = a3; p.M = B; p.dy = dph;
         float *part = (float *)(ws + o.pwfc);
-        launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s);
-        launch_reduce("fc_reduce", UnmapFc{(long)po.wfc, (long)po.bfc}, part, dW, (long)HID * FEAT, HID, sp.fc, 1.f, s);
+        launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s2);
+        launch_reduce("fc_reduce", UnmapFc{(long)po.wfc, (long)po.bfc}, part, dW, (long)HID * FEAT, HID, sp.fc, 1.f, s2);
     }
     {
         FcDgrad p;
         p.in = dph; p.M = B; p.w = w.wfcd; p.act = a3; p.out = dp3;
         launch_nt("fc_dgrad", p, B, FEAT / FcDgrad::BN, 1, s);
     }
-    // ---- conv3 ----
+    fork();   // d(pre3)
     {
         float *part = (float *)(ws + o.pw3);
         {
-            ProfScope ps("conv3_wgrad", s);
+            ProfScope ps("conv3_wgrad", s2);
             const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
             hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
-                               dim3(256), 0, s, a2, dp3, part, B, resident_spw(groups, 256) * CONV3_WG_G);
+                               dim3(256), 0, s2, a2, dp3, part, B, resident_spw(groups, 256) * CONV3_WG_G);
         }
-        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s);
+        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
     }
     {
         ResConv3Dgrad::Args p;
         p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = a2; p.out = dp2;
         launch_resident<ResConv3Dgrad>("conv3_dgrad", p, B, s);
     }
-    // ---- conv2 ----
+    fork();   // d(pre2)
     {
         float *part = (float *)(ws + o.pw2);
         {
-            ProfScope ps("conv2_wgrad", s);
+            ProfScope ps("conv2_wgrad", s2);
             const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
             hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 1>), dim3(sp.c2),
-                               dim3(256), 0, s, a1, dp2, part, B, resident_spw(groups, 256) * CONV2_WG_G);
+                               dim3(256), 0, s2, a1, dp2, part, B, resident_spw(groups, 256) * CONV2_WG_G);
         }
-        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s);
+        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
     }
     {
         ResConv2Dgrad::Args p;
         p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = a1; p.out = dp1;
         launch_resident<ResConv2Dgrad>("conv2_dgrad", p, B, s);
     }
-    // ---- conv1 (weight gradient only: the input is data) ----
+    // conv1: weight gradient only (the input is data)
     {
         float *part = (float *)(ws + o.pw1);
         {
@@ -422,6 +460,10 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         }
         // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
         launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
+    }
+    if (ss) {   // join: the caller's stream continues only after the side stream's work
+        hipEventRecord(ss->join, s2);
+        hipStreamWaitEvent(s, ss->join, 0);
     }
     return launched();
 }

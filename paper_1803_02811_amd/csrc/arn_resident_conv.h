@@ -36,6 +36,11 @@ namespace arn {
 //   dst_pix(p)   LDS pixel of source pixel p
 //   base_pix(pos) LDS pixel of tap (0,0) of output position pos
 //   tap_pix(t)   LDS pixel offset of tap t
+//   NBUF         LDS image buffers: 2 = double buffered by sample group (one barrier per
+//                group); 1 = single (two barriers) so that two or three workgroups share a CU
+//                and fill each other's staging and latency gaps
+//   PIPE         explicit half-tile software pipelining of the LDS fragment reads (needs
+//                registers for two half-tiles of fragments on top of the weights)
 //   MASK_ELEMS   0, or elements per sample of the tensor whose sign masks the output
 //                (ReLU derivative); its sign bits are staged to LDS with the image so
 //                that the epilogue needs no dependent global load
@@ -76,10 +81,11 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
     constexpr int NML = (NMQ + RESC_THREADS - 1) / RESC_THREADS;
     constexpr int MBUF = (NMQ + 15) / 16 * 16;
     static_assert(KS % 2 == 0, "k-steps split into two halves");
-    static_assert(BUF * 2 + MBUF * 2 <= 160 * 1024, "LDS budget");
+    constexpr int NBUF = C::NBUF;
+    static_assert((BUF + MBUF) * NBUF <= 160 * 1024, "LDS budget");
 
-    __shared__ u32x4 lds[2 * BUF / 16];
-    __shared__ uint8_t lds_mask[NMQ ? 2 * MBUF : 16];
+    __shared__ u32x4 lds[NBUF * BUF / 16];
+    __shared__ uint8_t lds_mask[NMQ ? NBUF * MBUF : 16];
     char *const lds_b = reinterpret_cast<char *>(lds);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
     }
 
     if constexpr (C::ZERO_FILL) {
-        for (int i = tid; i < 2 * BUF / 16; i += RESC_THREADS) lds[i] = zero_u4();
+        for (int i = tid; i < NBUF * BUF / 16; i += RESC_THREADS) lds[i] = zero_u4();
         __syncthreads();
     }
 
@@ -193,6 +199,17 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
         }
     };
 
+    auto tile_store = [&](int t, const f32x4 (&acc)[CT], int s, const uint8_t *mbits) __attribute__((always_inline)) {
+        const int orow = t * 16 + li;
+        const int rowc = orow < R ? orow : R - 1;
+        const int g = rowc / C::P, pos = rowc - g * C::P;
+        if (orow < R && s + g < s_end) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                a.store(s + g, g, pos, wave * (16 * CT) + ct * 16 + 4 * lg, acc[ct], lane_state[ct], mbits);
+        }
+    };
+
     gload(s_begin);
     int buf = 0;
     for (int s = s_begin; s < s_end; s += C::G) {
@@ -202,32 +219,40 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
         const char *img = lds_b + buf * BUF;
         const uint8_t *mbits = lds_mask + buf * MBUF;
 
-        bf16x8 fa_h[KH], fa_l[C::SPLIT ? KH : 1], fb_h[KH], fb_l[C::SPLIT ? KH : 1];
-        load_half(img, 0, 0, fa_h, fa_l);
+        if constexpr (C::PIPE) {
+            bf16x8 fa_h[KH], fa_l[C::SPLIT ? KH : 1], fb_h[KH], fb_l[C::SPLIT ? KH : 1];
+            load_half(img, 0, 0, fa_h, fa_l);
 #pragma unroll 1
-        for (int t = 0; t < NT; ++t) {
-            f32x4 acc[CT];
+            for (int t = 0; t < NT; ++t) {
+                f32x4 acc[CT];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-            load_half(img, t, 1, fb_h, fb_l);            // in flight during the first half's MFMAs
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_half(0, fa_h, fa_l, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            load_half(img, t + 1 < NT ? t + 1 : t, 0, fa_h, fa_l);   // next tile's first half
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_half(1, fb_h, fb_l, acc);
-            __builtin_amdgcn_sched_barrier(0);
-
-            const int orow = t * 16 + li;
-            const int rowc = orow < R ? orow : R - 1;
-            const int g = rowc / C::P, pos = rowc - g * C::P;
-            if (orow < R && s + g < s_end) {
+                for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                load_half(img, t, 1, fb_h, fb_l);            // in flight during the first half's MFMAs
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_half(0, fa_h, fa_l, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                load_half(img, t + 1 < NT ? t + 1 : t, 0, fa_h, fa_l);   // next tile's first half
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_half(1, fb_h, fb_l, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                tile_store(t, acc, s, mbits);
+            }
+        } else {
+#pragma unroll 1
+            for (int t = 0; t < NT; ++t) {
+                f32x4 acc[CT];
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    a.store(s + g, g, pos, wave * (16 * CT) + ct * 16 + 4 * lg, acc[ct], lane_state[ct], mbits);
+                for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                bf16x8 fh[KH], fl[C::SPLIT ? KH : 1];
+                load_half(img, t, 0, fh, fl);
+                mfma_half(0, fh, fl, acc);
+                load_half(img, t, 1, fh, fl);
+                mfma_half(1, fh, fl, acc);
+                tile_store(t, acc, s, mbits);
             }
         }
-        buf ^= 1;
+        if constexpr (NBUF == 1) __syncthreads();    // everyone is done reading before the next group is staged
+        if constexpr (NBUF == 2) buf ^= 1;
     }
 }
 
@@ -326,8 +351,8 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
 // windows of neighbouring positions are neighbouring LDS pixels.
 struct ResConv2Fwd {
     static constexpr int CI = C1, SRC_PIX = P1, LDS_PIX = P1, P = P2, HO = H2, CO = C2, K = KW2, G = 1;
-    static constexpr bool SPLIT = true, ZERO_FILL = false;
-    static constexpr int MASK_ELEMS = 0;
+    static constexpr bool SPLIT = true, ZERO_FILL = false, PIPE = false;
+    static constexpr int MASK_ELEMS = 0, NBUF = 1;
     __device__ static constexpr int dst_pix(int p) {
         const int y = p / H1, x = p - y * H1;
         return (y * 2 + (x & 1)) * (H1 / 2) + (x >> 1);
@@ -357,8 +382,8 @@ struct ResConv2Fwd {
 // conv3 forward: act2 [9][9][64] -> act3 [7][7][64], 3x3 stride 1
 struct ResConv3Fwd {
     static constexpr int CI = C2, SRC_PIX = P2, LDS_PIX = P2, P = P3, HO = H3, CO = C3, K = KW3, G = 2;
-    static constexpr bool SPLIT = true, ZERO_FILL = false;
-    static constexpr int MASK_ELEMS = 0;
+    static constexpr bool SPLIT = true, ZERO_FILL = false, PIPE = false;
+    static constexpr int MASK_ELEMS = 0, NBUF = 1;
     __device__ static constexpr int dst_pix(int p) { return p; }
     __device__ static constexpr int base_pix(int pos) {
         const int oy = pos / H3, ox = pos - oy * H3;
@@ -385,8 +410,8 @@ struct ResConv3Fwd {
 struct ResConv3Dgrad {
     static constexpr int PADW = H3 + 4;   // 11
     static constexpr int CI = C3, SRC_PIX = P3, LDS_PIX = PADW * PADW, P = P2, HO = H2, CO = C2, K = 9 * C3, G = 2;
-    static constexpr bool SPLIT = false, ZERO_FILL = true;
-    static constexpr int MASK_ELEMS = P2 * C2;
+    static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
+    static constexpr int MASK_ELEMS = P2 * C2, NBUF = 1;
     __device__ static constexpr int dst_pix(int p) { return (p / H3 + 2) * PADW + p % H3 + 2; }
     __device__ static constexpr int base_pix(int pos) { return (pos / H2) * PADW + pos % H2; }
     __device__ static constexpr int tap_pix(int t) { return (t / 3) * PADW + t % 3; }
@@ -413,8 +438,8 @@ struct ResConv3Dgrad {
 struct ResConv2Dgrad {
     static constexpr int PADW = H2 + 2;   // 11
     static constexpr int CI = C2, SRC_PIX = P2, LDS_PIX = PADW * PADW, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 2;
-    static constexpr bool SPLIT = false, ZERO_FILL = true;
-    static constexpr int MASK_ELEMS = P1 * C1;
+    static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
+    static constexpr int MASK_ELEMS = P1 * C1, NBUF = 1;
     __device__ static constexpr int dst_pix(int p) { return (p / H2 + 1) * PADW + p % H2 + 1; }
     __device__ static constexpr int base_pix(int pos) { return (pos / 10) * PADW + pos % 10; }
     __device__ static constexpr int tap_pix(int t) { return (t / 2) * PADW + t % 2; }
