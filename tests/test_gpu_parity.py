@@ -134,3 +134,55 @@ def test_full_batch_gradient_is_mean_of_shards(gu):
     scale = np.abs(mean).max()
     assert np.abs(full - mean).max() <= 2e-3 * scale + 1e-6
     assert abs(lf[0] - 0.5 * (halves[0][1][0] + halves[1][1][0])) < 1e-5
+
+
+# ---------------------------------------------------------------------------
+# Full workload sizes, in the launch configuration the benchmark times.
+# The oracle needs a few seconds per case on the GPU machine's host cores.
+# ---------------------------------------------------------------------------
+def test_full_size_a2c_b2048(gu):
+    """Workload 3 as benchmarked: B=2048 A2C step, every gradient tensor and the loss against the oracle."""
+    A, B = 18, 2048
+    flat = wl.he_normal_params(A, "pv", 2003)
+    batch = wl.actor_critic_batch(3, B=B)
+    spec = orc.NetSpec(A, "pv")
+    ref = orc.train_step_grads(flat, batch, "a2c", spec)
+    dW, loss = gu.GpuNet(A, "pv", flat).train(batch, "a2c")
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+    # the absolute term of the bar dominates at this batch size; also hold a purely relative bar
+    got, want = gu.per_tensor(dW, A, "pv"), gu.per_tensor(ref["flat"], A, "pv")
+    for name in want:
+        assert np.abs(got[name] - want[name]).max() <= 2e-2 * np.abs(want[name]).max(), name
+
+
+def test_full_size_ppo_b4096(gu):
+    """Workload 4: B=4096 PPO-clip step on uniform frames, old log-probs from perturbed oracle logits."""
+    A, B = 18, 4096
+    flat = wl.he_normal_params(A, "pv", 2004)
+    batch = wl.actor_critic_batch(4, B=B, normalise_adv=True)
+    spec = orc.NetSpec(A, "pv")
+    fwd = orc.forward(orc.unflatten(flat, spec), batch["obs"], spec)
+    noisy = fwd["logits"] + wl.logit_noise(4, B, A)
+    batch["old_logp"] = orc.log_softmax(noisy)[np.arange(B), batch["action"]].astype(np.float32)
+    ref = orc.train_step_grads(flat, batch, "ppo", spec)
+    rho = np.exp(orc.log_softmax(fwd["logits"])[np.arange(B), batch["action"]] - batch["old_logp"])
+    assert (~orc.ppo_active(rho, batch["adv"])).sum() > 20           # the clipped branch is exercised
+    dW, loss = gu.GpuNet(A, "pv", flat).train(batch, "ppo")
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+
+
+def test_full_size_c51_b8192(gu):
+    """Workload 5: B=8192 categorical step (target forward, projection, cross-entropy, all gradients)."""
+    A, B = 18, 8192
+    flat = wl.he_normal_params(A, "c51", 2005)
+    tflat = wl.he_normal_params(A, "c51", 3005)
+    batch = wl.c51_batch(5, B=B)
+    spec = orc.NetSpec(A, "c51")
+    ref = orc.train_step_grads(flat, batch, "c51", spec, flat_target_params=tflat)
+    assert batch["done"].sum() > 20
+    net = gu.GpuNet(A, "c51", flat)
+    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    _compare_grads(gu, dW, ref["flat"], A, "c51", loss, ref["loss"], ["total", "ce", None, None])
+    # properties that hold at any size: gradient of the categorical head's bias sums to zero per action
+    got = gu.per_tensor(dW, A, "c51")
+    assert np.abs(got["c51.b"].reshape(A, 51).sum(axis=1)).max() < 1e-4
