@@ -18,7 +18,7 @@ sys.path.insert(0, ROOT)
 # algorithmic multiply-accumulates per sample (dense, nothing avoided), A = 18 heads
 MACS = {"conv1": 3_276_800, "conv2": 2_654_208, "conv3": 1_806_336, "fc": 1_605_632, "head_pv": 19 * 512}
 FWD_FLOPS = 2 * sum(MACS.values())                                  # 18,705,408
-FWDBWD_FLOPS = 3 * FWD_FLOPS - 2 * 2 * MACS["conv1"]                # no conv1 input gradient: 49,562,624
+FWDBWD_FLOPS = 3 * FWD_FLOPS - 2 * MACS["conv1"]                    # no conv1 input gradient: 49,562,624
 KERNEL_FLOPS = {  # per sample, by instrumented kernel name
     "conv1_fwd": 2 * MACS["conv1"], "conv2_fwd": 2 * MACS["conv2"], "conv3_fwd": 2 * MACS["conv3"],
     "fc_fwd": 2 * MACS["fc"], "head_fwd": 2 * MACS["head_pv"],
@@ -53,7 +53,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--batch", type=int, default=2048)
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
+                    help="3 (default) = the headline A2C step at B=2048; 1, 2 = inference; 4 = PPO; 5 = C51")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-samples", type=int, default=0, help="oracle sample size (0 = auto, ~10-30 s)")
     args = ap.parse_args()
@@ -70,7 +72,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    A, B, k = 18, args.batch, 3
+    if args.workload != 3:
+        other_workload(args, arn, wl, np, torch)
+        return
+    A, B, k = 18, args.batch or 2048, 3
     cfg = arn.Config(A, arn.ARN_HEAD_PV)
     flat = wl.he_normal_params(A, "pv", 2000 + k)
     w = torch.from_numpy(flat).to(dev)
@@ -170,6 +175,71 @@ def main():
                                "sample": "first %d samples of the same batch, fwd+loss+bwd, %d repetitions, %.1f s"
                                          % (n, reps, t_total)}
     print(json.dumps(out))
+
+
+def other_workload(args, arn, wl, np, torch):
+    """Secondary report lines for the other workloads (same JSON shape, no per-kernel roofline)."""
+    dev, k = "cuda:0", args.workload
+    w = wl.WORKLOADS[k]
+    A, B, head = w["A"], args.batch or w["B"], w["head"]
+    cfg = arn.Config(A, arn.ARN_HEAD_PV if head == "pv" else arn.ARN_HEAD_C51)
+    flat = wl.he_normal_params(A, head, 2000 + k)
+    packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+    arn.weights_prepare(cfg, torch.from_numpy(flat).to(dev), packed)
+    stream = torch.cuda.current_stream()
+    to_dev = lambda d: {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for n, v in d.items()}
+    if w["kind"] == "forward":
+        obs = torch.from_numpy(wl.frames_for(k, B)).to(dev)
+        ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
+        logits = torch.empty(B, A, dtype=torch.float32, device=dev)
+        value = torch.empty(B, dtype=torch.float32, device=dev)
+        probs = torch.empty(B, A, dtype=torch.float32, device=dev)
+        greedy = torch.empty(B, dtype=torch.int32, device=dev)
+        step = lambda: arn.policy_forward(cfg, packed, obs, logits, value, probs, greedy, workspace=ws, stream=stream)
+        flops = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + (A + 1) * 512)
+        name = "policy_forward"
+    else:
+        ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
+        dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
+        loss = torch.empty(4, dtype=torch.float32, device=dev)
+        if w["kind"] == "ppo":
+            batch = to_dev(wl.actor_critic_batch(k, B=B, normalise_adv=True))
+            # sampling-policy log-probs: the current logits (from this library) perturbed by N(0, 0.05^2)
+            wsf = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
+            logits = torch.empty(B, A, dtype=torch.float32, device=dev)
+            value = torch.empty(B, dtype=torch.float32, device=dev)
+            arn.policy_forward(cfg, packed, batch["obs"], logits, value, workspace=wsf, stream=stream)
+            noisy = logits + torch.from_numpy(wl.logit_noise(k, B, A).astype(np.float32)).to(dev)
+            batch["old_logp"] = torch.log_softmax(noisy, dim=1).gather(1, batch["action"].long()[:, None])[:, 0].contiguous()
+            head_macs = (A + 1) * 512
+            tgt_flops = 0
+        else:
+            batch = to_dev(wl.c51_batch(k, B=B))
+            tpacked = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+            arn.weights_prepare(cfg, torch.from_numpy(wl.he_normal_params(A, head, 3000 + k)).to(dev), tpacked)
+            batch["w_target_packed"] = tpacked
+            head_macs = A * 51 * 512
+            tgt_flops = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + head_macs)
+        fwd = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + head_macs)
+        flops = 3 * fwd - 2 * MACS["conv1"] + tgt_flops
+        step = lambda: arn.train_step_grads(cfg, packed, batch, w["kind"], dW, loss, workspace=ws, stream=stream)
+        name = "train_step_grads:" + w["kind"]
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    print(json.dumps({
+        "metric": "Nature-CNN samples/sec (%s) at B=%d on 1 GPU" % (name, B), "value": round(B / sec, 1),
+        "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s (workload %d)" % (w["name"], k), "global_batch": B, "parallelism": "single-gpu"},
+        "mfma_frac_whole_step": round(B / sec * flops / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "algorithmic_flops_per_sample": flops}))
 
 
 if __name__ == "__main__":
