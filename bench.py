@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
                     help="3 (default) = the headline A2C step at B=2048; 1, 2 = inference; 4 = PPO; 5 = C51")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain device-to-device copy of MIB mebibytes a few times (reference for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--cpu-samples", type=int, default=0, help="oracle sample size (0 = auto, ~10-30 s)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -72,6 +75,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.calibrate_copy:
+        n = args.calibrate_copy * 1024 * 1024
+        src = torch.zeros(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "copies": 5}))
+        return
     if args.workload != 3:
         other_workload(args, arn, wl, np, torch)
         return
