@@ -166,8 +166,9 @@ Packed view_packed(const void *blob, const Dims &d) {
 
 // trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits [B][NH].
 // PV: the head leaves fp32 partial sums in the workspace (o.hp) for the consumer to finish.
+// masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on the online weights).
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                      float *z_out, hipStream_t s) {
+                      float *z_out, bool masks, hipStream_t s) {
     constexpr bool split = true;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *h = (__bf16 *)(ws + o.h);
@@ -177,16 +178,18 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
         hipLaunchKernelGGL(conv1_fwd_resident_kernel, dim3(cdiv(B, spw)), dim3(RES_THREADS), 0, s, obs, w.w1, w.w1l,
-                           w.b1, a1, a1l, B, spw);
+                           w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     {
         ResConv2Fwd::Args p;
         p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
+        p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
         launch_resident<ResConv2Fwd>("conv2_fwd", p, B, s);
     }
     {
         ResConv3Fwd::Args p;
         p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
+        p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
         launch_resident<ResConv3Fwd>("conv3_fwd", p, B, s);
     }
     {
@@ -301,7 +304,7 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     if (int e = check_arch()) return e;
     hipStream_t s = (hipStream_t)stream;
     const Packed w = view_packed(w_packed, d);
-    forward_launches(d, w, obs, B, (char *)workspace, o, logits, s);
+    forward_launches(d, w, obs, B, (char *)workspace, o, logits, false, s);
     if (d.head == ARN_HEAD_PV) {
         ProfScope ps("policy_epilogue", s);
         hipLaunchKernelGGL(policy_epilogue_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s,
@@ -356,20 +359,20 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         // target network on next states -> projected target m; its activations are then overwritten
         const Packed wt = view_packed(batch->w_target_packed, d);
         float *ztgt = (float *)(ws + o.ztgt), *m = (float *)(ws + o.m);
-        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, s);
+        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, false, s);
         {
             ProfScope ps("c51_target", s);
                 hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, B, d.A,
                                d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
                                (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
         }
-        forward_launches(d, w, batch->obs, B, ws, o, z, s);
+        forward_launches(d, w, batch->obs, B, ws, o, z, true, s);
         ProfScope ps("loss", s);
         hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
                            d.atoms, d.NHP, dz, lossp);
         hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, 0.f, 0.f, loss);
     } else {
-        forward_launches(d, w, batch->obs, B, ws, o, nullptr, s);
+        forward_launches(d, w, batch->obs, B, ws, o, nullptr, true, s);
         ProfScope ps("loss", s);
         hipLaunchKernelGGL(ac_loss_kernel, dim3(lblocks), dim3(LOSS_BLOCK), 0, s, (const float *)(ws + o.hp), w.bh,
                            batch->action, batch->adv, batch->ret, batch->old_logp,
@@ -415,7 +418,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     }
     {
         FcDgrad p;
-        p.in = dph; p.M = B; p.w = w.wfcd; p.act = a3; p.out = dp3;
+        p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
         launch_nt("fc_dgrad", p, B, FEAT / FcDgrad::BN, 1, s);
     }
     fork();   // d(pre3)
@@ -425,13 +428,13 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             ProfScope ps("conv3_wgrad", s2);
             const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
             hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
-                               dim3(256), 0, s2, a2, dp3, part, B, resident_spw(groups, 256) * CONV3_WG_G);
+                               dim3(256), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
         }
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
     }
     {
         ResConv3Dgrad::Args p;
-        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = a2; p.out = dp2;
+        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
         launch_resident<ResConv3Dgrad>("conv3_dgrad", p, B, s);
     }
     fork();   // d(pre2)
@@ -441,13 +444,13 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             ProfScope ps("conv2_wgrad", s2);
             const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
             hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 1>), dim3(sp.c2),
-                               dim3(256), 0, s2, a1, dp2, part, B, resident_spw(groups, 256) * CONV2_WG_G);
+                               dim3(256), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
         }
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
     }
     {
         ResConv2Dgrad::Args p;
-        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = a1; p.out = dp1;
+        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
         launch_resident<ResConv2Dgrad>("conv2_dgrad", p, B, s);
     }
     // conv1: weight gradient only (the input is data)

@@ -56,6 +56,19 @@ __device__ __forceinline__ void store_bf16x4_split(__bf16 *hi, __bf16 *lo, size_
     }
 }
 
+// ReLU sign bits of a 16x16 MFMA tile: lane (li = l%16, lg = l/16) holds channels 4*lg..4*lg+3
+// of position li; the four lanes of a position combine their nibbles into one 16-bit word
+// (bit c = value of channel c > 0), valid in every participating lane.
+__device__ __forceinline__ uint32_t sign_bits16(float a, float b, float c, float d, int lg) {
+    uint32_t t = ((a > 0.f ? 1u : 0u) | (b > 0.f ? 2u : 0u) | (c > 0.f ? 4u : 0u) | (d > 0.f ? 8u : 0u)) << (4 * lg);
+    // v_permlane16_swap / v_permlane32_swap (VALU, no LDS traffic): with both operands equal, the two
+    // results are the lane's own value and that of the lane 16 (32) away (checked on hardware)
+    const auto a16 = __builtin_amdgcn_permlane16_swap(t, t, false, false);
+    t = a16[0] | a16[1];
+    const auto a32 = __builtin_amdgcn_permlane32_swap(t, t, false, false);
+    return a32[0] | a32[1];
+}
+
 __device__ __forceinline__ f32x4 unpack_bf16x4(u32x2 u) {
     bf16x4 v = __builtin_bit_cast(bf16x4, u);
     f32x4 r = {(float)v[0], (float)v[1], (float)v[2], (float)v[3]};

@@ -130,6 +130,9 @@ inline int pick_split(long rows, int tiles, int target_wgs) {
     if (s > iters) s = iters;
     return (int)s;
 }
+// workgroups of the conv2 / conv3 weight-gradient kernels: each writes a full fp32 partial of dW, so fewer
+// workgroups mean less partial traffic; they run on the side stream next to the input-gradient kernels
+constexpr int WGRAD_WGS = 256;
 constexpr int CONV2_WG_G = 2, CONV3_WG_G = 4;   // samples staged per iteration by the conv2 / conv3 weight-gradient kernels
 // sample-resident weight-gradient kernels: samples per workgroup and number of workgroups
 inline int resident_spw(int B, int target_wgs) { return (B + target_wgs - 1) / target_wgs; }
@@ -140,8 +143,8 @@ inline int resident_groups(int B, int target_wgs) {
 inline Splits make_splits(const Dims &d, int B) {
     Splits s;
     s.c1 = resident_groups(B, 256);
-    s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, 256);
-    s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, 256);
+    s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS);
+    s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS);
     s.fc = pick_split(B, 49 * 4, 392);
     s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
     return s;
@@ -168,6 +171,7 @@ struct Workspace {
     size_t hp;                          // fp32 [HEAD_KSPLIT][B][32] partial sums of the policy/value head GEMM
     size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
+    size_t m1, m2, m3;                  // ReLU sign bits of act1..3 (bit e&7 of byte e>>3, NHWC element e), written by the forward
     size_t dz, dph, dp3, dp2, dp1;      // bf16 gradients at pre-activations
     size_t lossp;                       // fp32 [blocks][4] partial loss sums
     size_t pw1, pw2, pw3, pwfc, pwh;    // fp32 weight-gradient partials [split][N*K' + N]
@@ -198,6 +202,9 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
             w.ztgt = take(b * (size_t)d.NH * 4);
             w.m = take(b * (size_t)d.atoms * 4);
         }
+        w.m1 = take(b * P1 * C1 / 8);
+        w.m2 = take(b * P2 * C2 / 8);
+        w.m3 = take(b * FEAT / 8);
         w.dz = take(b * (size_t)d.NHP * 2);
         w.dph = take(b * HID * 2);
         w.dp3 = take(b * FEAT * 2);

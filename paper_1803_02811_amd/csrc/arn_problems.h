@@ -259,8 +259,8 @@ struct HeadDgrad : DenseGatherRt {
 // d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][3136], NHWC index
 struct FcDgrad : DenseGather<HID> {
     static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 2;
-    const __bf16 *w;     // [3136][512]
-    const __bf16 *act;   // act3
+    const __bf16 *w;          // [3136][512]
+    const uint8_t *maskbits;  // sign bits of act3, bit e&7 of byte e>>3 for element e = m*3136 + n
     __bf16 *out;
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
     __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
@@ -268,9 +268,9 @@ struct FcDgrad : DenseGather<HID> {
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
         if (m >= M) return;
         const size_t at = (size_t)m * FEAT + n;
-        const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
-        *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
-                                                          a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
+        const uint32_t mb = (uint32_t)maskbits[at >> 3] >> (at & 7);
+        *reinterpret_cast<u32x2 *>(out + at) =
+            pack_bf16x4(mb & 1 ? v[0] : 0.f, mb & 2 ? v[1] : 0.f, mb & 4 ? v[2] : 0.f, mb & 8 ? v[3] : 0.f);
     }
 };
 

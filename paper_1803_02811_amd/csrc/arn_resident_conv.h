@@ -42,32 +42,21 @@ namespace arn {
 //   PIPE         explicit half-tile software pipelining of the LDS fragment reads (needs
 //                registers for two half-tiles of fragments on top of the weights)
 //   MASK_ELEMS   0, or elements per sample of the tensor whose sign masks the output
-//                (ReLU derivative); its sign bits are staged to LDS with the image so
-//                that the epilogue needs no dependent global load
+//                (ReLU derivative); its sign bits (written by the forward kernels, one bit
+//                per element) are staged to LDS with the image so that the epilogue needs
+//                no dependent global load
 // and an Args struct with in, in_lo (SPLIT), w, w_lo (SPLIT), mask (MASK_ELEMS > 0),
 //   Lane lane(n)                      per-lane constants for channels n..n+3 (e.g. the bias)
 //   store(sample, pos, n, v, lane, maskbits)   epilogue for channels n..n+3 of one position;
 //                                     maskbits = LDS bytes, bit e&7 of byte e>>3 for element e
 //                                     of the G samples' mask tensors.
-// bit i = 1 where bf16 element i of the 16-byte word is > 0
-__device__ __forceinline__ uint8_t positive_bits(u32x4 v) {
-    auto two = [](uint32_t w) -> uint32_t {
-        const uint32_t lo = w & 0xffffu, hi = w >> 16;
-        return ((lo - 1u) < 0x7fffu ? 1u : 0u) | ((hi - 1u) < 0x7fffu ? 2u : 0u);   // 0x0001..0x7fff: positive
-    };
-    return (uint8_t)(two(v.x) | (two(v.y) << 2) | (two(v.z) << 4) | (two(v.w) << 6));
-}
-
-// Threads per workgroup of the sample-resident kernels.  resident_conv_kernel runs
-// one wavefront per SIMD with up to 512 VGPRs each: the weights (up to 144
-// registers) and two half-tiles of activation fragments stay in registers, and
-// the LDS reads of one half-tile are issued while the MFMAs of the previous one
-// run, which hides the LDS latency that a single wavefront would otherwise expose.
+// Threads per workgroup of the sample-resident kernels.  resident_conv_kernel uses four wavefronts
+// (one per SIMD); each keeps its share of the weights in registers.
 constexpr int RES_THREADS = 512;    // conv1 forward
 constexpr int RESC_THREADS = 256;   // resident_conv_kernel
 
 template <class C>
-__global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
+__global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
     constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
     constexpr int IMG = C::LDS_PIX * PS;                 // bytes of one sample's image
     constexpr int PARTS = C::SPLIT ? 2 : 1;              // hi (+ lo)
@@ -77,15 +66,18 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
     constexpr int R = C::G * C::P, NT = (R + 15) / 16;
     constexpr int CT = C::CO / 64;                       // 16-channel tiles per wavefront
     constexpr int KS = C::K / 32, KH = KS / 2;           // k-steps per tile and per half-tile
-    constexpr int NMQ = C::G * C::MASK_ELEMS / 8;        // mask chunks (8 elements -> 1 byte) per iteration
+    constexpr int MSB = C::MASK_ELEMS / 8;               // mask bytes per sample (1 bit per element)
+    constexpr int NMQ = C::G * MSB / 8;                  // 8-byte mask chunks per iteration
     constexpr int NML = (NMQ + RESC_THREADS - 1) / RESC_THREADS;
-    constexpr int MBUF = (NMQ + 15) / 16 * 16;
+    constexpr int MBUF = (NMQ * 8 + 15) / 16 * 16;
+    static_assert(MSB % 8 == 0, "mask bytes per sample in 8-byte chunks");
     static_assert(KS % 2 == 0, "k-steps split into two halves");
     constexpr int NBUF = C::NBUF;
     static_assert((BUF + MBUF) * NBUF <= 160 * 1024, "LDS budget");
 
     __shared__ u32x4 lds[NBUF * BUF / 16];
-    __shared__ uint8_t lds_mask[NMQ ? NBUF * MBUF : 16];
+    __shared__ u32x2 lds_mask8[NMQ ? NBUF * MBUF / 8 : 2];
+    uint8_t *const lds_mask = reinterpret_cast<uint8_t *>(lds_mask8);
     char *const lds_b = reinterpret_cast<char *>(lds);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -115,7 +107,8 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) lane_state[ct] = a.lane(wave * (16 * CT) + ct * 16 + 4 * lg);
 
-    u32x4 rh[NL], rl[C::SPLIT ? NL : 1], rm[NML ? NML : 1];
+    u32x4 rh[NL], rl[C::SPLIT ? NL : 1];
+    u32x2 rm[NML ? NML : 1];
     auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1 (clamped to the last valid one)
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -132,9 +125,9 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
             for (int i = 0; i < NML; ++i) {
                 int q = tid + RESC_THREADS * i;
                 q = q < NMQ ? q : NMQ - 1;
-                const int g = q / (C::MASK_ELEMS / 8), rem = q - g * (C::MASK_ELEMS / 8);
+                const int g = q / (MSB / 8), rem = q - g * (MSB / 8);
                 const int sg = s + g < s_end ? s + g : s_end - 1;
-                rm[i] = *reinterpret_cast<const u32x4 *>(a.mask + (size_t)sg * C::MASK_ELEMS + (size_t)rem * 8);
+                rm[i] = *reinterpret_cast<const u32x2 *>(a.mask + (size_t)sg * MSB + (size_t)rem * 8);
             }
         }
     };
@@ -155,7 +148,7 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
 #pragma unroll
             for (int i = 0; i < NML; ++i) {
                 const int q = tid + RESC_THREADS * i;
-                if (q < NMQ) lds_mask[buf * MBUF + q] = positive_bits(rm[i]);
+                if (q < NMQ) lds_mask8[buf * (MBUF / 8) + q] = rm[i];
             }
         }
     };
@@ -268,7 +261,8 @@ __global__ __launch_bounds__(RESC_THREADS) void resident_conv_kernel(const typen
 // two MFMAs per fragment (W_hi x, W_lo x).
 __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w, const __bf16 *__restrict__ w_lo,
-    const float *__restrict__ bias, __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo, int B, int spw) {
+    const float *__restrict__ bias, __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo,
+    uint8_t *__restrict__ mask_out, int B, int spw) {
     constexpr int IMG_U4 = OBS_BYTES / 16;                           // 1764 sixteen-pixel groups
     constexpr int NL = (IMG_U4 + RES_THREADS - 1) / RES_THREADS;     // 4
     constexpr int KS = KW1 / 32;                                     // 8
@@ -336,9 +330,14 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], b, acc, 0, 0, 0);
                 }
                 constexpr float sc = 1.0f / 255.0f;
-                store_bf16x4_split(out, out_lo, ((size_t)s * P1 + pos) * C1 + ct * 16 + 4 * lg,
-                                   fmaxf(acc[0] * sc + bs[ct].x, 0.f), fmaxf(acc[1] * sc + bs[ct].y, 0.f),
-                                   fmaxf(acc[2] * sc + bs[ct].z, 0.f), fmaxf(acc[3] * sc + bs[ct].w, 0.f));
+                const float r0 = fmaxf(acc[0] * sc + bs[ct].x, 0.f), r1 = fmaxf(acc[1] * sc + bs[ct].y, 0.f);
+                const float r2 = fmaxf(acc[2] * sc + bs[ct].z, 0.f), r3 = fmaxf(acc[3] * sc + bs[ct].w, 0.f);
+                const size_t at = ((size_t)s * P1 + pos) * C1 + ct * 16;
+                store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3);
+                if (mask_out) {
+                    const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
+                    if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
+                }
             }
         }
         buf ^= 1;
@@ -366,15 +365,24 @@ struct ResConv2Fwd {
         return (ky * 2 + (kx & 1)) * (H1 / 2) + (kx >> 1);
     }
     struct Args {
-        const __bf16 *in, *in_lo, *w, *w_lo, *mask;
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;
         const float *bias;
         __bf16 *out, *out_lo;
+        uint8_t *mask_out;     // sign bits of the output for the backward pass, or null
         typedef float4 Lane;
         __device__ __forceinline__ Lane lane(int n) const { return *reinterpret_cast<const float4 *>(bias + n); }
         __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &b,
                                               const uint8_t *) const {
-            store_bf16x4_split(out, out_lo, ((size_t)s * P2 + pos) * C2 + n, fmaxf(v[0] + b.x, 0.f),
-                               fmaxf(v[1] + b.y, 0.f), fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
+            const float r0 = fmaxf(v[0] + b.x, 0.f), r1 = fmaxf(v[1] + b.y, 0.f), r2 = fmaxf(v[2] + b.z, 0.f),
+                        r3 = fmaxf(v[3] + b.w, 0.f);
+            const size_t at = ((size_t)s * P2 + pos) * C2 + n;
+            store_bf16x4_split(out, out_lo, at, r0, r1, r2, r3);
+            if (mask_out) {
+                const int lg = (n >> 2) & 3;
+                const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
+                if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
+            }
         }
     };
 };
@@ -391,15 +399,24 @@ struct ResConv3Fwd {
     }
     __device__ static constexpr int tap_pix(int t) { return (t / K3) * H2 + t % K3; }
     struct Args {
-        const __bf16 *in, *in_lo, *w, *w_lo, *mask;
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;
         const float *bias;
         __bf16 *out, *out_lo;
+        uint8_t *mask_out;     // sign bits of the output for the backward pass, or null
         typedef float4 Lane;
         __device__ __forceinline__ Lane lane(int n) const { return *reinterpret_cast<const float4 *>(bias + n); }
         __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &b,
                                               const uint8_t *) const {
-            store_bf16x4_split(out, out_lo, ((size_t)s * P3 + pos) * C3 + n, fmaxf(v[0] + b.x, 0.f),
-                               fmaxf(v[1] + b.y, 0.f), fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
+            const float r0 = fmaxf(v[0] + b.x, 0.f), r1 = fmaxf(v[1] + b.y, 0.f), r2 = fmaxf(v[2] + b.z, 0.f),
+                        r3 = fmaxf(v[3] + b.w, 0.f);
+            const size_t at = ((size_t)s * P3 + pos) * C3 + n;
+            store_bf16x4_split(out, out_lo, at, r0, r1, r2, r3);
+            if (mask_out) {
+                const int lg = (n >> 2) & 3;
+                const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
+                if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
+            }
         }
     };
 };
@@ -416,7 +433,8 @@ struct ResConv3Dgrad {
     __device__ static constexpr int base_pix(int pos) { return (pos / H2) * PADW + pos % H2; }
     __device__ static constexpr int tap_pix(int t) { return (t / 3) * PADW + t % 3; }
     struct Args {
-        const __bf16 *in, *in_lo, *w, *w_lo, *mask;   // mask = act2
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;   // sign bits of act2
         __bf16 *out;
         struct Lane {};
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
@@ -444,7 +462,8 @@ struct ResConv2Dgrad {
     __device__ static constexpr int base_pix(int pos) { return (pos / 10) * PADW + pos % 10; }
     __device__ static constexpr int tap_pix(int t) { return (t / 2) * PADW + t % 2; }
     struct Args {
-        const __bf16 *in, *in_lo, *w, *w_lo, *mask;   // mask = act1
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;   // sign bits of act1
         __bf16 *out;
         struct Lane {};
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
