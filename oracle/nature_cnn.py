@@ -246,7 +246,10 @@ def greedy(z: np.ndarray) -> np.ndarray:
 
 
 def top2_gap(z: np.ndarray) -> np.ndarray:
+    """Largest minus second-largest entry along the last axis (infinite for a single entry)."""
     s = np.sort(np.asarray(z, dtype=np.float64), axis=-1)
+    if s.shape[-1] < 2:
+        return np.full(s.shape[:-1], np.inf)
     return s[..., -1] - s[..., -2]
 
 

@@ -186,3 +186,77 @@ def test_full_size_c51_b8192(gu):
     # properties that hold at any size: gradient of the categorical head's bias sums to zero per action
     got = gu.per_tensor(dW, A, "c51")
     assert np.abs(got["c51.b"].reshape(A, 51).sum(axis=1)).max() < 1e-4
+
+
+# ---------------------------------------------------------------------------
+# Edge and degenerate configurations
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("A", [1, 2, 31])
+def test_policy_head_extreme_action_counts(gu, A):
+    """Smallest and largest supported policy heads (A = 1: a single action, zero entropy)."""
+    B = 9
+    flat = wl.he_normal_params(A, "pv", 2100 + A, bias_std=0.1)
+    r = np.random.default_rng(A)
+    batch = dict(obs=wl.rect_frames(B, 1300 + A), action=r.integers(0, A, size=B).astype(np.int32),
+                 adv=r.standard_normal(B).astype(np.float32), ret=r.standard_normal(B).astype(np.float32))
+    spec = orc.NetSpec(A, "pv")
+    ref = orc.train_step_grads(flat, batch, "a2c", spec)
+    net = gu.GpuNet(A, "pv", flat)
+    out = net.forward(batch["obs"])
+    gu.tol_check(out["logits"], ref["cache"]["logits"], "logits")
+    gu.tol_check(out["value"], ref["cache"]["value"], "value")
+    np.testing.assert_allclose(out["probs"].sum(axis=1), 1.0, atol=1e-5)
+    dW, loss = net.train(batch, "a2c")
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+    if A == 1:
+        assert abs(loss[3]) < 1e-6 and abs(loss[1]) < 1e-6      # one action: no entropy, log pi = 0
+
+
+@pytest.mark.parametrize("A,atoms,vmin,vmax", [(3, 21, -5.0, 5.0), (1, 2, 0.0, 1.0), (18, 64, -10.0, 10.0)])
+def test_c51_other_supports(gu, A, atoms, vmin, vmax):
+    """Categorical head with other action counts, atom counts (2 and the maximum 64) and supports."""
+    B = 12
+    flat = wl.he_normal_params(A, "c51", 2200 + atoms, num_atoms=atoms, bias_std=0.1)
+    tflat = wl.he_normal_params(A, "c51", 3200 + atoms, num_atoms=atoms, bias_std=0.1)
+    r = np.random.default_rng(atoms)
+    obs, nxt = wl.rect_frames(B, 1400 + atoms, with_next=True)
+    batch = dict(obs=obs, next_obs=nxt, action=r.integers(0, A, size=B).astype(np.int32),
+                 reward=r.integers(-1, 2, size=B).astype(np.float32), done=(r.random(B) < 0.3).astype(np.uint8))
+    spec = orc.NetSpec(A, "c51", num_atoms=atoms)
+    hyper = orc.Hyper(v_min=vmin, v_max=vmax, gamma=0.9)
+    ref = orc.train_step_grads(flat, batch, "c51", spec, hyper=hyper, flat_target_params=tflat)
+    net = gu.GpuNet(A, "c51", flat, num_atoms=atoms, v_min=vmin, v_max=vmax, gamma=0.9)
+    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    got, want = wl.split_params(dW, A, "c51", atoms), wl.split_params(ref["flat"], A, "c51", atoms)
+    for name in want:
+        gu.tol_check(got[name], want[name], name)
+    gu.tol_check(loss[:1], np.array([ref["loss"]["total"]]), "loss")
+
+
+def test_black_frames_exact_zero_preactivations(gu):
+    """All-black frames with zero biases: conv1 pre-activations are exactly 0 and the ReLU
+    derivative there is 0, so nothing reaches conv1's parameters (and the oracle agrees)."""
+    A, B = 6, 5
+    flat = wl.he_normal_params(A, "pv", 2300)
+    r = np.random.default_rng(5)
+    batch = dict(obs=np.zeros((B, 4, 84, 84), dtype=np.uint8), action=r.integers(0, A, size=B).astype(np.int32),
+                 adv=r.standard_normal(B).astype(np.float32), ret=r.standard_normal(B).astype(np.float32))
+    spec = orc.NetSpec(A, "pv")
+    ref = orc.train_step_grads(flat, batch, "a2c", spec)
+    dW, loss = gu.GpuNet(A, "pv", flat).train(batch, "a2c")
+    got = gu.per_tensor(dW, A, "pv")
+    assert (got["conv1.W"] == 0).all() and (got["conv1.b"] == 0).all()
+    assert (ref["grads"]["conv1.W"] == 0).all()
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+
+
+def test_saturated_frames_and_large_batch_tail(gu):
+    """All-255 frames (largest pixel sums) and a batch that leaves ragged tails in every kernel."""
+    A, B = 18, 259
+    flat = wl.he_normal_params(A, "pv", 2301, bias_std=0.05)
+    obs = np.full((B, 4, 84, 84), 255, dtype=np.uint8)
+    obs[1::2] = wl.uniform_frames((B + 1) // 2, 1501)[: B // 2 + B % 2][: len(obs[1::2])]
+    ref, _ = _oracle_forward(flat, obs, A, "pv")
+    out = gu.GpuNet(A, "pv", flat).forward(obs)
+    gu.tol_check(out["logits"], ref["logits"], "logits")
+    gu.tol_check(out["value"], ref["value"], "value")
