@@ -48,6 +48,20 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def measured_traffic(kernel, B):
+    """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by what the same counter reads for a plain copy of known size); None if it covers another batch."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "a2c_b2048_traffic.json")
+    try:
+        with open(path) as f:
+            prof = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if prof.get("batch") != B:
+        return None
+    return prof.get("hbm_bytes_per_launch", {}).get(kernel)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +167,7 @@ def main():
         achieved = dom_flops / dom_s / 1e12
         roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    roofline["traffic"] = measured_traffic(dominant, B)
     roofline["avg_launch_us"] = round(avg_ms[dominant] * 1e3, 2)
     roofline["algorithmic_bytes_per_launch"] = dom_bytes
     roofline["algorithmic_flops_per_launch"] = dom_flops
