@@ -134,6 +134,47 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                          int loss_kind, float *dW, float *loss,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- Parameter update rules (appendix "Update Rule for Multi-Step Asynchronous Adam"; RMSProp as named in
+ * appendix "Experiment Details" and in the appendix on update rules) ----
+ * All arrays are device fp32 vectors of n entries, 16-byte aligned, updated in place; g is read only.
+ * Arithmetic is fp32; the step-count dependent scalars are formed on the host in fp64.
+ * Optional repack: if w_packed is not NULL, cfg must describe the network whose flat parameter vector theta
+ * is (n == arn_param_count(cfg), else ARN_ESHAPE) and the packed copy is rewritten from the new theta on
+ * the same stream, which makes a separate arn_weights_prepare call unnecessary.  With w_packed == NULL, cfg
+ * is ignored and n is arbitrary (>= 1).
+ * Errors: ARN_EINVAL for null/misaligned pointers, n == 0, t < 1, a decay outside [0,1), eps < 0. */
+
+/* RMSProp without momentum, squared gradients accumulated directly:
+ *   accu <- rho*accu + (1-rho)*g^2 ;  theta <- theta - lr*g / sqrt(accu + eps)      (eps inside the root)
+ * accu starts at zero (the caller clears it).  eps = 0 with accu = 0 and g = 0 gives 0/0 = NaN, as the
+ * formula does. */
+int arn_rmsprop_update(size_t n, float *theta, const float *g, float *accu, float lr, float rho, float eps,
+                       const arn_config *cfg, void *w_packed, void *stream);
+
+/* Adam, first block of equations of the appendix, with t the step count AFTER the increment (1 on the first
+ * call; the caller keeps it):
+ *   a = r*sqrt(1-beta2^t)/(1-beta1^t);  m <- beta1*m + (1-beta1)*g;  v <- beta2*v + (1-beta2)*g^2;
+ *   s = a*m/(sqrt(v) + eps);  theta <- theta - s.       m and v start at zero. */
+int arn_adam_update(size_t n, float *theta, const float *g, float *m, float *v, int64_t t, float r, float beta1,
+                    float beta2, float eps, const arn_config *cfg, void *w_packed, void *stream);
+
+/* Local step of the multi-step asynchronous rule: the Adam step above on the learner's own theta, m, v plus
+ * the second block of equations:  a_g <- beta1*a_g + g;  a_g2 <- beta2*a_g2 + g^2;  a_s <- a_s + s.
+ * The accumulators start at zero. */
+int arn_async_adam_local_step(size_t n, float *theta, const float *g, float *m, float *v, float *a_g, float *a_g2,
+                              float *a_s, int64_t t, float r, float beta1, float beta2, float eps,
+                              const arn_config *cfg, void *w_packed, void *stream);
+
+/* Merge into the central values (third block of equations), n_local = local steps since the last merge:
+ *   theta, theta_c <- theta_c - a_s;   m, m_c <- beta1^n_local*m_c + (1-beta1)*a_g;
+ *   v, v_c <- beta2^n_local*v_c + (1-beta2)*a_g2;   a_g, a_g2, a_s <- 0.
+ * The central arrays must be distinct from the local ones (ARN_EINVAL otherwise).  The call does not
+ * serialise learners: two merges into the same central arrays that overlap in time race; order them on one
+ * stream or with events.  The optional repack is of the learner's (new) theta. */
+int arn_async_adam_merge(size_t n, float *theta_c, float *m_c, float *v_c, float *theta, float *m, float *v,
+                         float *a_g, float *a_g2, float *a_s, int n_local, float beta1, float beta2,
+                         const arn_config *cfg, void *w_packed, void *stream);
+
 /* Optional instrumentation for benchmarks (not part of the paper's method).
  * While enabled, every kernel launch made by the calls above is bracketed by a
  * pair of HIP events on the caller's stream.  arn_profile_collect waits for the

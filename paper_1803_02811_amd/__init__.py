@@ -6,10 +6,12 @@ the first call does, and fails loudly if it has not been built.
 """
 from .binding import (ARN_HEAD_C51, ARN_HEAD_PV, ARN_LOSS_A2C, ARN_LOSS_C51, ARN_LOSS_PPO, ARN_MODE_FORWARD,
                       ARN_MODE_TRAIN, ArnError, Config, lib_path, load_library, packed_bytes, param_count,
-                      policy_forward, profile_collect, profile_enable, status_string, train_step_grads, weights_prepare, workspace_bytes)
+                      policy_forward, profile_collect, profile_enable, status_string, train_step_grads, weights_prepare,
+                      workspace_bytes, rmsprop_update, adam_update, async_adam_local_step, async_adam_merge)
 
 __all__ = [
     "ARN_HEAD_C51", "ARN_HEAD_PV", "ARN_LOSS_A2C", "ARN_LOSS_C51", "ARN_LOSS_PPO", "ARN_MODE_FORWARD",
     "ARN_MODE_TRAIN", "ArnError", "Config", "lib_path", "load_library", "packed_bytes", "param_count",
-    "policy_forward", "profile_collect", "profile_enable", "status_string", "train_step_grads", "weights_prepare", "workspace_bytes",
+    "policy_forward", "profile_collect", "profile_enable", "status_string", "train_step_grads", "weights_prepare",
+    "workspace_bytes", "rmsprop_update", "adam_update", "async_adam_local_step", "async_adam_merge",
 ]

@@ -66,6 +66,15 @@ def load_library():
         lib.arn_train_step_grads.restype = ctypes.c_int
         lib.arn_train_step_grads.argtypes = [cp, vp, ctypes.POINTER(_Batch), ctypes.c_int, ctypes.c_int, vp, vp, vp,
                                              ctypes.c_size_t, vp]
+        f, i64, sz = ctypes.c_float, ctypes.c_int64, ctypes.c_size_t
+        lib.arn_rmsprop_update.restype = ctypes.c_int
+        lib.arn_rmsprop_update.argtypes = [sz, vp, vp, vp, f, f, f, cp, vp, vp]
+        lib.arn_adam_update.restype = ctypes.c_int
+        lib.arn_adam_update.argtypes = [sz, vp, vp, vp, vp, i64, f, f, f, f, cp, vp, vp]
+        lib.arn_async_adam_local_step.restype = ctypes.c_int
+        lib.arn_async_adam_local_step.argtypes = [sz, vp, vp, vp, vp, vp, vp, vp, i64, f, f, f, f, cp, vp, vp]
+        lib.arn_async_adam_merge.restype = ctypes.c_int
+        lib.arn_async_adam_merge.argtypes = [sz, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, f, f, cp, vp, vp]
         lib.arn_profile_enable.restype = ctypes.c_int
         lib.arn_profile_enable.argtypes = [ctypes.c_int]
         lib.arn_profile_collect.restype = ctypes.c_int
@@ -127,6 +136,38 @@ def train_step_grads(cfg: Config, w_packed, batch: dict, loss_kind, dW, loss, *,
     _check(load_library().arn_train_step_grads(
         ctypes.byref(cfg), _ptr(w_packed), ctypes.byref(b), B, kind, _ptr(dW), _ptr(loss), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)), "arn_train_step_grads")
+
+
+def _cfg_ref(cfg):
+    return None if cfg is None else ctypes.byref(cfg)
+
+
+def rmsprop_update(theta, g, accu, *, lr, rho, eps, cfg: Optional[Config] = None, w_packed=None, stream=None) -> None:
+    _check(load_library().arn_rmsprop_update(
+        theta.numel(), _ptr(theta), _ptr(g), _ptr(accu), lr, rho, eps, _cfg_ref(cfg), _ptr(w_packed),
+        _stream(stream)), "arn_rmsprop_update")
+
+
+def adam_update(theta, g, m, v, *, t, r, beta1, beta2, eps, cfg: Optional[Config] = None, w_packed=None,
+                stream=None) -> None:
+    _check(load_library().arn_adam_update(
+        theta.numel(), _ptr(theta), _ptr(g), _ptr(m), _ptr(v), int(t), r, beta1, beta2, eps, _cfg_ref(cfg),
+        _ptr(w_packed), _stream(stream)), "arn_adam_update")
+
+
+def async_adam_local_step(theta, g, m, v, a_g, a_g2, a_s, *, t, r, beta1, beta2, eps, cfg: Optional[Config] = None,
+                          w_packed=None, stream=None) -> None:
+    _check(load_library().arn_async_adam_local_step(
+        theta.numel(), _ptr(theta), _ptr(g), _ptr(m), _ptr(v), _ptr(a_g), _ptr(a_g2), _ptr(a_s), int(t), r, beta1,
+        beta2, eps, _cfg_ref(cfg), _ptr(w_packed), _stream(stream)), "arn_async_adam_local_step")
+
+
+def async_adam_merge(theta_c, m_c, v_c, theta, m, v, a_g, a_g2, a_s, *, n_local, beta1, beta2,
+                     cfg: Optional[Config] = None, w_packed=None, stream=None) -> None:
+    _check(load_library().arn_async_adam_merge(
+        theta.numel(), _ptr(theta_c), _ptr(m_c), _ptr(v_c), _ptr(theta), _ptr(m), _ptr(v), _ptr(a_g), _ptr(a_g2),
+        _ptr(a_s), int(n_local), beta1, beta2, _cfg_ref(cfg), _ptr(w_packed), _stream(stream)),
+        "arn_async_adam_merge")
 
 
 def profile_enable(on: bool) -> None:

@@ -2,6 +2,7 @@
 // then a fixed sequence of kernel launches on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -13,6 +14,7 @@
 #include "arn_resident.h"
 #include "arn_resident_conv.h"
 #include "arn_small_kernels.h"
+#include "arn_update.h"
 
 using namespace arn;
 
@@ -218,12 +220,29 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
     }
 }
 
-MapHeadRow head_rows(const Dims &d, const ParamOffsets &po) {
-    MapHeadRow h;
-    h.wh = (long)po.wh; h.wv = (long)po.wv; h.bh = (long)po.bh; h.bv = (long)po.bv;
-    h.A = d.A; h.NH = d.NH; h.pv = d.head == ARN_HEAD_PV;
-    return h;
+// Lays the flat fp32 parameters out in every packed form, one launch.
+void launch_pack_all(const Dims &d, const float *w_fp32, void *w_packed, hipStream_t s) {
+    ProfScope ps("pack_all", s);
+    const PackPlan pl = make_pack_plan(d, w_packed);
+    hipLaunchKernelGGL(pack_all_kernel, dim3(pl.blocks), dim3(256), 0, s, pl, w_fp32);
 }
+
+// Shared argument checks of the update entry points.  Returns ARN_OK and fills *d_out when a repack is asked for.
+int check_update(size_t n, const arn_config *cfg, const void *w_packed, bool *repack, Dims *d_out) {
+    if (n == 0 || n > ((size_t)1 << 40)) return ARN_EINVAL;
+    *repack = w_packed != nullptr;
+    if (*repack) {
+        if (!cfg) return ARN_EINVAL;
+        if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+        *d_out = make_dims(cfg);
+        if (!d_out->ok) return ARN_ESHAPE;
+        if (n != param_offsets(*d_out).total) return ARN_ESHAPE;
+        if (!aligned(w_packed, 256)) return ARN_EINVAL;
+    }
+    return ARN_OK;
+}
+inline bool unit_interval(float b) { return b >= 0.f && b < 1.f; }
+inline unsigned update_blocks(size_t n) { return (unsigned)((n + 1023) / 1024); }
 
 }  // namespace
 
@@ -266,24 +285,7 @@ int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_pack
     if (!aligned(w_fp32, 16) || !aligned(w_packed, 256)) return ARN_EINVAL;
     if (int e = check_arch()) return e;
     hipStream_t s = (hipStream_t)stream;
-    const ParamOffsets po = param_offsets(d);
-    const PackedOffsets o = packed_offsets(d);
-    char *b = (char *)w_packed;
-    const MapHeadRow hr = head_rows(d, po);
-    launch_pack(MapIdentity{(long)po.w1}, w_fp32, b + o.w1, b + o.w1l, (long)C1 * KW1, s);
-    launch_pack(MapConvFwd<C1, K2>{(long)po.w2}, w_fp32, b + o.w2, b + o.w2l, (long)C2 * KW2, s);
-    launch_pack(MapConvFwd<C2, K3>{(long)po.w3}, w_fp32, b + o.w3, b + o.w3l, (long)C3 * KW3, s);
-    launch_pack(MapFcFwd{(long)po.wfc}, w_fp32, b + o.wfc, b + o.wfcl, (long)HID * FEAT, s);
-    launch_pack(MapHeadFwd{hr}, w_fp32, b + o.wh, b + o.whl, (long)d.NHP * HID, s);
-    launch_pack_f32(MapIdentity{(long)po.b1}, w_fp32, b + o.b1, C1, s);
-    launch_pack_f32(MapIdentity{(long)po.b2}, w_fp32, b + o.b2, C2, s);
-    launch_pack_f32(MapIdentity{(long)po.b3}, w_fp32, b + o.b3, C3, s);
-    launch_pack_f32(MapIdentity{(long)po.bfc}, w_fp32, b + o.bfc, HID, s);
-    launch_pack_f32(MapHeadBias{hr}, w_fp32, b + o.bh, d.NHP, s);
-    launch_pack(MapHeadDgrad{hr, d.NHP}, w_fp32, b + o.whd, nullptr, (long)HID * d.NHP, s);
-    launch_pack(MapFcDgrad{(long)po.wfc}, w_fp32, b + o.wfcd, nullptr, (long)FEAT * HID, s);
-    launch_pack(MapConv3Dgrad{(long)po.w3}, w_fp32, b + o.w3d, nullptr, (long)C2 * KW3, s);
-    launch_pack(MapConv2Dgrad{(long)po.w2}, w_fp32, b + o.w2d, nullptr, (long)4 * C1 * 256, s);
+    launch_pack_all(d, w_fp32, w_packed, s);
     return launched();
 }
 
@@ -468,6 +470,102 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         hipEventRecord(ss->join, s2);
         hipStreamWaitEvent(s, ss->join, 0);
     }
+    return launched();
+}
+
+int arn_rmsprop_update(size_t n, float *theta, const float *g, float *accu, float lr, float rho, float eps,
+                       const arn_config *cfg, void *w_packed, void *stream) {
+    bool repack;
+    Dims d;
+    if (int e = check_update(n, cfg, w_packed, &repack, &d)) return e;
+    if (!aligned(theta, 16) || !aligned(g, 16) || !aligned(accu, 16)) return ARN_EINVAL;
+    if (!unit_interval(rho) || !(eps >= 0.f) || !(lr == lr)) return ARN_EINVAL;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    UpdateArgs p = {};
+    p.theta = theta; p.g = g; p.v = accu; p.n = (long)n; p.a = lr; p.beta2 = rho; p.eps = eps;
+    {
+        ProfScope ps("rmsprop", s);
+        hipLaunchKernelGGL(update_kernel<RULE_RMSPROP>, dim3(update_blocks(n)), dim3(256), 0, s, p);
+    }
+    if (repack) launch_pack_all(d, theta, w_packed, s);
+    return launched();
+}
+
+namespace {
+// a = r sqrt(1 - beta2^t) / (1 - beta1^t), formed in fp64
+float adam_scale(int64_t t, float r, float beta1, float beta2) {
+    const double c1 = 1.0 - pow((double)beta1, (double)t), c2 = 1.0 - pow((double)beta2, (double)t);
+    return (float)((double)r * sqrt(c2) / c1);
+}
+}  // namespace
+
+int arn_adam_update(size_t n, float *theta, const float *g, float *m, float *v, int64_t t, float r, float beta1,
+                    float beta2, float eps, const arn_config *cfg, void *w_packed, void *stream) {
+    bool repack;
+    Dims d;
+    if (int e = check_update(n, cfg, w_packed, &repack, &d)) return e;
+    if (!aligned(theta, 16) || !aligned(g, 16) || !aligned(m, 16) || !aligned(v, 16)) return ARN_EINVAL;
+    if (t < 1 || !unit_interval(beta1) || !unit_interval(beta2) || !(eps >= 0.f) || !(r == r)) return ARN_EINVAL;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    UpdateArgs p = {};
+    p.theta = theta; p.g = g; p.m = m; p.v = v; p.n = (long)n;
+    p.a = adam_scale(t, r, beta1, beta2); p.beta1 = beta1; p.beta2 = beta2; p.eps = eps;
+    {
+        ProfScope ps("adam", s);
+        hipLaunchKernelGGL(update_kernel<RULE_ADAM>, dim3(update_blocks(n)), dim3(256), 0, s, p);
+    }
+    if (repack) launch_pack_all(d, theta, w_packed, s);
+    return launched();
+}
+
+int arn_async_adam_local_step(size_t n, float *theta, const float *g, float *m, float *v, float *a_g, float *a_g2,
+                              float *a_s, int64_t t, float r, float beta1, float beta2, float eps,
+                              const arn_config *cfg, void *w_packed, void *stream) {
+    bool repack;
+    Dims d;
+    if (int e = check_update(n, cfg, w_packed, &repack, &d)) return e;
+    if (!aligned(theta, 16) || !aligned(g, 16) || !aligned(m, 16) || !aligned(v, 16) || !aligned(a_g, 16) ||
+        !aligned(a_g2, 16) || !aligned(a_s, 16))
+        return ARN_EINVAL;
+    if (t < 1 || !unit_interval(beta1) || !unit_interval(beta2) || !(eps >= 0.f) || !(r == r)) return ARN_EINVAL;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    UpdateArgs p = {};
+    p.theta = theta; p.g = g; p.m = m; p.v = v; p.a_g = a_g; p.a_g2 = a_g2; p.a_s = a_s; p.n = (long)n;
+    p.a = adam_scale(t, r, beta1, beta2); p.beta1 = beta1; p.beta2 = beta2; p.eps = eps;
+    {
+        ProfScope ps("adam_local", s);
+        hipLaunchKernelGGL(update_kernel<RULE_ADAM_LOCAL>, dim3(update_blocks(n)), dim3(256), 0, s, p);
+    }
+    if (repack) launch_pack_all(d, theta, w_packed, s);
+    return launched();
+}
+
+int arn_async_adam_merge(size_t n, float *theta_c, float *m_c, float *v_c, float *theta, float *m, float *v,
+                         float *a_g, float *a_g2, float *a_s, int n_local, float beta1, float beta2,
+                         const arn_config *cfg, void *w_packed, void *stream) {
+    bool repack;
+    Dims d;
+    if (int e = check_update(n, cfg, w_packed, &repack, &d)) return e;
+    if (!aligned(theta_c, 16) || !aligned(m_c, 16) || !aligned(v_c, 16) || !aligned(theta, 16) || !aligned(m, 16) ||
+        !aligned(v, 16) || !aligned(a_g, 16) || !aligned(a_g2, 16) || !aligned(a_s, 16))
+        return ARN_EINVAL;
+    if (theta_c == theta || m_c == m || v_c == v) return ARN_EINVAL;
+    if (n_local < 0 || !unit_interval(beta1) || !unit_interval(beta2)) return ARN_EINVAL;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    UpdateArgs p = {};
+    p.theta_c = theta_c; p.m_c = m_c; p.v_c = v_c; p.theta = theta; p.m = m; p.v = v;
+    p.a_g = a_g; p.a_g2 = a_g2; p.a_s = a_s; p.n = (long)n; p.beta1 = beta1; p.beta2 = beta2;
+    p.beta1_n = (float)pow((double)beta1, (double)n_local);
+    p.beta2_n = (float)pow((double)beta2, (double)n_local);
+    {
+        ProfScope ps("adam_merge", s);
+        hipLaunchKernelGGL(merge_kernel, dim3(update_blocks(n)), dim3(256), 0, s, p);
+    }
+    if (repack) launch_pack_all(d, theta, w_packed, s);
     return launched();
 }
 

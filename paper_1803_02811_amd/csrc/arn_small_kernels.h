@@ -67,6 +67,12 @@ struct MapHeadRow {    // head row r of the packed head -> offset of its weight 
         return r < NH ? bh + r : -1;
     }
 };
+inline MapHeadRow head_rows(const Dims &d, const ParamOffsets &po) {
+    MapHeadRow h;
+    h.wh = (long)po.wh; h.wv = (long)po.wv; h.bh = (long)po.bh; h.bv = (long)po.bv;
+    h.A = d.A; h.NH = d.NH; h.pv = d.head == ARN_HEAD_PV;
+    return h;
+}
 struct MapHeadFwd {    // packed [r][j]
     MapHeadRow h;
     __device__ long operator()(long i) const {

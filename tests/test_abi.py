@@ -83,6 +83,30 @@ def test_argument_errors_are_reported_on_the_host(lib):
     assert "workspace" in arn.status_string(EWORKSPACE)
 
 
+def test_update_rule_argument_errors(lib):
+    cfg = arn.Config(18, arn.ARN_HEAD_PV)
+    c = ctypes.byref(cfg)
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    EINVAL, ESHAPE = -1, -2
+    n = arn.param_count(cfg)
+    assert lib.arn_rmsprop_update(0, fake, fake, fake, 1e-3, 0.9, 1e-6, None, None, None) == EINVAL
+    assert lib.arn_rmsprop_update(8, fake, odd, fake, 1e-3, 0.9, 1e-6, None, None, None) == EINVAL
+    assert lib.arn_rmsprop_update(8, fake, fake, fake, 1e-3, 1.0, 1e-6, None, None, None) == EINVAL   # rho = 1
+    assert lib.arn_rmsprop_update(8, fake, fake, fake, 1e-3, 0.9, -1.0, None, None, None) == EINVAL
+    assert lib.arn_rmsprop_update(n - 1, fake, fake, fake, 1e-3, 0.9, 1e-6, c, fake, None) == ESHAPE  # repack needs n
+    assert lib.arn_rmsprop_update(n, fake, fake, fake, 1e-3, 0.9, 1e-6, None, fake, None) == EINVAL   # ... and cfg
+    assert lib.arn_adam_update(8, fake, fake, fake, fake, 0, 1e-3, 0.9, 0.999, 1e-5, None, None, None) == EINVAL
+    assert lib.arn_adam_update(8, fake, fake, None, fake, 1, 1e-3, 0.9, 0.999, 1e-5, None, None, None) == EINVAL
+    assert lib.arn_adam_update(8, fake, fake, fake, fake, 1, 1e-3, 1.5, 0.999, 1e-5, None, None, None) == EINVAL
+    assert lib.arn_async_adam_local_step(8, fake, fake, fake, fake, fake, None, fake, 1, 1e-3, 0.9, 0.999, 1e-5,
+                                         None, None, None) == EINVAL
+    other = ctypes.c_void_p(0x2000)
+    assert lib.arn_async_adam_merge(8, fake, fake, fake, fake, other, other, other, other, other, 1, 0.9, 0.999,
+                                    None, None, None) == EINVAL      # theta_c aliases theta
+    assert lib.arn_async_adam_merge(8, fake, fake, fake, other, other, other, other, other, other, -1, 0.9, 0.999,
+                                    None, None, None) == EINVAL
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     """No CPU fallback: a missing libarn.so is an error, not a silent detour."""
     monkeypatch.setenv("ARN_LIBRARY", str(tmp_path / "nope.so"))

@@ -154,3 +154,17 @@ def c51_batch(k: int = 5, B: int | None = None) -> dict:
             "action": g.integers(0, w["A"], size=B).astype(np.int32),
             "reward": g.integers(-1, 2, size=B).astype(np.float32),
             "done": (g.random(B) < 0.01).astype(np.uint8)}
+
+
+def update_rule_inputs(n: int, steps: int, seed: int) -> dict:
+    """Inputs for the parameter-update rules: a parameter vector and `steps` gradient vectors, all exactly
+    representable in fp32.  Gradient magnitudes spread over five decades per entry, as gradients of a deep
+    network do across layers; a few entries are exactly zero (dead units).  Seeds: 4000 + seed."""
+    r = rng(4000 + seed)
+    theta = (r.standard_normal(n) * 0.05).astype(np.float32)
+    grads = []
+    for _ in range(steps):
+        g = r.standard_normal(n) * 10.0 ** r.uniform(-6.0, -1.0, size=n)
+        g[r.random(n) < 0.01] = 0.0
+        grads.append(g.astype(np.float32))
+    return dict(theta=theta, grads=grads)
