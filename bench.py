@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--update-rules", action="store_true",
+                    help="report the parameter-update kernels instead (secondary line)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
                     help="3 (default) = the headline A2C step at B=2048; 1, 2 = inference; 4 = PPO; 5 = C51")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -97,6 +99,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": n, "copies": 5}))
+        return
+    if args.update_rules:
+        update_rules_report(args, arn, wl, np, torch)
         return
     if args.workload != 3:
         other_workload(args, arn, wl, np, torch)
@@ -202,6 +207,90 @@ def main():
                                "sample": "first %d samples of the same batch, fwd+loss+bwd, %d repetitions, %.1f s"
                                          % (n, reps, t_total)}
     print(json.dumps(out))
+
+
+UPDATE_BYTES = {"rmsprop": 20, "adam": 28, "adam_local": 52, "adam_merge": 60}   # fp32 arrays read + written per parameter
+
+
+def update_rules_report(args, arn, wl, np, torch):
+    """Secondary line: the update kernels on the A=18 policy/value parameter vector (what one learner
+    iteration runs) and on a 64 Mi-entry vector (HBM-resident, shows the streaming rate), plus the whole
+    learner iteration gradient + Adam update + re-pack at B=2048."""
+    dev = "cuda:0"
+    cfg = arn.Config(18, arn.ARN_HEAD_PV)
+    stream = torch.cuda.current_stream()
+    report = {}
+    for label, n in (("params_a18", arn.param_count(cfg)), ("64Mi", 64 << 20)):
+        inp = wl.update_rule_inputs(min(n, 1 << 20), 1, seed=1)
+        rep = (n + inp["theta"].size - 1) // inp["theta"].size
+        th = torch.from_numpy(np.tile(inp["theta"], rep)[:n].copy()).to(dev)
+        g = torch.from_numpy(np.tile(inp["grads"][0], rep)[:n].copy()).to(dev)
+        st = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(8)]
+        packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev) if label == "params_a18" else None
+        calls = {
+            "rmsprop": lambda: arn.rmsprop_update(th, g, st[0], lr=7e-4, rho=0.99, eps=1e-6, stream=stream),
+            "adam": lambda: arn.adam_update(th, g, st[0], st[1], t=3, r=4.2e-4, beta1=0.9, beta2=0.999, eps=4e-5,
+                                            stream=stream),
+            "adam_local": lambda: arn.async_adam_local_step(th, g, st[0], st[1], st[2], st[3], st[4], t=3, r=4.2e-4,
+                                                            beta1=0.9, beta2=0.999, eps=4e-5, stream=stream),
+            "adam_merge": lambda: arn.async_adam_merge(st[5], st[6], st[7], th, st[0], st[1], st[2], st[3], st[4],
+                                                       n_local=2, beta1=0.9, beta2=0.999, stream=stream),
+        }
+        if packed is not None:
+            calls["adam+pack_all"] = lambda: arn.adam_update(th, g, st[0], st[1], t=3, r=4.2e-4, beta1=0.9,
+                                                             beta2=0.999, eps=4e-5, cfg=cfg, w_packed=packed,
+                                                             stream=stream)
+        arn.profile_enable(True)
+        for name, fn in calls.items():
+            for _ in range(args.warmup + args.steps):
+                fn()
+        torch.cuda.synchronize()
+        recs = arn.profile_collect(cap=16 * (args.warmup + args.steps) + 64)
+        arn.profile_enable(False)
+        per = {}
+        for name, ms in recs:
+            per.setdefault(name, []).append(ms)
+        rows = {}
+        for name, v in per.items():
+            us = 1e3 * float(np.mean(v[len(v) // 4:]))
+            rows[name] = {"us": round(us, 2)}
+            if name in UPDATE_BYTES:
+                gbs = UPDATE_BYTES[name] * n / (us * 1e-6) / 1e9
+                rows[name].update({"GB/s": round(gbs, 1), "hbm_frac": round(gbs / PEAK_HBM_GBS, 4)})
+        report[label] = {"n": n, "kernels": rows}
+    # whole learner iteration
+    k, B = 3, args.batch or 2048
+    flat = wl.he_normal_params(18, "pv", 2000 + k)
+    th = torch.from_numpy(flat).to(dev)
+    packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+    arn.weights_prepare(cfg, th, packed)
+    batch = {nm: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for nm, v in wl.actor_critic_batch(k, B=B).items()}
+    ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
+    dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
+    m, v = (torch.zeros_like(dW) for _ in range(2))
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+
+    def iteration(t):
+        arn.train_step_grads(cfg, packed, batch, "a2c", dW, loss, workspace=ws, stream=stream)
+        arn.adam_update(th, dW, m, v, t=t, r=1e-5, beta1=0.9, beta2=0.999, eps=0.01 / B, cfg=cfg, w_packed=packed,
+                        stream=stream)
+
+    for t in range(1, args.warmup + 1):
+        iteration(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup + 1, args.warmup + args.steps + 1):
+        iteration(t)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    print(json.dumps({
+        "metric": "Nature-CNN samples/sec (gradient + Adam update + re-pack) at B=%d on 1 GPU" % B,
+        "value": round(B / sec, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "learner iteration a2c_b%d + update rules" % B, "global_batch": B,
+                   "parallelism": "single-gpu"},
+        "update_kernels": report, "loss_finite": bool(torch.isfinite(loss).all().item())}))
 
 
 def other_workload(args, arn, wl, np, torch):

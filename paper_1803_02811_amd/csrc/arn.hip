@@ -125,16 +125,6 @@ void launch_reduce(const char *name, const F &f, const float *part, float *dW, l
                        wcount, splits, wscale, ng);
 }
 
-template <class F>
-void launch_pack(const F &f, const float *w, void *out, void *out_lo, long n, hipStream_t s) {
-    hipLaunchKernelGGL(pack_bf16_kernel<F>, dim3(cdiv(n, 256)), dim3(256), 0, s, f, w, (__bf16 *)out,
-                       (__bf16 *)out_lo, n);
-}
-template <class F>
-void launch_pack_f32(const F &f, const float *w, void *out, long n, hipStream_t s) {
-    hipLaunchKernelGGL(pack_f32_kernel<F>, dim3(cdiv(n, 256)), dim3(256), 0, s, f, w, (float *)out, n);
-}
-
 struct Packed {   // typed views of the packed blob
     const __bf16 *w1, *w2, *w3, *wfc, *wh, *whd, *wfcd, *w3d, *w2d;
     const __bf16 *w1l, *w2l, *w3l, *wfcl, *whl;

@@ -11,29 +11,10 @@
 namespace arn {
 
 // ----------------------------- weight packing ------------------------------
-// One launch per packed region; F maps a packed element index to the index of
-// its source in the flat fp32 vector (or -1 for padding).
-// With `out_lo`, also writes the residual lo = bf16(w - hi) used by the
-// three-product inference path.
-template <class F>
-__global__ void pack_bf16_kernel(F f, const float *__restrict__ w, __bf16 *__restrict__ out,
-                                 __bf16 *__restrict__ out_lo, long n) {
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const long s = f(i);
-    const float v = s >= 0 ? w[s] : 0.f;
-    const __bf16 hi = (__bf16)v;
-    out[i] = hi;
-    if (out_lo) out_lo[i] = (__bf16)(v - (float)hi);
-}
-template <class F>
-__global__ void pack_f32_kernel(F f, const float *__restrict__ w, float *__restrict__ out, long n) {
-    const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const long s = f(i);
-    out[i] = s >= 0 ? w[s] : 0.f;
-}
-
+// F maps a packed element index to the index of its source in the flat fp32
+// vector (or -1 for padding); pack_all_kernel applies the maps, writing
+// hi = bf16(w) and, for forward layouts, the residual lo = bf16(w - hi) used by
+// the three-product forward path.
 struct MapIdentity {   // conv1: canonical order is already [co][ci*64+ky*8+kx]
     long off;
     __device__ long operator()(long i) const { return off + i; }
