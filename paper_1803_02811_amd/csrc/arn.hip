@@ -11,6 +11,7 @@
 #include "arn_gemm.h"
 #include "arn_layout.h"
 #include "arn_problems.h"
+#include "arn_pv_head.h"
 #include "arn_resident.h"
 #include "arn_resident_conv.h"
 #include "arn_small_kernels.h"
@@ -157,7 +158,7 @@ Packed view_packed(const void *blob, const Dims &d) {
 }
 
 // trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits [B][NH].
-// PV: the head leaves fp32 partial sums in the workspace (o.hp) for the consumer to finish.
+// PV: stops after the fc GEMM, whose fp32 partial sums (o.fcp) the fused head kernel consumes.
 // masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on the online weights).
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                       float *z_out, bool masks, hipStream_t s) {
@@ -188,26 +189,30 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         FcFwd p;
         p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
         p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
+        p.to_partial = p.ksplit > 1 || d.head == ARN_HEAD_PV;
         split ? launch_nt_split("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s)
               : launch_nt("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s);
-        if (p.ksplit > 1) {
+        if (p.ksplit > 1 && d.head != ARN_HEAD_PV) {
             ProfScope ps("fc_finish", s);
             const long total = (long)B * HID;
             hipLaunchKernelGGL(fc_finish_kernel, dim3(cdiv(total / 4, 256)), dim3(256), 0, s, p.partial, p.ksplit,
                                w.bfc, h, hl, total);
         }
     }
-    if (d.head == ARN_HEAD_PV) {
-        // partial sums only; policy_epilogue_kernel / ac_loss_kernel finish the rows
-        HeadFwdPV p;
-        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.ksplit = HEAD_KSPLIT;
-        p.partial = (float *)(ws + o.hp);
-        launch_nt_split("head_fwd", p, B, 1, HEAD_KSPLIT, s);
-    } else {
+    if (d.head == ARN_HEAD_C51) {
         HeadFwdC51 p;
         p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh; p.z = z_out; p.ZW = d.NH;
         launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s);
     }
+    // policy/value head: the caller launches pv_head_kernel on the fc partial sums
+}
+
+// Arguments of the fused policy/value head kernel that both entry points share.
+PvHeadArgs pv_head_args(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o) {
+    PvHeadArgs p = {};
+    p.partial = (const float *)(ws + o.fcp); p.ks = fc_ksplit(B); p.bfc = w.bfc;
+    p.wh = w.wh; p.whl = w.whl; p.bh = w.bh; p.B = B; p.A = d.A;
+    return p;
 }
 
 // Lays the flat fp32 parameters out in every packed form, one launch.
@@ -298,9 +303,10 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     const Packed w = view_packed(w_packed, d);
     forward_launches(d, w, obs, B, (char *)workspace, o, logits, false, s);
     if (d.head == ARN_HEAD_PV) {
-        ProfScope ps("policy_epilogue", s);
-        hipLaunchKernelGGL(policy_epilogue_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s,
-                           (const float *)((char *)workspace + o.hp), w.bh, B, d.A, logits, value, probs, greedy);
+        ProfScope ps("pv_head", s);
+        PvHeadArgs p = pv_head_args(d, w, B, (char *)workspace, o);
+        p.logits = logits; p.value = value; p.probs = probs; p.greedy = greedy;
+        hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, PVH_ROWS)), dim3(PVH_THREADS), 0, s, p);
     } else if (value || probs || greedy) {
         ProfScope ps("c51_dist", s);
         hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, B, d.A,
@@ -362,16 +368,16 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         ProfScope ps("loss", s);
         hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
                            d.atoms, d.NHP, dz, lossp);
-        hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, 0.f, 0.f, loss);
     } else {
         forward_launches(d, w, batch->obs, B, ws, o, nullptr, true, s);
-        ProfScope ps("loss", s);
-        hipLaunchKernelGGL(ac_loss_kernel, dim3(lblocks), dim3(LOSS_BLOCK), 0, s, (const float *)(ws + o.hp), w.bh,
-                           batch->action, batch->adv, batch->ret, batch->old_logp,
-                           loss_kind == ARN_LOSS_PPO ? 1 : 0, cfg->clip_eps, cfg->value_coef, cfg->entropy_coef, B,
-                           d.A, dz, lossp);
-        hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, lossp, lblocks, B, cfg->value_coef,
-                           cfg->entropy_coef, loss);
+        // fc finish, head, objective, dz and the head's input gradient d(pre_fc) in one kernel
+        ProfScope ps("pv_head", s);
+        PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+        p.action = batch->action; p.adv = batch->adv; p.ret = batch->ret; p.old_logp = batch->old_logp;
+        p.ppo = loss_kind == ARN_LOSS_PPO ? 1 : 0;
+        p.clip_eps = cfg->clip_eps; p.value_coef = cfg->value_coef; p.entropy_coef = cfg->entropy_coef;
+        p.whd = w.whd; p.h = h; p.dz = dz; p.dph = dph; p.lossp = lossp;
+        hipLaunchKernelGGL(pv_head_kernel<true>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
     }
 
     // ---- backward ----
@@ -387,7 +393,14 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         hipStreamWaitEvent(s2, ss->fork[nfork], 0);
         ++nfork;
     };
-    fork();   // dz
+    fork();   // dz (and, for the policy/value head, d(pre_fc))
+    {
+        // the reported loss values are off the critical path: block partial sums are added on the side stream
+        ProfScope ps("loss_finalize", s2);
+        const bool pv = loss_kind != ARN_LOSS_C51;
+        hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s2, lossp, lblocks, B,
+                           pv ? cfg->value_coef : 0.f, pv ? cfg->entropy_coef : 0.f, loss);
+    }
     {
         HeadWgrad p;
         p.in = h; p.M = B; p.N1 = d.NHP; p.dy = dz;
@@ -395,7 +408,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         launch_tn("head_wgrad", p, part, B, d.NHP, HID, sp.hd, s2);
         launch_reduce("head_reduce", UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s2);
     }
-    {
+    if (d.head == ARN_HEAD_C51) {
         HeadDgrad p;
         p.in = dz; p.M = B; p.K = d.NHP; p.w = w.whd; p.h = h; p.out = dph;
         launch_nt("head_dgrad", p, B, HID / HeadDgrad::BN, 1, s);
@@ -406,7 +419,11 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         p.in = a3; p.M = B; p.dy = dph;
         float *part = (float *)(ws + o.pwfc);
         launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s2);
-        launch_reduce("fc_reduce", UnmapFc{(long)po.wfc, (long)po.bfc}, part, dW, (long)HID * FEAT, HID, sp.fc, 1.f, s2);
+        {
+            ProfScope ps("fc_reduce", s2);
+            hipLaunchKernelGGL(fc_reduce_kernel, dim3(HID + 1), dim3(256), 0, s2, part, dW, (long)po.wfc, (long)po.bfc,
+                               sp.fc);
+        }
     }
     {
         FcDgrad p;

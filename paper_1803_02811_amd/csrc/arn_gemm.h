@@ -337,6 +337,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
     constexpr int YROW = YC + 1, XROW = XC + 1;        // padded LDS row, in u32x4
     constexpr int Y_CH = 64 * YC / 256, X_CH = 64 * XC / 256;
     static_assert(TY >= 1 && TX >= 1 && Y_CH >= 1 && X_CH >= 1, "tile shape");
+    static_assert(256 % YC == 0 && (256 / YC) * BN1 * 4 <= 64 * YROW * 16, "bias-gradient scratch");
 
     __shared__ u32x4 sY[64 * YROW];
     __shared__ u32x4 sX[64 * XROW];
@@ -373,7 +374,10 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
         for (int b = 0; b < TX; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-    float bsum = 0.f;
+    // bias gradient (column sums of dY), kept by the workgroups of the first tile column: a thread always
+    // stages the same eight dY columns (256 is a multiple of YC), so it adds what it stages, in fp32
+    float bs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const bool keeps_bias = blockIdx.x == 0;
 
     if (m_begin < m_end) gload(m_begin);
     for (long mt = m_begin; mt < m_end; mt += 64) {
@@ -382,6 +386,11 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
         for (int i = 0; i < Y_CH; ++i) {
             const int c = tid + 256 * i;
             sY[(c / YC) * YROW + c % YC] = ry[i];
+            if (keeps_bias) {
+                const bf16x8 f = as_bf16x8(ry[i]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bs[e] += (float)f[e];
+            }
         }
 #pragma unroll
         for (int i = 0; i < X_CH; ++i) {
@@ -403,12 +412,6 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
                 for (int b = 0; b < TX; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[a], fx[b], acc[a][b], 0, 0, 0);
         }
-        if (blockIdx.x == 0 && tid < BN1) {
-            // column sums of the staged dY rows: bias gradient, summed in row order
-            const __bf16 *col = reinterpret_cast<const __bf16 *>(sY) + tid;
-#pragma unroll 8
-            for (int r = 0; r < 64; ++r) bsum += (float)col[r * YROW * 8];
-        }
     }
 
     float *out = part + (size_t)split * ((size_t)p.N1 * p.KP + p.N1);
@@ -424,7 +427,19 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
                 out[(size_t)n * p.KP + k] = acc[a][b][r];
             }
         }
-    if (blockIdx.x == 0 && tid < BN1) out[(size_t)p.N1 * p.KP + y0 + tid] = bsum;
+    if (keeps_bias) {
+        // the 256/YC threads that share a column add their sums in thread order
+        __syncthreads();
+        float *scr = reinterpret_cast<float *>(sY);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) scr[(tid / YC) * BN1 + (tid % YC) * 8 + e] = bs[e];
+        __syncthreads();
+        if (tid < BN1) {
+            float t = scr[tid];
+            for (int g = 1; g < 256 / YC; ++g) t += scr[g * BN1 + tid];
+            out[(size_t)p.N1 * p.KP + y0 + tid] = t;
+        }
+    }
 }
 
 }  // namespace arn

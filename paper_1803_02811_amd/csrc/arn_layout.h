@@ -159,7 +159,7 @@ inline int fc_ksplit(int B) {
     return ks;
 }
 
-constexpr int LOSS_BLOCK = 64;    // samples per block in the actor-critic loss kernel
+constexpr int LOSS_BLOCK = 16;    // samples per workgroup of the fused policy/value head kernel
 constexpr int HEAD_KSPLIT = 8;    // k ranges of the policy/value head GEMM (one 64-element k-tile each)
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
@@ -193,8 +193,9 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     w.a2l = take(b * P2 * C2 * 2);
     w.a3l = take(b * FEAT * 2);
     w.hl = take(b * HID * 2);
-    w.fcp = take((size_t)(fc_ksplit(B) > 1 ? fc_ksplit(B) : 0) * b * HID * 4);
-    w.hp = take(d.head == ARN_HEAD_PV ? (size_t)HEAD_KSPLIT * b * 32 * 4 : 0);
+    // the fused policy/value head kernel always reads fp32 partials; the categorical path only when k is split
+    w.fcp = take((size_t)(fc_ksplit(B) > 1 || d.head == ARN_HEAD_PV ? fc_ksplit(B) : 0) * b * HID * 4);
+    w.hp = take(0);
     if (mode == ARN_MODE_TRAIN) {
         w.z = take(d.head == ARN_HEAD_PV ? 0 : b * (size_t)d.NH * 4);
         w.zv = 0;

@@ -173,6 +173,7 @@ struct FcFwd : DenseGather<FEAT> {
     static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT, STAGES = 2;
     static constexpr bool ACT_LO = true;
     int ksplit;
+    bool to_partial;     // write fp32 partial sums even with ksplit == 1 (the consumer finishes the layer)
     const __bf16 *w, *w_lo = nullptr;
     const float *bias;
     __bf16 *out, *out_lo = nullptr;
@@ -184,7 +185,7 @@ struct FcFwd : DenseGather<FEAT> {
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {
         if (m >= M) return;
-        if (ksplit > 1) {
+        if (to_partial) {
             *reinterpret_cast<float4 *>(partial + ((size_t)z * M + m) * HID + n) = make_float4(v[0], v[1], v[2], v[3]);
             return;
         }

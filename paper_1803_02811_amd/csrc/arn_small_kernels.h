@@ -136,6 +136,31 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(F f, const float *
         dW[dst] = i < wcount ? t * wscale : t;
     }
 }
+// The fc layer's partials are [n][pos*64 + c] while the canonical weight is [n][c*49 + pos]: one workgroup
+// per output row n adds the splits with contiguous reads, permutes the row in LDS (stride 49 words: no bank
+// conflicts) and writes it out contiguously.  Workgroup HID handles the bias gradient.
+__global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW,
+                                                        long woff, long boff, int splits) {
+    __shared__ float row[FEAT];
+    constexpr long block = (long)HID * FEAT + HID;
+    const int n = blockIdx.x, tid = threadIdx.x;
+    if (n == HID) {
+        for (int j = tid; j < HID; j += 256) {
+            float s = 0.f;
+            for (int k = 0; k < splits; ++k) s += part[(size_t)k * block + (long)HID * FEAT + j];
+            dW[boff + j] = s;
+        }
+        return;
+    }
+    for (int k = tid; k < FEAT; k += 256) {
+        float s = 0.f;
+        for (int q = 0; q < splits; ++q) s += part[(size_t)q * block + (long)n * FEAT + k];
+        row[(k & 63) * P3 + (k >> 6)] = s;
+    }
+    __syncthreads();
+    for (int i = tid; i < FEAT; i += 256) dW[woff + (long)n * FEAT + i] = row[i];
+}
+
 template <int CIN, int KS, int COUT>
 struct UnmapConv {     // partial [co][(ky*KS+kx)*CIN+ci] then [co] bias
     long woff, boff;
@@ -205,156 +230,21 @@ __device__ __forceinline__ float wave_max(float v) {
     return __shfl(v, 0, 64);
 }
 
-// ------------------- policy / value head outputs (PV) -----------------------
-// The PV head GEMM (N = A+1 <= 32) is cut into HEAD_KSPLIT ranges of k so that it
-// fills more than a handful of CUs; it leaves fp32 partial sums part[z][B][32].
-// head_row adds them in z order and the bias: z[0..A-1] logits, z[A] value.
-__device__ __forceinline__ void head_row(const float *__restrict__ part, const float *__restrict__ bias, int B,
-                                         int n, float (&z)[32]) {
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        float4 s = *reinterpret_cast<const float4 *>(part + (size_t)n * 32 + 4 * q);
-        for (int k = 1; k < HEAD_KSPLIT; ++k) {
-            const float4 v = *reinterpret_cast<const float4 *>(part + ((size_t)k * B + n) * 32 + 4 * q);
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-        }
-        const float4 b = *reinterpret_cast<const float4 *>(bias + 4 * q);
-        z[4 * q] = s.x + b.x; z[4 * q + 1] = s.y + b.y; z[4 * q + 2] = s.z + b.z; z[4 * q + 3] = s.w + b.w;
-    }
-}
-
-// Inference epilogue: logits, value, softmax probabilities and the lowest-index
-// greedy action; one thread per sample.
-__global__ void policy_epilogue_kernel(const float *__restrict__ part, const float *__restrict__ bias, int B, int A,
-                                       float *__restrict__ logits, float *__restrict__ value,
-                                       float *__restrict__ probs, int32_t *__restrict__ greedy) {
-    const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= B) return;
-    float z[32];
-    head_row(part, bias, B, n, z);
-    float mx = -INFINITY, val = 0.f;
-    int arg = 0;
-#pragma unroll
-    for (int k = 0; k < 32; ++k) {
-        if (k < A) {
-            logits[(size_t)n * A + k] = z[k];
-            if (z[k] > mx) { mx = z[k]; arg = k; }
-        }
-        val = k == A ? z[k] : val;
-    }
-    value[n] = val;
-    if (greedy) greedy[n] = arg;
-    if (probs) {
-        float s = 0.f;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) s += k < A ? expf(z[k] - mx) : 0.f;
-        const float inv = 1.f / s;
-#pragma unroll
-        for (int k = 0; k < 32; ++k)
-            if (k < A) probs[(size_t)n * A + k] = expf(z[k] - mx) * inv;
-    }
-}
-
-// ------------------- actor-critic objectives (A2C, PPO) ---------------------
-// Section "RL Algorithm Background": advantage actor-critic gradient and the PPO
-// clipped surrogate; value regression and entropy bonus as batch means.
-// One thread per sample.  Writes the gradient at the head outputs as one bf16
-// row [NHP = 64] per sample (columns 0..A-1 logits, column A value, rest 0) and
-// one partial sum {policy, value, entropy} per block.
-__global__ __launch_bounds__(LOSS_BLOCK) void ac_loss_kernel(
-    const float *__restrict__ part, const float *__restrict__ bias, const int32_t *__restrict__ action,
-    const float *__restrict__ adv, const float *__restrict__ ret, const float *__restrict__ old_logp, int ppo,
-    float clip_eps, float value_coef, float entropy_coef, int B, int A, __bf16 *__restrict__ dz,
-    float *__restrict__ lossp) {
-    __shared__ float red[3][LOSS_BLOCK];
-    const int tid = threadIdx.x, n = blockIdx.x * LOSS_BLOCK + tid;
-    float pol = 0.f, val = 0.f, ent = 0.f;
-    if (n < B) {
-        float z[32];
-        head_row(part, bias, B, n, z);
-        float v = 0.f, mx = -INFINITY;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            v = k == A ? z[k] : v;
-            z[k] = k < A ? z[k] : -INFINITY;
-            mx = fmaxf(mx, z[k]);
-        }
-        float s = 0.f;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) s += k < A ? expf(z[k] - mx) : 0.f;
-        const float lse = mx + logf(s);
-        float H = 0.f;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const float lp = z[k] - lse;
-            z[k] = lp;                                   // z now holds log-probabilities
-            H -= k < A ? expf(lp) * lp : 0.f;
-        }
-        const int a = action[n];
-        float lpa = 0.f;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) lpa = k == a ? z[k] : lpa;
-        const float ad = adv[n];
-        float w;   // d(surrogate)/d(log pi(a))
-        if (ppo) {
-            const float rho = expf(lpa - old_logp[n]);
-            const float clipped = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
-            pol = -fminf(rho * ad, clipped * ad);
-            const bool active = (ad >= 0.f && rho <= 1.f + clip_eps) || (ad < 0.f && rho >= 1.f - clip_eps);
-            w = active ? ad * rho : 0.f;
-        } else {
-            pol = -lpa * ad;
-            w = ad;
-        }
-        const float dv = v - ret[n];
-        val = dv * dv;
-        ent = H;
-        const float invB = 1.f / (float)B;
-        float g[32];
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const float p = expf(z[k]);
-            const float gk = (-w * ((k == a ? 1.f : 0.f) - p) + entropy_coef * p * (z[k] + H)) * invB;
-            g[k] = k < A ? gk : (k == A ? value_coef * 2.f * dv * invB : 0.f);
-        }
-        typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-        u32x4_t *row = reinterpret_cast<u32x4_t *>(dz + (size_t)n * 64);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const bf16x8_t h = {(__bf16)g[8 * q],     (__bf16)g[8 * q + 1], (__bf16)g[8 * q + 2], (__bf16)g[8 * q + 3],
-                                (__bf16)g[8 * q + 4], (__bf16)g[8 * q + 5], (__bf16)g[8 * q + 6], (__bf16)g[8 * q + 7]};
-            row[q] = __builtin_bit_cast(u32x4_t, h);
-        }
-#pragma unroll
-        for (int q = 4; q < 8; ++q) row[q] = u32x4_t{0u, 0u, 0u, 0u};
-    }
-    red[0][tid] = pol;
-    red[1][tid] = val;
-    red[2][tid] = ent;
-    __syncthreads();
-    for (int o = LOSS_BLOCK / 2; o >= 1; o >>= 1) {
-        if (tid < o) {
-            red[0][tid] += red[0][tid + o];
-            red[1][tid] += red[1][tid + o];
-            red[2][tid] += red[2][tid + o];
-        }
-        __syncthreads();
-    }
-    if (tid < 3) lossp[blockIdx.x * 4 + tid] = red[tid][0];
-}
-
-// loss[0..3] = {total, policy|cross-entropy, value mse, entropy}: block partials
-// are added in block order by one thread.
-__global__ void loss_finalize_kernel(const float *__restrict__ lossp, int blocks, int B, float value_coef,
-                                     float entropy_coef, float *__restrict__ loss) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+// loss[0..3] = {total, policy|cross-entropy, value mse, entropy}: one wavefront;
+// lane l adds the partials of blocks l, l+64, ... in that order, then the lanes
+// are added in a fixed tree -- the same association on every run.
+__global__ __launch_bounds__(64) void loss_finalize_kernel(const float *__restrict__ lossp, int blocks, int B,
+                                                           float value_coef, float entropy_coef,
+                                                           float *__restrict__ loss) {
+    if (blockIdx.x != 0) return;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f;
-    for (int b = 0; b < blocks; ++b) {
+    for (int b = threadIdx.x; b < blocks; b += 64) {
         s0 += lossp[b * 4 + 0];
         s1 += lossp[b * 4 + 1];
         s2 += lossp[b * 4 + 2];
     }
+    s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2);
+    if (threadIdx.x != 0) return;
     const float inv = 1.f / (float)B;
     s0 *= inv; s1 *= inv; s2 *= inv;
     loss[0] = s0 + value_coef * s1 - entropy_coef * s2;
