@@ -28,14 +28,23 @@ namespace arn {
 
 // Conv description C supplies (all static):
 //   CI           input channels (32 or 64); a pixel is CI bf16, padded by 32 bytes in LDS
-//   SRC_PIX      pixels per sample in global memory;  LDS_PIX  pixels per sample in LDS
+//   SRC_PIX      pixels per sample in global memory;  IMG  bytes of one sample's image in LDS
 //   P, HO        output positions per sample (HO x HO)
 //   CO, K        output channels (64 or 128) and contraction length (taps * CI)
 //   G            samples per iteration;  SPLIT  three-product precision
 //   ZERO_FILL    LDS image has a zero border (input-gradient problems)
-//   dst_pix(p)   LDS pixel of source pixel p
-//   base_pix(pos) LDS pixel of tap (0,0) of output position pos
-//   tap_pix(t)   LDS pixel offset of tap t
+//   dst_off(p)   LDS byte offset (within the sample's image) of source pixel p
+//   base_off(pos) LDS byte offset of tap (0,0) of output position pos
+//   tap_off(t)   LDS byte offset of tap t relative to tap (0,0)
+//                LDS bank rule for the fragment reads (ds_read_b128, measured): the 64 lanes are served
+//                in four groups of 16 -- lanes {0-3, 12-15, 20-23, 24-27}, {4-7, 8-11, 16-19, 28-31}
+//                and the same plus 32 -- and a group is conflict-free when its 16-byte words fall in
+//                16 different 16-byte slots modulo 256 bytes.  A fragment read has lane (li, lg) at
+//                base_off(position li of the tile) + 16 lg; with a pixel stride of 32 mod 64 bytes it is
+//                conflict-free as long as base_off advances by exactly one pixel stride (mod 256) from
+//                every position to the next, also across the end of an output row and from one
+//                sample of the group to the next.  The images therefore pad every row (and the
+//                image) by the few 16-byte words that make those steps come out right.
 //   NBUF         LDS image buffers: 2 = double buffered by sample group (one barrier per
 //                group); 1 = single (two barriers) so that two or three workgroups share a CU
 //                and fill each other's staging and latency gaps
@@ -55,10 +64,23 @@ namespace arn {
 constexpr int RES_THREADS = 512;    // conv1 forward
 constexpr int RESC_THREADS = 256;   // resident_conv_kernel
 
+// true if base_off advances by the pixel stride (mod 256 bytes) between all consecutive rows of a sample group
+template <class C>
+constexpr bool layout_is_uniform() {
+    int prev = 0;
+    for (int row = 0; row < C::G * C::P; ++row) {
+        const int g = row / C::P, pos = row - g * C::P;
+        const int at = g * C::IMG + C::base_off(pos);
+        if (row > 0 && ((at - prev - C::PSB) & 255) != 0) return false;
+        prev = at;
+    }
+    return true;
+}
+
 template <class C>
 __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
     constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
-    constexpr int IMG = C::LDS_PIX * PS;                 // bytes of one sample's image
+    constexpr int IMG = C::IMG;                          // bytes of one sample's LDS image (rows padded, see below)
     constexpr int PARTS = C::SPLIT ? 2 : 1;              // hi (+ lo)
     constexpr int BUF = C::G * IMG * PARTS;              // one buffer: G samples, hi then lo
     constexpr int NQ = C::G * C::SRC_PIX * NCH;          // 16-byte chunks per part per iteration
@@ -74,6 +96,8 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     static_assert(KS % 2 == 0, "k-steps split into two halves");
     constexpr int NBUF = C::NBUF;
     static_assert((BUF + MBUF) * NBUF <= 160 * 1024, "LDS budget");
+    static_assert(C::PSB == PS && IMG % 16 == 0, "pixel stride / image alignment");
+    static_assert(layout_is_uniform<C>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
 
     __shared__ u32x4 lds[NBUF * BUF / 16];
     __shared__ u32x2 lds_mask8[NMQ ? NBUF * MBUF / 8 : 2];
@@ -139,7 +163,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
             if (q < NQ) {
                 const int p = q / NCH, c = q - p * NCH;          // p = g * SRC_PIX + source pixel
                 const int g = p / C::SRC_PIX, sp = p - g * C::SRC_PIX;
-                const int off = (g * C::LDS_PIX + C::dst_pix(sp)) * PS + c * 16;
+                const int off = g * IMG + C::dst_off(sp) + c * 16;
                 *reinterpret_cast<u32x4 *>(dst + off) = rh[i];
                 if constexpr (C::SPLIT) *reinterpret_cast<u32x4 *>(dst + C::G * IMG + off) = rl[i];
             }
@@ -159,12 +183,12 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
         int row = t * 16 + li;
         row = row < R ? row : R - 1;                     // padded rows recompute the last one; never stored
         const int g = row / C::P, pos = row - g * C::P;
-        const int base = (g * C::LDS_PIX + C::base_pix(pos)) * PS + 16 * lg;
+        const int base = g * IMG + C::base_off(pos) + 16 * lg;
 #pragma unroll
         for (int j = 0; j < KH; ++j) {
             const int ks = half * KH + j;
             const int tap = (32 * ks) / CI, ci0 = (32 * ks) % CI;
-            const int off = base + C::tap_pix(tap) * PS + ci0 * 2;
+            const int off = base + C::tap_off(tap) + ci0 * 2;
             fh[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + off));
             if constexpr (C::SPLIT) fl[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(img + C::G * IMG + off));
         }
@@ -349,21 +373,19 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
 // image keeps even and odd columns in separate planes so that the stride-2
 // windows of neighbouring positions are neighbouring LDS pixels.
 struct ResConv2Fwd {
-    static constexpr int CI = C1, SRC_PIX = P1, LDS_PIX = P1, P = P2, HO = H2, CO = C2, K = KW2, G = 1;
+    static constexpr int CI = C1, SRC_PIX = P1, P = P2, HO = H2, CO = C2, K = KW2, G = 1;
     static constexpr bool SPLIT = true, ZERO_FILL = false, PIPE = false;
     static constexpr int MASK_ELEMS = 0, NBUF = 1;
-    __device__ static constexpr int dst_pix(int p) {
-        const int y = p / H1, x = p - y * H1;
-        return (y * 2 + (x & 1)) * (H1 / 2) + (x >> 1);
+    // image rows 2r and 2r+1 form one block of four planes (row parity x column parity, 10 pixels each)
+    // plus one pixel of padding: 41 pixels, so that the first position of an output row follows the
+    // last of the row before at one pixel stride modulo 256 bytes
+    static constexpr int PSB = C1 * 2 + 32, PAIR = 41, IMG = (H1 / 2) * PAIR * PSB;
+    __device__ static constexpr int plane_pix(int y, int x) {
+        return (y >> 1) * PAIR + (y & 1) * H1 + (x & 1) * (H1 / 2) + (x >> 1);
     }
-    __device__ static constexpr int base_pix(int pos) {
-        const int oy = pos / H2, ox = pos - oy * H2;
-        return oy * (2 * H1) + ox;            // pixel (2oy, 2ox): row 2oy, even plane, column ox
-    }
-    __device__ static constexpr int tap_pix(int t) {
-        const int ky = t / K2, kx = t - ky * K2;
-        return (ky * 2 + (kx & 1)) * (H1 / 2) + (kx >> 1);
-    }
+    __device__ static constexpr int dst_off(int p) { return plane_pix(p / H1, p % H1) * PSB; }
+    __device__ static constexpr int base_off(int pos) { return plane_pix(2 * (pos / H2), 2 * (pos % H2)) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return plane_pix(t / K2, t % K2) * PSB; }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
         const uint8_t *mask;
@@ -389,15 +411,15 @@ struct ResConv2Fwd {
 
 // conv3 forward: act2 [9][9][64] -> act3 [7][7][64], 3x3 stride 1
 struct ResConv3Fwd {
-    static constexpr int CI = C2, SRC_PIX = P2, LDS_PIX = P2, P = P3, HO = H3, CO = C3, K = KW3, G = 2;
+    static constexpr int CI = C2, SRC_PIX = P2, P = P3, HO = H3, CO = C3, K = KW3, G = 2;
     static constexpr bool SPLIT = true, ZERO_FILL = false, PIPE = false;
     static constexpr int MASK_ELEMS = 0, NBUF = 1;
-    __device__ static constexpr int dst_pix(int p) { return p; }
-    __device__ static constexpr int base_pix(int pos) {
-        const int oy = pos / H3, ox = pos - oy * H3;
-        return oy * H2 + ox;
-    }
-    __device__ static constexpr int tap_pix(int t) { return (t / K3) * H2 + t % K3; }
+    // 9 pixels of 160 bytes per row + 192 bytes: position (oy+1, 0) then follows (oy, 6) at one pixel
+    // stride mod 256; the image is padded likewise for the step from sample g to g+1
+    static constexpr int PSB = C2 * 2 + 32, ROWB = H2 * PSB + 192, IMG = H2 * ROWB + 64;
+    __device__ static constexpr int dst_off(int p) { return (p / H2) * ROWB + (p % H2) * PSB; }
+    __device__ static constexpr int base_off(int pos) { return (pos / H3) * ROWB + (pos % H3) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return (t / K3) * ROWB + (t % K3) * PSB; }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
         const uint8_t *mask;
@@ -426,12 +448,14 @@ struct ResConv3Fwd {
 // d(pre2) [9][9][64] masked by act2 > 0.
 struct ResConv3Dgrad {
     static constexpr int PADW = H3 + 4;   // 11
-    static constexpr int CI = C3, SRC_PIX = P3, LDS_PIX = PADW * PADW, P = P2, HO = H2, CO = C2, K = 9 * C3, G = 2;
+    static constexpr int CI = C3, SRC_PIX = P3, P = P2, HO = H2, CO = C2, K = 9 * C3, G = 2;
     static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
     static constexpr int MASK_ELEMS = P2 * C2, NBUF = 1;
-    __device__ static constexpr int dst_pix(int p) { return (p / H3 + 2) * PADW + p % H3 + 2; }
-    __device__ static constexpr int base_pix(int pos) { return (pos / H2) * PADW + pos % H2; }
-    __device__ static constexpr int tap_pix(int t) { return (t / 3) * PADW + t % 3; }
+    // row and image padding as in the forward kernels (9 positions per output row over 11-pixel rows)
+    static constexpr int PSB = C3 * 2 + 32, ROWB = PADW * PSB + 192, IMG = 21664;
+    __device__ static constexpr int dst_off(int p) { return (p / H3 + 2) * ROWB + (p % H3 + 2) * PSB; }
+    __device__ static constexpr int base_off(int pos) { return (pos / H2) * ROWB + (pos % H2) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return (t / 3) * ROWB + (t % 3) * PSB; }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
         const uint8_t *mask;   // sign bits of act2
@@ -455,12 +479,14 @@ struct ResConv3Dgrad {
 // pixel (2u + phase/2, 2v + phase%2).  Output d(pre1) masked by act1 > 0.
 struct ResConv2Dgrad {
     static constexpr int PADW = H2 + 2;   // 11
-    static constexpr int CI = C2, SRC_PIX = P2, LDS_PIX = PADW * PADW, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 2;
+    static constexpr int CI = C2, SRC_PIX = P2, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 2;
     static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
     static constexpr int MASK_ELEMS = P1 * C1, NBUF = 1;
-    __device__ static constexpr int dst_pix(int p) { return (p / H2 + 1) * PADW + p % H2 + 1; }
-    __device__ static constexpr int base_pix(int pos) { return (pos / 10) * PADW + pos % 10; }
-    __device__ static constexpr int tap_pix(int t) { return (t / 2) * PADW + t % 2; }
+    // row and image padding as in the forward kernels (10 positions per output row over 11-pixel rows)
+    static constexpr int PSB = C2 * 2 + 32, ROWB = PADW * PSB + 96, IMG = 20608;
+    __device__ static constexpr int dst_off(int p) { return (p / H2 + 1) * ROWB + (p % H2 + 1) * PSB; }
+    __device__ static constexpr int base_off(int pos) { return (pos / 10) * ROWB + (pos % 10) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return (t / 2) * ROWB + (t % 2) * PSB; }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
         const uint8_t *mask;   // sign bits of act1
