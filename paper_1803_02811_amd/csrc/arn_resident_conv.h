@@ -21,6 +21,8 @@
 //   B (32 x 16): lane l holds col l%16, k = 8*(l/16) .. +7     -> activations, col = position
 //   D (16 x 16): lane l holds col l%16, rows 4*(l/16) + r, r = 0..3
 #pragma once
+#include <type_traits>
+
 #include "arn_gemm.h"
 #include "arn_layout.h"
 
@@ -279,9 +281,9 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
 // The sample is converted to a bf16 image in LDS once (each pixel is used by up
 // to four windows); a 32-wide k-step is four rows (ky) of eight pixels (kx) of
 // one input channel, so an activation fragment is 16 contiguous bytes of the
-// image.  Every wavefront keeps all of W1 (hi and lo parts) in registers; the 25
-// position tiles x 2 channel tiles of a sample are dealt round-robin to the eight
-// wavefronts.  Three-product precision with an exact activation operand needs
+// image.  A wavefront keeps one 16-channel tile of W1 (hi and lo parts) in registers;
+// the 25 position tiles of a sample are dealt round-robin to the four wavefront pairs.
+// Three-product precision with an exact activation operand needs
 // two MFMAs per fragment (W_hi x, W_lo x).
 __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w, const __bf16 *__restrict__ w_lo,
@@ -299,18 +301,16 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
 
-    bf16x8 wh[2][KS], wl[2][KS];
-    float4 bs[2];
+    // wavefront w owns channel tile w & 1 and position tiles (w >> 1) + 4j
+    const int ct = wave & 1, t0 = wave >> 1;
+    bf16x8 wh[KS], wl[KS];
+    const size_t wrow = (size_t)(ct * 16 + li) * KW1 + 8 * lg;
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-        const size_t row = (size_t)(ct * 16 + li) * KW1 + 8 * lg;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + row + 32 * ks));
-            wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + row + 32 * ks));
-        }
-        bs[ct] = *reinterpret_cast<const float4 *>(bias + ct * 16 + 4 * lg);
+    for (int ks = 0; ks < KS; ++ks) {
+        wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + wrow + 32 * ks));
+        wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + wrow + 32 * ks));
     }
+    const float4 bs = *reinterpret_cast<const float4 *>(bias + ct * 16 + 4 * lg);
 
     u32x4 rimg[NL];
     auto gload = [&](int s) __attribute__((always_inline)) {
@@ -319,6 +319,37 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         for (int i = 0; i < NL; ++i) {
             const int idx = tid + RES_THREADS * i;
             rimg[i] = src[idx < IMG_U4 ? idx : IMG_U4 - 1];
+        }
+    };
+
+    // activation fragments of position tile t: for each k-step, 16 bytes of the image (8 pixels of a row)
+    auto frag_load = [&](const char *img, int t, u32x2 (&f)[2 * KS]) __attribute__((always_inline)) {
+        const int pos = t * 16 + li, oy = pos / H1, ox = pos - oy * H1;
+        const int base = ((S1 * oy + lg) * IN_W + S1 * ox) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int off = base + ((ks >> 1) * (IN_H * IN_W) + (ks & 1) * 4 * IN_W) * 2;
+            f[2 * ks] = *reinterpret_cast<const u32x2 *>(img + off);
+            f[2 * ks + 1] = *reinterpret_cast<const u32x2 *>(img + off + 8);
+        }
+    };
+    auto unit = [&](int s, int t, const u32x2 (&f)[2 * KS]) __attribute__((always_inline)) {
+        const int pos = t * 16 + li;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 b = as_bf16x8(u32x4{f[2 * ks].x, f[2 * ks].y, f[2 * ks + 1].x, f[2 * ks + 1].y});
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ks], b, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ks], b, acc, 0, 0, 0);
+        }
+        constexpr float sc = 1.0f / 255.0f;
+        const float r0 = fmaxf(acc[0] * sc + bs.x, 0.f), r1 = fmaxf(acc[1] * sc + bs.y, 0.f);
+        const float r2 = fmaxf(acc[2] * sc + bs.z, 0.f), r3 = fmaxf(acc[3] * sc + bs.w, 0.f);
+        const size_t at = ((size_t)s * P1 + pos) * C1 + ct * 16;
+        store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3);
+        if (mask_out) {
+            const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
+            if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
         }
     };
 
@@ -336,34 +367,19 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         __syncthreads();
         if (s + 1 < s_end) gload(s + 1);
         const char *img = reinterpret_cast<const char *>(s_img[buf]);
+        // The fragments of the next position tile are read from LDS while the MFMAs of the current one
+        // run (two register sets, statically alternated).  Tiles t0 + 4j, j = 0..5, exist for every
+        // wavefront; tile 24 (j = 6) only for t0 = 0.
+        u32x2 fa[2 * KS], fb[2 * KS];
+        frag_load(img, t0, fa);
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-            // channel tile 0 starts at tile `wave`, channel tile 1 at tile (wave+4)%8: 6 or 7 units per wavefront
-#pragma unroll 1
-            for (int t = (wave + 4 * ct) & 7; t < NT; t += 8) {
-                const int pos = t * 16 + li, oy = pos / H1, ox = pos - oy * H1;
-                const int base = ((S1 * oy + lg) * IN_W + S1 * ox) * 2;
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const int off = base + ((ks >> 1) * (IN_H * IN_W) + (ks & 1) * 4 * IN_W) * 2;
-                    const u32x2 f0 = *reinterpret_cast<const u32x2 *>(img + off);
-                    const u32x2 f1 = *reinterpret_cast<const u32x2 *>(img + off + 8);
-                    const bf16x8 b = as_bf16x8(u32x4{f0.x, f0.y, f1.x, f1.y});
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wl[ct][ks], b, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[ct][ks], b, acc, 0, 0, 0);
-                }
-                constexpr float sc = 1.0f / 255.0f;
-                const float r0 = fmaxf(acc[0] * sc + bs[ct].x, 0.f), r1 = fmaxf(acc[1] * sc + bs[ct].y, 0.f);
-                const float r2 = fmaxf(acc[2] * sc + bs[ct].z, 0.f), r3 = fmaxf(acc[3] * sc + bs[ct].w, 0.f);
-                const size_t at = ((size_t)s * P1 + pos) * C1 + ct * 16;
-                store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3);
-                if (mask_out) {
-                    const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
-                    if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
-                }
-            }
+        for (int j = 0; j < 6; j += 2) {
+            frag_load(img, t0 + 4 * (j + 1), fb);
+            unit(s, t0 + 4 * j, fa);
+            if (j + 2 < 6 || t0 == 0) frag_load(img, t0 + 4 * (j + 2), fa);
+            unit(s, t0 + 4 * (j + 1), fb);
         }
+        if (t0 == 0) unit(s, NT - 1, fa);
         buf ^= 1;
     }
 }
