@@ -61,7 +61,9 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-    float bsum = 0.f;
+    // bias gradient: a thread always stages the same eight dY channels (chunk tid % 4 of a row), so it
+    // adds what it stages, in fp32; the 64 threads of a chunk are added in thread order at the end
+    float bs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // per-lane constants of the transposing reads
     const int o = lane & 15, G = lane >> 4;
@@ -74,7 +76,6 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
         const int t = 2 * wave + j, ci = t >> 1, ky = (t & 1) * 4 + ky_lane;
         xoff[j] = ((ci * IN_H + ky) * IN_W + kx0) * 2;
     }
-    const int bco = tid & 31, bpart = tid >> 5;
 
     if (s_begin < s_end) gload(s_begin);
     for (int s = s_begin; s < s_end; ++s) {
@@ -90,7 +91,12 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
             const int idx = tid + 256 * i;
-            if (idx < DY_U4) s_dy[idx] = rdy[i];
+            if (idx < DY_U4) {
+                s_dy[idx] = rdy[i];
+                const bf16x8 f = as_bf16x8(rdy[i]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bs[e] += (float)f[e];
+            }
         }
         __syncthreads();
         if (s + 1 < s_end) gload(s + 1);
@@ -109,10 +115,6 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
                 acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc[j], 0, 0, 0);
             }
         }
-        // bias gradient: eight threads per channel, 50 rows each, in row order
-        const __bf16 *col = reinterpret_cast<const __bf16 *>(s_dy) + bco;
-#pragma unroll 10
-        for (int r = 0; r < P1 / 8; ++r) bsum += (float)col[(bpart * (P1 / 8) + r) * C1];
     }
 
     float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
@@ -128,12 +130,12 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
     }
     __syncthreads();
     float *red = reinterpret_cast<float *>(s_dy);
-    red[tid] = bsum;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[(tid >> 2) * C1 + (tid & 3) * 8 + e] = bs[e];
     __syncthreads();
     if (tid < C1) {
-        float t = 0.f;
-#pragma unroll
-        for (int p8 = 0; p8 < 8; ++p8) t += red[p8 * 32 + tid];
+        float t = red[tid];
+        for (int g = 1; g < 64; ++g) t += red[g * C1 + tid];
         out[C1 * KW1 + tid] = t;
     }
 }
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     constexpr int NY = COUT / 32, NX = KP / 32, WAVES_X = 4 / WAVES_Y;
     constexpr int TY = NY / WAVES_Y, TX = NX / WAVES_X;
     static_assert(NY % WAVES_Y == 0 && NX % WAVES_X == 0, "tile split");
-    constexpr int BPARTS = 256 / COUT, BROWS = (R + BPARTS - 1) / BPARTS;
+    static_assert(256 % YCH == 0 && (256 / YCH) * COUT * 4 <= RPAD * YS, "bias-gradient scratch");
 
     __shared__ u32x4 s_x[G * PIX * PS / 16];
     __shared__ u32x4 s_dy[RPAD * YS / 16];
@@ -197,12 +199,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
         for (int b = 0; b < TX; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-    float bsum = 0.f;
+    float bs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // bias gradient of the thread's eight dY channels (chunk tid % YCH)
 
     const int o = lane & 15, Gq = lane >> 4;
     const int row_in_step = 8 * (Gq >> 1) + (o >> 2);
     const int col_lane = (16 * (Gq & 1) + 4 * (o & 3)) * 2;         // byte offset of the lane's 4 columns in a 32-column tile
-    const int bco = tid % COUT, bpart = tid / COUT;
 
     if (s_begin < s_end) gload(s_begin);
     for (int s = s_begin; s < s_end; s += G) {
@@ -225,6 +226,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
                 const int row = idx / YCH, c = idx - row * YCH;
                 const bool live = s + row / P < s_end;
                 *reinterpret_cast<u32x4 *>(yl + row * YS + c * 16) = live ? ry[i] : zero_u4();
+                if (live) {
+                    const bf16x8 f = as_bf16x8(ry[i]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bs[e] += (float)f[e];
+                }
             }
         }
         __syncthreads();
@@ -258,11 +264,6 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[a], fx, acc[a][b], 0, 0, 0);
             }
         }
-        // bias gradient: 256/COUT threads per channel, consecutive row blocks, in row order
-        if (bpart < BPARTS) {
-            const int r0 = bpart * BROWS, r1 = r0 + BROWS < R ? r0 + BROWS : R;
-            for (int r = r0; r < r1; ++r) bsum += (float)*reinterpret_cast<const __bf16 *>(yl + r * YS + bco * 2);
-        }
     }
 
     float *out = part + (size_t)blockIdx.x * (COUT * KP + COUT);
@@ -280,12 +281,12 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
         }
     __syncthreads();
     float *red = reinterpret_cast<float *>(s_dy);
-    red[tid] = bsum;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[(tid / YCH) * COUT + (tid % YCH) * 8 + e] = bs[e];
     __syncthreads();
     if (tid < COUT) {
-        float t = 0.f;
-#pragma unroll
-        for (int p8 = 0; p8 < BPARTS; ++p8) t += red[p8 * COUT + tid];
+        float t = red[tid];
+        for (int g = 1; g < 256 / YCH; ++g) t += red[g * COUT + tid];
         out[COUT * KP + tid] = t;
     }
 }
