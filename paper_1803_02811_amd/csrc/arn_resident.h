@@ -156,8 +156,8 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     constexpr int NXC = G * PIX * XCH, NYC = G * P * YCH;
     constexpr int NI = (NXC + 255) / 256, ND = (NYC + 255) / 256;
     constexpr int NY = COUT / 32, NX = KP / 32, WAVES_X = 4 / WAVES_Y;
-    constexpr int TY = NY / WAVES_Y, TX = NX / WAVES_X;
-    static_assert(NY % WAVES_Y == 0 && NX % WAVES_X == 0, "tile split");
+    constexpr int TY = NY / WAVES_Y, TX = (NX + WAVES_X - 1) / WAVES_X;   // the last wavefront along x may own fewer column tiles
+    static_assert(NY % WAVES_Y == 0, "tile split");
     static_assert(256 % YCH == 0 && (256 / YCH) * COUT * 4 <= RPAD * YS, "bias-gradient scratch");
 
     __shared__ u32x4 s_x[G * PIX * PS / 16];
@@ -255,6 +255,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
             }
 #pragma unroll
             for (int b = 0; b < TX; ++b) {
+                if (wx * TX + b >= NX) break;                // wavefront-uniform
                 const int k0 = (wx * TX + b) * 32, tap = k0 / CIN, ci0 = k0 - tap * CIN;
                 const int ky = tap / KS, kx = tap - ky * KS;
                 const int toff = (ky * HIN + kx) * PS + ci0 * 2;
@@ -272,6 +273,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     for (int a = 0; a < TY; ++a)
 #pragma unroll
         for (int b = 0; b < TX; ++b) {
+            if (wx * TX + b >= NX) break;
             const int k = (wx * TX + b) * 32 + fr;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {

@@ -112,17 +112,9 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
 
-    // weights of this wavefront's channels, all k, as A-operand fragments
+    // weights of this wavefront's channels, all k, as A-operand fragments (loaded below, after the
+    // first image loads have been issued, so that staging does not wait for them)
     bf16x8 wh[CT][KS], wl[C::SPLIT ? CT : 1][C::SPLIT ? KS : 1];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-        const size_t row = (size_t)(wave * (16 * CT) + ct * 16 + li) * C::K + 8 * lg;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w + row + 32 * ks));
-            if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + 32 * ks));
-        }
-    }
 
     if constexpr (C::ZERO_FILL) {
         for (int i = tid; i < NBUF * BUF / 16; i += RESC_THREADS) lds[i] = zero_u4();
@@ -230,6 +222,15 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     };
 
     gload(s_begin);
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const size_t row = (size_t)(wave * (16 * CT) + ct * 16 + li) * C::K + 8 * lg;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w + row + 32 * ks));
+            if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + 32 * ks));
+        }
+    }
     int buf = 0;
     for (int s = s_begin; s < s_end; s += C::G) {
         stage(buf);
@@ -304,12 +305,6 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     // wavefront w owns channel tile w & 1 and position tiles (w >> 1) + 4j
     const int ct = wave & 1, t0 = wave >> 1;
     bf16x8 wh[KS], wl[KS];
-    const size_t wrow = (size_t)(ct * 16 + li) * KW1 + 8 * lg;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + wrow + 32 * ks));
-        wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + wrow + 32 * ks));
-    }
     const float4 bs = *reinterpret_cast<const float4 *>(bias + ct * 16 + 4 * lg);
 
     u32x4 rimg[NL];
@@ -354,6 +349,12 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     };
 
     gload(s_begin);
+    const size_t wrow = (size_t)(ct * 16 + li) * KW1 + 8 * lg;   // after the first image loads: staging does not wait for the weights
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + wrow + 32 * ks));
+        wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + wrow + 32 * ks));
+    }
     int buf = 0;
     for (int s = s_begin; s < s_end; ++s) {
 #pragma unroll
