@@ -26,12 +26,25 @@ Where each piece comes from
 * Categorical DQN: same section (one sentence); the projected distributional
   Bellman target is the algorithm of the distributional-RL paper it cites.
 
+* DQN objective: same section, E[(y - Q(a|s))^2] with y = r + gamma max_a Q(a|s';theta-);
+  Double-DQN (the online network picks the action, the target network values it) and the
+  dueling aggregation Q = V + A - mean(A) are the rules of the two publications that
+  section cites for the epsilon-Rainbow agent.
+* Action selection: the sampler returns actions, not logits (section "Synchronized
+  Sampling"): a categorical draw for policy-gradient agents, epsilon-greedy for Q-learning
+  agents.  The uniform random numbers are inputs, so that both sides draw the same action.
+
 Readings taken where the paper is silent (each also listed in the design notes)
 * cross-correlation (no kernel flip); pixel scaling x = u8/255;
 * ReLU derivative at 0 is 0 (mask = pre > 0);
 * every loss term is a mean over the batch; entropy uses natural log;
 * advantages, returns, old log-probs and C51 targets are constants;
 * PPO clip boundaries are inclusive; argmax ties go to the lowest index;
+* DQN: squared error exactly as printed (no 1/2, no Huber clipping), mean over the batch;
+  the target is a constant; y = r where the transition is terminal; the dueling network
+  shares the 512-unit hidden layer between its value and advantage outputs;
+* categorical draw = inverse CDF: the first action whose cumulative probability exceeds u;
+  epsilon-greedy: u < epsilon takes action floor(u2 * A), otherwise the greedy action;
 * C51: the target network both selects and evaluates the next action; the
   projection is the triangular-kernel (gather) form, which conserves mass even
   when a shifted atom lands exactly on a support point.
@@ -149,7 +162,8 @@ PAPER_104x80 = Geometry(in_h=104, in_w=80, convs=((32, 8, 4, 0), (64, 4, 2, 1), 
 @dataclass(frozen=True)
 class NetSpec:
     num_actions: int = 18
-    head: str = "pv"            # "pv" = policy logits + value, "c51" = categorical
+    head: str = "pv"            # "pv" = policy logits + value, "c51" = categorical, "q" = scalar Q-values,
+                                # "duel" = advantage rows + a value row combined into Q-values
     num_atoms: int = 51
     geometry: Geometry = field(default_factory=Geometry)
 
@@ -170,6 +184,11 @@ def param_layout(spec: NetSpec) -> List[Tuple[str, Tuple[int, ...]]]:
     elif spec.head == "c51":
         n = spec.num_actions * spec.num_atoms
         out += [("c51.W", (n, g.hidden)), ("c51.b", (n,))]
+    elif spec.head == "q":
+        out += [("q.W", (spec.num_actions, g.hidden)), ("q.b", (spec.num_actions,))]
+    elif spec.head == "duel":
+        out += [("adv.W", (spec.num_actions, g.hidden)), ("adv.b", (spec.num_actions,)),
+                ("val.W", (1, g.hidden)), ("val.b", (1,))]
     else:
         raise ValueError(spec.head)
     return out
@@ -222,10 +241,50 @@ def forward(params: Dict[str, np.ndarray], obs_u8: np.ndarray, spec: NetSpec) ->
     if spec.head == "pv":
         cache["logits"] = h @ params["pi.W"].T + params["pi.b"]
         cache["value"] = (h @ params["v.W"].T + params["v.b"])[:, 0]
-    else:
+    elif spec.head == "c51":
         z = h @ params["c51.W"].T + params["c51.b"]
         cache["atom_logits"] = z.reshape(B, spec.num_actions, spec.num_atoms)
+    elif spec.head == "q":
+        cache["q"] = h @ params["q.W"].T + params["q.b"]
+    elif spec.head == "duel":
+        cache["adv"] = h @ params["adv.W"].T + params["adv.b"]
+        cache["val"] = (h @ params["val.W"].T + params["val.b"])[:, 0]
+        cache["q"] = dueling_aggregate(cache["adv"], cache["val"])
+    else:
+        raise ValueError(spec.head)
     return cache
+
+
+def dueling_aggregate(adv: np.ndarray, val: np.ndarray) -> np.ndarray:
+    """Q[n,a] = V[n] + A[n,a] - mean_a A[n,a]."""
+    adv = np.asarray(adv, dtype=np.float64)
+    return np.asarray(val, dtype=np.float64)[:, None] + adv - adv.mean(axis=1, keepdims=True)
+
+
+def dueling_aggregate_grad(dq: np.ndarray):
+    """Gradients at (A, V) of a scalar whose gradient at Q is dq."""
+    dq = np.asarray(dq, dtype=np.float64)
+    return dq - dq.mean(axis=1, keepdims=True), dq.sum(axis=1)
+
+
+def sample_categorical(probs: np.ndarray, u: np.ndarray) -> np.ndarray:
+    """Inverse-CDF draw: the first index whose cumulative probability exceeds u (the last one if rounding
+    leaves the total below u)."""
+    probs = np.asarray(probs, dtype=np.float64)
+    u = np.asarray(u, dtype=np.float64)
+    cdf = np.cumsum(probs, axis=1)
+    idx = (cdf > u[:, None]).argmax(axis=1)
+    none = ~(cdf > u[:, None]).any(axis=1)
+    idx[none] = probs.shape[1] - 1
+    return idx.astype(np.int32)
+
+
+def epsilon_greedy(q: np.ndarray, u: np.ndarray, u2: np.ndarray, epsilon: float) -> np.ndarray:
+    """u < epsilon: the uniformly random action floor(u2 * A); otherwise the lowest-index greedy action."""
+    q = np.asarray(q, dtype=np.float64)
+    A = q.shape[1]
+    rand = np.minimum((np.asarray(u2, dtype=np.float64) * A).astype(np.int64), A - 1)
+    return np.where(np.asarray(u, dtype=np.float64) < epsilon, rand, greedy(q)).astype(np.int32)
 
 
 def log_softmax(z: np.ndarray) -> np.ndarray:
@@ -413,8 +472,39 @@ def c51_loss_grad(atom_logits, action, m) -> np.ndarray:
 # --------------------------------------------------------------------------
 # backward through the network
 # --------------------------------------------------------------------------
+# --------------------------------------------------------------------------
+# DQN objective (section "RL Algorithm Background")
+# --------------------------------------------------------------------------
+def dqn_target(q_next_target, reward, done, gamma: float, q_next_online=None) -> np.ndarray:
+    """y = r + gamma (1 - done) Q(a*|s'; theta-), with a* = argmax of the target network's values, or of
+    the online network's values on s' when `q_next_online` is given (Double-DQN)."""
+    qt = np.asarray(q_next_target, dtype=np.float64)
+    sel = greedy(qt if q_next_online is None else np.asarray(q_next_online, dtype=np.float64))
+    boot = qt[np.arange(qt.shape[0]), sel]
+    live = 1.0 - np.asarray(done, dtype=np.float64)
+    return np.asarray(reward, dtype=np.float64) + gamma * live * boot
+
+
+def dqn_loss_value(q, action, y) -> dict:
+    """mean_n (y_n - Q[n, a_n])^2."""
+    q = np.asarray(q, dtype=np.float64)
+    td = np.asarray(y, dtype=np.float64) - q[np.arange(q.shape[0]), np.asarray(action)]
+    return {"total": float(np.mean(td * td)), "td": float(np.mean(td * td))}
+
+
+def dqn_loss_grad(q, action, y) -> np.ndarray:
+    """d loss / d Q: 2 (Q[n,a_n] - y_n) / B at the taken action, zero elsewhere (y is a constant)."""
+    q = np.asarray(q, dtype=np.float64)
+    B = q.shape[0]
+    rows = np.arange(B)
+    a = np.asarray(action)
+    g = np.zeros_like(q)
+    g[rows, a] = 2.0 * (q[rows, a] - np.asarray(y, dtype=np.float64)) / B
+    return g
+
+
 def backward(params: Dict[str, np.ndarray], cache: dict, spec: NetSpec, *, dlogits=None,
-             dvalue=None, datom_logits=None) -> Dict[str, np.ndarray]:
+             dvalue=None, datom_logits=None, dq=None) -> Dict[str, np.ndarray]:
     """Chain rule from gradients at the heads to every parameter (layout = params)."""
     g = spec.geometry
     grads: Dict[str, np.ndarray] = {}
@@ -426,11 +516,22 @@ def backward(params: Dict[str, np.ndarray], cache: dict, spec: NetSpec, *, dlogi
         grads["v.W"] = dvalue[None, :] @ h
         grads["v.b"] = np.array([dvalue.sum()])
         dh = dlogits @ params["pi.W"] + dvalue[:, None] * params["v.W"]
-    else:
+    elif spec.head == "c51":
         dz = datom_logits.reshape(B, -1)
         grads["c51.W"] = dz.T @ h
         grads["c51.b"] = dz.sum(axis=0)
         dh = dz @ params["c51.W"]
+    elif spec.head == "q":
+        grads["q.W"] = dq.T @ h
+        grads["q.b"] = dq.sum(axis=0)
+        dh = dq @ params["q.W"]
+    else:
+        dadv, dval = dueling_aggregate_grad(dq)
+        grads["adv.W"] = dadv.T @ h
+        grads["adv.b"] = dadv.sum(axis=0)
+        grads["val.W"] = dval[None, :] @ h
+        grads["val.b"] = np.array([dval.sum()])
+        dh = dadv @ params["adv.W"] + dval[:, None] * params["val.W"]
     dpre_fc = dh * (cache["pre_fc"] > 0)
     nconv = len(g.convs)
     feat = cache[f"act{nconv}"]
@@ -455,6 +556,7 @@ class Hyper:
     gamma: float = 0.99
     v_min: float = -10.0
     v_max: float = 10.0
+    double_q: bool = False
 
 
 def train_step_grads(flat_params, batch: dict, loss_kind: str, spec: NetSpec,
@@ -462,7 +564,7 @@ def train_step_grads(flat_params, batch: dict, loss_kind: str, spec: NetSpec,
     """Forward, objective and backward for one batch.
 
     batch keys -- a2c: obs, action, adv, ret; ppo: + old_logp;
-    c51: obs, action, next_obs, reward, done (and `flat_target_params`).
+    c51, dqn: obs, action, next_obs, reward, done (and `flat_target_params`).
     Returns {"loss": {...}, "grads": {name: array}, "flat": flat gradient, ...}.
     """
     params = unflatten(flat_params, spec)
@@ -493,6 +595,16 @@ def train_step_grads(flat_params, batch: dict, loss_kind: str, spec: NetSpec,
         d = c51_loss_grad(cache["atom_logits"], batch["action"], tgt["m"])
         grads = backward(params, cache, spec, datom_logits=d)
         out["datom_logits"] = d
+    elif loss_kind == "dqn":
+        tparams = unflatten(flat_target_params, spec)
+        q_next_t = forward(tparams, batch["next_obs"], spec)["q"]
+        q_next_o = forward(params, batch["next_obs"], spec)["q"] if hyper.double_q else None
+        y = dqn_target(q_next_t, batch["reward"], batch["done"], hyper.gamma, q_next_o)
+        out["target"] = y
+        out["loss"] = dqn_loss_value(cache["q"], batch["action"], y)
+        d = dqn_loss_grad(cache["q"], batch["action"], y)
+        grads = backward(params, cache, spec, dq=d)
+        out["dq"] = d
     else:
         raise ValueError(loss_kind)
     out["grads"] = grads

@@ -82,8 +82,14 @@ def param_shapes(num_actions: int, head: str, num_atoms: int = 51) -> List[Tuple
            ("fc.W", (512, 3136)), ("fc.b", (512,))]
     if head == "pv":
         out += [("pi.W", (num_actions, 512)), ("pi.b", (num_actions,)), ("v.W", (1, 512)), ("v.b", (1,))]
-    else:
+    elif head == "c51":
         out += [("c51.W", (num_actions * num_atoms, 512)), ("c51.b", (num_actions * num_atoms,))]
+    elif head == "q":
+        out += [("q.W", (num_actions, 512)), ("q.b", (num_actions,))]
+    elif head == "duel":
+        out += [("adv.W", (num_actions, 512)), ("adv.b", (num_actions,)), ("val.W", (1, 512)), ("val.b", (1,))]
+    else:
+        raise ValueError(head)
     return out
 
 
@@ -168,3 +174,10 @@ def update_rule_inputs(n: int, steps: int, seed: int) -> dict:
         g[r.random(n) < 0.01] = 0.0
         grads.append(g.astype(np.float32))
     return dict(theta=theta, grads=grads)
+
+
+def action_uniforms(B: int, seed: int) -> dict:
+    """The two uniform [0,1) numbers per sample that action selection consumes (u: the categorical draw or
+    the explore/exploit coin; u2: which random action), as fp32.  Seeds: 5000 + seed."""
+    r = rng(5000 + seed)
+    return {"u": r.random(B).astype(np.float32), "u2": r.random(B).astype(np.float32)}
