@@ -7,16 +7,19 @@
  * Processing" calls the standard 3-convolutional-layer network:
  *   uint8 [4,84,84] -> /255 -> conv 8x8/4 x32 -> conv 4x4/2 x64 -> conv 3x3/1 x64
  *   -> fc 3136->512 (ReLU after every hidden layer) -> heads.
- * Heads: policy logits [A] + value [1]   (head_kind ARN_HEAD_PV), or
- *        categorical atom logits [A,51]   (head_kind ARN_HEAD_C51).
+ * Heads: policy logits [A] + value [1]   (head_kind ARN_HEAD_PV),
+ *        categorical atom logits [A,51]   (head_kind ARN_HEAD_C51),
+ *        scalar action values Q [A]       (head_kind ARN_HEAD_Q), or
+ *        advantages [A] + state value [1] combined as Q = V + A - mean(A)
+ *                                         (head_kind ARN_HEAD_DUEL; one shared hidden layer).
  *
  * Two operations follow the paper's problem statement:
  *   - batched action-selection inference: one forward over all simulators'
  *     observations per environment step (section "Synchronized Sampling");
  *   - the local gradient of a training batch, step 1 of the synchronous
  *     data-parallel update (section "Synchronous Multi-GPU Optimization"), for
- *     the advantage actor-critic, PPO clipped-surrogate and Categorical-DQN
- *     objectives (section "RL Algorithm Background").
+ *     the advantage actor-critic, PPO clipped-surrogate, Categorical-DQN and
+ *     DQN (optionally Double-DQN) objectives (section "RL Algorithm Background").
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers owned by the caller and must be
@@ -41,6 +44,8 @@
  *   (fc input index = c*49 + y*7 + x), then
  *   PV : pi.W[A,512] pi.b[A] v.W[1,512] v.b[1]
  *   C51: c51.W[A*atoms,512] (row a*atoms+j) c51.b[A*atoms]
+ *   Q  : q.W[A,512] q.b[A]
+ *   DUEL: adv.W[A,512] adv.b[A] val.W[1,512] val.b[1]        (same shape as PV)
  */
 #ifndef ARN_H
 #define ARN_H
@@ -62,19 +67,20 @@ typedef enum {
     ARN_EHIP = -6        /* a HIP runtime call or launch failed */
 } arn_status;
 
-enum { ARN_HEAD_PV = 0, ARN_HEAD_C51 = 1 };
-enum { ARN_LOSS_A2C = 0, ARN_LOSS_PPO = 1, ARN_LOSS_C51 = 2 };
+enum { ARN_HEAD_PV = 0, ARN_HEAD_C51 = 1, ARN_HEAD_Q = 2, ARN_HEAD_DUEL = 3 };
+enum { ARN_LOSS_A2C = 0, ARN_LOSS_PPO = 1, ARN_LOSS_C51 = 2, ARN_LOSS_DQN = 3 };
 enum { ARN_MODE_FORWARD = 0, ARN_MODE_TRAIN = 1 };
 
 typedef struct {
-    int32_t num_actions;   /* 1..31 for PV; 1..18 for C51 */
-    int32_t head_kind;     /* ARN_HEAD_PV or ARN_HEAD_C51 */
+    int32_t num_actions;   /* 1..31 for PV, Q, DUEL; 1..18 for C51 */
+    int32_t head_kind;     /* ARN_HEAD_PV, ARN_HEAD_C51, ARN_HEAD_Q or ARN_HEAD_DUEL */
     int32_t num_atoms;     /* C51 only: 2..64 (51 in the paper's Categorical DQN) */
     float v_min, v_max;    /* C51 support end points (-10, 10) */
-    float gamma;           /* C51 discount (0.99) */
+    float gamma;           /* C51 and DQN discount (0.99) */
     float clip_eps;        /* PPO clip range (0.1) */
     float value_coef;      /* weight of mean((V-ret)^2) (0.5) */
     float entropy_coef;    /* weight of the mean-entropy bonus (0.01) */
+    int32_t double_q;      /* DQN: 1 = the online network picks the next action (Double-DQN), 0 = the target network */
 } arn_config;
 
 /* Number of fp32 entries of the flat parameter vector; 0 on a bad config. */
@@ -98,14 +104,29 @@ int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_pack
 
 /* Batched action-selection inference (section "Synchronized Sampling").
  *   obs    : uint8 [B,4,84,84] (NCHW), read only
- *   logits : PV: fp32 [B,A]; C51: fp32 [B,A,atoms].  Required.
+ *   logits : PV: fp32 [B,A]; C51: fp32 [B,A,atoms]; Q, DUEL: the action values Q [B,A].  Required.
  *   value  : PV: fp32 [B], required.  C51: expected action values Q [B,A], or NULL.
- *   probs  : PV: softmax over actions [B,A]; C51: softmax over atoms [B,A,atoms]; or NULL
- *   greedy : int32 [B] -- lowest-index argmax of the logits (PV) or of Q (C51); or NULL
+ *            Q, DUEL: max_a Q [B], required.
+ *   probs  : PV: softmax over actions [B,A]; C51: softmax over atoms [B,A,atoms]; or NULL.
+ *            Must be NULL for Q and DUEL (ARN_ESHAPE otherwise).
+ *   greedy : int32 [B] -- lowest-index argmax of the logits (PV) or of Q (C51, Q, DUEL); or NULL
  * Outputs are overwritten.  Workspace contents are undefined afterwards. */
 int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B,
                        float *logits, float *value, float *probs, int32_t *greedy,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Inference that returns actions, as the paper's sampler does (section "Synchronized Sampling": the
+ * simulator processes receive actions, not logits).  The random numbers are inputs:
+ *   u, u2  : fp32 [B], uniform in [0,1)
+ *   PV     : categorical draw by inverse CDF -- the first action whose cumulative probability exceeds
+ *            u (the last action if rounding leaves the total below u); u2 and epsilon are ignored.
+ *   C51, Q, DUEL: epsilon-greedy -- u < epsilon takes action floor(u2*A), otherwise the greedy action.
+ *   action : int32 [B], overwritten.  Required.
+ *   logp   : PV: fp32 [B] log pi(action) (what PPO later needs as old_logp), or NULL; must be NULL otherwise.
+ * Same workspace as arn_policy_forward (ARN_MODE_FORWARD). */
+int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, const float *u,
+                   const float *u2, float epsilon, int32_t *action, float *logp, void *workspace,
+                   size_t workspace_bytes, void *stream);
 
 typedef struct {
     const uint8_t *obs;        /* [B,4,84,84] */
@@ -113,10 +134,10 @@ typedef struct {
     const float *adv;          /* [B]  a2c, ppo: advantage estimates (constants) */
     const float *ret;          /* [B]  a2c, ppo: value regression targets */
     const float *old_logp;     /* [B]  ppo: log pi_old(a|s) */
-    const uint8_t *next_obs;   /* [B,4,84,84]  c51 */
-    const float *reward;       /* [B]  c51 */
-    const uint8_t *done;       /* [B]  c51: 1 = terminal transition */
-    const void *w_target_packed; /* c51: packed target-network parameters */
+    const uint8_t *next_obs;   /* [B,4,84,84]  c51, dqn */
+    const float *reward;       /* [B]  c51, dqn */
+    const uint8_t *done;       /* [B]  c51, dqn: 1 = terminal transition */
+    const void *w_target_packed; /* c51, dqn: packed target-network parameters */
 } arn_batch;
 
 /* Local gradient of one training batch (step 1 of section "Synchronous
@@ -127,9 +148,12 @@ typedef struct {
  *   c51: -mean(sum_i m_i log p_i(s,a)), m = projection onto the support of the
  *        target network's distribution for its greedy next action, shifted by
  *        reward and gamma (1-done).
+ *   dqn: mean((y - Q(s,a))^2), y = reward + gamma (1-done) Q(s', a*; target network), a* = the greedy
+ *        action of the target network on s', or of the online network when cfg->double_q is set
+ *        (one more forward pass); y is a constant.
  *   dW   : fp32 [arn_param_count], overwritten with dLoss/dW in canonical order
- *   loss : fp32 [4], overwritten: {total, policy (or cross-entropy), value mse, entropy}
- * loss_kind a2c/ppo need head PV; c51 needs head C51. */
+ *   loss : fp32 [4], overwritten: {total, policy (or cross-entropy, or squared TD error), value mse, entropy}
+ * loss_kind a2c/ppo need head PV; c51 needs head C51; dqn needs head Q or DUEL (ARN_ESHAPE otherwise). */
 int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_batch *batch, int B,
                          int loss_kind, float *dW, float *loss,
                          void *workspace, size_t workspace_bytes, void *stream);

@@ -6,21 +6,24 @@ import ctypes
 import os
 from typing import Optional
 
-ARN_HEAD_PV, ARN_HEAD_C51 = 0, 1
-ARN_LOSS_A2C, ARN_LOSS_PPO, ARN_LOSS_C51 = 0, 1, 2
+ARN_HEAD_PV, ARN_HEAD_C51, ARN_HEAD_Q, ARN_HEAD_DUEL = 0, 1, 2, 3
+ARN_LOSS_A2C, ARN_LOSS_PPO, ARN_LOSS_C51, ARN_LOSS_DQN = 0, 1, 2, 3
 ARN_MODE_FORWARD, ARN_MODE_TRAIN = 0, 1
-LOSS_KINDS = {"a2c": ARN_LOSS_A2C, "ppo": ARN_LOSS_PPO, "c51": ARN_LOSS_C51}
+LOSS_KINDS = {"a2c": ARN_LOSS_A2C, "ppo": ARN_LOSS_PPO, "c51": ARN_LOSS_C51, "dqn": ARN_LOSS_DQN}
+HEAD_KINDS = {"pv": ARN_HEAD_PV, "c51": ARN_HEAD_C51, "q": ARN_HEAD_Q, "duel": ARN_HEAD_DUEL}
 
 
 class Config(ctypes.Structure):
     """Mirror of arn_config."""
     _fields_ = [("num_actions", ctypes.c_int32), ("head_kind", ctypes.c_int32), ("num_atoms", ctypes.c_int32),
                 ("v_min", ctypes.c_float), ("v_max", ctypes.c_float), ("gamma", ctypes.c_float),
-                ("clip_eps", ctypes.c_float), ("value_coef", ctypes.c_float), ("entropy_coef", ctypes.c_float)]
+                ("clip_eps", ctypes.c_float), ("value_coef", ctypes.c_float), ("entropy_coef", ctypes.c_float),
+                ("double_q", ctypes.c_int32)]
 
     def __init__(self, num_actions=18, head_kind=ARN_HEAD_PV, num_atoms=51, v_min=-10.0, v_max=10.0, gamma=0.99,
-                 clip_eps=0.1, value_coef=0.5, entropy_coef=0.01):
-        super().__init__(num_actions, head_kind, num_atoms, v_min, v_max, gamma, clip_eps, value_coef, entropy_coef)
+                 clip_eps=0.1, value_coef=0.5, entropy_coef=0.01, double_q=0):
+        super().__init__(num_actions, head_kind, num_atoms, v_min, v_max, gamma, clip_eps, value_coef, entropy_coef,
+                         int(double_q))
 
 
 class _Batch(ctypes.Structure):
@@ -63,6 +66,8 @@ def load_library():
         lib.arn_weights_prepare.argtypes = [cp, vp, vp, vp]
         lib.arn_policy_forward.restype = ctypes.c_int
         lib.arn_policy_forward.argtypes = [cp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.arn_policy_act.restype = ctypes.c_int
+        lib.arn_policy_act.argtypes = [cp, vp, vp, ctypes.c_int, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
         lib.arn_train_step_grads.restype = ctypes.c_int
         lib.arn_train_step_grads.argtypes = [cp, vp, ctypes.POINTER(_Batch), ctypes.c_int, ctypes.c_int, vp, vp, vp,
                                              ctypes.c_size_t, vp]
@@ -126,6 +131,13 @@ def policy_forward(cfg: Config, w_packed, obs, logits, value=None, probs=None, g
     _check(load_library().arn_policy_forward(
         ctypes.byref(cfg), _ptr(w_packed), _ptr(obs), B, _ptr(logits), _ptr(value), _ptr(probs), _ptr(greedy),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "arn_policy_forward")
+
+
+def policy_act(cfg: Config, w_packed, obs, u, u2, action, logp=None, *, epsilon=0.0, workspace, stream=None) -> None:
+    B = int(obs.shape[0])
+    _check(load_library().arn_policy_act(
+        ctypes.byref(cfg), _ptr(w_packed), _ptr(obs), B, _ptr(u), _ptr(u2), float(epsilon), _ptr(action), _ptr(logp),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "arn_policy_act")
 
 
 def train_step_grads(cfg: Config, w_packed, batch: dict, loss_kind, dW, loss, *, workspace, stream=None) -> None:

@@ -22,6 +22,7 @@ using namespace arn;
 namespace {
 
 inline bool aligned(const void *p, size_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline bool known_head(int k) { return k == ARN_HEAD_PV || k == ARN_HEAD_C51 || k == ARN_HEAD_Q || k == ARN_HEAD_DUEL; }
 
 // gfx950 check, cached per device
 int check_arch() {
@@ -53,11 +54,11 @@ struct ProfScope {
         if (!on) return;
         ProfRecord r{name, nullptr, nullptr};
         if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) { on = false; return; }
-        hipEventRecord(r.start, s);
+        (void)hipEventRecord(r.start, s);
         g_prof.push_back(r);
     }
     ~ProfScope() {
-        if (on) hipEventRecord(g_prof.back().stop, s);
+        if (on) (void)hipEventRecord(g_prof.back().stop, s);
     }
 };
 
@@ -189,10 +190,10 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         FcFwd p;
         p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
         p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
-        p.to_partial = p.ksplit > 1 || d.head == ARN_HEAD_PV;
+        p.to_partial = p.ksplit > 1 || d.small;
         split ? launch_nt_split("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s)
               : launch_nt("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s);
-        if (p.ksplit > 1 && d.head != ARN_HEAD_PV) {
+        if (p.ksplit > 1 && !d.small) {
             ProfScope ps("fc_finish", s);
             const long total = (long)B * HID;
             hipLaunchKernelGGL(fc_finish_kernel, dim3(cdiv(total / 4, 256)), dim3(256), 0, s, p.partial, p.ksplit,
@@ -212,6 +213,7 @@ PvHeadArgs pv_head_args(const Dims &d, const Packed &w, int B, char *ws, const W
     PvHeadArgs p = {};
     p.partial = (const float *)(ws + o.fcp); p.ks = fc_ksplit(B); p.bfc = w.bfc;
     p.wh = w.wh; p.whl = w.whl; p.bh = w.bh; p.B = B; p.A = d.A;
+    p.qmode = d.head == ARN_HEAD_Q ? 1 : d.head == ARN_HEAD_DUEL ? 2 : 0;
     return p;
 }
 
@@ -228,7 +230,7 @@ int check_update(size_t n, const arn_config *cfg, const void *w_packed, bool *re
     *repack = w_packed != nullptr;
     if (*repack) {
         if (!cfg) return ARN_EINVAL;
-        if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+        if (!known_head(cfg->head_kind)) return ARN_EKIND;
         *d_out = make_dims(cfg);
         if (!d_out->ok) return ARN_ESHAPE;
         if (n != param_offsets(*d_out).total) return ARN_ESHAPE;
@@ -274,7 +276,7 @@ size_t arn_workspace_bytes(const arn_config *cfg, int B, int mode) {
 
 int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_packed, void *stream) {
     if (!cfg) return ARN_EINVAL;
-    if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+    if (!known_head(cfg->head_kind)) return ARN_EKIND;
     const Dims d = make_dims(cfg);
     if (!d.ok) return ARN_ESHAPE;
     if (!aligned(w_fp32, 16) || !aligned(w_packed, 256)) return ARN_EINVAL;
@@ -288,21 +290,22 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
                        float *value, float *probs, int32_t *greedy, void *workspace, size_t workspace_bytes,
                        void *stream) {
     if (!cfg || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
-    if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
+    if (!known_head(cfg->head_kind)) return ARN_EKIND;
     const Dims d = make_dims(cfg);
     if (!d.ok) return ARN_ESHAPE;
     if (!aligned(w_packed, 256) || !aligned(obs, 16) || !aligned(logits, 16) || !aligned(workspace, 256))
         return ARN_EINVAL;
-    if (d.head == ARN_HEAD_PV && !aligned(value, 16)) return ARN_EINVAL;
+    if (d.small && !aligned(value, 16)) return ARN_EINVAL;
     if ((value && !aligned(value, 16)) || (probs && !aligned(probs, 16)) || (greedy && !aligned(greedy, 16)))
         return ARN_EINVAL;
+    if (d.qhead && probs) return ARN_ESHAPE;
     const Workspace o = make_workspace(d, B, ARN_MODE_FORWARD);
     if (workspace_bytes < o.total) return ARN_EWORKSPACE;
     if (int e = check_arch()) return e;
     hipStream_t s = (hipStream_t)stream;
     const Packed w = view_packed(w_packed, d);
     forward_launches(d, w, obs, B, (char *)workspace, o, logits, false, s);
-    if (d.head == ARN_HEAD_PV) {
+    if (d.small) {
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, (char *)workspace, o);
         p.logits = logits; p.value = value; p.probs = probs; p.greedy = greedy;
@@ -316,18 +319,57 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     return launched();
 }
 
+int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, const float *u,
+                   const float *u2, float epsilon, int32_t *action, float *logp, void *workspace,
+                   size_t workspace_bytes, void *stream) {
+    if (!cfg || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
+    if (!known_head(cfg->head_kind)) return ARN_EKIND;
+    const Dims d = make_dims(cfg);
+    if (!d.ok) return ARN_ESHAPE;
+    if (!aligned(w_packed, 256) || !aligned(obs, 16) || !aligned(u, 16) || !aligned(action, 16) ||
+        !aligned(workspace, 256))
+        return ARN_EINVAL;
+    const bool policy = d.head == ARN_HEAD_PV;
+    if (!policy && (!aligned(u2, 16) || !(epsilon >= 0.f && epsilon <= 1.f))) return ARN_EINVAL;
+    if (logp && (!policy || !aligned(logp, 16))) return policy ? ARN_EINVAL : ARN_ESHAPE;
+    const Workspace o = make_workspace(d, B, ARN_MODE_FORWARD);
+    if (workspace_bytes < o.total) return ARN_EWORKSPACE;
+    if (int e = check_arch()) return e;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const Packed w = view_packed(w_packed, d);
+    float *z = (float *)(ws + o.z);   // categorical head only
+    forward_launches(d, w, obs, B, ws, o, z, false, s);
+    if (d.small) {
+        ProfScope ps("pv_head", s);
+        PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+        p.u = u; p.u2 = u2; p.epsilon = epsilon; p.act_out = action; p.logp_out = logp;
+        hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, PVH_ROWS)), dim3(PVH_THREADS), 0, s, p);
+    } else {
+        ProfScope ps("c51_dist", s);
+        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, z, B, d.A, d.atoms,
+                           cfg->v_min, cfg->v_max, cfg->gamma, (const float *)nullptr, (const uint8_t *)nullptr,
+                           (float *)nullptr, (float *)nullptr, action, (float *)nullptr);
+        hipLaunchKernelGGL(epsilon_greedy_kernel, dim3(cdiv(B, 256)), dim3(256), 0, s, action, u, u2, epsilon, d.A, B);
+    }
+    return launched();
+}
+
 int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_batch *batch, int B, int loss_kind,
                          float *dW, float *loss, void *workspace, size_t workspace_bytes, void *stream) {
     if (!cfg || !batch || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
-    if (cfg->head_kind != ARN_HEAD_PV && cfg->head_kind != ARN_HEAD_C51) return ARN_EKIND;
-    if (loss_kind != ARN_LOSS_A2C && loss_kind != ARN_LOSS_PPO && loss_kind != ARN_LOSS_C51) return ARN_EKIND;
+    if (!known_head(cfg->head_kind)) return ARN_EKIND;
+    if (loss_kind != ARN_LOSS_A2C && loss_kind != ARN_LOSS_PPO && loss_kind != ARN_LOSS_C51 &&
+        loss_kind != ARN_LOSS_DQN)
+        return ARN_EKIND;
     const Dims d = make_dims(cfg);
     if (!d.ok) return ARN_ESHAPE;
     if ((loss_kind == ARN_LOSS_C51) != (d.head == ARN_HEAD_C51)) return ARN_ESHAPE;
+    if ((loss_kind == ARN_LOSS_DQN) != d.qhead) return ARN_ESHAPE;
     if (!aligned(w_packed, 256) || !aligned(batch->obs, 16) || !aligned(batch->action, 16) || !aligned(dW, 16) ||
         !aligned(loss, 16) || !aligned(workspace, 256))
         return ARN_EINVAL;
-    if (loss_kind != ARN_LOSS_C51) {
+    if (loss_kind == ARN_LOSS_A2C || loss_kind == ARN_LOSS_PPO) {
         if (!aligned(batch->adv, 16) || !aligned(batch->ret, 16)) return ARN_EINVAL;
         if (loss_kind == ARN_LOSS_PPO && !aligned(batch->old_logp, 16)) return ARN_EINVAL;
     } else {
@@ -369,13 +411,40 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
                            d.atoms, d.NHP, dz, lossp);
     } else {
+        const Packed *wt = nullptr;
+        Packed wt_view;
+        if (loss_kind == ARN_LOSS_DQN) {
+            // target network on the next states -> Q(s', .); with Double-DQN the online network on the next
+            // states -> its greedy action.  The activations of these passes are then overwritten.
+            wt_view = view_packed(batch->w_target_packed, d);
+            wt = &wt_view;
+            forward_launches(d, *wt, batch->next_obs, B, ws, o, nullptr, false, s);
+            {
+                ProfScope ps("q_target", s);
+                PvHeadArgs p = pv_head_args(d, *wt, B, ws, o);
+                p.logits = (float *)(ws + o.qt);
+                hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
+            }
+            if (cfg->double_q) {
+                forward_launches(d, w, batch->next_obs, B, ws, o, nullptr, false, s);
+                ProfScope ps("q_select", s);
+                PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+                p.greedy = (int32_t *)(ws + o.astar);
+                hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
+            }
+        }
         forward_launches(d, w, batch->obs, B, ws, o, nullptr, true, s);
         // fc finish, head, objective, dz and the head's input gradient d(pre_fc) in one kernel
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, ws, o);
         p.action = batch->action; p.adv = batch->adv; p.ret = batch->ret; p.old_logp = batch->old_logp;
-        p.ppo = loss_kind == ARN_LOSS_PPO ? 1 : 0;
+        p.objective = loss_kind == ARN_LOSS_PPO ? 1 : loss_kind == ARN_LOSS_DQN ? 2 : 0;
         p.clip_eps = cfg->clip_eps; p.value_coef = cfg->value_coef; p.entropy_coef = cfg->entropy_coef;
+        if (loss_kind == ARN_LOSS_DQN) {
+            p.q_next = (const float *)(ws + o.qt);
+            p.a_star = cfg->double_q ? (const int32_t *)(ws + o.astar) : nullptr;
+            p.reward = batch->reward; p.done = batch->done; p.gamma = cfg->gamma;
+        }
         p.whd = w.whd; p.h = h; p.dz = dz; p.dph = dph; p.lossp = lossp;
         hipLaunchKernelGGL(pv_head_kernel<true>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
     }
@@ -389,15 +458,15 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     int nfork = 0;
     auto fork = [&]() {   // work queued on s2 from here on sees everything queued on s so far
         if (!ss) return;
-        hipEventRecord(ss->fork[nfork], s);
-        hipStreamWaitEvent(s2, ss->fork[nfork], 0);
+        (void)hipEventRecord(ss->fork[nfork], s);
+        (void)hipStreamWaitEvent(s2, ss->fork[nfork], 0);
         ++nfork;
     };
     fork();   // dz (and, for the policy/value head, d(pre_fc))
     {
         // the reported loss values are off the critical path: block partial sums are added on the side stream
         ProfScope ps("loss_finalize", s2);
-        const bool pv = loss_kind != ARN_LOSS_C51;
+        const bool pv = loss_kind == ARN_LOSS_A2C || loss_kind == ARN_LOSS_PPO;
         hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s2, lossp, lblocks, B,
                            pv ? cfg->value_coef : 0.f, pv ? cfg->entropy_coef : 0.f, loss);
     }
@@ -474,8 +543,8 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
     }
     if (ss) {   // join: the caller's stream continues only after the side stream's work
-        hipEventRecord(ss->join, s2);
-        hipStreamWaitEvent(s, ss->join, 0);
+        (void)hipEventRecord(ss->join, s2);
+        (void)hipStreamWaitEvent(s, ss->join, 0);
     }
     return launched();
 }
@@ -585,15 +654,15 @@ int arn_profile_collect(char *names, float *ms, int cap) {
     int n = 0;
     for (const ProfRecord &r : g_prof) {
         float t = 0.f;
-        if (r.stop && hipEventSynchronize(r.stop) == hipSuccess) hipEventElapsedTime(&t, r.start, r.stop);
+        if (r.stop && hipEventSynchronize(r.stop) == hipSuccess) (void)hipEventElapsedTime(&t, r.start, r.stop);
         if (n < cap && names && ms) {
             strncpy(names + (size_t)n * 32, r.name, 31);
             names[(size_t)n * 32 + 31] = 0;
             ms[n] = t;
             ++n;
         }
-        if (r.start) hipEventDestroy(r.start);
-        if (r.stop) hipEventDestroy(r.stop);
+        if (r.start) (void)hipEventDestroy(r.start);
+        if (r.stop) (void)hipEventDestroy(r.stop);
     }
     g_prof.clear();
     return n;

@@ -26,8 +26,11 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Dims {
     int A = 0, head = 0, atoms = 0;
-    int NH = 0;    // real head rows: A+1 (PV) or A*atoms (C51)
+    int NH = 0;    // real head rows: A+1 (PV, DUEL), A (Q) or A*atoms (C51)
     int NHP = 0;   // head rows padded to a multiple of 64 (MFMA k-tile of the head dgrad)
+    bool small = false;   // at most 32 head rows: the fused head kernel follows the fc GEMM (PV, Q, DUEL)
+    bool vrow = false;    // the row after the A action rows is a state value (PV, DUEL)
+    bool qhead = false;   // the head outputs are action values (Q, DUEL)
     bool ok = false;
 };
 
@@ -36,10 +39,13 @@ inline Dims make_dims(const arn_config *c) {
     if (!c) return d;
     d.A = c->num_actions;
     d.head = c->head_kind;
-    if (d.head == ARN_HEAD_PV) {
+    if (d.head == ARN_HEAD_PV || d.head == ARN_HEAD_Q || d.head == ARN_HEAD_DUEL) {
         if (d.A < 1 || d.A > 31) return d;
         d.atoms = 1;
-        d.NH = d.A + 1;
+        d.small = true;
+        d.vrow = d.head != ARN_HEAD_Q;
+        d.qhead = d.head != ARN_HEAD_PV;
+        d.NH = d.A + (d.vrow ? 1 : 0);
     } else if (d.head == ARN_HEAD_C51) {
         d.atoms = c->num_atoms;
         if (d.A < 1 || d.A > 18 || d.atoms < 2 || d.atoms > 64) return d;
@@ -68,7 +74,7 @@ inline ParamOffsets param_offsets(const Dims &d) {
     o.b3 = p; p += C3;
     o.wfc = p; p += (size_t)HID * FEAT;
     o.bfc = p; p += HID;
-    if (d.head == ARN_HEAD_PV) {
+    if (d.vrow) {
         o.wh = p; p += (size_t)d.A * HID;
         o.bh = p; p += d.A;
         o.wv = p; p += HID;
@@ -171,6 +177,7 @@ struct Workspace {
     size_t hp;                          // fp32 [HEAD_KSPLIT][B][32] partial sums of the policy/value head GEMM
     size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
+    size_t qt, astar;                   // DQN: target-net Q(s',.) fp32 [B][A]; Double-DQN: online greedy action on s' int32 [B]
     size_t m1, m2, m3;                  // ReLU sign bits of act1..3 (bit e&7 of byte e>>3, NHWC element e), written by the forward
     size_t dz, dph, dp3, dp2, dp1;      // bf16 gradients at pre-activations
     size_t lossp;                       // fp32 [blocks][4] partial loss sums
@@ -178,7 +185,7 @@ struct Workspace {
     size_t total;
 };
 inline int loss_blocks(const Dims &d, int B) {
-    return d.head == ARN_HEAD_PV ? (B + LOSS_BLOCK - 1) / LOSS_BLOCK : (B + C51_WAVES - 1) / C51_WAVES;
+    return d.small ? (B + LOSS_BLOCK - 1) / LOSS_BLOCK : (B + C51_WAVES - 1) / C51_WAVES;
 }
 inline Workspace make_workspace(const Dims &d, int B, int mode) {
     Workspace w{};
@@ -194,11 +201,17 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     w.a3l = take(b * FEAT * 2);
     w.hl = take(b * HID * 2);
     // the fused policy/value head kernel always reads fp32 partials; the categorical path only when k is split
-    w.fcp = take((size_t)(fc_ksplit(B) > 1 || d.head == ARN_HEAD_PV ? fc_ksplit(B) : 0) * b * HID * 4);
+    w.fcp = take((size_t)(fc_ksplit(B) > 1 || d.small ? fc_ksplit(B) : 0) * b * HID * 4);
     w.hp = take(0);
+    // categorical head: atom logits of arn_policy_act (arn_policy_forward writes them to its `logits` argument)
+    if (mode == ARN_MODE_FORWARD) w.z = take(d.small ? 0 : b * (size_t)d.NH * 4);
     if (mode == ARN_MODE_TRAIN) {
-        w.z = take(d.head == ARN_HEAD_PV ? 0 : b * (size_t)d.NH * 4);
+        w.z = take(d.small ? 0 : b * (size_t)d.NH * 4);
         w.zv = 0;
+        if (d.qhead) {
+            w.qt = take(b * (size_t)d.A * 4);
+            w.astar = take(b * 4);
+        }
         if (d.head == ARN_HEAD_C51) {
             w.ztgt = take(b * (size_t)d.NH * 4);
             w.m = take(b * (size_t)d.atoms * 4);

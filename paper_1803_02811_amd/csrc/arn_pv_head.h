@@ -4,6 +4,11 @@
 //   3. inference: logits, value, softmax, lowest-index greedy action                    (section "Synchronized Sampling")
 //      training:  A2C / PPO objective terms and their gradient dz at the head outputs   (section "RL Algorithm Background")
 //   4. training: d(pre_fc) = (W_head^T dz) * [h > 0]    (single bf16 MFMA, contraction over the 32 head rows)
+// The same kernel serves the action-value heads (scalar Q rows, or advantage rows + a value row combined as
+// Q = V + A - mean(A)): inference then returns Q, max Q and the greedy action; training evaluates the DQN
+// objective mean((y - Q(s,a))^2) with y from the target network's values on the next state (section "RL
+// Algorithm Background").  With random numbers as inputs the inference variant also draws the action
+// (categorical by inverse CDF, or epsilon-greedy), as the paper's sampler returns actions, not logits.
 // The head is tiny (at most 32 rows); as separate launches these steps cost several times their arithmetic in
 // launch latency and in trips of h through HBM, and they all sit on the critical path between the forward
 // and the backward pass.
@@ -33,13 +38,27 @@ struct PvHeadArgs {
     const __bf16 *wh, *whl; // head weights [64][512] hi / lo; rows A+1.. are zero
     const float *bh;        // [64] head bias (policy rows then the value row)
     int B, A;
-    // inference outputs
+    int qmode;              // 0: policy logits + value row; 1: scalar Q rows; 2: advantage rows + value row -> Q
+    // inference outputs (each may be null)
     float *logits, *value, *probs;
     int32_t *greedy;
+    // action draw (inference): u, u2 uniform [0,1) per sample; qmode 0: categorical by inverse CDF with u;
+    // otherwise epsilon-greedy (u < epsilon: floor(u2 * A)); act_out null = no draw
+    const float *u, *u2;
+    float epsilon;
+    int32_t *act_out;
+    float *logp_out;        // qmode 0: log pi(drawn action), or null
     // training inputs
     const int32_t *action;
     const float *adv, *ret, *old_logp;
-    int ppo;
+    int objective;          // 0 a2c, 1 ppo, 2 dqn
+    // dqn: target-network values on the next state [B][A]; the action that is bootstrapped from (null: the
+    // argmax of q_next itself); reward, done, discount
+    const float *q_next;
+    const int32_t *a_star;
+    const float *reward;
+    const uint8_t *done;
+    float gamma;
     float clip_eps, value_coef, entropy_coef;
     const __bf16 *whd;      // head weights for the input gradient [512][64] (k = head row contiguous)
     // training outputs
@@ -52,6 +71,19 @@ struct PvHeadArgs {
 __device__ __forceinline__ float group16_sum(float v) {   // same bits in all 16 lanes of the group
 #pragma unroll
     for (int o = 8; o >= 1; o >>= 1) v += __shfl_xor(v, o, 16);
+    return v;
+}
+__device__ __forceinline__ float group16_scan(float v, int c) {   // inclusive prefix sum over the 16 lanes of the group
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+        const float t = __shfl_up(v, o, 16);
+        if (c >= o) v += t;
+    }
+    return v;
+}
+__device__ __forceinline__ int group16_min(int v) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o, 16));
     return v;
 }
 __device__ __forceinline__ float group16_max(float v) {
@@ -94,9 +126,14 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
             wd[t] = *reinterpret_cast<const u32x4 *>(p.whd + (size_t)((wave * 8 + t) * 16 + fi) * 64 + fg * 8);
         if (live) {
             a = p.action[n];
-            ad = p.adv[n];
-            rt = p.ret[n];
-            if (p.ppo) olp = p.old_logp[n];
+            if (p.objective == 2) {
+                ad = p.reward[n];                       // dqn: reward
+                rt = p.done[n] ? 0.f : p.gamma;          //      discount of the bootstrap term
+            } else {
+                ad = p.adv[n];
+                rt = p.ret[n];
+                if (p.objective == 1) olp = p.old_logp[n];
+            }
         }
     }
     const float bz0 = p.bh[c], bz1 = p.bh[c + 16];
@@ -163,66 +200,129 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         z0 += a0; z1 += a1;
     }
     const int A = p.A;
-    // value = head row A
+    const bool on0 = c < A, on1 = c + 16 < A;
+    // value = head row A (policy/value and dueling heads)
     const float vsel = A < 16 ? z0 : z1;
     const float v = __shfl(vsel, A & 15, 16);
-    const bool on0 = c < A, on1 = c + 16 < A;
+    if (p.qmode == 2) {   // Q = V + A - mean(A)
+        const float mean = group16_sum((on0 ? z0 : 0.f) + (on1 ? z1 : 0.f)) / (float)A;
+        z0 = v + z0 - mean;
+        z1 = v + z1 - mean;
+    }
     const float x0 = on0 ? z0 : -INFINITY, x1 = on1 ? z1 : -INFINITY;
     const float mx = group16_max(fmaxf(x0, x1));
-    const float e0 = on0 ? expf(x0 - mx) : 0.f, e1 = on1 ? expf(x1 - mx) : 0.f;
-    const float s = group16_sum(e0 + e1);
+    // lowest index among the maxima: the maximum is known, take the smallest index that attains it
+    const int arg = group16_min(x0 == mx ? c : (x1 == mx ? c + 16 : 64));
 
     if constexpr (!TRAIN) {
+        const bool policy = p.qmode == 0;
+        float e0 = 0.f, e1 = 0.f, s = 1.f;
+        if (policy) {
+            e0 = on0 ? expf(x0 - mx) : 0.f;
+            e1 = on1 ? expf(x1 - mx) : 0.f;
+            s = group16_sum(e0 + e1);
+        }
         if (live) {
-            if (on0) p.logits[(size_t)n * A + c] = z0;
-            if (on1) p.logits[(size_t)n * A + c + 16] = z1;
-            if (c == 0) p.value[n] = v;
-            if (p.probs) {
+            if (p.logits) {
+                if (on0) p.logits[(size_t)n * A + c] = z0;
+                if (on1) p.logits[(size_t)n * A + c + 16] = z1;
+            }
+            if (p.value && c == 0) p.value[n] = policy ? v : mx;
+            if (p.probs && policy) {
                 const float inv = 1.f / s;
                 if (on0) p.probs[(size_t)n * A + c] = e0 * inv;
                 if (on1) p.probs[(size_t)n * A + c + 16] = e1 * inv;
             }
+            if (p.greedy && c == 0) p.greedy[n] = arg;
         }
-        if (p.greedy) {
-            // lowest index among the maxima: the maximum is known, take the smallest index that attains it
-            int idx = x0 == mx ? c : (x1 == mx ? c + 16 : 64);
-#pragma unroll
-            for (int o = 8; o >= 1; o >>= 1) idx = min(idx, __shfl_xor(idx, o, 16));
-            if (live && c == 0) p.greedy[n] = idx;
+        if (p.act_out) {
+            const float uu = live ? p.u[n] : 0.f;
+            int act;
+            if (policy) {
+                // inverse CDF on the unnormalised weights: first k with sum_{j<=k} e_j > u * s
+                const float c0 = group16_scan(e0, c);
+                const float tot0 = __shfl(c0, 15, 16);
+                const float c1 = tot0 + group16_scan(e1, c);
+                const float thr = uu * s;
+                act = group16_min(on0 && c0 > thr ? c : (on1 && c1 > thr ? c + 16 : 64));
+                act = act < A ? act : A - 1;
+                if (p.logp_out) {
+                    const float lse = mx + logf(s);
+                    const float lp = group16_sum((c == act ? x0 - lse : 0.f) + (c + 16 == act ? x1 - lse : 0.f));
+                    if (live && c == 0) p.logp_out[n] = lp;
+                }
+            } else {
+                const int rnd = min((int)((double)(live ? p.u2[n] : 0.f) * (double)A), A - 1);   // exact product
+                act = uu < p.epsilon ? rnd : arg;
+            }
+            if (live && c == 0) p.act_out[n] = act;
         }
         return;
     } else {
         // ---- 3. objective terms and the gradient at the head outputs ----
-        const float lse = mx + logf(s);
-        const float lp0 = x0 - lse, lp1 = x1 - lse;                 // log-probabilities (-inf where off)
-        const float q0 = on0 ? expf(lp0) : 0.f, q1 = on1 ? expf(lp1) : 0.f;
-        const float H = -group16_sum((on0 ? q0 * lp0 : 0.f) + (on1 ? q1 * lp1 : 0.f));
-        const float lpa = group16_sum((c == a ? lp0 : 0.f) + (c + 16 == a ? lp1 : 0.f));
-        float pol, w;   // w = d(surrogate)/d(log pi(a))
-        if (p.ppo) {
-            const float rho = expf(lpa - olp);
-            const float clipped = fminf(fmaxf(rho, 1.f - p.clip_eps), 1.f + p.clip_eps);
-            pol = -fminf(rho * ad, clipped * ad);
-            const bool active = (ad >= 0.f && rho <= 1.f + p.clip_eps) || (ad < 0.f && rho >= 1.f - p.clip_eps);
-            w = active ? ad * rho : 0.f;
-        } else {
-            pol = -lpa * ad;
-            w = ad;
-        }
-        const float dv = v - rt;
         const float invB = 1.f / (float)p.B;
-        float g0 = on0 ? (-w * ((c == a ? 1.f : 0.f) - q0) + p.entropy_coef * q0 * (lp0 + H)) * invB : 0.f;
-        float g1 = on1 ? (-w * ((c + 16 == a ? 1.f : 0.f) - q1) + p.entropy_coef * q1 * (lp1 + H)) * invB : 0.f;
-        const float gv = p.value_coef * 2.f * dv * invB;
-        if (c == A) g0 = gv;
-        if (c + 16 == A) g1 = gv;
+        float g0, g1, t0 = 0.f, t1 = 0.f, t2 = 0.f;   // dz of the lane's two rows; the sample's three loss terms
+        if (p.objective == 2) {
+            // DQN: y = r + gamma (1 - done) Q(s', a*; target network); ad = reward, rt = discount
+            float qn0 = on0 && live ? p.q_next[(size_t)n * A + c] : -INFINITY;
+            float qn1 = on1 && live ? p.q_next[(size_t)n * A + c + 16] : -INFINITY;
+            int as;
+            if (p.a_star) {
+                as = live ? p.a_star[n] : 0;
+            } else {
+                const float qm = group16_max(fmaxf(qn0, qn1));
+                as = group16_min(qn0 == qm ? c : (qn1 == qm ? c + 16 : 64));
+            }
+            const float boot = group16_sum((c == as && on0 ? qn0 : 0.f) + (c + 16 == as && on1 ? qn1 : 0.f));
+            const float y = ad + rt * (live ? boot : 0.f);
+            const float qa = group16_sum((c == a && on0 ? z0 : 0.f) + (c + 16 == a && on1 ? z1 : 0.f));
+            const float td = qa - y;
+            t0 = td * td;
+            const float g = 2.f * td * invB;
+            if (p.qmode == 2) {   // through Q = V + A - mean(A): dA_k = g (delta_ka - 1/A), dV = g
+                const float share = g / (float)A;
+                g0 = on0 ? (c == a ? g : 0.f) - share : 0.f;
+                g1 = on1 ? (c + 16 == a ? g : 0.f) - share : 0.f;
+                if (c == A) g0 = g;
+                if (c + 16 == A) g1 = g;
+            } else {
+                g0 = on0 && c == a ? g : 0.f;
+                g1 = on1 && c + 16 == a ? g : 0.f;
+            }
+        } else {
+            const float e0 = on0 ? expf(x0 - mx) : 0.f, e1 = on1 ? expf(x1 - mx) : 0.f;
+            const float s = group16_sum(e0 + e1);
+            const float lse = mx + logf(s);
+            const float lp0 = x0 - lse, lp1 = x1 - lse;                 // log-probabilities (-inf where off)
+            const float q0 = on0 ? expf(lp0) : 0.f, q1 = on1 ? expf(lp1) : 0.f;
+            const float H = -group16_sum((on0 ? q0 * lp0 : 0.f) + (on1 ? q1 * lp1 : 0.f));
+            const float lpa = group16_sum((c == a ? lp0 : 0.f) + (c + 16 == a ? lp1 : 0.f));
+            float pol, w;   // w = d(surrogate)/d(log pi(a))
+            if (p.objective == 1) {
+                const float rho = expf(lpa - olp);
+                const float clipped = fminf(fmaxf(rho, 1.f - p.clip_eps), 1.f + p.clip_eps);
+                pol = -fminf(rho * ad, clipped * ad);
+                const bool active = (ad >= 0.f && rho <= 1.f + p.clip_eps) || (ad < 0.f && rho >= 1.f - p.clip_eps);
+                w = active ? ad * rho : 0.f;
+            } else {
+                pol = -lpa * ad;
+                w = ad;
+            }
+            const float dv = v - rt;
+            g0 = on0 ? (-w * ((c == a ? 1.f : 0.f) - q0) + p.entropy_coef * q0 * (lp0 + H)) * invB : 0.f;
+            g1 = on1 ? (-w * ((c + 16 == a ? 1.f : 0.f) - q1) + p.entropy_coef * q1 * (lp1 + H)) * invB : 0.f;
+            const float gv = p.value_coef * 2.f * dv * invB;
+            if (c == A) g0 = gv;
+            if (c + 16 == A) g1 = gv;
+            t0 = pol; t1 = dv * dv; t2 = H;
+        }
         if (!live) g0 = g1 = 0.f;
         sDz[srow * PVH_DZS + c] = (__bf16)g0;
         sDz[srow * PVH_DZS + c + 16] = (__bf16)g1;
         if (c == 0) {
-            sRed[0][srow] = live ? pol : 0.f;
-            sRed[1][srow] = live ? dv * dv : 0.f;
-            sRed[2][srow] = live ? H : 0.f;
+            sRed[0][srow] = live ? t0 : 0.f;
+            sRed[1][srow] = live ? t1 : 0.f;
+            sRed[2][srow] = live ? t2 : 0.f;
         }
         __syncthreads();
         if (tid < 3) {   // block partial sums in sample order

@@ -36,7 +36,7 @@ struct MapFcFwd {      // packed [n][pos*64+c]  <-  Wfc[n][c*49+pos]
         return off + (long)n * FEAT + c * P3 + pos;
     }
 };
-struct MapHeadRow {    // head row r of the packed head -> offset of its weight row / bias, or -1
+struct MapHeadRow {    // head row r of the packed head -> offset of its weight row / bias, or -1 (pv: A action rows then a value row)
     long wh, wv, bh, bv;
     int A, NH, pv;
     __device__ long wrow(int r) const {
@@ -51,7 +51,7 @@ struct MapHeadRow {    // head row r of the packed head -> offset of its weight 
 inline MapHeadRow head_rows(const Dims &d, const ParamOffsets &po) {
     MapHeadRow h;
     h.wh = (long)po.wh; h.wv = (long)po.wv; h.bh = (long)po.bh; h.bv = (long)po.bv;
-    h.A = d.A; h.NH = d.NH; h.pv = d.head == ARN_HEAD_PV;
+    h.A = d.A; h.NH = d.NH; h.pv = d.vrow;
     return h;
 }
 struct MapHeadFwd {    // packed [r][j]
@@ -251,6 +251,17 @@ __global__ __launch_bounds__(64) void loss_finalize_kernel(const float *__restri
     loss[1] = s0;
     loss[2] = s1;
     loss[3] = s2;
+}
+
+// epsilon-greedy on top of a greedy action: u < epsilon takes the uniformly random action floor(u2 * A)
+__global__ void epsilon_greedy_kernel(int32_t *__restrict__ action, const float *__restrict__ u,
+                                      const float *__restrict__ u2, float epsilon, int A, int B) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= B) return;
+    if (u[n] < epsilon) {
+        const int r = (int)((double)u2[n] * (double)A);   // exact product of an fp32 and a small integer
+        action[n] = r < A - 1 ? r : A - 1;
+    }
 }
 
 // ------------------------- Categorical DQN target ---------------------------

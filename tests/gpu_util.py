@@ -25,7 +25,7 @@ class GpuNet:
 
     def __init__(self, num_actions, head, flat_params, num_atoms=51, **hyper):
         self.head = head
-        self.cfg = arn.Config(num_actions, arn.ARN_HEAD_PV if head == "pv" else arn.ARN_HEAD_C51, num_atoms, **hyper)
+        self.cfg = arn.Config(num_actions, arn.HEAD_KINDS[head], num_atoms, **hyper)
         self.A, self.atoms = num_actions, num_atoms
         self.nparam = arn.param_count(self.cfg)
         assert self.nparam == flat_params.size
@@ -50,6 +50,12 @@ class GpuNet:
         obs = torch.from_numpy(obs_np).to(DEV)
         ws = self.workspace(B, arn.ARN_MODE_FORWARD)
         greedy = torch.empty(B, dtype=torch.int32, device=DEV)
+        if self.head in ("q", "duel"):
+            logits = torch.empty(B, self.A, dtype=torch.float32, device=DEV)
+            value = torch.empty(B, dtype=torch.float32, device=DEV)
+            arn.policy_forward(self.cfg, self.packed, obs, logits, value, None, greedy, workspace=ws)
+            torch.cuda.synchronize()
+            return dict(q=logits.cpu().numpy(), value=value.cpu().numpy(), greedy=greedy.cpu().numpy())
         if self.head == "pv":
             logits = torch.empty(B, self.A, dtype=torch.float32, device=DEV)
             value = torch.empty(B, dtype=torch.float32, device=DEV)
@@ -62,6 +68,17 @@ class GpuNet:
         torch.cuda.synchronize()
         return dict(logits=logits.cpu().numpy(), value=value.cpu().numpy(), probs=probs.cpu().numpy(),
                     greedy=greedy.cpu().numpy())
+
+    def act(self, obs_np, u, u2, epsilon=0.0, want_logp=False):
+        B = obs_np.shape[0]
+        obs = torch.from_numpy(obs_np).to(DEV)
+        ws = self.workspace(B, arn.ARN_MODE_FORWARD)
+        action = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+        logp = torch.empty(B, dtype=torch.float32, device=DEV) if want_logp else None
+        arn.policy_act(self.cfg, self.packed, obs, torch.from_numpy(u).to(DEV), torch.from_numpy(u2).to(DEV), action,
+                       logp, epsilon=epsilon, workspace=ws)
+        torch.cuda.synchronize()
+        return action.cpu().numpy(), (logp.cpu().numpy() if want_logp else None)
 
     def device_batch(self, batch_np, target_packed=None):
         out = {}

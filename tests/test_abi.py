@@ -83,6 +83,37 @@ def test_argument_errors_are_reported_on_the_host(lib):
     assert "workspace" in arn.status_string(EWORKSPACE)
 
 
+def test_action_value_heads_and_act_argument_errors(lib):
+    q = arn.Config(18, arn.ARN_HEAD_Q)
+    duel = arn.Config(18, arn.ARN_HEAD_DUEL)
+    pv = arn.Config(18, arn.ARN_HEAD_PV)
+    assert arn.param_count(q) == orc.param_count(orc.NetSpec(18, "q")) == 1_693_362
+    assert arn.param_count(duel) == arn.param_count(pv) == orc.param_count(orc.NetSpec(18, "duel"))
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    EINVAL, ESHAPE, EKIND = -1, -2, -3
+    big = 1 << 40
+    cq, cp = ctypes.byref(q), ctypes.byref(pv)
+    # action-value heads have no probabilities
+    assert lib.arn_policy_forward(cq, fake, fake, 4, fake, fake, fake, None, fake, big, None) == ESHAPE
+    assert lib.arn_policy_forward(cq, fake, fake, 4, fake, None, None, None, fake, big, None) == EINVAL   # max Q required
+    # dqn needs an action-value head and vice versa
+    batch = arn.binding._Batch(*([0x1000] * 9))
+    b = ctypes.byref(batch)
+    assert lib.arn_train_step_grads(cp, fake, b, 4, arn.ARN_LOSS_DQN, fake, fake, fake, big, None) == ESHAPE
+    assert lib.arn_train_step_grads(cq, fake, b, 4, arn.ARN_LOSS_A2C, fake, fake, fake, big, None) == ESHAPE
+    nonext = arn.binding._Batch(*([0x1000] * 5 + [None] * 4))
+    assert lib.arn_train_step_grads(cq, fake, ctypes.byref(nonext), 4, arn.ARN_LOSS_DQN, fake, fake, fake, big,
+                                    None) == EINVAL
+    # arn_policy_act
+    assert lib.arn_policy_act(cp, fake, fake, 4, None, fake, 0.0, fake, None, fake, big, None) == EINVAL      # u
+    assert lib.arn_policy_act(cp, fake, fake, 4, fake, None, 0.0, None, None, fake, big, None) == EINVAL      # action
+    assert lib.arn_policy_act(cq, fake, fake, 4, fake, None, 0.1, fake, None, fake, big, None) == EINVAL      # u2
+    assert lib.arn_policy_act(cq, fake, fake, 4, fake, fake, 1.5, fake, None, fake, big, None) == EINVAL      # epsilon
+    assert lib.arn_policy_act(cq, fake, fake, 4, fake, fake, 0.1, fake, fake, fake, big, None) == ESHAPE      # logp
+    assert lib.arn_policy_act(cp, fake, fake, 4, fake, None, 0.0, fake, odd, fake, big, None) == EINVAL
+    assert lib.arn_policy_act(cp, fake, fake, 4, fake, None, 0.0, fake, None, fake, 16, None) == -4
+
+
 def test_update_rule_argument_errors(lib):
     cfg = arn.Config(18, arn.ARN_HEAD_PV)
     c = ctypes.byref(cfg)
