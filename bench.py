@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--dqn", action="store_true",
+                    help="report the Double-DQN (dueling head) gradient step and the action-drawing inference "
+                         "instead (secondary lines)")
     ap.add_argument("--update-rules", action="store_true",
                     help="report the parameter-update kernels instead (secondary line)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
@@ -102,6 +105,9 @@ def main():
         return
     if args.update_rules:
         update_rules_report(args, arn, wl, np, torch)
+        return
+    if args.dqn:
+        dqn_report(args, arn, wl, np, torch)
         return
     if args.workload != 3:
         other_workload(args, arn, wl, np, torch)
@@ -291,6 +297,64 @@ def update_rules_report(args, arn, wl, np, torch):
         "config": {"workload": "learner iteration a2c_b%d + update rules" % B, "global_batch": B,
                    "parallelism": "single-gpu"},
         "update_kernels": report, "loss_finite": bool(torch.isfinite(loss).all().item())}))
+
+
+def dqn_report(args, arn, wl, np, torch):
+    """Secondary lines: Double-DQN with the dueling head at B = 2048 (three forward passes + backward) and
+    the sampler's inference that returns drawn actions at B = 256."""
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    to_dev = lambda d: {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for n, v in d.items()}
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps
+
+    A, B = 18, args.batch or 2048
+    cfg = arn.Config(A, arn.ARN_HEAD_DUEL, double_q=1)
+    packed, tpacked = (torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev) for _ in range(2))
+    arn.weights_prepare(cfg, torch.from_numpy(wl.he_normal_params(A, "duel", 2005)).to(dev), packed)
+    arn.weights_prepare(cfg, torch.from_numpy(wl.he_normal_params(A, "duel", 3005)).to(dev), tpacked)
+    batch = to_dev(wl.c51_batch(5, B=B))
+    batch["w_target_packed"] = tpacked
+    ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
+    dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+    sec = timed(lambda: arn.train_step_grads(cfg, packed, batch, "dqn", dW, loss, workspace=ws, stream=stream))
+    fwd = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + (A + 1) * 512)
+    flops = 3 * fwd - 2 * MACS["conv1"] + 2 * fwd
+    print(json.dumps({
+        "metric": "Nature-CNN samples/sec (train_step_grads:dqn, double + dueling) at B=%d on 1 GPU" % B,
+        "value": round(B / sec, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "double_dqn_dueling_b%d" % B, "global_batch": B, "parallelism": "single-gpu"},
+        "mfma_frac_whole_step": round(B / sec * flops / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "algorithmic_flops_per_sample": flops, "loss_finite": bool(torch.isfinite(loss).all().item())}))
+
+    Bi = 256
+    cfgp = arn.Config(A, arn.ARN_HEAD_PV)
+    pp = torch.empty(arn.packed_bytes(cfgp), dtype=torch.uint8, device=dev)
+    arn.weights_prepare(cfgp, torch.from_numpy(wl.he_normal_params(A, "pv", 2002)).to(dev), pp)
+    obs = torch.from_numpy(wl.frames_for(2, Bi)).to(dev)
+    un = to_dev(wl.action_uniforms(Bi, 3))
+    wsf = torch.empty(arn.workspace_bytes(cfgp, Bi, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
+    act = torch.empty(Bi, dtype=torch.int32, device=dev)
+    logp = torch.empty(Bi, dtype=torch.float32, device=dev)
+    sec = timed(lambda: arn.policy_act(cfgp, pp, obs, un["u"], un["u2"], act, logp, workspace=wsf, stream=stream))
+    print(json.dumps({
+        "metric": "Nature-CNN samples/sec (policy_act, categorical draw) at B=%d on 1 GPU" % Bi,
+        "value": round(Bi / sec, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "act_b%d (256 simulators, one environment step)" % Bi, "global_batch": Bi,
+                   "parallelism": "single-gpu"}}))
 
 
 def other_workload(args, arn, wl, np, torch):
