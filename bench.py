@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--dqn", action="store_true",
                     help="report the Double-DQN (dueling head) gradient step and the action-drawing inference "
                          "instead (secondary lines)")
+    ap.add_argument("--alternating", action="store_true",
+                    help="latency study of the two-group alternating sampler inference, host buffers included "
+                         "(secondary line)")
     ap.add_argument("--update-rules", action="store_true",
                     help="report the parameter-update kernels instead (secondary line)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
@@ -108,6 +111,9 @@ def main():
         return
     if args.dqn:
         dqn_report(args, arn, wl, np, torch)
+        return
+    if args.alternating:
+        alternating_report(args, arn, wl, np, torch)
         return
     if args.workload != 3:
         other_workload(args, arn, wl, np, torch)
@@ -355,6 +361,77 @@ def dqn_report(args, arn, wl, np, torch):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "act_b%d (256 simulators, one environment step)" % Bi, "global_batch": Bi,
                    "parallelism": "single-gpu"}}))
+
+
+def alternating_report(args, arn, wl, np, torch):
+    """Section "Synchronized Sampling": the simulators are split into two groups that alternate, so that one
+    group's inference runs while the other group's simulators step.  Here the simulators are no-ops; what is
+    measured is the GPU side including the host hand-over: observations start in pinned host memory, actions
+    end there.  Per group and environment step: H2D copy of uint8 frames -> arn_policy_act -> D2H copy of the
+    int32 actions, each group on a stream of its own (default priority).  Reported against one group of all
+    simulators handled back to back."""
+    dev, A, n_sims = "cuda:0", 18, args.batch or 256
+    cfg = arn.Config(A, arn.ARN_HEAD_PV)
+    packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+    arn.weights_prepare(cfg, torch.from_numpy(wl.he_normal_params(A, "pv", 2002)).to(dev), packed)
+    frames = wl.frames_for(2, n_sims)
+    un = wl.action_uniforms(n_sims, 4)
+
+    class Group:
+        def __init__(self, lo, hi):
+            n = hi - lo
+            self.n = n
+            self.stream = torch.cuda.Stream()
+            self.h_obs = torch.from_numpy(frames[lo:hi].copy()).pin_memory()
+            self.h_act = torch.empty(n, dtype=torch.int32).pin_memory()
+            self.d_obs = torch.empty((n, 4, 84, 84), dtype=torch.uint8, device=dev)
+            self.d_act = torch.empty(n, dtype=torch.int32, device=dev)
+            self.u = torch.from_numpy(un["u"][lo:hi].copy()).to(dev)
+            self.u2 = torch.from_numpy(un["u2"][lo:hi].copy()).to(dev)
+            self.ws = torch.empty(arn.workspace_bytes(cfg, n, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
+            self.done = torch.cuda.Event()
+
+        def issue(self):
+            with torch.cuda.stream(self.stream):
+                self.d_obs.copy_(self.h_obs, non_blocking=True)
+                arn.policy_act(cfg, packed, self.d_obs, self.u, self.u2, self.d_act, workspace=self.ws,
+                               stream=self.stream)
+                self.h_act.copy_(self.d_act, non_blocking=True)
+                self.done.record(self.stream)
+
+        def wait(self):
+            self.done.synchronize()
+
+    def run(groups, steps):
+        # steady state of the alternation: a group's next request is issued as soon as its actions are back
+        # (its simulators are no-ops), while the other group's request is in flight
+        for g in groups:
+            g.issue()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            for g in groups:
+                g.wait()
+                g.issue()
+        for g in groups:
+            g.wait()
+        return (time.perf_counter() - t0) / steps
+
+    half = n_sims // 2
+    two = [Group(0, half), Group(half, n_sims)]
+    one = [Group(0, n_sims)]
+    run(two, args.warmup), run(one, args.warmup)
+    t_two, t_one = run(two, args.steps), run(one, args.steps)
+    torch.cuda.synchronize()
+    ok = bool(((two[0].h_act >= 0) & (two[0].h_act < A)).all() and ((one[0].h_act >= 0) & (one[0].h_act < A)).all())
+    print(json.dumps({
+        "metric": "sampler inference, simulator-steps/sec with host hand-over (two alternating groups of %d)" % half,
+        "value": round(n_sims / t_two, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(t_two * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "alternating_act_%d+%d, pinned host frames in, actions out" % (half, n_sims - half),
+                   "global_batch": n_sims, "parallelism": "single-gpu, two streams"},
+        "one_group_ms_per_step": round(t_one * 1e3, 4), "one_group_samples_per_s": round(n_sims / t_one, 1),
+        "actions_valid": ok}))
 
 
 def other_workload(args, arn, wl, np, torch):
