@@ -132,7 +132,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step():
-        arn.train_step_grads(cfg, packed, batch, "a2c", dW, loss, workspace=ws, stream=stream)
+        arn.train_step_grads(cfg, packed, batch, "a2c", dW, loss, workspace=ws, stream=torch.cuda.current_stream())
 
     def timed(fn, steps):
         torch.cuda.synchronize()
@@ -153,11 +153,22 @@ def main():
     val = torch.empty(B, dtype=torch.float32, device=dev)
 
     def fwd():
-        arn.policy_forward(cfg, packed, batch["obs"], logits, val, workspace=wsf, stream=stream)
+        arn.policy_forward(cfg, packed, batch["obs"], logits, val, workspace=wsf, stream=torch.cuda.current_stream())
 
     for _ in range(args.warmup):
         fwd()
     sec_fwd = timed(fwd, args.steps)
+
+    # the same calls captured once into HIP graphs and replayed (what a tight training / serving loop would do)
+    def graph_time(fn):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        for _ in range(args.warmup):
+            g.replay()
+        return timed(g.replay, args.steps)
+
+    sec_graph, sec_fwd_graph = graph_time(step), graph_time(fwd)
 
     # per-kernel durations: the same K steps again with a HIP event pair around every launch
     arn.profile_enable(True)
@@ -199,6 +210,8 @@ def main():
         "mfma_frac_whole_step": round(value * FWDBWD_FLOPS / 1e12 / PEAK_BF16_TFLOPS, 4),
         "forward_samples_per_s": round(B / sec_fwd, 1),
         "forward_ms": round(sec_fwd * 1e3, 4),
+        "graph_replay_ms_per_step": round(sec_graph * 1e3, 4),
+        "graph_replay_forward_ms": round(sec_fwd_graph * 1e3, 4),
         "kernel_us": {n: round(v * 1e3, 2) for n, v in sorted(avg_ms.items(), key=lambda kv: -kv[1])},
         "roofline": roofline,
     }
