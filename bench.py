@@ -174,6 +174,7 @@ def main():
     arn.profile_enable(True)
     for _ in range(args.steps):
         step()
+        arn.profile_null(torch.cuda.current_stream())
     torch.cuda.synchronize()
     recs = arn.profile_collect(cap=64 * args.steps + 64)
     arn.profile_enable(False)
@@ -181,7 +182,9 @@ def main():
     for name, ms in recs:
         tot, cnt = per.get(name, (0.0, 0))
         per[name] = (tot + ms, cnt + 1)
-    avg_ms = {n: t / c for n, (t, c) in per.items()}
+    # an event pair around nothing measures what the pair itself adds; it is subtracted from every kernel
+    null_ms = per.pop("null")[0] / args.steps
+    avg_ms = {n: max(t / c - null_ms, 0.0) for n, (t, c) in per.items()}
     dominant = max((n for n in avg_ms if n in KERNEL_FLOPS), key=avg_ms.get)
     dom_s = avg_ms[dominant] * 1e-3
     dom_flops = KERNEL_FLOPS[dominant] * B
@@ -197,6 +200,7 @@ def main():
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
     roofline["traffic"] = measured_traffic(dominant, B)
     roofline["avg_launch_us"] = round(avg_ms[dominant] * 1e3, 2)
+    roofline["event_pair_overhead_us"] = round(null_ms * 1e3, 2)
     roofline["algorithmic_bytes_per_launch"] = dom_bytes
     roofline["algorithmic_flops_per_launch"] = dom_flops
 

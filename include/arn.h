@@ -207,6 +207,9 @@ int arn_async_adam_merge(size_t n, float *theta_c, float *m_c, float *v_c, float
  * float[cap] -- frees the events and returns the number written.  Process-wide
  * state; not thread-safe. */
 int arn_profile_enable(int on);
+/* Records an event pair around no work on `stream` (name "null"): the instrumentation's own contribution to
+ * every recorded duration, for the caller to subtract. */
+int arn_profile_null(void *stream);
 int arn_profile_collect(char *names, float *ms, int cap);
 
 /* Human-readable name of a status code (static storage). */

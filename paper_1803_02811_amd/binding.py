@@ -82,6 +82,8 @@ def load_library():
         lib.arn_async_adam_merge.argtypes = [sz, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, f, f, cp, vp, vp]
         lib.arn_profile_enable.restype = ctypes.c_int
         lib.arn_profile_enable.argtypes = [ctypes.c_int]
+        lib.arn_profile_null.restype = ctypes.c_int
+        lib.arn_profile_null.argtypes = [vp]
         lib.arn_profile_collect.restype = ctypes.c_int
         lib.arn_profile_collect.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         _LIB = lib
@@ -184,6 +186,10 @@ def async_adam_merge(theta_c, m_c, v_c, theta, m, v, a_g, a_g2, a_s, *, n_local,
 
 def profile_enable(on: bool) -> None:
     load_library().arn_profile_enable(1 if on else 0)
+
+
+def profile_null(stream=None) -> None:
+    load_library().arn_profile_null(_stream(stream))
 
 
 def profile_collect(cap: int = 4096):
