@@ -166,7 +166,6 @@ inline int fc_ksplit(int B) {
 }
 
 constexpr int LOSS_BLOCK = 16;    // samples per workgroup of the fused policy/value head kernel
-constexpr int HEAD_KSPLIT = 8;    // k ranges of the policy/value head GEMM (one 64-element k-tile each)
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
 // byte offsets into the workspace
@@ -174,7 +173,6 @@ struct Workspace {
     size_t a1, a2, a3, h;               // bf16 NHWC activations
     size_t a1l, a2l, a3l, hl;           // their low parts (written and read by the forward pass only)
     size_t fcp;                         // fp32 [ksplit][B][512] partial sums of the fc forward GEMM
-    size_t hp;                          // fp32 [HEAD_KSPLIT][B][32] partial sums of the policy/value head GEMM
     size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
     size_t qt, astar;                   // DQN: target-net Q(s',.) fp32 [B][A]; Double-DQN: online greedy action on s' int32 [B]
@@ -202,7 +200,6 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     w.hl = take(b * HID * 2);
     // the fused policy/value head kernel always reads fp32 partials; the categorical path only when k is split
     w.fcp = take((size_t)(fc_ksplit(B) > 1 || d.small ? fc_ksplit(B) : 0) * b * HID * 4);
-    w.hp = take(0);
     // categorical head: atom logits of arn_policy_act (arn_policy_forward writes them to its `logits` argument)
     if (mode == ARN_MODE_FORWARD) w.z = take(d.small ? 0 : b * (size_t)d.NH * 4);
     if (mode == ARN_MODE_TRAIN) {
