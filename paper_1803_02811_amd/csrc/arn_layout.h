@@ -161,7 +161,7 @@ inline int fc_ksplit(int B) {
     const int tiles = ((B + 127) / 128) * 4;
     int ks = 256 / tiles;
     if (ks < 1) ks = 1;
-    if (ks > 49) ks = 49;
+    if (ks > 16) ks = 16;   // the consumer adds the ranges one after the other: more of them costs it more than the GEMM gains
     return ks;
 }
 

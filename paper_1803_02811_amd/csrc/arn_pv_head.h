@@ -145,7 +145,23 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         float4 acc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = *reinterpret_cast<const float4 *>(src + 64 * j);
-        for (int z = 1; z < p.ks; ++z) {
+        // the k ranges are added in order; four ranges (32 loads) are in flight at a time
+        int z = 1;
+        for (; z + 4 <= p.ks; z += 4) {
+            float4 v[4][8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    v[q][j] = *reinterpret_cast<const float4 *>(src + (size_t)(z + q) * plane + 64 * j);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    acc[j].x += v[q][j].x; acc[j].y += v[q][j].y; acc[j].z += v[q][j].z; acc[j].w += v[q][j].w;
+                }
+        }
+        for (; z < p.ks; ++z) {
             float4 v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4 *>(src + (size_t)z * plane + 64 * j);
