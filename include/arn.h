@@ -32,6 +32,11 @@
  *     next to the caller's stream; it is forked from and joined back to `stream`
  *     with events inside the call, so to the caller the call behaves as if all
  *     of its work were on `stream`.  Set ARN_SINGLE_STREAM=1 to disable it.
+ *     That stream and its events are shared by all calls on a device: two
+ *     arn_train_step_grads calls issued concurrently from different host threads
+ *     on the same device are not supported (issue them from one thread, on one
+ *     or several streams; successive calls are ordered by the events).  The
+ *     profiling switch (arn_profile_*) is likewise process-global.
  *   - Return value: ARN_OK (0) or a negative arn_status.  Argument errors are
  *     detected on the host before anything is launched.
  *   - Arithmetic: bf16 MFMA operands, fp32 accumulation, fp32 epilogues and
