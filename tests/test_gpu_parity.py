@@ -260,3 +260,28 @@ def test_saturated_frames_and_large_batch_tail(gu):
     out = gu.GpuNet(A, "pv", flat).forward(obs)
     gu.tol_check(out["logits"], ref["logits"], "logits")
     gu.tol_check(out["value"], ref["value"], "value")
+
+
+def test_single_stream_mode_gives_the_same_bits(gu, tmp_path):
+    """ARN_SINGLE_STREAM=1 keeps every kernel on the caller's stream; the fixed summation order makes the
+    gradient bit-identical to the two-stream run.  The switch is read once per process, hence the child."""
+    import os
+    import subprocess
+    import sys
+    A, B = 18, 70
+    flat = wl.he_normal_params(A, "pv", 2003)
+    batch = wl.actor_critic_batch(3, B=B)
+    dW, loss = gu.GpuNet(A, "pv", flat).train(batch, "a2c")
+    out = tmp_path / "dw.npy"
+    code = (
+        "import sys, numpy as np\n"
+        f"sys.path.insert(0, {os.path.dirname(os.path.dirname(os.path.abspath(__file__)))!r})\n"
+        "import workloads as wl\n"
+        "from tests import gpu_util as gu\n"
+        f"flat = wl.he_normal_params({A}, 'pv', 2003)\n"
+        f"dW, loss = gu.GpuNet({A}, 'pv', flat).train(wl.actor_critic_batch(3, B={B}), 'a2c')\n"
+        f"np.save({str(out)!r}, np.concatenate([dW, loss]))\n")
+    env = dict(os.environ, ARN_SINGLE_STREAM="1")
+    subprocess.run([sys.executable, "-c", code], check=True, env=env, timeout=110)
+    other = np.load(out)
+    assert np.array_equal(other[:-4], dW) and np.array_equal(other[-4:], loss)
