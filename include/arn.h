@@ -135,7 +135,7 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
 
 typedef struct {
     const uint8_t *obs;        /* [B,4,84,84] */
-    const int32_t *action;     /* [B], 0 <= a < A */
+    const int32_t *action;     /* [B], 0 <= a < A (values outside are clamped into range, not reported) */
     const float *adv;          /* [B]  a2c, ppo: advantage estimates (constants) */
     const float *ret;          /* [B]  a2c, ppo: value regression targets */
     const float *old_logp;     /* [B]  ppo: log pi_old(a|s) */

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         for (int t = 0; t < 8; ++t)
             wd[t] = *reinterpret_cast<const u32x4 *>(p.whd + (size_t)((wave * 8 + t) * 16 + fi) * 64 + fg * 8);
         if (live) {
-            a = p.action[n];
+            a = min(max(p.action[n], 0), p.A - 1);
             if (p.objective == 2) {
                 ad = p.reward[n];                       // dqn: reward
                 rt = p.done[n] ? 0.f : p.gamma;          //      discount of the bootstrap term

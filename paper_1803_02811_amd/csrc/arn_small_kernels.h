@@ -316,7 +316,7 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, n = blockIdx.x * C51_WAVES + wv;
     float ce = 0.f;
     if (n < B) {
-        const int a = action[n];
+        const int a = min(max(action[n], 0), A - 1);   // an out-of-range action must not become an out-of-range read
         const bool on = lane < atoms;
         const float x = on ? z[((size_t)n * A + a) * atoms + lane] : -INFINITY;
         const float mx = wave_max(x);
