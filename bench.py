@@ -44,6 +44,10 @@ KERNEL_BYTES_PER_LAUNCH = {  # bf16 weights read (forward / input gradient) or f
     "conv1_wgrad": 4 * 8192, "conv2_wgrad": 4 * 32768, "conv3_wgrad": 4 * 36864, "fc_wgrad": 4 * 1605632,
     "head_wgrad": 4 * 9728,
 }
+# whole step, per sample: the forward's bytes, then observations again, saved activations once, and every
+# activation gradient written and read once
+FWDBWD_BYTES = sum(KERNEL_BYTES[k] for k in ("conv1_fwd", "conv2_fwd", "conv3_fwd", "fc_fwd", "head_fwd")) \
+    + ACT["obs"] + (ACT["a1"] + ACT["a2"] + ACT["a3"] + ACT["h"]) + 2 * (ACT["a1"] + ACT["a2"] + ACT["a3"] + ACT["h"])
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
@@ -212,6 +216,7 @@ def main():
         "config": {"workload": "a2c_grad_step_B%d_A18 (256 envs x 8 steps, rectangle frames)" % B,
                    "global_batch": B, "parallelism": "single-gpu"},
         "mfma_frac_whole_step": round(value * FWDBWD_FLOPS / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "hbm_frac_whole_step": round(value * FWDBWD_BYTES / 1e9 / PEAK_HBM_GBS, 4),
         "forward_samples_per_s": round(B / sec_fwd, 1),
         "forward_ms": round(sec_fwd * 1e3, 4),
         "graph_replay_ms_per_step": round(sec_graph * 1e3, 4),
