@@ -91,12 +91,12 @@ SideStream *side_stream() {
 template <class P>
 void launch_nt(const char *name, const P &p, long M, int n_tiles, int z, hipStream_t s) {
     ProfScope ps(name, s);
-    hipLaunchKernelGGL((gemm_nt_kernel<P, false>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((gemm_nt_kernel<P, false>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(ThreadsOf<P>::value), 0, s, p);
 }
 template <class P>
 void launch_nt_split(const char *name, const P &p, long M, int n_tiles, int z, hipStream_t s) {
     ProfScope ps(name, s);
-    hipLaunchKernelGGL((gemm_nt_kernel<P, true>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((gemm_nt_kernel<P, true>), dim3(cdiv(M, P::BM), n_tiles, z), dim3(ThreadsOf<P>::value), 0, s, p);
 }
 
 template <class P>

@@ -154,11 +154,35 @@ struct StagesOf<P, decltype((void)P::STAGES)> {
     static constexpr int value = P::STAGES;
 };
 
+// Problems with a static member THREADS = 512 run eight wavefronts per workgroup (two per SIMD, so that one
+// wavefront's LDS waits overlap the other's MFMAs); the default is 256.
+template <class P, class = void>
+struct ThreadsOf {
+    static constexpr int value = 256;
+};
+template <class P>
+struct ThreadsOf<P, decltype((void)P::THREADS)> {
+    static constexpr int value = P::THREADS;
+};
+// Problems with a member function prefetch(m, n) have it called for every output quad before the k loop;
+// its result (for example the ReLU-derivative bits of the quad) is handed to store(), which then needs no
+// dependent load in the epilogue.
+template <class P, class = void>
+struct HasPrefetch {
+    static constexpr bool value = false;
+};
+template <class P>
+struct HasPrefetch<P, decltype((void)&P::prefetch)> {
+    static constexpr bool value = true;
+};
+
 template <class P, bool SPLIT = false>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
-    constexpr int BM = P::BM, BN = P::BN, WN = P::WAVES_N, WM = 4 / WN;
+__global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p) {
+    constexpr int NT = ThreadsOf<P>::value, NW = NT / 64, RS = NT / 8;   // threads, wavefronts, rows staged per pass
+    constexpr int BM = P::BM, BN = P::BN, WN = P::WAVES_N, WM = NW / WN;
     constexpr int TN = BN / (32 * WN), TM = BM / (32 * WM);
-    constexpr int A_CH = BM / 32, W_CH = BN / 32;     // 16-byte chunks staged per thread and k-tile
+    constexpr int A_CH = BM / RS, W_CH = BN / RS;     // 16-byte chunks staged per thread and k-tile
+    static_assert(BM % RS == 0 && BN % RS == 0, "staging passes");
     constexpr bool ALO = ActLo<P, SPLIT>::value;
     int kt_begin = 0, KT = p.K / 64;
     if constexpr (HasKSplit<P>::value) {
@@ -180,16 +204,16 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
     const int wn = wave % WN, wm = wave / WN;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN, z = blockIdx.z;
     const int kc = tid & 7;      // which 16-byte chunk of the 128-byte k-tile row
-    const int r0 = tid >> 3;     // first staged row; this thread also stages r0+32, r0+64, ...
+    const int r0 = tid >> 3;     // first staged row; this thread also stages r0+RS, r0+2RS, ...
 
     typename P::Row rows[A_CH];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) rows[i] = p.row(m0 + r0 + 32 * i, z);
+    for (int i = 0; i < A_CH; ++i) rows[i] = p.row(m0 + r0 + RS * i, z);
     const u32x4 *wsrc[W_CH];
     const u32x4 *wsrc2[W_CH];
 #pragma unroll
     for (int i = 0; i < W_CH; ++i) {
-        const size_t at = (size_t)(n0 + r0 + 32 * i) * p.K;
+        const size_t at = (size_t)(n0 + r0 + RS * i) * p.K;
         wsrc[i] = reinterpret_cast<const u32x4 *>(p.weights(z) + at) + kc;
         if constexpr (SPLIT) wsrc2[i] = reinterpret_cast<const u32x4 *>(p.weights_lo(z) + at) + kc;
     }
@@ -219,17 +243,27 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
     auto stage = [&](int st) __attribute__((always_inline)) {   // registers -> LDS stage st
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
-            sA[st * SA + (r0 + 32 * i) * LDS_ROW + kc] = ra[i];
-            if constexpr (ALO) sA2[st * SA + (r0 + 32 * i) * LDS_ROW + kc] = ra2[i];
+            sA[st * SA + (r0 + RS * i) * LDS_ROW + kc] = ra[i];
+            if constexpr (ALO) sA2[st * SA + (r0 + RS * i) * LDS_ROW + kc] = ra2[i];
         }
 #pragma unroll
         for (int i = 0; i < W_CH; ++i) {
-            sW[st * SW + (r0 + 32 * i) * LDS_ROW + kc] = rw[i];
-            if constexpr (SPLIT) sW2[st * SW + (r0 + 32 * i) * LDS_ROW + kc] = rw2[i];
+            sW[st * SW + (r0 + RS * i) * LDS_ROW + kc] = rw[i];
+            if constexpr (SPLIT) sW2[st * SW + (r0 + RS * i) * LDS_ROW + kc] = rw2[i];
         }
     };
 
     const int fr = lane & 31, fg = lane >> 5;
+    uint32_t pre[HasPrefetch<P>::value ? TN : 1][HasPrefetch<P>::value ? TM : 1][4];
+    if constexpr (HasPrefetch<P>::value) {
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    pre[a][b][q] = p.prefetch(m0 + (wm * TM + b) * 32 + fr, n0 + (wn * TN + a) * 32 + 8 * q + 4 * fg);
+    }
     gload(kt_begin);
     stage(0);
     if (kt_begin + 1 < KT) gload(kt_begin + 1);
@@ -287,7 +321,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const P p) {
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + (wn * TN + a) * 32 + 8 * q + 4 * fg;
                 f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-                p.store(m, n, v, z);
+                if constexpr (HasPrefetch<P>::value) p.store(m, n, v, z, pre[a][b][q]);
+                else p.store(m, n, v, z);
             }
         }
 }

@@ -64,7 +64,7 @@ struct DenseGatherRt {
 // partials in z order and applies bias, ReLU and the hi/lo split.  With
 // ksplit == 1 the epilogue does that directly.
 struct FcFwd : DenseGather<FEAT> {
-    static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT, STAGES = 2;
+    static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT, STAGES = 2, THREADS = 512;
     static constexpr bool ACT_LO = true;
     int ksplit;
     bool to_partial;     // write fp32 partial sums even with ksplit == 1 (the consumer finishes the layer)
@@ -141,10 +141,14 @@ struct FcDgrad : DenseGather<HID> {
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
     __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
-    __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
+    // the four ReLU-derivative bits of output quad (m, n..n+3), fetched before the k loop
+    __device__ __forceinline__ uint32_t prefetch(int m, int n) const {
+        const size_t at = (size_t)(m < M ? m : 0) * FEAT + n;
+        return (uint32_t)maskbits[at >> 3] >> (at & 7);
+    }
+    __device__ __forceinline__ void store(int m, int n, f32x4 v, int, uint32_t mb) const {
         if (m >= M) return;
         const size_t at = (size_t)m * FEAT + n;
-        const uint32_t mb = (uint32_t)maskbits[at >> 3] >> (at & 7);
         *reinterpret_cast<u32x2 *>(out + at) =
             pack_bf16x4(mb & 1 ? v[0] : 0.f, mb & 2 ? v[1] : 0.f, mb & 4 ? v[2] : 0.f, mb & 8 ? v[3] : 0.f);
     }
