@@ -536,7 +536,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         float *part = (float *)(ws + o.pw1);
         {
             ProfScope ps("conv1_wgrad", s);
-            hipLaunchKernelGGL(conv1_wgrad_resident_kernel, dim3(sp.c1), dim3(256), 0, s, batch->obs, dp1, part, B,
+            hipLaunchKernelGGL(conv1_wgrad_resident_kernel, dim3(sp.c1), dim3(C1W_THREADS), 0, s, batch->obs, dp1, part, B,
                                resident_spw(B, 256));
         }
         // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor

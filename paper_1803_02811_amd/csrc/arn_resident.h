@@ -27,12 +27,14 @@ __device__ __forceinline__ bf16x8 tr_pair(const char *lds_base, int off_a, int o
 // conv1: x = uint8 observation [4][84][84] (k' = ci*64 + ky*8 + kx, window at
 // (4oy, 4ox)), dY = d(pre1) [400][32].  part[wg] = [32][256] then [32] bias sums.
 // The 1/255 pixel scale is applied by the reduction.
-__global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t *__restrict__ obs,
+constexpr int C1W_THREADS = 512;   // eight wavefronts: one 32-column tile of dW1 each, two per SIMD
+__global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const uint8_t *__restrict__ obs,
                                                                    const __bf16 *__restrict__ dy,
                                                                    float *__restrict__ part, int B, int spw) {
     constexpr int IMG_U4 = OBS_BYTES / 16;        // 1764 sixteen-pixel groups per sample
     constexpr int DY_U4 = P1 * C1 * 2 / 16;       // 1600
-    constexpr int NI = (IMG_U4 + 255) / 256, ND = (DY_U4 + 255) / 256;   // 7, 7
+    constexpr int NT = C1W_THREADS;
+    constexpr int NI = (IMG_U4 + NT - 1) / NT, ND = (DY_U4 + NT - 1) / NT;   // 4, 4
     __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][84][84]
     __shared__ u32x4 s_dy[DY_U4];                 // bf16 [400][32]
 
@@ -46,23 +48,21 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
         const u32x4 *dsrc = reinterpret_cast<const u32x4 *>(dy + (size_t)s * P1 * C1);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = tid + NT * i;
             rimg[i] = src[idx < IMG_U4 ? idx : IMG_U4 - 1];
         }
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = tid + NT * i;
             rdy[i] = dsrc[idx < DY_U4 ? idx : DY_U4 - 1];
         }
     };
 
-    f32x16 acc[2];
+    f32x16 acc;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // bias gradient: a thread always stages the same eight dY channels (chunk tid % 4 of a row), so it
-    // adds what it stages, in fp32; the 64 threads of a chunk are added in thread order at the end
+    // adds what it stages, in fp32; the 128 threads of a chunk are added in thread order at the end
     float bs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // per-lane constants of the transposing reads
@@ -70,19 +70,15 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
     const int row_in_step = 8 * (G >> 1) + (o >> 2);          // + 4 for the second read
     const int ycol_off = (16 * (G & 1) + 4 * (o & 3)) * 2;    // byte offset inside a dY row
     const int ky_lane = 2 * (G & 1) + ((o & 3) >> 1), kx0 = 4 * (o & 1);
-    int xoff[2];                                               // byte offset of (ci, ky, kx0) for the wave's two column tiles
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int t = 2 * wave + j, ci = t >> 1, ky = (t & 1) * 4 + ky_lane;
-        xoff[j] = ((ci * IN_H + ky) * IN_W + kx0) * 2;
-    }
+    // byte offset of (ci, ky, kx0) for the wavefront's column tile (tile t = ci*2 + upper/lower four kernel rows)
+    const int xoff = (((wave >> 1) * IN_H + (wave & 1) * 4 + ky_lane) * IN_W + kx0) * 2;
 
     if (s_begin < s_end) gload(s_begin);
     for (int s = s_begin; s < s_end; ++s) {
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = tid + NT * i;
             if (idx < IMG_U4) {
                 s_img[2 * idx] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
                 s_img[2 * idx + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
@@ -90,7 +86,7 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
         }
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = tid + NT * i;
             if (idx < DY_U4) {
                 s_dy[idx] = rdy[i];
                 const bf16x8 f = as_bf16x8(rdy[i]);
@@ -109,23 +105,19 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
             const int oya = ma / H1, oxa = ma - oya * H1, oyb = mb / H1, oxb = mb - oyb * H1;
             const int pa = (S1 * oya * IN_W + S1 * oxa) * 2, pb = (S1 * oyb * IN_W + S1 * oxb) * 2;
             const bf16x8 fy = tr_pair(dyl, ma * (C1 * 2) + ycol_off, mb * (C1 * 2) + ycol_off);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const bf16x8 fx = tr_pair(img, pa + xoff[j], pb + xoff[j]);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc[j], 0, 0, 0);
-            }
+            const bf16x8 fx = tr_pair(img, pa + xoff, pb + xoff);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc, 0, 0, 0);
         }
     }
 
     float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
     const int fr = lane & 31, fg = lane >> 5;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int k = (2 * wave + j) * 32 + fr;
+    {
+        const int k = wave * 32 + fr;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int n = 8 * (r >> 2) + 4 * fg + (r & 3);
-            out[n * KW1 + k] = acc[j][r];
+            out[n * KW1 + k] = acc[r];
         }
     }
     __syncthreads();
@@ -135,7 +127,7 @@ __global__ __launch_bounds__(256) void conv1_wgrad_resident_kernel(const uint8_t
     __syncthreads();
     if (tid < C1) {
         float t = red[tid];
-        for (int g = 1; g < 64; ++g) t += red[g * C1 + tid];
+        for (int g = 1; g < NT / 4; ++g) t += red[g * C1 + tid];
         out[C1 * KW1 + tid] = t;
     }
 }
