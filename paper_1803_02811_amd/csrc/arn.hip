@@ -505,8 +505,8 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         {
             ProfScope ps("conv3_wgrad", s2);
             const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 1>), dim3(sp.c3),
-                               dim3(256), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
+                               dim3(CW_THREADS), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
         }
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
     }
@@ -521,8 +521,8 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         {
             ProfScope ps("conv2_wgrad", s2);
             const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 1>), dim3(sp.c2),
-                               dim3(256), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 2>), dim3(sp.c2),
+                               dim3(CW_THREADS), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
         }
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
     }

@@ -137,8 +137,9 @@ __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const
 // LDS pixels and dY rows are padded (PS, YS bytes) so that the four rows touched
 // by one transposing read fall into different banks.  WAVES_Y wavefronts split
 // the COUT/32 row tiles, the others split the column tiles.
+constexpr int CW_THREADS = 512;   // eight wavefronts, two per SIMD: one hides the other's LDS latency
 template <int CIN, int HIN, int KS, int STRIDE, int HOUT, int COUT, int G, int WAVES_Y>
-__global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *__restrict__ x,
+__global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const __bf16 *__restrict__ x,
                                                                   const __bf16 *__restrict__ dy,
                                                                   float *__restrict__ part, int B, int spw) {
     constexpr int PIX = HIN * HIN, P = HOUT * HOUT, KP = KS * KS * CIN;
@@ -146,11 +147,12 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     constexpr int R = G * P, KSTEPS = (R + 15) / 16, RPAD = KSTEPS * 16;
     constexpr int XCH = CIN / 8, YCH = COUT / 8;                     // 16-byte chunks per pixel / per dY row
     constexpr int NXC = G * PIX * XCH, NYC = G * P * YCH;
-    constexpr int NI = (NXC + 255) / 256, ND = (NYC + 255) / 256;
-    constexpr int NY = COUT / 32, NX = KP / 32, WAVES_X = 4 / WAVES_Y;
+    constexpr int NT = CW_THREADS;
+    constexpr int NI = (NXC + NT - 1) / NT, ND = (NYC + NT - 1) / NT;
+    constexpr int NY = COUT / 32, NX = KP / 32, WAVES_X = (NT / 64) / WAVES_Y;
     constexpr int TY = NY / WAVES_Y, TX = (NX + WAVES_X - 1) / WAVES_X;   // the last wavefront along x may own fewer column tiles
     static_assert(NY % WAVES_Y == 0, "tile split");
-    static_assert(256 % YCH == 0 && (256 / YCH) * COUT * 4 <= RPAD * YS, "bias-gradient scratch");
+    static_assert(NT % YCH == 0 && (NT / YCH) * COUT * 4 <= RPAD * YS, "bias-gradient scratch");
 
     __shared__ u32x4 s_x[G * PIX * PS / 16];
     __shared__ u32x4 s_dy[RPAD * YS / 16];
@@ -161,14 +163,14 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
 
     // rows R..RPAD of dY stay zero for the whole kernel
-    for (int i = tid; i < (RPAD - R) * YS / 16; i += 256) s_dy[R * YS / 16 + i] = zero_u4();
+    for (int i = tid; i < (RPAD - R) * YS / 16; i += NT) s_dy[R * YS / 16 + i] = zero_u4();
 
     u32x4 rx[NI], ry[ND];
     auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1; those at or beyond s_end are read from s_end-1 and zeroed on store
         const int last = s_end - 1;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            int idx = tid + 256 * i;
+            int idx = tid + NT * i;
             idx = idx < NXC ? idx : NXC - 1;
             const int g = idx / (PIX * XCH), rem = idx - g * (PIX * XCH);
             const int sg = s + g < s_end ? s + g : last;
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
         }
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-            int idx = tid + 256 * i;
+            int idx = tid + NT * i;
             idx = idx < NYC ? idx : NYC - 1;
             const int g = idx / (P * YCH), rem = idx - g * (P * YCH);
             const int sg = s + g < s_end ? s + g : last;
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
         char *yl = reinterpret_cast<char *>(s_dy);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = tid + NT * i;
             if (idx < NXC) {
                 const int pix = idx / XCH, c = idx - pix * XCH;
                 const bool live = s + pix / PIX < s_end;
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
         }
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = tid + NT * i;
             if (idx < NYC) {
                 const int row = idx / YCH, c = idx - row * YCH;
                 const bool live = s + row / P < s_end;
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_resident_kernel(const __bf16 *
     __syncthreads();
     if (tid < COUT) {
         float t = red[tid];
-        for (int g = 1; g < 256 / YCH; ++g) t += red[g * COUT + tid];
+        for (int g = 1; g < NT / YCH; ++g) t += red[g * COUT + tid];
         out[COUT * KP + tid] = t;
     }
 }
