@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--alternating", action="store_true",
                     help="latency study of the two-group alternating sampler inference, host buffers included "
                          "(secondary line)")
+    ap.add_argument("--paper-geometry", action="store_true",
+                    help="secondary report: the A2C gradient step and inference on the paper's own 104x80 frames with "
+                         "padded conv2/conv3 (gathered-contraction kernels), per-kernel times included")
     ap.add_argument("--update-rules", action="store_true",
                     help="report the parameter-update kernels instead (secondary line)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
@@ -118,6 +121,9 @@ def main():
         return
     if args.alternating:
         alternating_report(args, arn, wl, np, torch)
+        return
+    if args.paper_geometry:
+        paper_geometry_report(args, arn, wl, np, torch)
         return
     if args.workload != 3:
         other_workload(args, arn, wl, np, torch)
@@ -454,6 +460,66 @@ def alternating_report(args, arn, wl, np, torch):
                    "global_batch": n_sims, "parallelism": "single-gpu, two streams"},
         "one_group_ms_per_step": round(t_one * 1e3, 4), "one_group_samples_per_s": round(n_sims / t_one, 1),
         "actions_valid": ok}))
+
+
+def paper_geometry_report(args, arn, wl, np, torch):
+    """A2C gradient step and action-selection inference on the frame size and padding of the paper's own runs
+    (appendix "Atari Frame Processing"): 104x80 frames, 25x19 -> 12x9 -> 12x9 feature maps, fc 6912 -> 512."""
+    dev, A, B, k = "cuda:0", 18, args.batch or 2048, 3
+    frame, fc_in = wl.PAPER_FRAME, wl.FC_INPUTS[wl.PAPER_FRAME]
+    macs = {"conv1": 25 * 19 * 256 * 32, "conv2": 12 * 9 * 512 * 64, "conv3": 12 * 9 * 576 * 64, "fc": fc_in * 512,
+            "head": (A + 1) * 512}
+    fwd_flops = 2 * sum(macs.values())
+    fwdbwd_flops = 3 * fwd_flops - 2 * macs["conv1"]
+    cfg = arn.Config(A, arn.ARN_HEAD_PV, geometry=arn.ARN_GEOM_PAPER)
+    flat = wl.he_normal_params(A, "pv", 2000 + k, fc_inputs=fc_in)
+    packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+    arn.weights_prepare(cfg, torch.from_numpy(flat).to(dev), packed)
+    batch = {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev)
+             for n, v in wl.actor_critic_batch(k, B=B, frame=frame).items()}
+    ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
+    dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
+    loss = torch.empty(4, dtype=torch.float32, device=dev)
+    logits = torch.empty(B, A, dtype=torch.float32, device=dev)
+    val = torch.empty(B, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    step = lambda: arn.train_step_grads(cfg, packed, batch, "a2c", dW, loss, workspace=ws, stream=stream)
+    fwd = lambda: arn.policy_forward(cfg, packed, batch["obs"], logits, val, workspace=ws, stream=stream)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps
+
+    sec, sec_fwd = timed(step), timed(fwd)
+    arn.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+        arn.profile_null(stream)
+    torch.cuda.synchronize()
+    per = {}
+    for name, ms in arn.profile_collect(cap=64 * args.steps + 64):
+        tot, cnt = per.get(name, (0.0, 0))
+        per[name] = (tot + ms, cnt + 1)
+    arn.profile_enable(False)
+    null_ms = per.pop("null")[0] / args.steps
+    avg_ms = {n: max(t / c - null_ms, 0.0) for n, (t, c) in per.items()}
+    print(json.dumps({
+        "metric": "Nature-CNN samples/sec (fwd+bwd, 104x80 frames, padded conv2/conv3) at B=%d on 1 GPU" % B,
+        "value": round(B / sec, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "a2c_grad_step_B%d_A18 on 104x80 frames (25x19 -> 12x9 -> 12x9, fc 6912)" % B,
+                   "global_batch": B, "parallelism": "single-gpu"},
+        "mfma_frac_whole_step": round(B / sec * fwdbwd_flops / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "forward_samples_per_s": round(B / sec_fwd, 1), "forward_ms": round(sec_fwd * 1e3, 4),
+        "algorithmic_flops_per_sample": {"forward": fwd_flops, "forward_backward": fwdbwd_flops},
+        "kernel_us": {n: round(v * 1e3, 2) for n, v in sorted(avg_ms.items(), key=lambda kv: -kv[1])}}))
 
 
 def other_workload(args, arn, wl, np, torch):

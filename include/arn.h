@@ -7,6 +7,9 @@
  * Processing" calls the standard 3-convolutional-layer network:
  *   uint8 [4,84,84] -> /255 -> conv 8x8/4 x32 -> conv 4x4/2 x64 -> conv 3x3/1 x64
  *   -> fc 3136->512 (ReLU after every hidden layer) -> heads.
+ * With geometry ARN_GEOM_PAPER the same layers take the frame size and padding the
+ * appendix states for the paper's own runs: uint8 [4,104,80], no padding on conv1,
+ * padding 1 on conv2 and conv3, feature maps 25x19 -> 12x9 -> 12x9, fc 6912->512.
  * Heads: policy logits [A] + value [1]   (head_kind ARN_HEAD_PV),
  *        categorical atom logits [A,51]   (head_kind ARN_HEAD_C51),
  *        scalar action values Q [A]       (head_kind ARN_HEAD_Q), or
@@ -46,7 +49,7 @@
  * Flat fp32 parameter / gradient vector, canonical order (row-major tensors):
  *   conv1.W[32,4,8,8] conv1.b[32] conv2.W[64,32,4,4] conv2.b[64]
  *   conv3.W[64,64,3,3] conv3.b[64] fc.W[512,3136] fc.b[512]
- *   (fc input index = c*49 + y*7 + x), then
+ *   (fc input index = c*49 + y*7 + x; ARN_GEOM_PAPER: fc.W[512,6912], index c*108 + y*9 + x), then
  *   PV : pi.W[A,512] pi.b[A] v.W[1,512] v.b[1]
  *   C51: c51.W[A*atoms,512] (row a*atoms+j) c51.b[A*atoms]
  *   Q  : q.W[A,512] q.b[A]
@@ -75,6 +78,9 @@ typedef enum {
 enum { ARN_HEAD_PV = 0, ARN_HEAD_C51 = 1, ARN_HEAD_Q = 2, ARN_HEAD_DUEL = 3 };
 enum { ARN_LOSS_A2C = 0, ARN_LOSS_PPO = 1, ARN_LOSS_C51 = 2, ARN_LOSS_DQN = 3 };
 enum { ARN_MODE_FORWARD = 0, ARN_MODE_TRAIN = 1 };
+/* frame size and padding of the convolution stack (appendix "Atari Frame Processing") */
+enum { ARN_GEOM_84 = 0,      /* 84x84 frames, no padding: 20x20 -> 9x9 -> 7x7, fc input 3136 */
+       ARN_GEOM_PAPER = 1 }; /* 104x80 frames, padding 1 on conv2/conv3: 25x19 -> 12x9 -> 12x9, fc input 6912 */
 
 typedef struct {
     int32_t num_actions;   /* 1..31 for PV, Q, DUEL; 1..18 for C51 */
@@ -86,6 +92,7 @@ typedef struct {
     float value_coef;      /* weight of mean((V-ret)^2) (0.5) */
     float entropy_coef;    /* weight of the mean-entropy bonus (0.01) */
     int32_t double_q;      /* DQN: 1 = the online network picks the next action (Double-DQN), 0 = the target network */
+    int32_t geometry;      /* ARN_GEOM_84 (0) or ARN_GEOM_PAPER; anything else is ARN_ESHAPE */
 } arn_config;
 
 /* Number of fp32 entries of the flat parameter vector; 0 on a bad config. */
@@ -108,7 +115,7 @@ size_t arn_workspace_bytes(const arn_config *cfg, int B, int mode);
 int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_packed, void *stream);
 
 /* Batched action-selection inference (section "Synchronized Sampling").
- *   obs    : uint8 [B,4,84,84] (NCHW), read only
+ *   obs    : uint8 [B,4,84,84] (NCHW; [B,4,104,80] with ARN_GEOM_PAPER), read only
  *   logits : PV: fp32 [B,A]; C51: fp32 [B,A,atoms]; Q, DUEL: the action values Q [B,A].  Required.
  *   value  : PV: fp32 [B], required.  C51: expected action values Q [B,A], or NULL.
  *            Q, DUEL: max_a Q [B], required.

@@ -9,8 +9,10 @@ from typing import Optional
 ARN_HEAD_PV, ARN_HEAD_C51, ARN_HEAD_Q, ARN_HEAD_DUEL = 0, 1, 2, 3
 ARN_LOSS_A2C, ARN_LOSS_PPO, ARN_LOSS_C51, ARN_LOSS_DQN = 0, 1, 2, 3
 ARN_MODE_FORWARD, ARN_MODE_TRAIN = 0, 1
+ARN_GEOM_84, ARN_GEOM_PAPER = 0, 1
 LOSS_KINDS = {"a2c": ARN_LOSS_A2C, "ppo": ARN_LOSS_PPO, "c51": ARN_LOSS_C51, "dqn": ARN_LOSS_DQN}
 HEAD_KINDS = {"pv": ARN_HEAD_PV, "c51": ARN_HEAD_C51, "q": ARN_HEAD_Q, "duel": ARN_HEAD_DUEL}
+GEOMETRIES = {"84": ARN_GEOM_84, "paper": ARN_GEOM_PAPER}
 
 
 class Config(ctypes.Structure):
@@ -18,12 +20,12 @@ class Config(ctypes.Structure):
     _fields_ = [("num_actions", ctypes.c_int32), ("head_kind", ctypes.c_int32), ("num_atoms", ctypes.c_int32),
                 ("v_min", ctypes.c_float), ("v_max", ctypes.c_float), ("gamma", ctypes.c_float),
                 ("clip_eps", ctypes.c_float), ("value_coef", ctypes.c_float), ("entropy_coef", ctypes.c_float),
-                ("double_q", ctypes.c_int32)]
+                ("double_q", ctypes.c_int32), ("geometry", ctypes.c_int32)]
 
     def __init__(self, num_actions=18, head_kind=ARN_HEAD_PV, num_atoms=51, v_min=-10.0, v_max=10.0, gamma=0.99,
-                 clip_eps=0.1, value_coef=0.5, entropy_coef=0.01, double_q=0):
+                 clip_eps=0.1, value_coef=0.5, entropy_coef=0.01, double_q=0, geometry=ARN_GEOM_84):
         super().__init__(num_actions, head_kind, num_atoms, v_min, v_max, gamma, clip_eps, value_coef, entropy_coef,
-                         int(double_q))
+                         int(double_q), int(geometry))
 
 
 class _Batch(ctypes.Structure):

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "arn_gemm.h"
+#include "arn_generic.h"
 #include "arn_layout.h"
 #include "arn_problems.h"
 #include "arn_pv_head.h"
@@ -158,16 +159,71 @@ Packed view_packed(const void *blob, const Dims &d) {
     return p;
 }
 
+// fc layer (three products) and, for the categorical head, the head GEMM; shared by both geometries
+template <int FEAT_>
+void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o, float *z_out,
+                          hipStream_t s) {
+    __bf16 *a3 = (__bf16 *)(ws + o.a3), *a3l = (__bf16 *)(ws + o.a3l);
+    __bf16 *h = (__bf16 *)(ws + o.h), *hl = (__bf16 *)(ws + o.hl);
+    {
+        typedef FcFwdT<FEAT_> Fc;
+        Fc p;
+        p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
+        p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
+        p.to_partial = p.ksplit > 1 || d.small;
+        launch_nt_split("fc_fwd", p, B, HID / Fc::BN, p.ksplit, s);
+        if (p.ksplit > 1 && !d.small) {
+            ProfScope ps("fc_finish", s);
+            const long total = (long)B * HID;
+            hipLaunchKernelGGL(fc_finish_kernel, dim3(cdiv(total / 4, 256)), dim3(256), 0, s, p.partial, p.ksplit,
+                               w.bfc, h, hl, total);
+        }
+    }
+    if (d.head == ARN_HEAD_C51) {
+        HeadFwdC51 p;
+        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh; p.z = z_out; p.ZW = d.NH;
+        launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s);
+    }
+    // policy/value and action-value heads: the caller launches pv_head_kernel on the fc partial sums
+}
+
+// Convolutions of geometry G as gathered contractions (three products; conv1's pixel operand is exact: two)
+template <class G>
+void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                     float *z_out, hipStream_t s) {
+    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
+    __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
+    {
+        Conv1FwdG<G> p;
+        p.obs = obs; p.M = B * G::P1; p.w = w.w1; p.w_lo = w.w1l; p.bias = w.b1; p.out = a1; p.out_lo = a1l;
+        launch_nt_split("conv1_fwd", p, p.M, 1, 1, s);
+    }
+    {
+        Conv2FwdG<G> p;
+        p.in = a1; p.lo_off = a1l - a1; p.M = B * G::P2; p.w = w.w2; p.w_lo = w.w2l; p.bias = w.b2;
+        p.out = a2; p.out_lo = a2l;
+        launch_nt_split("conv2_fwd", p, p.M, 1, 1, s);
+    }
+    {
+        Conv3FwdG<G> p;
+        p.in = a2; p.lo_off = a2l - a2; p.M = B * G::P3; p.w = w.w3; p.w_lo = w.w3l; p.bias = w.b3;
+        p.out = a3; p.out_lo = a3l;
+        launch_nt_split("conv3_fwd", p, p.M, 1, 1, s);
+    }
+    fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, s);
+}
+
 // trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits [B][NH].
 // PV: stops after the fc GEMM, whose fp32 partial sums (o.fcp) the fused head kernel consumes.
 // masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on the online weights).
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                       float *z_out, bool masks, hipStream_t s) {
-    constexpr bool split = true;
+    if (d.geom == ARN_GEOM_PAPER) {   // the gathered path keeps no sign bits: its backward reads the activations
+        forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, s);
+        return;
+    }
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
-    __bf16 *h = (__bf16 *)(ws + o.h);
-    __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l);
-    __bf16 *a3l = (__bf16 *)(ws + o.a3l), *hl = (__bf16 *)(ws + o.hl);
+    __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
     {
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
@@ -186,26 +242,151 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
         launch_resident<ResConv3Fwd>("conv3_fwd", p, B, s);
     }
+    fc_and_head_launches<FEAT>(d, w, B, ws, o, z_out, s);
+}
+
+// Events that let work queued on the side stream see everything queued on the caller's stream so far.
+struct Fork {
+    SideStream *ss = nullptr;
+    hipStream_t s = nullptr, s2 = nullptr;
+    int n = 0;
+    void operator()() {
+        if (!ss) return;
+        (void)hipEventRecord(ss->fork[n], s);
+        (void)hipStreamWaitEvent(s2, ss->fork[n], 0);
+        ++n;
+    }
+};
+
+// Backward pass below d(pre_fc), 84x84 network: sample-resident kernels.  The input-gradient chain
+// (fc -> conv3 -> conv2, then conv1's weight gradient) runs on the caller's stream; every other weight
+// gradient and its reduction runs on the side stream as soon as the gradient it consumes exists.
+void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                             const ParamOffsets &po, const Splits &sp, float *dW, Fork &fk) {
+    hipStream_t s = fk.s, s2 = fk.s2;
+    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
+    __bf16 *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
+    __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
     {
-        FcFwd p;
-        p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
-        p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
-        p.to_partial = p.ksplit > 1 || d.small;
-        split ? launch_nt_split("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s)
-              : launch_nt("fc_fwd", p, B, HID / FcFwd::BN, p.ksplit, s);
-        if (p.ksplit > 1 && !d.small) {
-            ProfScope ps("fc_finish", s);
-            const long total = (long)B * HID;
-            hipLaunchKernelGGL(fc_finish_kernel, dim3(cdiv(total / 4, 256)), dim3(256), 0, s, p.partial, p.ksplit,
-                               w.bfc, h, hl, total);
+        FcWgrad p;
+        p.in = a3; p.M = B; p.dy = dph;
+        float *part = (float *)(ws + o.pwfc);
+        launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s2);
+        {
+            ProfScope ps("fc_reduce", s2);
+            hipLaunchKernelGGL((fc_reduce_kernel<FEAT, P3>), dim3(HID + 1), dim3(256), 0, s2, part, dW, (long)po.wfc, (long)po.bfc,
+                               sp.fc);
         }
     }
-    if (d.head == ARN_HEAD_C51) {
-        HeadFwdC51 p;
-        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh; p.z = z_out; p.ZW = d.NH;
-        launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s);
+    {
+        FcDgrad p;
+        p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
+        launch_nt("fc_dgrad", p, B, FEAT / FcDgrad::BN, 1, s);
     }
-    // policy/value head: the caller launches pv_head_kernel on the fc partial sums
+    fk();   // d(pre3)
+    {
+        float *part = (float *)(ws + o.pw3);
+        {
+            ProfScope ps("conv3_wgrad", s2);
+            const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
+                               dim3(CW_THREADS), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
+        }
+        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
+    }
+    {
+        ResConv3Dgrad::Args p;
+        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
+        launch_resident<ResConv3Dgrad>("conv3_dgrad", p, B, s);
+    }
+    fk();   // d(pre2)
+    {
+        float *part = (float *)(ws + o.pw2);
+        {
+            ProfScope ps("conv2_wgrad", s2);
+            const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 2>), dim3(sp.c2),
+                               dim3(CW_THREADS), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
+        }
+        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
+    }
+    {
+        ResConv2Dgrad::Args p;
+        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
+        launch_resident<ResConv2Dgrad>("conv2_dgrad", p, B, s);
+    }
+    // conv1: weight gradient only (the input is data)
+    {
+        float *part = (float *)(ws + o.pw1);
+        {
+            ProfScope ps("conv1_wgrad", s);
+            hipLaunchKernelGGL(conv1_wgrad_resident_kernel, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part, B,
+                               resident_spw(B, 256));
+        }
+        // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
+        launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
+    }
+}
+
+// The same for geometry G with the gathered contraction kernels; ReLU derivatives are read from the
+// stored activations.
+template <class G>
+void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                            const ParamOffsets &po, const Splits &sp, float *dW, Fork &fk) {
+    hipStream_t s = fk.s, s2 = fk.s2;
+    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
+    __bf16 *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
+    __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
+    {
+        typedef Wgrad<DenseGather<G::FEAT>, 128, 64, 2, HID, G::FEAT> FcW;
+        FcW p;
+        p.in = a3; p.M = B; p.dy = dph;
+        float *part = (float *)(ws + o.pwfc);
+        launch_tn("fc_wgrad", p, part, B, HID, G::FEAT, sp.fc, s2);
+        ProfScope ps("fc_reduce", s2);
+        hipLaunchKernelGGL((fc_reduce_kernel<G::FEAT, G::P3>), dim3(HID + 1), dim3(256), 0, s2, part, dW, (long)po.wfc,
+                           (long)po.bfc, sp.fc);
+    }
+    {
+        FcDgradAct<G::FEAT> p;
+        p.in = dph; p.M = B; p.w = w.wfcd; p.act = a3; p.out = dp3;
+        launch_nt("fc_dgrad", p, B, G::FEAT / 64, 1, s);
+    }
+    fk();   // d(pre3)
+    {
+        Conv3WgradG<G> p;
+        p.in = a2; p.M = B * G::P3; p.dy = dp3;
+        float *part = (float *)(ws + o.pw3);
+        launch_tn("conv3_wgrad", p, part, p.M, C3, KW3, sp.c3, s2);
+        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
+    }
+    {
+        Conv3DgradG<G> p;
+        p.dpre = dp3; p.w = w.w3d; p.act = a2; p.out = dp2; p.M = B * G::P2;
+        launch_nt("conv3_dgrad", p, p.M, 1, 1, s);
+    }
+    fk();   // d(pre2)
+    {
+        Conv2WgradG<G> p;
+        p.in = a1; p.M = B * G::P2; p.dy = dp2;
+        float *part = (float *)(ws + o.pw2);
+        launch_tn("conv2_wgrad", p, part, p.M, C2, KW2, sp.c2, s2);
+        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
+    }
+    {
+        Conv2DgradG<G> p;
+        p.dpre = dp2; p.w = w.w2d; p.act = a1; p.out = dp1; p.M = B * Conv2DgradG<G>::U * Conv2DgradG<G>::V;
+        launch_nt("conv2_dgrad", p, p.M, 1, 4, s);
+    }
+    // conv1: weight gradient only (the input is data)
+    {
+        Conv1WgradG<G> p;
+        p.obs = obs; p.M = B * G::P1; p.dy = dp1;
+        float *part = (float *)(ws + o.pw1);
+        launch_tn("conv1_wgrad", p, part, p.M, C1, KW1, sp.c1, s);
+        // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
+        launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
+    }
 }
 
 // Arguments of the fused policy/value head kernel that both entry points share.
@@ -453,16 +634,13 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     // The input-gradient chain (head -> fc -> conv3 -> conv2, then conv1's weight gradient) runs on the
     // caller's stream; every other weight gradient and its reduction runs on the side stream as soon as
     // the gradient it consumes exists.
-    SideStream *ss = side_stream();
-    hipStream_t s2 = ss ? ss->stream : s;
-    int nfork = 0;
-    auto fork = [&]() {   // work queued on s2 from here on sees everything queued on s so far
-        if (!ss) return;
-        (void)hipEventRecord(ss->fork[nfork], s);
-        (void)hipStreamWaitEvent(s2, ss->fork[nfork], 0);
-        ++nfork;
-    };
-    fork();   // dz (and, for the policy/value head, d(pre_fc))
+    Fork fk;
+    fk.ss = side_stream();
+    fk.s = s;
+    fk.s2 = fk.ss ? fk.ss->stream : s;
+    SideStream *ss = fk.ss;
+    hipStream_t s2 = fk.s2;
+    fk();   // dz (and, for the policy/value head, d(pre_fc))
     {
         // the reported loss values are off the critical path: block partial sums are added on the side stream
         ProfScope ps("loss_finalize", s2);
@@ -482,66 +660,9 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         p.in = dz; p.M = B; p.K = d.NHP; p.w = w.whd; p.h = h; p.out = dph;
         launch_nt("head_dgrad", p, B, HID / HeadDgrad::BN, 1, s);
     }
-    fork();   // d(pre_fc)
-    {
-        FcWgrad p;
-        p.in = a3; p.M = B; p.dy = dph;
-        float *part = (float *)(ws + o.pwfc);
-        launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s2);
-        {
-            ProfScope ps("fc_reduce", s2);
-            hipLaunchKernelGGL(fc_reduce_kernel, dim3(HID + 1), dim3(256), 0, s2, part, dW, (long)po.wfc, (long)po.bfc,
-                               sp.fc);
-        }
-    }
-    {
-        FcDgrad p;
-        p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
-        launch_nt("fc_dgrad", p, B, FEAT / FcDgrad::BN, 1, s);
-    }
-    fork();   // d(pre3)
-    {
-        float *part = (float *)(ws + o.pw3);
-        {
-            ProfScope ps("conv3_wgrad", s2);
-            const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
-                               dim3(CW_THREADS), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
-        }
-        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
-    }
-    {
-        ResConv3Dgrad::Args p;
-        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
-        launch_resident<ResConv3Dgrad>("conv3_dgrad", p, B, s);
-    }
-    fork();   // d(pre2)
-    {
-        float *part = (float *)(ws + o.pw2);
-        {
-            ProfScope ps("conv2_wgrad", s2);
-            const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 2>), dim3(sp.c2),
-                               dim3(CW_THREADS), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
-        }
-        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
-    }
-    {
-        ResConv2Dgrad::Args p;
-        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
-        launch_resident<ResConv2Dgrad>("conv2_dgrad", p, B, s);
-    }
-    // conv1: weight gradient only (the input is data)
-    {
-        float *part = (float *)(ws + o.pw1);
-        {
-            ProfScope ps("conv1_wgrad", s);
-            hipLaunchKernelGGL(conv1_wgrad_resident_kernel, dim3(sp.c1), dim3(C1W_THREADS), 0, s, batch->obs, dp1, part, B,
-                               resident_spw(B, 256));
-        }
-        // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
-        launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
-    }
+    fk();   // d(pre_fc)
+    if (d.geom == ARN_GEOM_PAPER) backward_trunk_generic<GeoPaper>(w, batch->obs, B, ws, o, po, sp, dW, fk);
+    else backward_trunk_resident(w, batch->obs, B, ws, o, po, sp, dW, fk);
     if (ss) {   // join: the caller's stream continues only after the side stream's work
         (void)hipEventRecord(ss->join, s2);
         (void)hipStreamWaitEvent(s, ss->join, 0);

@@ -372,7 +372,9 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
     constexpr int YROW = YC + 1, XROW = XC + 1;        // padded LDS row, in u32x4
     constexpr int Y_CH = 64 * YC / 256, X_CH = 64 * XC / 256;
     static_assert(TY >= 1 && TX >= 1 && Y_CH >= 1 && X_CH >= 1, "tile shape");
-    static_assert(256 % YC == 0 && (256 / YC) * BN1 * 4 <= 64 * YROW * 16, "bias-gradient scratch");
+    constexpr int BIAS_SCRATCH = (256 / YC) * BN1 * 4;   // bytes: one partial bias sum per thread and column
+    constexpr bool SCRATCH_IN_Y = BIAS_SCRATCH <= 64 * YROW * 16;
+    static_assert(256 % YC == 0 && (SCRATCH_IN_Y || BIAS_SCRATCH <= 64 * XROW * 16), "bias-gradient scratch");
 
     __shared__ u32x4 sY[64 * YROW];
     __shared__ u32x4 sX[64 * XROW];
@@ -465,7 +467,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
     if (keeps_bias) {
         // the 256/YC threads that share a column add their sums in thread order
         __syncthreads();
-        float *scr = reinterpret_cast<float *>(sY);
+        float *scr = reinterpret_cast<float *>(SCRATCH_IN_Y ? sY : sX);
 #pragma unroll
         for (int e = 0; e < 8; ++e) scr[(tid / YC) * BN1 + (tid % YC) * 8 + e] = bs[e];
         __syncthreads();

@@ -24,6 +24,24 @@ constexpr int HID = 512;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Frame size and padding of the convolution stack as compile-time constants (the filter shapes above are
+// common to both).  Geo84 restates the constants above; GeoPaper is the appendix's own setting: 104x80
+// frames, no padding on conv1, padding 1 on conv2 and conv3.
+template <int IN_H_, int IN_W_, int PAD2_, int PAD3_>
+struct Geometry {
+    static constexpr int IN_H = IN_H_, IN_W = IN_W_, PAD2 = PAD2_, PAD3 = PAD3_;
+    static constexpr int H1 = (IN_H - K1) / S1 + 1, W1 = (IN_W - K1) / S1 + 1;
+    static constexpr int H2 = (H1 + 2 * PAD2 - K2) / S2 + 1, W2 = (W1 + 2 * PAD2 - K2) / S2 + 1;
+    static constexpr int H3 = (H2 + 2 * PAD3 - K3) / S3 + 1, W3 = (W2 + 2 * PAD3 - K3) / S3 + 1;
+    static constexpr int P1 = H1 * W1, P2 = H2 * W2, P3 = H3 * W3;
+    static constexpr int OBS_BYTES = IN_C * IN_H * IN_W, FEAT = C3 * P3;
+};
+typedef Geometry<84, 84, 0, 0> Geo84;
+typedef Geometry<104, 80, 1, 1> GeoPaper;
+static_assert(Geo84::P1 == P1 && Geo84::P2 == P2 && Geo84::P3 == P3 && Geo84::FEAT == FEAT, "84x84 constants");
+static_assert(GeoPaper::H1 == 25 && GeoPaper::W1 == 19 && GeoPaper::H2 == 12 && GeoPaper::W2 == 9 &&
+              GeoPaper::H3 == 12 && GeoPaper::W3 == 9 && GeoPaper::FEAT == 6912, "appendix: 25x19 -> 12x9 -> 12x9");
+
 struct Dims {
     int A = 0, head = 0, atoms = 0;
     int NH = 0;    // real head rows: A+1 (PV, DUEL), A (Q) or A*atoms (C51)
@@ -31,6 +49,8 @@ struct Dims {
     bool small = false;   // at most 32 head rows: the fused head kernel follows the fc GEMM (PV, Q, DUEL)
     bool vrow = false;    // the row after the A action rows is a state value (PV, DUEL)
     bool qhead = false;   // the head outputs are action values (Q, DUEL)
+    int geom = ARN_GEOM_84;
+    int p1 = P1, p2 = P2, p3 = P3, feat = FEAT, obs_bytes = OBS_BYTES;   // positions per sample after conv1..3, fc inputs, bytes per observation
     bool ok = false;
 };
 
@@ -39,6 +59,13 @@ inline Dims make_dims(const arn_config *c) {
     if (!c) return d;
     d.A = c->num_actions;
     d.head = c->head_kind;
+    d.geom = c->geometry;
+    if (d.geom == ARN_GEOM_PAPER) {
+        d.p1 = GeoPaper::P1; d.p2 = GeoPaper::P2; d.p3 = GeoPaper::P3;
+        d.feat = GeoPaper::FEAT; d.obs_bytes = GeoPaper::OBS_BYTES;
+    } else if (d.geom != ARN_GEOM_84) {
+        return d;
+    }
     if (d.head == ARN_HEAD_PV || d.head == ARN_HEAD_Q || d.head == ARN_HEAD_DUEL) {
         if (d.A < 1 || d.A > 31) return d;
         d.atoms = 1;
@@ -72,7 +99,7 @@ inline ParamOffsets param_offsets(const Dims &d) {
     o.b2 = p; p += C2;
     o.w3 = p; p += (size_t)C3 * KW3;
     o.b3 = p; p += C3;
-    o.wfc = p; p += (size_t)HID * FEAT;
+    o.wfc = p; p += (size_t)HID * d.feat;
     o.bfc = p; p += HID;
     if (d.vrow) {
         o.wh = p; p += (size_t)d.A * HID;
@@ -103,7 +130,7 @@ inline PackedOffsets packed_offsets(const Dims &d) {
     o.w1 = take((size_t)C1 * KW1 * 2);
     o.w2 = take((size_t)C2 * KW2 * 2);
     o.w3 = take((size_t)C3 * KW3 * 2);
-    o.wfc = take((size_t)HID * FEAT * 2);
+    o.wfc = take((size_t)HID * d.feat * 2);
     o.wh = take((size_t)d.NHP * HID * 2);
     o.b1 = take(C1 * 4);
     o.b2 = take(C2 * 4);
@@ -114,10 +141,10 @@ inline PackedOffsets packed_offsets(const Dims &d) {
     o.w1l = take((size_t)C1 * KW1 * 2);
     o.w2l = take((size_t)C2 * KW2 * 2);
     o.w3l = take((size_t)C3 * KW3 * 2);
-    o.wfcl = take((size_t)HID * FEAT * 2);
+    o.wfcl = take((size_t)HID * d.feat * 2);
     o.whl = take((size_t)d.NHP * HID * 2);
     o.whd = take((size_t)HID * d.NHP * 2);
-    o.wfcd = take((size_t)FEAT * HID * 2);
+    o.wfcd = take((size_t)d.feat * HID * 2);
     o.w3d = take((size_t)C2 * KW3 * 2);
     o.w2d = take((size_t)4 * C1 * 4 * C2 * 2);
     o.total = p;
@@ -148,6 +175,16 @@ inline int resident_groups(int B, int target_wgs) {
 }
 inline Splits make_splits(const Dims &d, int B) {
     Splits s;
+    if (d.geom != ARN_GEOM_84) {
+        // gathered (implicit-GEMM) weight-gradient kernels: rows = samples x positions, cut so that about
+        // 1024 (512 for the dense layers) workgroups exist
+        s.c1 = pick_split((long)B * d.p1, 2, 1024);
+        s.c2 = pick_split((long)B * d.p2, 4, 1024);
+        s.c3 = pick_split((long)B * d.p3, 9, 1024);
+        s.fc = pick_split(B, (d.feat / 64) * 4, 512);
+        s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
+        return s;
+    }
     s.c1 = resident_groups(B, 256);
     s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS);
     s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS);
@@ -190,13 +227,14 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     size_t p = 0;
     auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes, 256); return at; };
     const size_t b = (size_t)B;
-    w.a1 = take(b * P1 * C1 * 2);
-    w.a2 = take(b * P2 * C2 * 2);
-    w.a3 = take(b * FEAT * 2);
+    const size_t p1 = (size_t)d.p1, p2 = (size_t)d.p2, feat = (size_t)d.feat;
+    w.a1 = take(b * p1 * C1 * 2);
+    w.a2 = take(b * p2 * C2 * 2);
+    w.a3 = take(b * feat * 2);
     w.h = take(b * HID * 2);
-    w.a1l = take(b * P1 * C1 * 2);
-    w.a2l = take(b * P2 * C2 * 2);
-    w.a3l = take(b * FEAT * 2);
+    w.a1l = take(b * p1 * C1 * 2);
+    w.a2l = take(b * p2 * C2 * 2);
+    w.a3l = take(b * feat * 2);
     w.hl = take(b * HID * 2);
     // the fused policy/value head kernel always reads fp32 partials; the categorical path only when k is split
     w.fcp = take((size_t)(fc_ksplit(B) > 1 || d.small ? fc_ksplit(B) : 0) * b * HID * 4);
@@ -213,20 +251,20 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
             w.ztgt = take(b * (size_t)d.NH * 4);
             w.m = take(b * (size_t)d.atoms * 4);
         }
-        w.m1 = take(b * P1 * C1 / 8);
-        w.m2 = take(b * P2 * C2 / 8);
-        w.m3 = take(b * FEAT / 8);
+        w.m1 = take(b * p1 * C1 / 8);
+        w.m2 = take(b * p2 * C2 / 8);
+        w.m3 = take(b * feat / 8);
         w.dz = take(b * (size_t)d.NHP * 2);
         w.dph = take(b * HID * 2);
-        w.dp3 = take(b * FEAT * 2);
-        w.dp2 = take(b * P2 * C2 * 2);
-        w.dp1 = take(b * P1 * C1 * 2);
+        w.dp3 = take(b * feat * 2);
+        w.dp2 = take(b * p2 * C2 * 2);
+        w.dp1 = take(b * p1 * C1 * 2);
         w.lossp = take((size_t)loss_blocks(d, B) * 4 * 4);
         const Splits s = make_splits(d, B);
         w.pw1 = take((size_t)s.c1 * ((size_t)C1 * KW1 + C1) * 4);
         w.pw2 = take((size_t)s.c2 * ((size_t)C2 * KW2 + C2) * 4);
         w.pw3 = take((size_t)s.c3 * ((size_t)C3 * KW3 + C3) * 4);
-        w.pwfc = take((size_t)s.fc * ((size_t)HID * FEAT + HID) * 4);
+        w.pwfc = take((size_t)s.fc * ((size_t)HID * feat + HID) * 4);
         w.pwh = take((size_t)s.hd * ((size_t)d.NHP * HID + d.NHP) * 4);
     }
     w.total = p;

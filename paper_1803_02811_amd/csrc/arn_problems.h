@@ -63,8 +63,10 @@ struct DenseGatherRt {
 // of k-tiles and writes an fp32 partial [z][M][512]; fc_finish_kernel adds the
 // partials in z order and applies bias, ReLU and the hi/lo split.  With
 // ksplit == 1 the epilogue does that directly.
-struct FcFwd : DenseGather<FEAT> {
-    static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT, STAGES = 2, THREADS = 512;
+template <int FEAT_>
+struct FcFwdT : DenseGather<FEAT_> {
+    typedef typename DenseGather<FEAT_>::Row Row;
+    static constexpr int BM = 128, BN = 128, WAVES_N = 2, K = FEAT_, STAGES = 2, THREADS = 512;
     static constexpr bool ACT_LO = true;
     int ksplit;
     bool to_partial;     // write fp32 partial sums even with ksplit == 1 (the consumer finishes the layer)
@@ -72,12 +74,13 @@ struct FcFwd : DenseGather<FEAT> {
     const float *bias;
     __bf16 *out, *out_lo = nullptr;
     float *partial;
-    __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
-    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
-    __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
+    __device__ __forceinline__ Row row(int m, int) const { return this->row_at(m); }
+    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return this->load_at(r, k); }
+    __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return this->load_lo_at(r, k); }
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {
+        const int M = this->M;
         if (m >= M) return;
         if (to_partial) {
             *reinterpret_cast<float4 *>(partial + ((size_t)z * M + m) * HID + n) = make_float4(v[0], v[1], v[2], v[3]);
@@ -88,6 +91,7 @@ struct FcFwd : DenseGather<FEAT> {
                            fmaxf(v[2] + b.z, 0.f), fmaxf(v[3] + b.w, 0.f));
     }
 };
+typedef FcFwdT<FEAT> FcFwd;
 
 // categorical head: rows of the packed head matrix are the A*atoms categorical rows
 // C51: atom logits fp32 [M][A*atoms] with bias.
@@ -132,11 +136,12 @@ struct HeadDgrad : DenseGatherRt {
     }
 };
 
-// d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][3136], NHWC index
-struct FcDgrad : DenseGather<HID> {
-    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 2;
-    const __bf16 *w;          // [3136][512]
-    const uint8_t *maskbits;  // sign bits of act3, bit e&7 of byte e>>3 for element e = m*3136 + n
+// d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][FEAT], NHWC index
+template <int FEAT_>
+struct FcDgradT : DenseGather<HID> {
+    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 2, FEAT = FEAT_;
+    const __bf16 *w;          // [FEAT][512]
+    const uint8_t *maskbits;  // sign bits of act3, bit e&7 of byte e>>3 for element e = m*FEAT + n
     __bf16 *out;
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
     __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
@@ -153,6 +158,7 @@ struct FcDgrad : DenseGather<HID> {
             pack_bf16x4(mb & 1 ? v[0] : 0.f, mb & 2 ? v[1] : 0.f, mb & 4 ? v[2] : 0.f, mb & 8 ? v[3] : 0.f);
     }
 };
+typedef FcDgradT<FEAT> FcDgrad;
 
 // --------------------------- weight gradients -----------------------------
 // part[n][k] = sum_m dY[m][n] act(m,k); dY is a dense [M][N1] bf16 matrix.

@@ -29,11 +29,12 @@ struct MapConvFwd {    // packed [co][(ky*KS+kx)*CIN+ci]  <-  W[co][ci][ky][kx]
         return off + (((long)co * CIN + ci) * KS + ky) * KS + kx;
     }
 };
-struct MapFcFwd {      // packed [n][pos*64+c]  <-  Wfc[n][c*49+pos]
+struct MapFcFwd {      // packed [n][pos*64+c]  <-  Wfc[n][c*P3+pos]   (P3 positions after conv3, feat = 64 P3)
     long off;
+    int feat, p3;
     __device__ long operator()(long i) const {
-        const int n = (int)(i / FEAT), k = (int)(i % FEAT), pos = k >> 6, c = k & 63;
-        return off + (long)n * FEAT + c * P3 + pos;
+        const int n = (int)(i / feat), k = (int)(i % feat), pos = k >> 6, c = k & 63;
+        return off + (long)n * feat + c * p3 + pos;
     }
 };
 struct MapHeadRow {    // head row r of the packed head -> offset of its weight row / bias, or -1 (pv: A action rows then a value row)
@@ -73,11 +74,12 @@ struct MapHeadDgrad {  // packed [j][r]  (NHP columns)
         return b < 0 ? -1 : b + i / NHP;
     }
 };
-struct MapFcDgrad {    // packed [pos*64+c][n]  <-  Wfc[n][c*49+pos]
+struct MapFcDgrad {    // packed [pos*64+c][n]  <-  Wfc[n][c*P3+pos]
     long off;
+    int feat, p3;
     __device__ long operator()(long i) const {
         const int k = (int)(i / HID), n = (int)(i % HID), pos = k >> 6, c = k & 63;
-        return off + (long)n * FEAT + c * P3 + pos;
+        return off + (long)n * feat + c * p3 + pos;
     }
 };
 struct MapConv3Dgrad { // packed [ci][(ty*3+tx)*64+co]  <-  W3[co][ci][2-ty][2-tx]
@@ -136,9 +138,10 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(F f, const float *
         dW[dst] = i < wcount ? t * wscale : t;
     }
 }
-// The fc layer's partials are [n][pos*64 + c] while the canonical weight is [n][c*49 + pos]: one workgroup
-// per output row n adds the splits with contiguous reads, permutes the row in LDS (stride 49 words: no bank
-// conflicts) and writes it out contiguously.  Workgroup HID handles the bias gradient.
+// The fc layer's partials are [n][pos*64 + c] while the canonical weight is [n][c*P3 + pos]: one workgroup
+// per output row n adds the splits with contiguous reads, permutes the row in LDS (stride 49 words at
+// 84x84: no bank conflicts) and writes it out contiguously.  Workgroup HID handles the bias gradient.
+template <int FEAT, int P3>
 __global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict__ part, float *__restrict__ dW,
                                                         long woff, long boff, int splits) {
     __shared__ float row[FEAT];
@@ -175,14 +178,6 @@ struct UnmapConv {     // partial [co][(ky*KS+kx)*CIN+ci] then [co] bias
 struct UnmapConv1 {
     long woff, boff;
     __device__ long operator()(long i) const { return i >= C1 * KW1 ? boff + (i - C1 * KW1) : woff + i; }
-};
-struct UnmapFc {
-    long woff, boff;
-    __device__ long operator()(long i) const {
-        if (i >= (long)HID * FEAT) return boff + (i - (long)HID * FEAT);
-        const int n = (int)(i / FEAT), k = (int)(i % FEAT), pos = k >> 6, c = k & 63;
-        return woff + (long)n * FEAT + c * P3 + pos;
-    }
 };
 struct UnmapHead {
     MapHeadRow h;

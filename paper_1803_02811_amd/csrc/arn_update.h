@@ -141,6 +141,7 @@ struct PackPlan {
     long w1, w2, w3, wfc, b1, b2, b3, bfc;   // offsets in the flat vector
     MapHeadRow hr;
     int NHP;
+    int feat, p3;   // fc inputs and positions after conv3
     int blocks;
 };
 
@@ -153,6 +154,8 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     pl.b1 = (long)po.b1; pl.b2 = (long)po.b2; pl.b3 = (long)po.b3; pl.bfc = (long)po.bfc;
     pl.hr = head_rows(d, po);
     pl.NHP = d.NHP;
+    pl.feat = d.feat;
+    pl.p3 = d.p3;
     auto set = [&](int k, long n, size_t out, size_t lo, bool has_lo) {
         pl.seg[k].n = n;
         pl.seg[k].out = b + out;
@@ -161,7 +164,7 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     set(PK_W1, (long)C1 * KW1, o.w1, o.w1l, true);
     set(PK_W2, (long)C2 * KW2, o.w2, o.w2l, true);
     set(PK_W3, (long)C3 * KW3, o.w3, o.w3l, true);
-    set(PK_WFC, (long)HID * FEAT, o.wfc, o.wfcl, true);
+    set(PK_WFC, (long)HID * d.feat, o.wfc, o.wfcl, true);
     set(PK_WH, (long)d.NHP * HID, o.wh, o.whl, true);
     set(PK_B1, C1, o.b1, 0, false);
     set(PK_B2, C2, o.b2, 0, false);
@@ -169,7 +172,7 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     set(PK_BFC, HID, o.bfc, 0, false);
     set(PK_BH, d.NHP, o.bh, 0, false);
     set(PK_WHD, (long)HID * d.NHP, o.whd, 0, false);
-    set(PK_WFCD, (long)FEAT * HID, o.wfcd, 0, false);
+    set(PK_WFCD, (long)d.feat * HID, o.wfcd, 0, false);
     set(PK_W3D, (long)C2 * KW3, o.w3d, 0, false);
     set(PK_W2D, (long)4 * C1 * 256, o.w2d, 0, false);
     int blk = 0;
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float 
     case PK_W1: s = pl.w1 + i; break;
     case PK_W2: s = MapConvFwd<C1, K2>{pl.w2}(i); break;
     case PK_W3: s = MapConvFwd<C2, K3>{pl.w3}(i); break;
-    case PK_WFC: s = MapFcFwd{pl.wfc}(i); break;
+    case PK_WFC: s = MapFcFwd{pl.wfc, pl.feat, pl.p3}(i); break;
     case PK_WH: s = MapHeadFwd{pl.hr}(i); break;
     case PK_B1: s = pl.b1 + i; break;
     case PK_B2: s = pl.b2 + i; break;
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float 
     case PK_BFC: s = pl.bfc + i; break;
     case PK_BH: s = MapHeadBias{pl.hr}(i); break;
     case PK_WHD: s = MapHeadDgrad{pl.hr, pl.NHP}(i); break;
-    case PK_WFCD: s = MapFcDgrad{pl.wfc}(i); break;
+    case PK_WFCD: s = MapFcDgrad{pl.wfc, pl.feat, pl.p3}(i); break;
     case PK_W3D: s = MapConv3Dgrad{pl.w3}(i); break;
     default: s = MapConv2Dgrad{pl.w2}(i); break;
     }

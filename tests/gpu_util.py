@@ -23,9 +23,9 @@ def tol_check(got, ref, name, rel=1e-2, abs_=1e-3):
 class GpuNet:
     """Packed weights + workspace for one config; thin wrapper over the binding."""
 
-    def __init__(self, num_actions, head, flat_params, num_atoms=51, **hyper):
+    def __init__(self, num_actions, head, flat_params, num_atoms=51, geometry="84", **hyper):
         self.head = head
-        self.cfg = arn.Config(num_actions, arn.HEAD_KINDS[head], num_atoms, **hyper)
+        self.cfg = arn.Config(num_actions, arn.HEAD_KINDS[head], num_atoms, geometry=arn.GEOMETRIES[geometry], **hyper)
         self.A, self.atoms = num_actions, num_atoms
         self.nparam = arn.param_count(self.cfg)
         assert self.nparam == flat_params.size
@@ -104,5 +104,5 @@ class GpuNet:
         return dW.cpu().numpy(), loss.cpu().numpy()
 
 
-def per_tensor(flat, A, head, atoms=51):
-    return wl.split_params(np.asarray(flat), A, head, atoms)
+def per_tensor(flat, A, head, atoms=51, fc_inputs=wl.FC_INPUTS[wl.FRAME]):
+    return wl.split_params(np.asarray(flat), A, head, atoms, fc_inputs)

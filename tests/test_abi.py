@@ -38,6 +38,22 @@ def test_param_counts_match_the_oracle_layout(lib):
     assert arn.param_count(arn.Config(18, arn.ARN_HEAD_C51)) == 2_155_062
 
 
+def test_paper_geometry_sizes(lib):
+    """Appendix "Atari Frame Processing": 104x80 frames, conv2/conv3 padded by 1 -> 12x9 feature map, fc 6912 -> 512."""
+    for A, head, okind in [(18, arn.ARN_HEAD_PV, "pv"), (18, arn.ARN_HEAD_C51, "c51"), (6, arn.ARN_HEAD_DUEL, "duel")]:
+        cfg = arn.Config(A, head, geometry=arn.ARN_GEOM_PAPER)
+        assert arn.param_count(cfg) == orc.param_count(orc.NetSpec(A, okind, geometry=orc.PAPER_104x80))
+    cfg = arn.Config(18, geometry=arn.ARN_GEOM_PAPER)
+    assert arn.param_count(cfg) == 1_693_875 + 512 * (6912 - 3136)
+    assert arn.packed_bytes(cfg) > arn.packed_bytes(arn.Config(18))
+    assert arn.workspace_bytes(cfg, 64, arn.ARN_MODE_TRAIN) > arn.workspace_bytes(arn.Config(18), 64, arn.ARN_MODE_TRAIN)
+    bad = arn.Config(18, geometry=2)
+    assert arn.param_count(bad) == 0 and arn.packed_bytes(bad) == 0
+    assert arn.workspace_bytes(bad, 64, arn.ARN_MODE_FORWARD) == 0
+    fake = ctypes.c_void_p(1 << 20)
+    assert lib.arn_weights_prepare(ctypes.byref(bad), fake, fake, None) == -2
+
+
 def test_sizes_and_bad_configs(lib):
     cfg = arn.Config(18, arn.ARN_HEAD_PV)
     assert arn.packed_bytes(cfg) > 2 * 1_693_875          # bf16 copies of every matrix

@@ -6,6 +6,9 @@ import workloads as wl
 from oracle import nature_cnn as orc
 
 SMALL = orc.Geometry(in_ch=2, in_h=20, in_w=20, convs=((3, 4, 2, 0), (4, 3, 1, 0), (4, 2, 1, 0)), hidden=6)
+# a small non-square stack padded like the paper's own (appendix "Atari Frame Processing": no padding on the first
+# layer, padding 1 on a stride-2 4x4 and on a stride-1 3x3 layer)
+SMALL_PADDED = orc.Geometry(in_ch=2, in_h=22, in_w=18, convs=((3, 4, 2, 0), (4, 4, 2, 1), (4, 3, 1, 1)), hidden=6)
 
 
 def _rand_params(spec, seed, bias=True):
@@ -78,24 +81,26 @@ def _total_loss(flat, spec, batch, kind, tflat=None):
     return orc.c51_loss_value(c["atom_logits"], batch["action"], m)["total"]
 
 
-@pytest.mark.parametrize("kind", ["a2c", "ppo", "c51"])
-def test_whole_backward_by_finite_differences(kind):
+@pytest.mark.parametrize("kind,geometry", [("a2c", SMALL), ("ppo", SMALL), ("c51", SMALL), ("a2c", SMALL_PADDED),
+                                           ("c51", SMALL_PADDED)])
+def test_whole_backward_by_finite_differences(kind, geometry):
     """Central differences of the scalar loss on a sample of coordinates of every
-    tensor, small geometry, non-zero biases, B = 3."""
+    tensor, small geometries (one of them padded and non-square), non-zero biases, B = 3."""
     r = np.random.default_rng(21)
     A = 4
-    spec = orc.NetSpec(A, "c51" if kind == "c51" else "pv", num_atoms=5, geometry=SMALL)
+    spec = orc.NetSpec(A, "c51" if kind == "c51" else "pv", num_atoms=5, geometry=geometry)
+    frame = (2, geometry.in_h, geometry.in_w)
     flat = orc.flatten(_rand_params(spec, 22), spec)
     tflat = orc.flatten(_rand_params(spec, 23), spec)
     B = 3
-    obs = r.integers(0, 256, size=(B, 2, 20, 20), dtype=np.uint8)
+    obs = r.integers(0, 256, size=(B,) + frame, dtype=np.uint8)
     batch = dict(obs=obs, action=r.integers(0, A, size=B), adv=r.standard_normal(B), ret=r.standard_normal(B))
     if kind == "ppo":
         c = orc.forward(orc.unflatten(flat, spec), obs, spec)
         lp = orc.log_softmax(c["logits"])[np.arange(B), batch["action"]]
         batch["old_logp"] = lp + np.array([0.05, -0.05, 0.3])
     if kind == "c51":
-        batch.update(next_obs=r.integers(0, 256, size=(B, 2, 20, 20), dtype=np.uint8),
+        batch.update(next_obs=r.integers(0, 256, size=(B,) + frame, dtype=np.uint8),
                      reward=np.array([1.0, -1.0, 0.0]), done=np.array([0, 0, 1], dtype=np.uint8))
     out = orc.train_step_grads(flat, batch, kind, spec, flat_target_params=tflat)
     g = out["flat"]

@@ -20,6 +20,10 @@ from typing import Dict, List, Sequence, Tuple
 import numpy as np
 
 FRAME = (4, 84, 84)
+# the frame size of the paper's own runs (appendix "Atari Frame Processing": 104x80, convolutions padded so
+# that the feature map is 12x9) and the fc input sizes that go with the two frame sizes
+PAPER_FRAME = (4, 104, 80)
+FC_INPUTS = {FRAME: 64 * 7 * 7, PAPER_FRAME: 64 * 12 * 9}
 
 WORKLOADS = {
     1: dict(name="fwd_b16", B=16, A=6, head="pv", kind="forward", frames="uniform"),
@@ -34,12 +38,12 @@ def rng(seed: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(seed))
 
 
-def uniform_frames(B: int, seed: int) -> np.ndarray:
-    """uint8 [B,4,84,84], every pixel i.i.d. uniform on 0..255."""
-    return rng(seed).integers(0, 256, size=(B,) + FRAME, dtype=np.uint8)
+def uniform_frames(B: int, seed: int, frame: Tuple[int, int, int] = FRAME) -> np.ndarray:
+    """uint8 [B,4,H,W], every pixel i.i.d. uniform on 0..255."""
+    return rng(seed).integers(0, 256, size=(B,) + tuple(frame), dtype=np.uint8)
 
 
-def rect_frames(B: int, seed: int, with_next: bool = False):
+def rect_frames(B: int, seed: int, with_next: bool = False, frame: Tuple[int, int, int] = FRAME):
     """Smooth structured stacks: black background, 4..12 random rectangles of
     side 4..32 and intensity 1..255 (later ones overwrite earlier ones); frame f
     of a stack is frame 0 translated by f*(dx,dy), dx,dy in +-{1,2,3}, zero
@@ -47,7 +51,7 @@ def rect_frames(B: int, seed: int, with_next: bool = False):
     1..3 followed by frame 0 translated by 4*(dx,dy).
     """
     g = rng(seed)
-    C, H, W = FRAME
+    C, H, W = frame
     obs = np.zeros((B, C, H, W), dtype=np.uint8)
     nxt = np.zeros((B, C, H, W), dtype=np.uint8) if with_next else None
     for n in range(B):
@@ -74,12 +78,13 @@ def _shift(img: np.ndarray, dy: int, dx: int) -> np.ndarray:
     return out
 
 
-def param_shapes(num_actions: int, head: str, num_atoms: int = 51) -> List[Tuple[str, Tuple[int, ...]]]:
+def param_shapes(num_actions: int, head: str, num_atoms: int = 51,
+                 fc_inputs: int = FC_INPUTS[FRAME]) -> List[Tuple[str, Tuple[int, ...]]]:
     """Canonical flat order of the parameter vector (interface, fixed by the C header)."""
     out = [("conv1.W", (32, 4, 8, 8)), ("conv1.b", (32,)),
            ("conv2.W", (64, 32, 4, 4)), ("conv2.b", (64,)),
            ("conv3.W", (64, 64, 3, 3)), ("conv3.b", (64,)),
-           ("fc.W", (512, 3136)), ("fc.b", (512,))]
+           ("fc.W", (512, fc_inputs)), ("fc.b", (512,))]
     if head == "pv":
         out += [("pi.W", (num_actions, 512)), ("pi.b", (num_actions,)), ("v.W", (1, 512)), ("v.b", (1,))]
     elif head == "c51":
@@ -94,12 +99,12 @@ def param_shapes(num_actions: int, head: str, num_atoms: int = 51) -> List[Tuple
 
 
 def he_normal_params(num_actions: int, head: str, seed: int, num_atoms: int = 51,
-                     bias_std: float = 0.0) -> np.ndarray:
+                     bias_std: float = 0.0, fc_inputs: int = FC_INPUTS[FRAME]) -> np.ndarray:
     """Flat fp32 vector: every weight tensor ~ N(0, 2/fan_in); biases 0, or
     N(0, bias_std^2) when a test wants the bias paths exercised."""
     g = rng(seed)
     parts = []
-    for name, shp in param_shapes(num_actions, head, num_atoms):
+    for name, shp in param_shapes(num_actions, head, num_atoms, fc_inputs):
         if name.endswith(".W"):
             fan_in = int(np.prod(shp[1:]))
             parts.append(g.standard_normal(shp).reshape(-1) * np.sqrt(2.0 / fan_in))
@@ -108,9 +113,10 @@ def he_normal_params(num_actions: int, head: str, seed: int, num_atoms: int = 51
     return np.concatenate(parts).astype(np.float32)
 
 
-def split_params(flat: np.ndarray, num_actions: int, head: str, num_atoms: int = 51) -> Dict[str, np.ndarray]:
+def split_params(flat: np.ndarray, num_actions: int, head: str, num_atoms: int = 51,
+                 fc_inputs: int = FC_INPUTS[FRAME]) -> Dict[str, np.ndarray]:
     out, o = {}, 0
-    for name, shp in param_shapes(num_actions, head, num_atoms):
+    for name, shp in param_shapes(num_actions, head, num_atoms, fc_inputs):
         n = int(np.prod(shp))
         out[name] = flat[o:o + n].reshape(shp)
         o += n
@@ -118,17 +124,18 @@ def split_params(flat: np.ndarray, num_actions: int, head: str, num_atoms: int =
     return out
 
 
-def frames_for(k: int, B: int | None = None, with_next: bool = False):
+def frames_for(k: int, B: int | None = None, with_next: bool = False, frame: Tuple[int, int, int] = FRAME):
     w = WORKLOADS[k]
     B = w["B"] if B is None else B
     if w["frames"] == "uniform":
         if with_next:
-            return uniform_frames(B, 1000 + k), uniform_frames(B, 1500 + k)
-        return uniform_frames(B, 1000 + k)
-    return rect_frames(B, 1000 + k, with_next=with_next)
+            return uniform_frames(B, 1000 + k, frame), uniform_frames(B, 1500 + k, frame)
+        return uniform_frames(B, 1000 + k, frame)
+    return rect_frames(B, 1000 + k, with_next=with_next, frame=frame)
 
 
-def actor_critic_batch(k: int, B: int | None = None, normalise_adv: bool = False) -> dict:
+def actor_critic_batch(k: int, B: int | None = None, normalise_adv: bool = False,
+                       frame: Tuple[int, int, int] = FRAME) -> dict:
     """obs, action ~ U{0..A-1}, adv ~ N(0,1) (optionally standardised over the
     batch with population std + 1e-8), ret ~ N(0,1)."""
     w = WORKLOADS[k]
@@ -137,7 +144,7 @@ def actor_critic_batch(k: int, B: int | None = None, normalise_adv: bool = False
     adv = g.standard_normal(B)
     if normalise_adv:
         adv = (adv - adv.mean()) / (adv.std() + 1e-8)
-    return {"obs": frames_for(k, B),
+    return {"obs": frames_for(k, B, frame=frame),
             "action": g.integers(0, w["A"], size=B).astype(np.int32),
             "adv": adv.astype(np.float32),
             "ret": g.standard_normal(B).astype(np.float32)}
@@ -149,13 +156,13 @@ def logit_noise(k: int, B: int, A: int, std: float = 0.05) -> np.ndarray:
     return rng(1200 + k).standard_normal((B, A)) * std
 
 
-def c51_batch(k: int = 5, B: int | None = None) -> dict:
+def c51_batch(k: int = 5, B: int | None = None, frame: Tuple[int, int, int] = FRAME) -> dict:
     """obs / next_obs (a real frame-stack transition), action ~ U{0..17},
     reward ~ U{-1,0,1}, done ~ Bernoulli(0.01)."""
     w = WORKLOADS[k]
     B = w["B"] if B is None else B
     g = rng(1100 + k)
-    obs, nxt = frames_for(k, B, with_next=True)
+    obs, nxt = frames_for(k, B, with_next=True, frame=frame)
     return {"obs": obs, "next_obs": nxt,
             "action": g.integers(0, w["A"], size=B).astype(np.int32),
             "reward": g.integers(-1, 2, size=B).astype(np.float32),
