@@ -376,7 +376,7 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     {
         Conv2DgradG<G> p;
         p.dpre = dp2; p.w = w.w2d; p.act = a1; p.out = dp1; p.M = B * Conv2DgradG<G>::U * Conv2DgradG<G>::V;
-        launch_nt("conv2_dgrad", p, p.M, 1, 4, s);
+        launch_nt("conv2_dgrad", p, p.M, 1, 1, s);
     }
     // conv1: weight gradient only (the input is data)
     {

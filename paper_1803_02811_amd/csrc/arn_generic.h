@@ -199,13 +199,14 @@ struct Conv3DgradG {
     }
 };
 
-// conv2 input gradient (stride 2) as four phase problems, z = 2*py + px.  In coordinates of the padded
-// input, (yp, xp) = (y + PAD2, x + PAD2) = (2u + py, 2v + px); rows are (n,u,v), and
-// k = (ty*2+tx)*64 + co reads d(pre2)[n, u-1+ty, v-1+tx, co] against W2[co][ci][py+2(1-ty)][px+2(1-tx)].
-// Rows whose (y, x) falls outside act1 (only with padding) are computed and dropped.
+// conv2 input gradient (stride 2).  In coordinates of the padded input, (yp, xp) = (y + PAD2, x + PAD2) =
+// (2u + py, 2v + px); rows are (n,u,v), and for phase z = 2*py + px, k = (ty*2+tx)*64 + co reads
+// d(pre2)[n, u-1+ty, v-1+tx, co] against W2[co][ci][py+2(1-ty)][px+2(1-tx)].  The four phases read the same
+// d(pre2) windows, so they are the 4 x 32 output columns (column = z*32 + ci) of one contraction.
+// Outputs whose (y, x) falls outside act1 (only with padding) are computed and dropped.
 template <class G>
 struct Conv2DgradG {
-    static constexpr int BM = 128, BN = 32, WAVES_N = 1, K = 4 * C2;
+    static constexpr int BM = 128, BN = 4 * C1, WAVES_N = 2, K = 4 * C2;
     static constexpr int U = ((G::H1 - 1 + G::PAD2) >> 1) + 1, V = ((G::W1 - 1 + G::PAD2) >> 1) + 1;
     const __bf16 *dpre;  // d(pre2) [B,H2,W2,64]
     const __bf16 *w;     // [4][32 ci][4*64]
@@ -233,13 +234,14 @@ struct Conv2DgradG {
         const long at = ok ? r.base + (ty * G::W2 + tx) * C2 + (k & 63) : 0;
         return keep_or_zero(*reinterpret_cast<const u32x4 *>(dpre + at), ok);
     }
-    __device__ __forceinline__ const __bf16 *weights(int z) const { return w + (size_t)z * C1 * K; }
-    __device__ __forceinline__ void store(int m, int n, f32x4 v, int z) const {
+    __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
+    __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
         if (m >= M) return;
+        const int z = n >> 5, ci = n & 31;
         const int s = m / (U * V), rem = m - s * (U * V), u = rem / V, vv = rem - u * V;
         const int y = 2 * u + (z >> 1) - G::PAD2, x = 2 * vv + (z & 1) - G::PAD2;
         if ((unsigned)y >= (unsigned)G::H1 || (unsigned)x >= (unsigned)G::W1) return;
-        store_masked_by_act(out, act, (((size_t)s * G::H1 + y) * G::W1 + x) * C1 + n, v);
+        store_masked_by_act(out, act, (((size_t)s * G::H1 + y) * G::W1 + x) * C1 + ci, v);
     }
 };
 

@@ -122,6 +122,37 @@ def test_gradients_bit_reproducible_and_mean_of_shards(gu):
     assert np.abs(d1 - mean).max() <= 2e-3 * np.abs(mean).max() + 1e-6
 
 
+def test_full_size_a2c_b2048(gu):
+    """The A2C step at the batch size the benchmark times (B=2048), every gradient tensor against the oracle."""
+    A, B = 18, 2048
+    flat = wl.he_normal_params(A, "pv", 2003, fc_inputs=FC)
+    batch = wl.actor_critic_batch(3, B=B, frame=FRAME)
+    ref = orc.train_step_grads(flat, batch, "a2c", _spec(A, "pv"))
+    dW, loss = _net(gu, A, "pv", flat).train(batch, "a2c")
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+    got, want = gu.per_tensor(dW, A, "pv", fc_inputs=FC), gu.per_tensor(ref["flat"], A, "pv", fc_inputs=FC)
+    for name in want:   # the absolute term of the bar dominates at this batch size; also hold a relative bar
+        assert np.abs(got[name] - want[name]).max() <= 2e-2 * np.abs(want[name]).max(), name
+
+
+@pytest.mark.parametrize("fill", [0, 255])
+def test_constant_frames(gu, fill):
+    """Black and saturated frames: with zero biases a black frame gives pre-activations of exactly zero
+    everywhere (ReLU derivative 0 there), and the padded borders must contribute nothing."""
+    A, B = 6, 5
+    flat = wl.he_normal_params(A, "pv", 2107, bias_std=0.0 if fill == 0 else 0.1, fc_inputs=FC)
+    r = np.random.default_rng(fill)
+    batch = dict(obs=np.full((B,) + FRAME, fill, dtype=np.uint8), action=r.integers(0, A, size=B).astype(np.int32),
+                 adv=r.standard_normal(B).astype(np.float32), ret=r.standard_normal(B).astype(np.float32))
+    ref = orc.train_step_grads(flat, batch, "a2c", _spec(A, "pv"))
+    dW, loss = _net(gu, A, "pv", flat).train(batch, "a2c")
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+    if fill == 0:
+        got = gu.per_tensor(dW, A, "pv", fc_inputs=FC)
+        for name in ("conv1.W", "conv1.b", "conv2.W", "conv3.W", "fc.W"):
+            assert not got[name].any(), name
+
+
 def test_bad_geometry_is_rejected(gu):
     import paper_1803_02811_amd as arn
     cfg = arn.Config(18, geometry=2)
