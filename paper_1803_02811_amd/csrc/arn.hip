@@ -114,8 +114,14 @@ template <class C>
 void launch_resident(const char *name, const typename C::Args &a, int B, hipStream_t s) {
     ProfScope ps(name, s);
     const int groups = (B + C::G - 1) / C::G;
-    const int spw = resident_spw(groups, C::NBUF == 1 ? 512 : 256) * C::G;   // single-buffered kernels share a CU
-    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(cdiv(B, spw)), dim3(RESC_THREADS), 0, s, a, B, spw);
+    const int target = C::NBUF == 1 ? 512 : 256;                              // single-buffered kernels share a CU
+    const int spw = resident_spw(groups, target) * C::G;
+    // with few sample groups, the position tiles of a group are dealt to several workgroups
+    constexpr int tiles = (C::G * C::P + 15) / 16;
+    const int wgs = (int)cdiv(B, spw);
+    int parts = 128 / wgs;   // every extra workgroup repeats the weight fetch and the staging: measured to pay only up to about 128 workgroups
+    parts = parts < 1 ? 1 : parts > tiles ? tiles : parts;
+    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(wgs, parts), dim3(RESC_THREADS), 0, s, a, B, spw);
 }
 
 template <class F>
@@ -227,8 +233,9 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
     {
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
-        hipLaunchKernelGGL(conv1_fwd_resident_kernel, dim3(cdiv(B, spw)), dim3(RES_THREADS), 0, s, obs, w.w1, w.w1l,
-                           w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
+        const int parts = 3 * B <= 256 ? 3 : 1;   // few samples: three workgroups share one (one workgroup fits per CU)
+        hipLaunchKernelGGL(conv1_fwd_resident_kernel, dim3(cdiv(B, spw), parts), dim3(RES_THREADS), 0, s, obs, w.w1,
+                           w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     {
         ResConv2Fwd::Args p;
@@ -389,6 +396,9 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     }
 }
 
+// Samples per workgroup of the head kernel in the inference calls: small batches are spread over more CUs
+inline int infer_rows_per_block(int B) { return B <= 512 ? 4 : B <= 4096 ? 8 : PVH_ROWS; }
+
 // Arguments of the fused policy/value head kernel that both entry points share.
 PvHeadArgs pv_head_args(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o) {
     PvHeadArgs p = {};
@@ -490,7 +500,8 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, (char *)workspace, o);
         p.logits = logits; p.value = value; p.probs = probs; p.greedy = greedy;
-        hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, PVH_ROWS)), dim3(PVH_THREADS), 0, s, p);
+        p.rpb = infer_rows_per_block(B);
+        hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
     } else if (value || probs || greedy) {
         ProfScope ps("c51_dist", s);
         hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, B, d.A,
@@ -525,7 +536,8 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, ws, o);
         p.u = u; p.u2 = u2; p.epsilon = epsilon; p.act_out = action; p.logp_out = logp;
-        hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, PVH_ROWS)), dim3(PVH_THREADS), 0, s, p);
+        p.rpb = infer_rows_per_block(B);
+        hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
     } else {
         ProfScope ps("c51_dist", s);
         hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, z, B, d.A, d.atoms,
@@ -604,6 +616,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                 ProfScope ps("q_target", s);
                 PvHeadArgs p = pv_head_args(d, *wt, B, ws, o);
                 p.logits = (float *)(ws + o.qt);
+                p.rpb = LOSS_BLOCK;
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
             if (cfg->double_q) {
@@ -611,6 +624,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                 ProfScope ps("q_select", s);
                 PvHeadArgs p = pv_head_args(d, w, B, ws, o);
                 p.greedy = (int32_t *)(ws + o.astar);
+                p.rpb = LOSS_BLOCK;
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
         }

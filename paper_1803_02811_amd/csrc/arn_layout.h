@@ -202,7 +202,7 @@ inline int fc_ksplit(int B) {
     return ks;
 }
 
-constexpr int LOSS_BLOCK = 16;    // samples per workgroup of the fused policy/value head kernel
+constexpr int LOSS_BLOCK = 8;     // samples per workgroup of the fused policy/value head kernel in the gradient step (at most 16)
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
 // byte offsets into the workspace

@@ -38,6 +38,8 @@ struct PvHeadArgs {
     const __bf16 *wh, *whl; // head weights [64][512] hi / lo; rows A+1.. are zero
     const float *bh;        // [64] head bias (policy rows then the value row)
     int B, A;
+    int rpb;                // inference: samples per workgroup (1..16; 0 = 16).  Small batches spread over more
+                            // workgroups, because one CU's L1 rate bounds the addition of the fc partial sums
     int qmode;              // 0: policy logits + value row; 1: scalar Q rows; 2: advantage rows + value row -> Q
     // inference outputs (each may be null)
     float *logits, *value, *probs;
@@ -101,10 +103,11 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
     __shared__ float sRed[3][PVH_ROWS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n0 = blockIdx.x * PVH_ROWS;
+    const int rpb = TRAIN ? LOSS_BLOCK : (p.rpb <= 0 ? PVH_ROWS : p.rpb);
+    const int n0 = blockIdx.x * rpb;
     const int srow = tid >> 4, c = tid & 15;              // sample within the block, lane within its group of 16
     const int n = n0 + srow;
-    const bool live = n < p.B;
+    const bool live = srow < rpb && n < p.B;
 
     // weight fragments and per-sample scalars do not depend on step 1: their loads go first
     const int fi = lane & 15, fg = lane >> 4;
@@ -144,6 +147,9 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         const float *src = p.partial + (size_t)(live ? n : 0) * HID + c * 4;
         float4 acc[8];
 #pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live) {   // rows past the batch (or past this block's share) load nothing
+#pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = *reinterpret_cast<const float4 *>(src + 64 * j);
         // the k ranges are added in order; four ranges (32 loads) are in flight at a time
         int z = 1;
@@ -167,6 +173,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
             for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4 *>(src + (size_t)z * plane + 64 * j);
 #pragma unroll
             for (int j = 0; j < 8; ++j) { acc[j].x += v[j].x; acc[j].y += v[j].y; acc[j].z += v[j].z; acc[j].w += v[j].w; }
+        }
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -349,7 +356,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         }
         if (tid < PVH_ROWS * 8) {   // dz rows [64] as eight 16-byte words; columns 32.. are zero
             const int r = tid >> 3, q = tid & 7;
-            if (n0 + r < p.B) {
+            if (r < rpb && n0 + r < p.B) {
                 const u32x4 val = q < 4 ? *reinterpret_cast<const u32x4 *>(sDz + r * PVH_DZS + 8 * q) : zero_u4();
                 *reinterpret_cast<u32x4 *>(p.dz + (size_t)(n0 + r) * 64 + 8 * q) = val;
             }
@@ -357,7 +364,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
 
         // ---- 4. input gradient of the head: 32 tiles of 16 hidden units, 8 per wave ----
         const bf16x8 dzf = as_bf16x8(*reinterpret_cast<const u32x4 *>(sDz + fi * PVH_DZS + fg * 8));
-        const bool row_live = n0 + fi < p.B;
+        const bool row_live = fi < rpb && n0 + fi < p.B;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const int j0 = (wave * 8 + t) * 16;

@@ -111,6 +111,8 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
+    // small batches: gridDim.y workgroups share a sample group, each taking every gridDim.y-th position tile
+    const int t_first = blockIdx.y, t_step = gridDim.y;
 
     // weights of this wavefront's channels, all k, as A-operand fragments (loaded below, after the
     // first image loads have been issued, so that staging does not wait for them)
@@ -241,9 +243,9 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
 
         if constexpr (C::PIPE) {
             bf16x8 fa_h[KH], fa_l[C::SPLIT ? KH : 1], fb_h[KH], fb_l[C::SPLIT ? KH : 1];
-            load_half(img, 0, 0, fa_h, fa_l);
+            load_half(img, t_first < NT ? t_first : 0, 0, fa_h, fa_l);
 #pragma unroll 1
-            for (int t = 0; t < NT; ++t) {
+            for (int t = t_first; t < NT; t += t_step) {
                 f32x4 acc[CT];
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_half(0, fa_h, fa_l, acc);
                 __builtin_amdgcn_sched_barrier(0);
-                load_half(img, t + 1 < NT ? t + 1 : t, 0, fa_h, fa_l);   // next tile's first half
+                load_half(img, t + t_step < NT ? t + t_step : t, 0, fa_h, fa_l);   // next tile's first half
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_half(1, fb_h, fb_l, acc);
                 __builtin_amdgcn_sched_barrier(0);
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
             }
         } else {
 #pragma unroll 1
-            for (int t = 0; t < NT; ++t) {
+            for (int t = t_first; t < NT; t += t_step) {
                 f32x4 acc[CT];
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -372,15 +374,28 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         // run (two register sets, statically alternated).  Tiles t0 + 4j, j = 0..5, exist for every
         // wavefront; tile 24 (j = 6) only for t0 = 0.
         u32x2 fa[2 * KS], fb[2 * KS];
-        frag_load(img, t0, fa);
+        if (gridDim.y == 1) {
+            frag_load(img, t0, fa);
 #pragma unroll
-        for (int j = 0; j < 6; j += 2) {
+            for (int j = 0; j < 6; j += 2) {
+                frag_load(img, t0 + 4 * (j + 1), fb);
+                unit(s, t0 + 4 * j, fa);
+                if (j + 2 < 6 || t0 == 0) frag_load(img, t0 + 4 * (j + 2), fa);
+                unit(s, t0 + 4 * (j + 1), fb);
+            }
+            if (t0 == 0) unit(s, NT - 1, fa);
+        } else {
+            // small batches: three workgroups per sample, each taking one pair of this wavefront's tiles
+            // (the last one also tile 24)
+            const int j = 2 * (int)blockIdx.y;
+            const bool tail = j == 4 && t0 == 0;
+            frag_load(img, t0 + 4 * j, fa);
             frag_load(img, t0 + 4 * (j + 1), fb);
             unit(s, t0 + 4 * j, fa);
-            if (j + 2 < 6 || t0 == 0) frag_load(img, t0 + 4 * (j + 2), fa);
+            if (tail) frag_load(img, NT - 1, fa);
             unit(s, t0 + 4 * (j + 1), fb);
+            if (tail) unit(s, NT - 1, fa);
         }
-        if (t0 == 0) unit(s, NT - 1, fa);
         buf ^= 1;
     }
 }
