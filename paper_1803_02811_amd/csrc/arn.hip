@@ -168,7 +168,7 @@ Packed view_packed(const void *blob, const Dims &d) {
 // fc layer (three products) and, for the categorical head, the head GEMM; shared by both geometries
 template <int FEAT_>
 void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o, float *z_out,
-                          hipStream_t s) {
+                          int zstride, hipStream_t s) {
     __bf16 *a3 = (__bf16 *)(ws + o.a3), *a3l = (__bf16 *)(ws + o.a3l);
     __bf16 *h = (__bf16 *)(ws + o.h), *hl = (__bf16 *)(ws + o.hl);
     {
@@ -187,7 +187,7 @@ void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const
     }
     if (d.head == ARN_HEAD_C51) {
         HeadFwdC51 p;
-        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh; p.z = z_out; p.ZW = d.NH;
+        p.in = h; p.lo_off = hl - h; p.M = B; p.w = w.wh; p.w_lo = w.whl; p.bias = w.bh; p.z = z_out; p.ZW = d.NH; p.ZS = zstride;
         launch_nt_split("head_fwd", p, B, d.NHP / 64, 1, s);
     }
     // policy/value and action-value heads: the caller launches pv_head_kernel on the fc partial sums
@@ -196,7 +196,7 @@ void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const
 // Convolutions of geometry G as gathered contractions (three products; conv1's pixel operand is exact: two)
 template <class G>
 void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                     float *z_out, hipStream_t s) {
+                     float *z_out, int zstride, hipStream_t s) {
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
     {
@@ -216,16 +216,17 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
         p.out = a3; p.out_lo = a3l;
         launch_nt_split("conv3_fwd", p, p.M, 1, 1, s);
     }
-    fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, s);
+    fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, zstride, s);
 }
 
-// trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits [B][NH].
+// trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits, rows of zstride floats
+// (NH = dense, or NHP for the library's own buffers).
 // PV: stops after the fc GEMM, whose fp32 partial sums (o.fcp) the fused head kernel consumes.
 // masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on the online weights).
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                      float *z_out, bool masks, hipStream_t s) {
+                      float *z_out, int zstride, bool masks, hipStream_t s) {
     if (d.geom == ARN_GEOM_PAPER) {   // the gathered path keeps no sign bits: its backward reads the activations
-        forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, s);
+        forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, s);
         return;
     }
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
@@ -249,7 +250,7 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
         launch_resident<ResConv3Fwd>("conv3_fwd", p, B, s);
     }
-    fc_and_head_launches<FEAT>(d, w, B, ws, o, z_out, s);
+    fc_and_head_launches<FEAT>(d, w, B, ws, o, z_out, zstride, s);
 }
 
 // Events that let work queued on the side stream see everything queued on the caller's stream so far.
@@ -495,7 +496,7 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     if (int e = check_arch()) return e;
     hipStream_t s = (hipStream_t)stream;
     const Packed w = view_packed(w_packed, d);
-    forward_launches(d, w, obs, B, (char *)workspace, o, logits, false, s);
+    forward_launches(d, w, obs, B, (char *)workspace, o, logits, d.NH, false, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, (char *)workspace, o);
@@ -504,7 +505,7 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
         hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
     } else if (value || probs || greedy) {
         ProfScope ps("c51_dist", s);
-        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, B, d.A,
+        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, logits, d.NH, B, d.A,
                            d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, (const float *)nullptr,
                            (const uint8_t *)nullptr, probs, value, greedy, (float *)nullptr);
     }
@@ -531,7 +532,7 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
     char *ws = (char *)workspace;
     const Packed w = view_packed(w_packed, d);
     float *z = (float *)(ws + o.z);   // categorical head only
-    forward_launches(d, w, obs, B, ws, o, z, false, s);
+    forward_launches(d, w, obs, B, ws, o, z, d.NHP, false, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, ws, o);
@@ -540,7 +541,7 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
         hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
     } else {
         ProfScope ps("c51_dist", s);
-        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, z, B, d.A, d.atoms,
+        hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, z, d.NHP, B, d.A, d.atoms,
                            cfg->v_min, cfg->v_max, cfg->gamma, (const float *)nullptr, (const uint8_t *)nullptr,
                            (float *)nullptr, (float *)nullptr, action, (float *)nullptr);
         hipLaunchKernelGGL(epsilon_greedy_kernel, dim3(cdiv(B, 256)), dim3(256), 0, s, action, u, u2, epsilon, d.A, B);
@@ -592,16 +593,16 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         // target network on next states -> projected target m; its activations are then overwritten
         const Packed wt = view_packed(batch->w_target_packed, d);
         float *ztgt = (float *)(ws + o.ztgt), *m = (float *)(ws + o.m);
-        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, false, s);
+        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, d.NHP, false, s);
         {
             ProfScope ps("c51_target", s);
-                hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, B, d.A,
+                hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, d.NHP, B, d.A,
                                d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
                                (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
         }
-        forward_launches(d, w, batch->obs, B, ws, o, z, true, s);
+        forward_launches(d, w, batch->obs, B, ws, o, z, d.NHP, true, s);
         ProfScope ps("loss", s);
-        hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, m, batch->action, B, d.A,
+        hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, d.NHP, m, batch->action, B, d.A,
                            d.atoms, d.NHP, dz, lossp);
     } else {
         const Packed *wt = nullptr;
@@ -611,7 +612,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             // states -> its greedy action.  The activations of these passes are then overwritten.
             wt_view = view_packed(batch->w_target_packed, d);
             wt = &wt_view;
-            forward_launches(d, *wt, batch->next_obs, B, ws, o, nullptr, false, s);
+            forward_launches(d, *wt, batch->next_obs, B, ws, o, nullptr, 0, false, s);
             {
                 ProfScope ps("q_target", s);
                 PvHeadArgs p = pv_head_args(d, *wt, B, ws, o);
@@ -620,7 +621,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
             if (cfg->double_q) {
-                forward_launches(d, w, batch->next_obs, B, ws, o, nullptr, false, s);
+                forward_launches(d, w, batch->next_obs, B, ws, o, nullptr, 0, false, s);
                 ProfScope ps("q_select", s);
                 PvHeadArgs p = pv_head_args(d, w, B, ws, o);
                 p.greedy = (int32_t *)(ws + o.astar);
@@ -628,7 +629,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
         }
-        forward_launches(d, w, batch->obs, B, ws, o, nullptr, true, s);
+        forward_launches(d, w, batch->obs, B, ws, o, nullptr, 0, true, s);
         // fc finish, head, objective, dz and the head's input gradient d(pre_fc) in one kernel
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, ws, o);

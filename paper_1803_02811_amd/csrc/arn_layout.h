@@ -210,7 +210,7 @@ struct Workspace {
     size_t a1, a2, a3, h;               // bf16 NHWC activations
     size_t a1l, a2l, a3l, hl;           // their low parts (written and read by the forward pass only)
     size_t fcp;                         // fp32 [ksplit][B][512] partial sums of the fc forward GEMM
-    size_t z, zv;                       // fp32 head outputs (train): logits / atom logits, value
+    size_t z, zv;                       // categorical head: fp32 atom logits, rows padded to NHP floats
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
     size_t qt, astar;                   // DQN: target-net Q(s',.) fp32 [B][A]; Double-DQN: online greedy action on s' int32 [B]
     size_t m1, m2, m3;                  // ReLU sign bits of act1..3 (bit e&7 of byte e>>3, NHWC element e), written by the forward
@@ -239,16 +239,16 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
     // the fused policy/value head kernel always reads fp32 partials; the categorical path only when k is split
     w.fcp = take((size_t)(fc_ksplit(B) > 1 || d.small ? fc_ksplit(B) : 0) * b * HID * 4);
     // categorical head: atom logits of arn_policy_act (arn_policy_forward writes them to its `logits` argument)
-    if (mode == ARN_MODE_FORWARD) w.z = take(d.small ? 0 : b * (size_t)d.NH * 4);
+    if (mode == ARN_MODE_FORWARD) w.z = take(d.small ? 0 : b * (size_t)d.NHP * 4);
     if (mode == ARN_MODE_TRAIN) {
-        w.z = take(d.small ? 0 : b * (size_t)d.NH * 4);
+        w.z = take(d.small ? 0 : b * (size_t)d.NHP * 4);
         w.zv = 0;
         if (d.qhead) {
             w.qt = take(b * (size_t)d.A * 4);
             w.astar = take(b * 4);
         }
         if (d.head == ARN_HEAD_C51) {
-            w.ztgt = take(b * (size_t)d.NH * 4);
+            w.ztgt = take(b * (size_t)d.NHP * 4);
             w.m = take(b * (size_t)d.atoms * 4);
         }
         w.m1 = take(b * p1 * C1 / 8);

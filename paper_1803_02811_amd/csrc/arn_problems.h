@@ -94,14 +94,16 @@ struct FcFwdT : DenseGather<FEAT_> {
 typedef FcFwdT<FEAT> FcFwd;
 
 // categorical head: rows of the packed head matrix are the A*atoms categorical rows
-// C51: atom logits fp32 [M][A*atoms] with bias.
+// C51: atom logits fp32 [M][ZS] with bias; ZS = ZW (dense, the inference output) or the padded head width
+// (the gradient step's own buffers: 16-byte stores).
 struct HeadFwdC51 : DenseGather<HID> {
     static constexpr int BM = 128, BN = 64, WAVES_N = 1, K = HID;
     static constexpr bool ACT_LO = true;
     const __bf16 *w, *w_lo = nullptr;
-    const float *bias;
-    float *z;       // [M][ZW]
+    const float *bias;   // padded head width entries (zeros past ZW)
+    float *z;       // [M][ZS]
     int ZW;         // A*atoms
+    int ZS;         // row stride in floats: ZW, or a multiple of 64 >= ZW
     __device__ __forceinline__ Row row(int m, int) const { return row_at(m); }
     __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return load_at(r, k); }
     __device__ __forceinline__ u32x4 load_lo(const Row &r, int k) const { return load_lo_at(r, k); }
@@ -109,10 +111,18 @@ struct HeadFwdC51 : DenseGather<HID> {
     __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
         if (m >= M) return;
+        const float4 b = *reinterpret_cast<const float4 *>(bias + n);
+        float *dst = z + (size_t)m * ZS + n;
+        if (ZS != ZW) {                        // padded rows: every column exists
+            *reinterpret_cast<float4 *>(dst) = make_float4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
+        } else if ((ZW & 1) == 0) {            // dense rows of even length: n and m*ZW are even, 8-byte stores
+            if (n + 1 < ZW) *reinterpret_cast<float2 *>(dst) = make_float2(v[0] + b.x, v[1] + b.y);
+            if (n + 3 < ZW) *reinterpret_cast<float2 *>(dst + 2) = make_float2(v[2] + b.z, v[3] + b.w);
+        } else {
+            const float r[4] = {v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int c = n + e;
-            if (c < ZW) z[(size_t)m * ZW + c] = v[e] + bias[c];
+            for (int e = 0; e < 4; ++e)
+                if (n + e < ZW) dst[e] = r[e];
         }
     }
 };

@@ -261,12 +261,12 @@ __global__ void epsilon_greedy_kernel(int32_t *__restrict__ action, const float 
 
 // ------------------------- Categorical DQN target ---------------------------
 // One wavefront per sample, lane j = atom j.  From atom logits [A][atoms] of
-// one network: per-action softmax, expected values Q, lowest-index argmax.
+// one network (rows of `zstride` floats): per-action softmax, expected values Q, lowest-index argmax.
 // With `m_out`, also the projection of the greedy action's distribution onto
 // the support after the shift T_j = clip(r + gamma (1-done) z_j):
 //     m_i = sum_j p_j max(0, 1 - |T_j - z_i| / delta).
 __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
-    const float *__restrict__ zin, int B, int A, int atoms, float v_min, float v_max, float gamma,
+    const float *__restrict__ zin, int zstride, int B, int A, int atoms, float v_min, float v_max, float gamma,
     const float *__restrict__ reward, const uint8_t *__restrict__ done, float *__restrict__ probs,
     float *__restrict__ q_out, int32_t *__restrict__ greedy, float *__restrict__ m_out) {
     const int lane = threadIdx.x & 63, n = blockIdx.x * C51_WAVES + (threadIdx.x >> 6);
@@ -277,8 +277,8 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
     float best_q = -INFINITY, best_p = 0.f;
     int best_a = 0;
     for (int a = 0; a < A; ++a) {
-        const size_t at = ((size_t)n * A + a) * atoms + lane;
-        const float x = on ? zin[at] : -INFINITY;
+        const size_t at = ((size_t)n * A + a) * atoms + lane;   // dense outputs; the logits row has `zstride` floats
+        const float x = on ? zin[(size_t)n * zstride + a * atoms + lane] : -INFINITY;
         const float mx = wave_max(x);
         const float e = on ? expf(x - mx) : 0.f;
         const float p = e / wave_sum(e);
@@ -305,15 +305,15 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
 // L_n = -sum_i m_i log p_i(s_n, a_n);  d/dlogit[a_n][i] = (p_i sum(m) - m_i)/B, other rows 0.
 // One wavefront per sample writes the whole bf16 gradient row [NHP].
 __global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
-    const float *__restrict__ z, const float *__restrict__ m_in, const int32_t *__restrict__ action, int B, int A,
-    int atoms, int NHP, __bf16 *__restrict__ dz, float *__restrict__ lossp) {
+    const float *__restrict__ z, int zstride, const float *__restrict__ m_in, const int32_t *__restrict__ action,
+    int B, int A, int atoms, int NHP, __bf16 *__restrict__ dz, float *__restrict__ lossp) {
     __shared__ float red[C51_WAVES];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, n = blockIdx.x * C51_WAVES + wv;
     float ce = 0.f;
     if (n < B) {
         const int a = min(max(action[n], 0), A - 1);   // an out-of-range action must not become an out-of-range read
         const bool on = lane < atoms;
-        const float x = on ? z[((size_t)n * A + a) * atoms + lane] : -INFINITY;
+        const float x = on ? z[(size_t)n * zstride + a * atoms + lane] : -INFINITY;
         const float mx = wave_max(x);
         const float e = on ? expf(x - mx) : 0.f;
         const float s = wave_sum(e);
