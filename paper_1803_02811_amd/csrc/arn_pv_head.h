@@ -22,6 +22,7 @@
 #include <stdint.h>
 
 #include "arn_gemm.h"
+#include "arn_lanes.h"
 #include "arn_layout.h"
 
 namespace arn {
@@ -70,11 +71,7 @@ struct PvHeadArgs {
     float *lossp;           // [blocks][4] partial sums {policy, value, entropy}
 };
 
-__device__ __forceinline__ float group16_sum(float v) {   // same bits in all 16 lanes of the group
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) v += __shfl_xor(v, o, 16);
-    return v;
-}
+__device__ __forceinline__ float group16_sum(float v) { return row16_sum(v); }   // same bits in all 16 lanes of the group
 __device__ __forceinline__ float group16_scan(float v, int c) {   // inclusive prefix sum over the 16 lanes of the group
 #pragma unroll
     for (int o = 1; o < 16; o <<= 1) {
@@ -83,16 +80,8 @@ __device__ __forceinline__ float group16_scan(float v, int c) {   // inclusive p
     }
     return v;
 }
-__device__ __forceinline__ int group16_min(int v) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) v = min(v, __shfl_xor(v, o, 16));
-    return v;
-}
-__device__ __forceinline__ float group16_max(float v) {
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 16));
-    return v;
-}
+__device__ __forceinline__ int group16_min(int v) { return row16_min(v); }
+__device__ __forceinline__ float group16_max(float v) { return row16_max(v); }
 
 template <bool TRAIN>
 __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p) {

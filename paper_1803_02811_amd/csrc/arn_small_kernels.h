@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "arn_lanes.h"
 #include "arn_layout.h"
 
 namespace arn {
@@ -213,18 +214,6 @@ __global__ void fc_finish_kernel(const float *__restrict__ partial, int ksplit, 
     }
 }
 
-// ------------------------------ reductions ---------------------------------
-__device__ __forceinline__ float wave_sum(float v) {     // result valid in every lane, same bits
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_down(v, o, 64);
-    return __shfl(v, 0, 64);
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_down(v, o, 64));
-    return __shfl(v, 0, 64);
-}
-
 // loss[0..3] = {total, policy|cross-entropy, value mse, entropy}: one wavefront;
 // lane l adds the partials of blocks l, l+64, ... in that order, then the lanes
 // are added in a fixed tree -- the same association on every run.
@@ -294,7 +283,7 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
         const float inv_delta = 1.f / delta;
         float m = 0.f;
         for (int j = 0; j < atoms; ++j) {
-            const float pj = __shfl(best_p, j, 64), Tj = __shfl(T, j, 64);
+            const float pj = lane_value(best_p, j), Tj = lane_value(T, j);
             m += pj * fmaxf(0.f, 1.f - fabsf(Tj - zj) * inv_delta);
         }
         if (on) m_out[(size_t)n * atoms + lane] = m;
