@@ -369,9 +369,9 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
     }
     {
-        Conv3DgradG<G> p;
-        p.dpre = dp3; p.w = w.w3d; p.act = a2; p.out = dp2; p.M = B * G::P2;
-        launch_nt("conv3_dgrad", p, p.M, 1, 1, s);
+        typename ResConv3DgradGeo<G>::Args p;
+        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = nullptr; p.act = a2; p.out = dp2;
+        launch_resident<ResConv3DgradGeo<G>>("conv3_dgrad", p, B, s);
     }
     fk();   // d(pre2)
     {
@@ -382,9 +382,9 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
     }
     {
-        Conv2DgradG<G> p;
-        p.dpre = dp2; p.w = w.w2d; p.act = a1; p.out = dp1; p.M = B * Conv2DgradG<G>::U * Conv2DgradG<G>::V;
-        launch_nt("conv2_dgrad", p, p.M, 1, 1, s);
+        typename ResConv2DgradGeo<G>::Args p;
+        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = nullptr; p.act = a1; p.out = dp1;
+        launch_resident<ResConv2DgradGeo<G>>("conv2_dgrad", p, B, s);
     }
     // conv1: weight gradient only (the input is data)
     {

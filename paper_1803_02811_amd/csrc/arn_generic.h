@@ -1,8 +1,9 @@
 // The convolution layers for any frame size and padding (template parameter G, a Geometry from
 // arn_layout.h) as instances of the two contraction kernels in arn_gemm.h: the activation operand is
 // gathered on the fly (implicit im2col) with zeros where a window reaches into the padding.  This is the
-// path of the appendix's own setting (104x80 frames, padding 1 on conv2 and conv3); the 84x84 network has
-// sample-resident kernels of its own (arn_resident_conv.h, arn_resident.h) and does not come through here.
+// path of the appendix's own setting (104x80 frames, padding 1 on conv2 and conv3) for the forward
+// convolutions and the weight gradients; the 84x84 network has sample-resident kernels of its own
+// (arn_resident_conv.h, arn_resident.h) and does not come through here.
 //
 // Activations are NHWC bf16: act1 [B,H1,W1,32], act2 [B,H2,W2,64], act3 [B,H3,W3,64] (= the fc input with
 // index (y*W3+x)*64 + c; the packed fc weights are permuted to match).  Gradients at pre-activations use
@@ -160,90 +161,7 @@ struct FcDgradAct : DenseGather<HID> {
     }
 };
 
-// conv3 input gradient as a gather: rows are act2 positions (n,y,x); with OFF = K3-1-PAD3,
-// k = (ty*3+tx)*64 + co reads d(pre3)[n, y-OFF+ty, x-OFF+tx, co] (zero outside the H3 x W3 map) against
-// W3[co][ci][2-ty][2-tx]; the epilogue applies act2's ReLU mask.
-template <class G>
-struct Conv3DgradG {
-    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = 9 * C3, OFF = K3 - 1 - G::PAD3;
-    const __bf16 *dpre;  // d(pre3) [B,H3,W3,64]
-    const __bf16 *w;     // [64 ci][9*64]
-    const __bf16 *act;   // act2
-    __bf16 *out;         // d(pre2) [B,H2,W2,64]
-    int M;               // B * P2
-    struct Row {
-        long base;
-        int y0, x0;
-        bool ok;
-    };
-    __device__ __forceinline__ Row row(int m, int) const {
-        Row r;
-        r.ok = m < M;
-        const int mm = r.ok ? m : 0;
-        const int n = mm / G::P2, rem = mm - n * G::P2, y = rem / G::W2, x = rem - y * G::W2;
-        r.y0 = y - OFF;
-        r.x0 = x - OFF;
-        r.base = (((long)n * G::H3 + r.y0) * G::W3 + r.x0) * C3;
-        return r;
-    }
-    __device__ __forceinline__ u32x4 load(const Row &r, int k) const {
-        const int tap = k >> 6, ty = tap / 3, tx = tap - ty * 3;
-        const bool ok = r.ok && (unsigned)(r.y0 + ty) < (unsigned)G::H3 && (unsigned)(r.x0 + tx) < (unsigned)G::W3;
-        const long at = ok ? r.base + (ty * G::W3 + tx) * C3 + (k & 63) : 0;   // clamp, load, then zero
-        return keep_or_zero(*reinterpret_cast<const u32x4 *>(dpre + at), ok);
-    }
-    __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
-    __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
-        if (m >= M) return;
-        store_masked_by_act(out, act, (size_t)m * C2 + n, v);
-    }
-};
-
-// conv2 input gradient (stride 2).  In coordinates of the padded input, (yp, xp) = (y + PAD2, x + PAD2) =
-// (2u + py, 2v + px); rows are (n,u,v), and for phase z = 2*py + px, k = (ty*2+tx)*64 + co reads
-// d(pre2)[n, u-1+ty, v-1+tx, co] against W2[co][ci][py+2(1-ty)][px+2(1-tx)].  The four phases read the same
-// d(pre2) windows, so they are the 4 x 32 output columns (column = z*32 + ci) of one contraction.
-// Outputs whose (y, x) falls outside act1 (only with padding) are computed and dropped.
-template <class G>
-struct Conv2DgradG {
-    static constexpr int BM = 128, BN = 4 * C1, WAVES_N = 2, K = 4 * C2;
-    static constexpr int U = ((G::H1 - 1 + G::PAD2) >> 1) + 1, V = ((G::W1 - 1 + G::PAD2) >> 1) + 1;
-    const __bf16 *dpre;  // d(pre2) [B,H2,W2,64]
-    const __bf16 *w;     // [4][32 ci][4*64]
-    const __bf16 *act;   // act1
-    __bf16 *out;         // d(pre1) [B,H1,W1,32]
-    int M;               // B * U * V
-    struct Row {
-        long base;
-        int u, v;
-        bool ok;
-    };
-    __device__ __forceinline__ Row row(int m, int) const {
-        Row r;
-        r.ok = m < M;
-        const int mm = r.ok ? m : 0;
-        const int n = mm / (U * V), rem = mm - n * (U * V);
-        r.u = rem / V;
-        r.v = rem - r.u * V;
-        r.base = (((long)n * G::H2 + r.u - 1) * G::W2 + r.v - 1) * C2;
-        return r;
-    }
-    __device__ __forceinline__ u32x4 load(const Row &r, int k) const {
-        const int tap = k >> 6, ty = tap >> 1, tx = tap & 1;
-        const bool ok = r.ok && (unsigned)(r.u - 1 + ty) < (unsigned)G::H2 && (unsigned)(r.v - 1 + tx) < (unsigned)G::W2;
-        const long at = ok ? r.base + (ty * G::W2 + tx) * C2 + (k & 63) : 0;
-        return keep_or_zero(*reinterpret_cast<const u32x4 *>(dpre + at), ok);
-    }
-    __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
-    __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
-        if (m >= M) return;
-        const int z = n >> 5, ci = n & 31;
-        const int s = m / (U * V), rem = m - s * (U * V), u = rem / V, vv = rem - u * V;
-        const int y = 2 * u + (z >> 1) - G::PAD2, x = 2 * vv + (z & 1) - G::PAD2;
-        if ((unsigned)y >= (unsigned)G::H1 || (unsigned)x >= (unsigned)G::W1) return;
-        store_masked_by_act(out, act, (((size_t)s * G::H1 + y) * G::W1 + x) * C1 + ci, v);
-    }
-};
+// (conv3 / conv2 input gradients: ResConv3DgradGeo / ResConv2DgradGeo in arn_resident_conv.h)
 
 // --------------------------- weight gradients -----------------------------
 template <class G>

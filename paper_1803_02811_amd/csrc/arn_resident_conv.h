@@ -538,4 +538,81 @@ struct ResConv2Dgrad {
     };
 };
 
+// ---------------------------------------------------------------------------
+// Input gradients for any geometry Geo (arn_layout.h), used by the padded 104x80 network.  Same kernel and the
+// same LDS bank rule as above; the row and image padding that makes the fragment reads conflict free is
+// computed from the map sizes.  The ReLU derivative is read from the stored activation in the epilogue.
+constexpr int pad_to_step(int have, int want) { return (((want - have) % 256) + 256) % 256; }
+
+// conv3 (3x3, stride 1, padding PAD3): d(pre3) [H3][W3][64] zero-padded by OFF = 2 - PAD3 on every side;
+// tap (ty,tx) reads padded (y+ty, x+tx) against W3[co][ci][2-ty][2-tx]; output d(pre2) [H2][W2][64].
+template <class Geo>
+struct ResConv3DgradGeo {
+    static constexpr int OFF = K3 - 1 - Geo::PAD3, PADH = Geo::H3 + 2 * OFF, PADW = Geo::W3 + 2 * OFF;
+    static_assert(PADH - 2 == Geo::H2 && PADW - 2 == Geo::W2, "stride-1 3x3 correlation over the padded gradient");
+    static constexpr int CI = C3, SRC_PIX = Geo::P3, P = Geo::P2, CO = C2, K = 9 * C3, G = 2;
+    static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
+    static constexpr int MASK_ELEMS = 0, NBUF = 1;
+    static constexpr int PSB = C3 * 2 + 32;
+    // W2 positions per output row: the first position of the next row must follow at one pixel stride mod 256
+    static constexpr int ROWB = PADW * PSB + pad_to_step(PADW * PSB, Geo::W2 * PSB);
+    static constexpr int LAST = (Geo::H2 - 1) * ROWB + (Geo::W2 - 1) * PSB;
+    static constexpr int IMG = PADH * ROWB + pad_to_step(PADH * ROWB, LAST + PSB);
+    __device__ static constexpr int dst_off(int p) { return (p / Geo::W3 + OFF) * ROWB + (p % Geo::W3 + OFF) * PSB; }
+    __device__ static constexpr int base_off(int pos) { return (pos / Geo::W2) * ROWB + (pos % Geo::W2) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return (t / 3) * ROWB + (t % 3) * PSB; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;   // unused
+        const __bf16 *act;     // act2
+        __bf16 *out;
+        struct Lane {};
+        __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *) const {
+            const size_t at = ((size_t)s * Geo::P2 + pos) * C2 + n;
+            const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+            *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
+                                                              a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
+        }
+    };
+};
+
+// conv2 (4x4, stride 2, padding PAD2): d(pre2) [H2][W2][64] zero-padded by 1.  In coordinates of the padded
+// input, (y + PAD2, x + PAD2) = (2u + py, 2v + px); the four phases (py,px) share their fragments, so they are
+// the 4 x 32 channels of one 2x2 stride-1 correlation over positions (u,v); channel n = phase*32 + ci lands at
+// act1 pixel (2u + py - PAD2, 2v + px - PAD2) if that is inside the map.
+template <class Geo>
+struct ResConv2DgradGeo {
+    static constexpr int U = ((Geo::H1 - 1 + Geo::PAD2) >> 1) + 1, V = ((Geo::W1 - 1 + Geo::PAD2) >> 1) + 1;
+    static constexpr int PADH = Geo::H2 + 2, PADW = Geo::W2 + 2;
+    static_assert(U <= PADH - 1 && V <= PADW - 1, "every 2x2 window lies inside the padded gradient");
+    static constexpr int CI = C2, SRC_PIX = Geo::P2, P = U * V, CO = 4 * C1, K = 4 * C2, G = 2;
+    static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
+    static constexpr int MASK_ELEMS = 0, NBUF = 1;
+    static constexpr int PSB = C2 * 2 + 32;
+    static constexpr int ROWB = PADW * PSB + pad_to_step(PADW * PSB, V * PSB);
+    static constexpr int LAST = (U - 1) * ROWB + (V - 1) * PSB;
+    static constexpr int IMG = PADH * ROWB + pad_to_step(PADH * ROWB, LAST + PSB);
+    __device__ static constexpr int dst_off(int p) { return (p / Geo::W2 + 1) * ROWB + (p % Geo::W2 + 1) * PSB; }
+    __device__ static constexpr int base_off(int pos) { return (pos / V) * ROWB + (pos % V) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return (t / 2) * ROWB + (t % 2) * PSB; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;   // unused
+        const __bf16 *act;     // act1
+        __bf16 *out;
+        struct Lane {};
+        __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *) const {
+            const int phase = n >> 5, ci = n & 31, u = pos / V, vv = pos - u * V;
+            const int y = 2 * u + (phase >> 1) - Geo::PAD2, x = 2 * vv + (phase & 1) - Geo::PAD2;
+            if ((unsigned)y >= (unsigned)Geo::H1 || (unsigned)x >= (unsigned)Geo::W1) return;
+            const size_t at = (((size_t)s * Geo::H1 + y) * Geo::W1 + x) * C1 + ci;
+            const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+            *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
+                                                              a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
+        }
+    };
+};
+
 }  // namespace arn
