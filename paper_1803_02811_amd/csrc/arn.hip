@@ -297,7 +297,7 @@ void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *w
         {
             ProfScope ps("conv3_wgrad", s2);
             const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, K3, S3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, H2, K3, S3, 0, H3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
                                dim3(CW_THREADS), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
         }
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
@@ -313,7 +313,7 @@ void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *w
         {
             ProfScope ps("conv2_wgrad", s2);
             const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, K2, S2, H2, C2, CONV2_WG_G, 2>), dim3(sp.c2),
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, H1, K2, S2, 0, H2, H2, C2, CONV2_WG_G, 2>), dim3(sp.c2),
                                dim3(CW_THREADS), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
         }
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
@@ -362,10 +362,14 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     }
     fk();   // d(pre3)
     {
-        Conv3WgradG<G> p;
-        p.in = a2; p.M = B * G::P3; p.dy = dp3;
         float *part = (float *)(ws + o.pw3);
-        launch_tn("conv3_wgrad", p, part, p.M, C3, KW3, sp.c3, s2);
+        {
+            ProfScope ps("conv3_wgrad", s2);
+            const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, G::H2, G::W2, K3, S3, G::PAD3, G::H3, G::W3, C3, CONV3_WG_G, 2>),
+                               dim3(sp.c3), dim3(CW_THREADS), 0, s2, a2, dp3, part, B,
+                               resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
+        }
         launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
     }
     {
@@ -375,10 +379,14 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     }
     fk();   // d(pre2)
     {
-        Conv2WgradG<G> p;
-        p.in = a1; p.M = B * G::P2; p.dy = dp2;
         float *part = (float *)(ws + o.pw2);
-        launch_tn("conv2_wgrad", p, part, p.M, C2, KW2, sp.c2, s2);
+        {
+            ProfScope ps("conv2_wgrad", s2);
+            const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
+            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, G::H1, G::W1, K2, S2, G::PAD2, G::H2, G::W2, C2, CONV2_WG_G, 2>),
+                               dim3(sp.c2), dim3(CW_THREADS), 0, s2, a1, dp2, part, B,
+                               resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
+        }
         launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
     }
     {

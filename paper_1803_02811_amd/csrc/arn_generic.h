@@ -166,9 +166,6 @@ struct FcDgradAct : DenseGather<HID> {
 // --------------------------- weight gradients -----------------------------
 template <class G>
 using Conv1WgradG = Wgrad<ObsGatherG<G>, 32, 128, 4, C1, KW1>;
-template <class G>
-using Conv2WgradG = Wgrad<Conv2GatherG<G>, 64, 128, 4, C2, KW2>;
-template <class G>
-using Conv3WgradG = Wgrad<Conv3GatherG<G>, 64, 64, 2, C3, KW3>;
+// (conv2 / conv3 weight gradients: conv_wgrad_resident_kernel in arn_resident.h)
 
 }  // namespace arn

@@ -176,11 +176,11 @@ inline int resident_groups(int B, int target_wgs) {
 inline Splits make_splits(const Dims &d, int B) {
     Splits s;
     if (d.geom != ARN_GEOM_84) {
-        // gathered (implicit-GEMM) weight-gradient kernels: rows = samples x positions, cut so that about
-        // 1024 (512 for the dense layers) workgroups exist
+        // gathered (implicit-GEMM) weight-gradient kernels (conv1, fc, head): rows = samples x positions, cut so
+        // that about 1024 (512 for the dense layers) workgroups exist
         s.c1 = pick_split((long)B * d.p1, 2, 1024);
-        s.c2 = pick_split((long)B * d.p2, 4, 1024);
-        s.c3 = pick_split((long)B * d.p3, 9, 1024);
+        s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS);   // sample-resident kernels, as below
+        s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS);
         s.fc = pick_split(B, (d.feat / 64) * 4, 512);
         s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
         return s;

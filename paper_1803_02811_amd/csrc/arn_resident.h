@@ -132,17 +132,20 @@ __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const
     }
 }
 
-// conv2 / conv3: x = NHWC bf16 activations [HIN][HIN][CIN] of G samples per
-// iteration (k' = (ky*KS + kx)*CIN + ci), dY = d(pre) rows [G*HOUT*HOUT][COUT].
+// conv2 / conv3: x = NHWC bf16 activations [HIN][WIN][CIN] of G samples per
+// iteration (k' = (ky*KS + kx)*CIN + ci), dY = d(pre) rows [G*HOUT*WOUT][COUT].
+// With PAD > 0 the LDS image of a sample has a zero border of PAD pixels (cleared once; only the
+// interior is restaged), so windows that reach into the padding read zeros.
 // LDS pixels and dY rows are padded (PS, YS bytes) so that the four rows touched
 // by one transposing read fall into different banks.  WAVES_Y wavefronts split
 // the COUT/32 row tiles, the others split the column tiles.
 constexpr int CW_THREADS = 512;   // eight wavefronts, two per SIMD: one hides the other's LDS latency
-template <int CIN, int HIN, int KS, int STRIDE, int HOUT, int COUT, int G, int WAVES_Y>
+template <int CIN, int HIN, int WIN, int KS, int STRIDE, int PAD, int HOUT, int WOUT, int COUT, int G, int WAVES_Y>
 __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const __bf16 *__restrict__ x,
                                                                   const __bf16 *__restrict__ dy,
                                                                   float *__restrict__ part, int B, int spw) {
-    constexpr int PIX = HIN * HIN, P = HOUT * HOUT, KP = KS * KS * CIN;
+    constexpr int PIX = HIN * WIN, P = HOUT * WOUT, KP = KS * KS * CIN;
+    constexpr int HP = HIN + 2 * PAD, WP = WIN + 2 * PAD, PIXP = HP * WP;   // LDS image with its zero border
     constexpr int PS = CIN * 2 + 16, YS = COUT * 2 + 16;            // padded strides in bytes
     constexpr int R = G * P, KSTEPS = (R + 15) / 16, RPAD = KSTEPS * 16;
     constexpr int XCH = CIN / 8, YCH = COUT / 8;                     // 16-byte chunks per pixel / per dY row
@@ -154,16 +157,19 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
     static_assert(NY % WAVES_Y == 0, "tile split");
     static_assert(NT % YCH == 0 && (NT / YCH) * COUT * 4 <= RPAD * YS, "bias-gradient scratch");
 
-    __shared__ u32x4 s_x[G * PIX * PS / 16];
+    __shared__ u32x4 s_x[G * PIXP * PS / 16];
     __shared__ u32x4 s_dy[RPAD * YS / 16];
+    static_assert((G * PIXP * PS + RPAD * YS) <= 160 * 1024, "LDS budget");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wy = wave % WAVES_Y, wx = wave / WAVES_Y;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
 
-    // rows R..RPAD of dY stay zero for the whole kernel
+    // rows R..RPAD of dY stay zero for the whole kernel, and so does the border of the images
     for (int i = tid; i < (RPAD - R) * YS / 16; i += NT) s_dy[R * YS / 16 + i] = zero_u4();
+    if constexpr (PAD > 0)
+        for (int i = tid; i < G * PIXP * PS / 16; i += NT) s_x[i] = zero_u4();
 
     u32x4 rx[NI], ry[ND];
     auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1; those at or beyond s_end are read from s_end-1 and zeroed on store
@@ -209,8 +215,10 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
             const int idx = tid + NT * i;
             if (idx < NXC) {
                 const int pix = idx / XCH, c = idx - pix * XCH;
-                const bool live = s + pix / PIX < s_end;
-                *reinterpret_cast<u32x4 *>(xl + pix * PS + c * 16) = live ? rx[i] : zero_u4();
+                const int g = pix / PIX, rem = pix - g * PIX, yy = rem / WIN, xx = rem - yy * WIN;
+                const bool live = s + g < s_end;
+                *reinterpret_cast<u32x4 *>(xl + (g * PIXP + (yy + PAD) * WP + xx + PAD) * PS + c * 16) =
+                    live ? rx[i] : zero_u4();
             }
         }
 #pragma unroll
@@ -238,8 +246,8 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
             for (int h = 0; h < 2; ++h) {
                 int m = h ? mb : ma;
                 m = m < R ? m : R - 1;                       // padded rows: any in-range window (their dY is zero)
-                const int g = m / P, rem = m - g * P, oy = rem / HOUT, ox = rem - oy * HOUT;
-                base[h] = (g * PIX + STRIDE * oy * HIN + STRIDE * ox) * PS + col_lane;
+                const int g = m / P, rem = m - g * P, oy = rem / WOUT, ox = rem - oy * WOUT;
+                base[h] = (g * PIXP + STRIDE * oy * WP + STRIDE * ox) * PS + col_lane;   // window origin in the bordered image
             }
             bf16x8 fy[TY];
 #pragma unroll
@@ -252,7 +260,7 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
                 if (wx * TX + b >= NX) break;                // wavefront-uniform
                 const int k0 = (wx * TX + b) * 32, tap = k0 / CIN, ci0 = k0 - tap * CIN;
                 const int ky = tap / KS, kx = tap - ky * KS;
-                const int toff = (ky * HIN + kx) * PS + ci0 * 2;
+                const int toff = (ky * WP + kx) * PS + ci0 * 2;
                 const bf16x8 fx = tr_pair(xl, base[0] + toff, base[1] + toff);
 #pragma unroll
                 for (int a = 0; a < TY; ++a)
