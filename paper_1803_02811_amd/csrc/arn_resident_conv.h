@@ -79,6 +79,18 @@ constexpr bool layout_is_uniform() {
     return true;
 }
 
+// Args with a member function prefetch(sample, pos, n) have it called for every output quad of a position
+// tile before the tile's MFMAs; its 8-byte result (for example the stored activation whose sign masks the
+// output) is handed to store() as a last argument, which then needs no dependent load in the epilogue.
+template <class A, class = void>
+struct ArgsPrefetch {
+    static constexpr bool value = false;
+};
+template <class A>
+struct ArgsPrefetch<A, decltype((void)&A::prefetch)> {
+    static constexpr bool value = true;
+};
+
 template <class C>
 __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
     constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
@@ -212,14 +224,29 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
         }
     };
 
-    auto tile_store = [&](int t, const f32x4 (&acc)[CT], int s, const uint8_t *mbits) __attribute__((always_inline)) {
+    constexpr bool HASPRE = ArgsPrefetch<typename C::Args>::value;
+    auto tile_prefetch = [&](int t, int s, u32x2 (&pre)[CT]) __attribute__((always_inline)) {
+        if constexpr (HASPRE) {
+            const int orow = t * 16 + li;
+            const int rowc = orow < R ? orow : R - 1;
+            const int g = rowc / C::P, pos = rowc - g * C::P;
+            const int sg = s + g < s_end ? s + g : s_end - 1;      // always a valid sample; unused rows are not stored
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) pre[ct] = a.prefetch(sg, pos, wave * (16 * CT) + ct * 16 + 4 * lg);
+        }
+    };
+    auto tile_store = [&](int t, const f32x4 (&acc)[CT], int s, const uint8_t *mbits, const u32x2 (&pre)[CT])
+                          __attribute__((always_inline)) {
         const int orow = t * 16 + li;
         const int rowc = orow < R ? orow : R - 1;
         const int g = rowc / C::P, pos = rowc - g * C::P;
         if (orow < R && s + g < s_end) {
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-                a.store(s + g, g, pos, wave * (16 * CT) + ct * 16 + 4 * lg, acc[ct], lane_state[ct], mbits);
+            for (int ct = 0; ct < CT; ++ct) {
+                const int n = wave * (16 * CT) + ct * 16 + 4 * lg;
+                if constexpr (HASPRE) a.store(s + g, g, pos, n, acc[ct], lane_state[ct], mbits, pre[ct]);
+                else a.store(s + g, g, pos, n, acc[ct], lane_state[ct], mbits);
+            }
         }
     };
 
@@ -249,6 +276,8 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
                 f32x4 acc[CT];
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                u32x2 pre[CT];
+                tile_prefetch(t, s, pre);
                 load_half(img, t, 1, fb_h, fb_l);            // in flight during the first half's MFMAs
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_half(0, fa_h, fa_l, acc);
@@ -257,7 +286,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_half(1, fb_h, fb_l, acc);
                 __builtin_amdgcn_sched_barrier(0);
-                tile_store(t, acc, s, mbits);
+                tile_store(t, acc, s, mbits, pre);
             }
         } else {
 #pragma unroll 1
@@ -266,11 +295,13 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
                 bf16x8 fh[KH], fl[C::SPLIT ? KH : 1];
+                u32x2 pre[CT];
+                tile_prefetch(t, s, pre);
                 load_half(img, t, 0, fh, fl);
                 mfma_half(0, fh, fl, acc);
                 load_half(img, t, 1, fh, fl);
                 mfma_half(1, fh, fl, acc);
-                tile_store(t, acc, s, mbits);
+                tile_store(t, acc, s, mbits, pre);
             }
         }
         if constexpr (NBUF == 1) __syncthreads();    // everyone is done reading before the next group is staged
@@ -541,7 +572,8 @@ struct ResConv2Dgrad {
 // ---------------------------------------------------------------------------
 // Input gradients for any geometry Geo (arn_layout.h), used by the padded 104x80 network.  Same kernel and the
 // same LDS bank rule as above; the row and image padding that makes the fragment reads conflict free is
-// computed from the map sizes.  The ReLU derivative is read from the stored activation in the epilogue.
+// computed from the map sizes.  The ReLU derivative is taken from the stored activation, fetched before a
+// tile's MFMAs.
 constexpr int pad_to_step(int have, int want) { return (((want - have) % 256) + 256) % 256; }
 
 // conv3 (3x3, stride 1, padding PAD3): d(pre3) [H3][W3][64] zero-padded by OFF = 2 - PAD3 on every side;
@@ -568,9 +600,13 @@ struct ResConv3DgradGeo {
         __bf16 *out;
         struct Lane {};
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
-        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *) const {
+        __device__ __forceinline__ u32x2 prefetch(int s, int pos, int n) const {
+            return *reinterpret_cast<const u32x2 *>(act + ((size_t)s * Geo::P2 + pos) * C2 + n);
+        }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *,
+                                              u32x2 pre) const {
             const size_t at = ((size_t)s * Geo::P2 + pos) * C2 + n;
-            const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+            const f32x4 a = unpack_bf16x4(pre);
             *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
                                                               a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
         }
@@ -603,12 +639,22 @@ struct ResConv2DgradGeo {
         __bf16 *out;
         struct Lane {};
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
-        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *) const {
+        // element offset of channel quad n of position pos in act1 / d(pre1), or -1 outside the map
+        __device__ __forceinline__ long at_of(int s, int pos, int n) const {
             const int phase = n >> 5, ci = n & 31, u = pos / V, vv = pos - u * V;
             const int y = 2 * u + (phase >> 1) - Geo::PAD2, x = 2 * vv + (phase & 1) - Geo::PAD2;
-            if ((unsigned)y >= (unsigned)Geo::H1 || (unsigned)x >= (unsigned)Geo::W1) return;
-            const size_t at = (((size_t)s * Geo::H1 + y) * Geo::W1 + x) * C1 + ci;
-            const f32x4 a = unpack_bf16x4(*reinterpret_cast<const u32x2 *>(act + at));
+            if ((unsigned)y >= (unsigned)Geo::H1 || (unsigned)x >= (unsigned)Geo::W1) return -1;
+            return (((long)s * Geo::H1 + y) * Geo::W1 + x) * C1 + ci;
+        }
+        __device__ __forceinline__ u32x2 prefetch(int s, int pos, int n) const {
+            const long at = at_of(s, pos, n);
+            return *reinterpret_cast<const u32x2 *>(act + (at < 0 ? 0 : at));
+        }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *,
+                                              u32x2 pre) const {
+            const long at = at_of(s, pos, n);
+            if (at < 0) return;
+            const f32x4 a = unpack_bf16x4(pre);
             *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
                                                               a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
         }
