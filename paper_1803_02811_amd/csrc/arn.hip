@@ -196,13 +196,14 @@ void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const
 // Convolutions of geometry G as gathered contractions (three products; conv1's pixel operand is exact: two)
 template <class G>
 void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                     float *z_out, int zstride, hipStream_t s) {
+                     float *z_out, int zstride, bool masks, hipStream_t s) {
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
     {
-        Conv1FwdG<G> p;
-        p.obs = obs; p.M = B * G::P1; p.w = w.w1; p.w_lo = w.w1l; p.bias = w.b1; p.out = a1; p.out_lo = a1l;
-        launch_nt_split("conv1_fwd", p, p.M, 1, 1, s);
+        ProfScope ps("conv1_fwd", s);
+        const int spw = resident_spw(B, 256);
+        hipLaunchKernelGGL(conv1_fwd_resident_kernel<G>, dim3(cdiv(B, spw), 1), dim3(RES_THREADS), 0, s, obs, w.w1,
+                           w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     {
         Conv2FwdG<G> p;
@@ -226,7 +227,7 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                       float *z_out, int zstride, bool masks, hipStream_t s) {
     if (d.geom == ARN_GEOM_PAPER) {   // the gathered path keeps no sign bits: its backward reads the activations
-        forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, s);
+        forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
         return;
     }
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
@@ -235,7 +236,7 @@ void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B,
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
         const int parts = 3 * B <= 256 ? 3 : 1;   // few samples: three workgroups share one (one workgroup fits per CU)
-        hipLaunchKernelGGL(conv1_fwd_resident_kernel, dim3(cdiv(B, spw), parts), dim3(RES_THREADS), 0, s, obs, w.w1,
+        hipLaunchKernelGGL(conv1_fwd_resident_kernel<Geo84>, dim3(cdiv(B, spw), parts), dim3(RES_THREADS), 0, s, obs, w.w1,
                            w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     {

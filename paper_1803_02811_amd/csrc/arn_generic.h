@@ -89,27 +89,7 @@ template <class G>
 using Conv3GatherG = ConvGatherG<C2, G::H2, G::W2, K3, S3, G::PAD3, G::H3, G::W3>;
 
 // ------------------------------ forward ----------------------------------
-template <class G>
-struct Conv1FwdG : ObsGatherG<G> {
-    typedef typename ObsGatherG<G>::Row Row;
-    static constexpr int BM = 128, BN = 32, WAVES_N = 1, K = KW1;
-    static constexpr bool ACT_LO = false;   // pixels are exact in bf16: two products
-    const __bf16 *w, *w_lo = nullptr;
-    const float *bias;
-    __bf16 *out, *out_lo = nullptr;
-    __device__ __forceinline__ Row row(int m, int) const { return this->row_at(m); }
-    __device__ __forceinline__ u32x4 load(const Row &r, int k) const { return this->load_at(r, k); }
-    __device__ __forceinline__ u32x4 load_lo(const Row &, int) const { return zero_u4(); }
-    __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
-    __device__ __forceinline__ const __bf16 *weights_lo(int) const { return w_lo; }
-    __device__ __forceinline__ void store(int m, int n, f32x4 v, int) const {
-        if (m >= this->M) return;
-        const float4 b = *reinterpret_cast<const float4 *>(bias + n);
-        constexpr float s = 1.0f / 255.0f;
-        store_bf16x4_split(out, out_lo, (size_t)m * C1 + n, fmaxf(v[0] * s + b.x, 0.f), fmaxf(v[1] * s + b.y, 0.f),
-                           fmaxf(v[2] * s + b.z, 0.f), fmaxf(v[3] * s + b.w, 0.f));
-    }
-};
+// (conv1 forward: conv1_fwd_resident_kernel<G> in arn_resident_conv.h)
 
 template <class Gather, int COUT, int K_>
 struct ConvFwdG : Gather {

@@ -310,24 +310,29 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
 }
 
 // ---------------------------------------------------------------------------
-// conv1 forward: uint8 observation [4][84][84] -> act1 [20][20][32], 8x8 stride 4,
+// conv1 forward: uint8 observation [4][IN_H][IN_W] -> act1 [H1][W1][32] (84x84 -> 20x20), 8x8 stride 4,
 // fused with the uint8 -> bf16 unpack (exact) and the 1/255 scale (fp32 epilogue).
 // The sample is converted to a bf16 image in LDS once (each pixel is used by up
 // to four windows); a 32-wide k-step is four rows (ky) of eight pixels (kx) of
 // one input channel, so an activation fragment is 16 contiguous bytes of the
 // image.  A wavefront keeps one 16-channel tile of W1 (hi and lo parts) in registers;
-// the 25 position tiles of a sample are dealt round-robin to the four wavefront pairs.
-// Three-product precision with an exact activation operand needs
+// the position tiles of a sample (25 at 84x84; the last one may be ragged) are dealt round-robin to the four
+// wavefront pairs.  Three-product precision with an exact activation operand needs
 // two MFMAs per fragment (W_hi x, W_lo x).
+template <class Geo>
 __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w, const __bf16 *__restrict__ w_lo,
     const float *__restrict__ bias, __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo,
     uint8_t *__restrict__ mask_out, int B, int spw) {
-    constexpr int IMG_U4 = OBS_BYTES / 16;                           // 1764 sixteen-pixel groups
+    constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
+    static_assert(OBS_BYTES % 16 == 0, "a sample is copied in 16-byte words");
+    constexpr int IMG_U4 = OBS_BYTES / 16;                           // sixteen-pixel groups (1764 at 84x84)
     constexpr int NL = (IMG_U4 + RES_THREADS - 1) / RES_THREADS;     // 4
     constexpr int KS = KW1 / 32;                                     // 8
-    constexpr int NT = P1 / 16;                                      // 25 position tiles, no remainder
-    __shared__ u32x4 s_img[2][2 * IMG_U4];                           // bf16 [4][84][84], double buffered
+    constexpr int NT = (P1 + 15) / 16;                               // position tiles (25 at 84x84, no remainder)
+    constexpr bool RAGGED = P1 % 16 != 0;
+    __shared__ u32x4 s_img[2][2 * IMG_U4];                           // bf16 [4][IN_H][IN_W], double buffered
+    static_assert(sizeof(u32x4) * 4 * IMG_U4 <= 160 * 1024, "LDS budget");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
@@ -352,7 +357,9 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
 
     // activation fragments of position tile t: for each k-step, 16 bytes of the image (8 pixels of a row)
     auto frag_load = [&](const char *img, int t, u32x2 (&f)[2 * KS]) __attribute__((always_inline)) {
-        const int pos = t * 16 + li, oy = pos / H1, ox = pos - oy * H1;
+        int pos = t * 16 + li;
+        if constexpr (RAGGED) pos = pos < P1 ? pos : P1 - 1;       // rows past the last position recompute it; never stored
+        const int oy = pos / W1, ox = pos - oy * W1;
         const int base = ((S1 * oy + lg) * IN_W + S1 * ox) * 2;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -374,10 +381,11 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         const float r0 = fmaxf(acc[0] * sc + bs.x, 0.f), r1 = fmaxf(acc[1] * sc + bs.y, 0.f);
         const float r2 = fmaxf(acc[2] * sc + bs.z, 0.f), r3 = fmaxf(acc[3] * sc + bs.w, 0.f);
         const size_t at = ((size_t)s * P1 + pos) * C1 + ct * 16;
-        store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3);
+        const bool live = !RAGGED || pos < P1;
+        if (live) store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3);
         if (mask_out) {
-            const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
-            if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
+            const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);     // all lanes take part
+            if (lg == 0 && live) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
         }
     };
 
@@ -405,7 +413,20 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         // run (two register sets, statically alternated).  Tiles t0 + 4j, j = 0..5, exist for every
         // wavefront; tile 24 (j = 6) only for t0 = 0.
         u32x2 fa[2 * KS], fb[2 * KS];
-        if (gridDim.y == 1) {
+        if constexpr (NT != 25) {
+            // any tile count: this wavefront's tiles t0, t0 + 4, ... in pairs, then the odd one
+            const int nj = (NT - t0 + 3) / 4;
+            frag_load(img, t0, fa);
+            int j = 0;
+#pragma unroll 1
+            for (; j + 1 < nj; j += 2) {
+                frag_load(img, t0 + 4 * (j + 1), fb);
+                unit(s, t0 + 4 * j, fa);
+                if (j + 2 < nj) frag_load(img, t0 + 4 * (j + 2), fa);
+                unit(s, t0 + 4 * (j + 1), fb);
+            }
+            if (j < nj) unit(s, t0 + 4 * j, fa);
+        } else if (gridDim.y == 1) {
             frag_load(img, t0, fa);
 #pragma unroll
             for (int j = 0; j < 6; j += 2) {
