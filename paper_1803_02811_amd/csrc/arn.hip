@@ -329,7 +329,7 @@ void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *w
         float *part = (float *)(ws + o.pw1);
         {
             ProfScope ps("conv1_wgrad", s);
-            hipLaunchKernelGGL(conv1_wgrad_resident_kernel, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part, B,
+            hipLaunchKernelGGL(conv1_wgrad_resident_kernel<Geo84>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part, B,
                                resident_spw(B, 256));
         }
         // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
@@ -397,10 +397,12 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     }
     // conv1: weight gradient only (the input is data)
     {
-        Conv1WgradG<G> p;
-        p.obs = obs; p.M = B * G::P1; p.dy = dp1;
         float *part = (float *)(ws + o.pw1);
-        launch_tn("conv1_wgrad", p, part, p.M, C1, KW1, sp.c1, s);
+        {
+            ProfScope ps("conv1_wgrad", s);
+            hipLaunchKernelGGL(conv1_wgrad_resident_kernel<G>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part, B,
+                               resident_spw(B, 256));
+        }
         // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
         launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
     }

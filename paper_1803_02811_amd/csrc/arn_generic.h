@@ -144,8 +144,7 @@ struct FcDgradAct : DenseGather<HID> {
 // (conv3 / conv2 input gradients: ResConv3DgradGeo / ResConv2DgradGeo in arn_resident_conv.h)
 
 // --------------------------- weight gradients -----------------------------
-template <class G>
-using Conv1WgradG = Wgrad<ObsGatherG<G>, 32, 128, 4, C1, KW1>;
+// (conv1 weight gradient: conv1_wgrad_resident_kernel<G> in arn_resident.h)
 // (conv2 / conv3 weight gradients: conv_wgrad_resident_kernel in arn_resident.h)
 
 }  // namespace arn

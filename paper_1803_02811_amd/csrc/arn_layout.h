@@ -176,9 +176,9 @@ inline int resident_groups(int B, int target_wgs) {
 inline Splits make_splits(const Dims &d, int B) {
     Splits s;
     if (d.geom != ARN_GEOM_84) {
-        // gathered (implicit-GEMM) weight-gradient kernels (conv1, fc, head): rows = samples x positions, cut so
-        // that about 1024 (512 for the dense layers) workgroups exist
-        s.c1 = pick_split((long)B * d.p1, 2, 1024);
+        // the dense layers' weight-gradient GEMMs are cut along the batch so that about 512 workgroups exist;
+        // the convolutions use the sample-resident kernels, as below
+        s.c1 = resident_groups(B, 256);
         s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS);   // sample-resident kernels, as below
         s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS);
         s.fc = pick_split(B, (d.feat / 64) * 4, 512);

@@ -24,23 +24,30 @@ __device__ __forceinline__ bf16x8 tr_pair(const char *lds_base, int off_a, int o
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// conv1: x = uint8 observation [4][84][84] (k' = ci*64 + ky*8 + kx, window at
-// (4oy, 4ox)), dY = d(pre1) [400][32].  part[wg] = [32][256] then [32] bias sums.
+// conv1: x = uint8 observation [4][IN_H][IN_W] of geometry Geo (k' = ci*64 + ky*8 + kx, window at
+// (4oy, 4ox)), dY = d(pre1) [P1][32] (P1 = 400 at 84x84).  part[wg] = [32][256] then [32] bias sums.
 // The 1/255 pixel scale is applied by the reduction.
 constexpr int C1W_THREADS = 512;   // eight wavefronts: one 32-column tile of dW1 each, two per SIMD
+template <class Geo>
 __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const uint8_t *__restrict__ obs,
                                                                    const __bf16 *__restrict__ dy,
                                                                    float *__restrict__ part, int B, int spw) {
-    constexpr int IMG_U4 = OBS_BYTES / 16;        // 1764 sixteen-pixel groups per sample
-    constexpr int DY_U4 = P1 * C1 * 2 / 16;       // 1600
+    constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
+    constexpr int IMG_U4 = OBS_BYTES / 16;        // sixteen-pixel groups per sample (1764 at 84x84)
+    constexpr int DY_U4 = P1 * C1 * 2 / 16;       // 1600 at 84x84
+    constexpr int KSTEPS = (P1 + 15) / 16, RPAD = KSTEPS * 16;   // contraction steps; dY rows P1..RPAD stay zero
     constexpr int NT = C1W_THREADS;
     constexpr int NI = (IMG_U4 + NT - 1) / NT, ND = (DY_U4 + NT - 1) / NT;   // 4, 4
-    __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][84][84]
-    __shared__ u32x4 s_dy[DY_U4];                 // bf16 [400][32]
+    static_assert(OBS_BYTES % 16 == 0 && (P1 * C1 * 2) % 16 == 0, "samples are copied in 16-byte words");
+    __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][IN_H][IN_W]
+    __shared__ u32x4 s_dy[RPAD * C1 * 2 / 16];    // bf16 [RPAD][32]
+    static_assert((NT / 4) * C1 * 4 <= RPAD * C1 * 2, "bias-gradient scratch");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
+    if constexpr (RPAD > P1)
+        for (int i = DY_U4 + tid; i < RPAD * C1 * 2 / 16; i += NT) s_dy[i] = zero_u4();
 
     u32x4 rimg[NI], rdy[ND];
     auto gload = [&](int s) __attribute__((always_inline)) {
@@ -100,9 +107,11 @@ __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const
         const char *img = reinterpret_cast<const char *>(s_img);
         const char *dyl = reinterpret_cast<const char *>(s_dy);
 #pragma unroll 5
-        for (int ks = 0; ks < P1 / 16; ++ks) {
+        for (int ks = 0; ks < KSTEPS; ++ks) {
             const int ma = 16 * ks + row_in_step, mb = ma + 4;
-            const int oya = ma / H1, oxa = ma - oya * H1, oyb = mb / H1, oxb = mb - oyb * H1;
+            // rows past the last position (their dY is zero) take the last position's window
+            const int wa = RPAD > P1 && ma >= P1 ? P1 - 1 : ma, wb = RPAD > P1 && mb >= P1 ? P1 - 1 : mb;
+            const int oya = wa / W1, oxa = wa - oya * W1, oyb = wb / W1, oxb = wb - oyb * W1;
             const int pa = (S1 * oya * IN_W + S1 * oxa) * 2, pb = (S1 * oyb * IN_W + S1 * oxb) * 2;
             const bf16x8 fy = tr_pair(dyl, ma * (C1 * 2) + ycol_off, mb * (C1 * 2) + ycol_off);
             const bf16x8 fx = tr_pair(img, pa + xoff, pb + xoff);
