@@ -208,13 +208,13 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
     {
         Conv2FwdG<G> p;
         p.in = a1; p.lo_off = a1l - a1; p.M = B * G::P2; p.w = w.w2; p.w_lo = w.w2l; p.bias = w.b2;
-        p.out = a2; p.out_lo = a2l;
+        p.out = a2; p.out_lo = a2l; p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
         launch_nt_split("conv2_fwd", p, p.M, 1, 1, s);
     }
     {
         Conv3FwdG<G> p;
         p.in = a2; p.lo_off = a2l - a2; p.M = B * G::P3; p.w = w.w3; p.w_lo = w.w3l; p.bias = w.b3;
-        p.out = a3; p.out_lo = a3l;
+        p.out = a3; p.out_lo = a3l; p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
         launch_nt_split("conv3_fwd", p, p.M, 1, 1, s);
     }
     fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, zstride, s);
@@ -226,7 +226,7 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
 // masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on the online weights).
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                       float *z_out, int zstride, bool masks, hipStream_t s) {
-    if (d.geom == ARN_GEOM_PAPER) {   // the gathered path keeps no sign bits: its backward reads the activations
+    if (d.geom == ARN_GEOM_PAPER) {
         forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
         return;
     }
@@ -337,8 +337,7 @@ void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *w
     }
 }
 
-// The same for geometry G with the gathered contraction kernels; ReLU derivatives are read from the
-// stored activations.
+// The same for geometry G: the same kernels, instantiated for its map sizes and padding.
 template <class G>
 void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                             const ParamOffsets &po, const Splits &sp, float *dW, Fork &fk) {
@@ -357,8 +356,8 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
                            (long)po.bfc, sp.fc);
     }
     {
-        FcDgradAct<G::FEAT> p;
-        p.in = dph; p.M = B; p.w = w.wfcd; p.act = a3; p.out = dp3;
+        FcDgradT<G::FEAT> p;
+        p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
         launch_nt("fc_dgrad", p, B, G::FEAT / 64, 1, s);
     }
     fk();   // d(pre3)
@@ -375,7 +374,7 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     }
     {
         typename ResConv3DgradGeo<G>::Args p;
-        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = nullptr; p.act = a2; p.out = dp2;
+        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
         launch_resident<ResConv3DgradGeo<G>>("conv3_dgrad", p, B, s);
     }
     fk();   // d(pre2)
@@ -392,7 +391,7 @@ void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws
     }
     {
         typename ResConv2DgradGeo<G>::Args p;
-        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = nullptr; p.act = a1; p.out = dp1;
+        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
         launch_resident<ResConv2DgradGeo<G>>("conv2_dgrad", p, B, s);
     }
     // conv1: weight gradient only (the input is data)

@@ -79,18 +79,6 @@ constexpr bool layout_is_uniform() {
     return true;
 }
 
-// Args with a member function prefetch(sample, pos, n) have it called for every output quad of a position
-// tile before the tile's MFMAs; its 8-byte result (for example the stored activation whose sign masks the
-// output) is handed to store() as a last argument, which then needs no dependent load in the epilogue.
-template <class A, class = void>
-struct ArgsPrefetch {
-    static constexpr bool value = false;
-};
-template <class A>
-struct ArgsPrefetch<A, decltype((void)&A::prefetch)> {
-    static constexpr bool value = true;
-};
-
 template <class C>
 __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
     constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
@@ -103,10 +91,12 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     constexpr int CT = C::CO / 64;                       // 16-channel tiles per wavefront
     constexpr int KS = C::K / 32, KH = KS / 2;           // k-steps per tile and per half-tile
     constexpr int MSB = C::MASK_ELEMS / 8;               // mask bytes per sample (1 bit per element)
-    constexpr int NMQ = C::G * MSB / 8;                  // 8-byte mask chunks per iteration
+    constexpr int MW = MSB % 8 == 0 ? 8 : 4;             // mask bytes are copied in 8-byte words where a sample's share allows
+    typedef typename std::conditional<MW == 8, u32x2, uint32_t>::type MWord;
+    constexpr int NMQ = C::G * MSB / MW;                 // mask words per iteration
     constexpr int NML = (NMQ + RESC_THREADS - 1) / RESC_THREADS;
-    constexpr int MBUF = (NMQ * 8 + 15) / 16 * 16;
-    static_assert(MSB % 8 == 0, "mask bytes per sample in 8-byte chunks");
+    constexpr int MBUF = (NMQ * MW + 15) / 16 * 16;
+    static_assert(C::MASK_ELEMS % 8 == 0 && MSB % MW == 0, "mask bytes per sample in whole words");
     static_assert(KS % 2 == 0, "k-steps split into two halves");
     constexpr int NBUF = C::NBUF;
     static_assert((BUF + MBUF) * NBUF <= 160 * 1024, "LDS budget");
@@ -114,7 +104,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     static_assert(layout_is_uniform<C>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
 
     __shared__ u32x4 lds[NBUF * BUF / 16];
-    __shared__ u32x2 lds_mask8[NMQ ? NBUF * MBUF / 8 : 2];
+    __shared__ MWord lds_mask8[NMQ ? NBUF * MBUF / MW : 2];
     uint8_t *const lds_mask = reinterpret_cast<uint8_t *>(lds_mask8);
     char *const lds_b = reinterpret_cast<char *>(lds);
 
@@ -140,7 +130,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     for (int ct = 0; ct < CT; ++ct) lane_state[ct] = a.lane(wave * (16 * CT) + ct * 16 + 4 * lg);
 
     u32x4 rh[NL], rl[C::SPLIT ? NL : 1];
-    u32x2 rm[NML ? NML : 1];
+    MWord rm[NML ? NML : 1];
     auto gload = [&](int s) __attribute__((always_inline)) {   // samples s .. s+G-1 (clamped to the last valid one)
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -157,9 +147,9 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
             for (int i = 0; i < NML; ++i) {
                 int q = tid + RESC_THREADS * i;
                 q = q < NMQ ? q : NMQ - 1;
-                const int g = q / (MSB / 8), rem = q - g * (MSB / 8);
+                const int g = q / (MSB / MW), rem = q - g * (MSB / MW);
                 const int sg = s + g < s_end ? s + g : s_end - 1;
-                rm[i] = *reinterpret_cast<const u32x2 *>(a.mask + (size_t)sg * MSB + (size_t)rem * 8);
+                rm[i] = *reinterpret_cast<const MWord *>(a.mask + (size_t)sg * MSB + (size_t)rem * MW);
             }
         }
     };
@@ -180,7 +170,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
 #pragma unroll
             for (int i = 0; i < NML; ++i) {
                 const int q = tid + RESC_THREADS * i;
-                if (q < NMQ) lds_mask8[buf * (MBUF / 8) + q] = rm[i];
+                if (q < NMQ) lds_mask8[buf * (MBUF / MW) + q] = rm[i];
             }
         }
     };
@@ -224,29 +214,14 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
         }
     };
 
-    constexpr bool HASPRE = ArgsPrefetch<typename C::Args>::value;
-    auto tile_prefetch = [&](int t, int s, u32x2 (&pre)[CT]) __attribute__((always_inline)) {
-        if constexpr (HASPRE) {
-            const int orow = t * 16 + li;
-            const int rowc = orow < R ? orow : R - 1;
-            const int g = rowc / C::P, pos = rowc - g * C::P;
-            const int sg = s + g < s_end ? s + g : s_end - 1;      // always a valid sample; unused rows are not stored
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) pre[ct] = a.prefetch(sg, pos, wave * (16 * CT) + ct * 16 + 4 * lg);
-        }
-    };
-    auto tile_store = [&](int t, const f32x4 (&acc)[CT], int s, const uint8_t *mbits, const u32x2 (&pre)[CT])
-                          __attribute__((always_inline)) {
+    auto tile_store = [&](int t, const f32x4 (&acc)[CT], int s, const uint8_t *mbits) __attribute__((always_inline)) {
         const int orow = t * 16 + li;
         const int rowc = orow < R ? orow : R - 1;
         const int g = rowc / C::P, pos = rowc - g * C::P;
         if (orow < R && s + g < s_end) {
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                const int n = wave * (16 * CT) + ct * 16 + 4 * lg;
-                if constexpr (HASPRE) a.store(s + g, g, pos, n, acc[ct], lane_state[ct], mbits, pre[ct]);
-                else a.store(s + g, g, pos, n, acc[ct], lane_state[ct], mbits);
-            }
+            for (int ct = 0; ct < CT; ++ct)
+                a.store(s + g, g, pos, wave * (16 * CT) + ct * 16 + 4 * lg, acc[ct], lane_state[ct], mbits);
         }
     };
 
@@ -276,8 +251,6 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
                 f32x4 acc[CT];
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-                u32x2 pre[CT];
-                tile_prefetch(t, s, pre);
                 load_half(img, t, 1, fb_h, fb_l);            // in flight during the first half's MFMAs
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_half(0, fa_h, fa_l, acc);
@@ -286,7 +259,7 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_half(1, fb_h, fb_l, acc);
                 __builtin_amdgcn_sched_barrier(0);
-                tile_store(t, acc, s, mbits, pre);
+                tile_store(t, acc, s, mbits);
             }
         } else {
 #pragma unroll 1
@@ -295,13 +268,11 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
                 bf16x8 fh[KH], fl[C::SPLIT ? KH : 1];
-                u32x2 pre[CT];
-                tile_prefetch(t, s, pre);
                 load_half(img, t, 0, fh, fl);
                 mfma_half(0, fh, fl, acc);
                 load_half(img, t, 1, fh, fl);
                 mfma_half(1, fh, fl, acc);
-                tile_store(t, acc, s, mbits, pre);
+                tile_store(t, acc, s, mbits);
             }
         }
         if constexpr (NBUF == 1) __syncthreads();    // everyone is done reading before the next group is staged
@@ -593,8 +564,7 @@ struct ResConv2Dgrad {
 // ---------------------------------------------------------------------------
 // Input gradients for any geometry Geo (arn_layout.h), used by the padded 104x80 network.  Same kernel and the
 // same LDS bank rule as above; the row and image padding that makes the fragment reads conflict free is
-// computed from the map sizes.  The ReLU derivative is taken from the stored activation, fetched before a
-// tile's MFMAs.
+// computed from the map sizes.
 constexpr int pad_to_step(int have, int want) { return (((want - have) % 256) + 256) % 256; }
 
 // conv3 (3x3, stride 1, padding PAD3): d(pre3) [H3][W3][64] zero-padded by OFF = 2 - PAD3 on every side;
@@ -605,7 +575,7 @@ struct ResConv3DgradGeo {
     static_assert(PADH - 2 == Geo::H2 && PADW - 2 == Geo::W2, "stride-1 3x3 correlation over the padded gradient");
     static constexpr int CI = C3, SRC_PIX = Geo::P3, P = Geo::P2, CO = C2, K = 9 * C3, G = 2;
     static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
-    static constexpr int MASK_ELEMS = 0, NBUF = 1;
+    static constexpr int MASK_ELEMS = Geo::P2 * C2, NBUF = 1;
     static constexpr int PSB = C3 * 2 + 32;
     // W2 positions per output row: the first position of the next row must follow at one pixel stride mod 256
     static constexpr int ROWB = PADW * PSB + pad_to_step(PADW * PSB, Geo::W2 * PSB);
@@ -616,20 +586,16 @@ struct ResConv3DgradGeo {
     __device__ static constexpr int tap_off(int t) { return (t / 3) * ROWB + (t % 3) * PSB; }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
-        const uint8_t *mask;   // unused
-        const __bf16 *act;     // act2
+        const uint8_t *mask;   // sign bits of act2
         __bf16 *out;
         struct Lane {};
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
-        __device__ __forceinline__ u32x2 prefetch(int s, int pos, int n) const {
-            return *reinterpret_cast<const u32x2 *>(act + ((size_t)s * Geo::P2 + pos) * C2 + n);
-        }
-        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *,
-                                              u32x2 pre) const {
-            const size_t at = ((size_t)s * Geo::P2 + pos) * C2 + n;
-            const f32x4 a = unpack_bf16x4(pre);
-            *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
-                                                              a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
+        __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
+                                              const uint8_t *mbits) const {
+            const int e = (g * Geo::P2 + pos) * C2 + n;
+            const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
+            *reinterpret_cast<u32x2 *>(out + ((size_t)s * Geo::P2 + pos) * C2 + n) =
+                pack_bf16x4(m & 1 ? v[0] : 0.f, m & 2 ? v[1] : 0.f, m & 4 ? v[2] : 0.f, m & 8 ? v[3] : 0.f);
         }
     };
 };
@@ -645,7 +611,7 @@ struct ResConv2DgradGeo {
     static_assert(U <= PADH - 1 && V <= PADW - 1, "every 2x2 window lies inside the padded gradient");
     static constexpr int CI = C2, SRC_PIX = Geo::P2, P = U * V, CO = 4 * C1, K = 4 * C2, G = 2;
     static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
-    static constexpr int MASK_ELEMS = 0, NBUF = 1;
+    static constexpr int MASK_ELEMS = Geo::P1 * C1, NBUF = 1;
     static constexpr int PSB = C2 * 2 + 32;
     static constexpr int ROWB = PADW * PSB + pad_to_step(PADW * PSB, V * PSB);
     static constexpr int LAST = (U - 1) * ROWB + (V - 1) * PSB;
@@ -655,29 +621,20 @@ struct ResConv2DgradGeo {
     __device__ static constexpr int tap_off(int t) { return (t / 2) * ROWB + (t % 2) * PSB; }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
-        const uint8_t *mask;   // unused
-        const __bf16 *act;     // act1
+        const uint8_t *mask;   // sign bits of act1
         __bf16 *out;
         struct Lane {};
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
-        // element offset of channel quad n of position pos in act1 / d(pre1), or -1 outside the map
-        __device__ __forceinline__ long at_of(int s, int pos, int n) const {
+        __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
+                                              const uint8_t *mbits) const {
             const int phase = n >> 5, ci = n & 31, u = pos / V, vv = pos - u * V;
             const int y = 2 * u + (phase >> 1) - Geo::PAD2, x = 2 * vv + (phase & 1) - Geo::PAD2;
-            if ((unsigned)y >= (unsigned)Geo::H1 || (unsigned)x >= (unsigned)Geo::W1) return -1;
-            return (((long)s * Geo::H1 + y) * Geo::W1 + x) * C1 + ci;
-        }
-        __device__ __forceinline__ u32x2 prefetch(int s, int pos, int n) const {
-            const long at = at_of(s, pos, n);
-            return *reinterpret_cast<const u32x2 *>(act + (at < 0 ? 0 : at));
-        }
-        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &, const uint8_t *,
-                                              u32x2 pre) const {
-            const long at = at_of(s, pos, n);
-            if (at < 0) return;
-            const f32x4 a = unpack_bf16x4(pre);
-            *reinterpret_cast<u32x2 *>(out + at) = pack_bf16x4(a[0] > 0.f ? v[0] : 0.f, a[1] > 0.f ? v[1] : 0.f,
-                                                              a[2] > 0.f ? v[2] : 0.f, a[3] > 0.f ? v[3] : 0.f);
+            if ((unsigned)y >= (unsigned)Geo::H1 || (unsigned)x >= (unsigned)Geo::W1) return;
+            const int pix = y * Geo::W1 + x;
+            const int e = (g * Geo::P1 + pix) * C1 + ci;
+            const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
+            *reinterpret_cast<u32x2 *>(out + ((size_t)s * Geo::P1 + pix) * C1 + ci) =
+                pack_bf16x4(m & 1 ? v[0] : 0.f, m & 2 ? v[1] : 0.f, m & 4 ? v[2] : 0.f, m & 8 ? v[3] : 0.f);
         }
     };
 };
