@@ -212,10 +212,10 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
         launch_nt_split("conv2_fwd", p, p.M, 1, 1, s);
     }
     {
-        Conv3FwdG<G> p;
-        p.in = a2; p.lo_off = a2l - a2; p.M = B * G::P3; p.w = w.w3; p.w_lo = w.w3l; p.bias = w.b3;
-        p.out = a3; p.out_lo = a3l; p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
-        launch_nt_split("conv3_fwd", p, p.M, 1, 1, s);
+        typename ResConv3FwdGeo<G>::Args p;
+        p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
+        p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
+        launch_resident<ResConv3FwdGeo<G>>("conv3_fwd", p, B, s);
     }
     fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, zstride, s);
 }

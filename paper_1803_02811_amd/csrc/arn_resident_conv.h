@@ -565,7 +565,48 @@ struct ResConv2Dgrad {
 // Input gradients for any geometry Geo (arn_layout.h), used by the padded 104x80 network.  Same kernel and the
 // same LDS bank rule as above; the row and image padding that makes the fragment reads conflict free is
 // computed from the map sizes.
+
 constexpr int pad_to_step(int have, int want) { return (((want - have) % 256) + 256) % 256; }
+
+// conv3 forward (3x3, stride 1, padding PAD3 > 0): act2 [H2][W2][64] with a zero border of PAD3 pixels,
+// act3 [H3][W3][64]; three products.
+template <class Geo>
+struct ResConv3FwdGeo {
+    static_assert(Geo::PAD3 > 0, "the unpadded case has a layout of its own (ResConv3Fwd)");
+    static constexpr int PADH = Geo::H2 + 2 * Geo::PAD3, PADW = Geo::W2 + 2 * Geo::PAD3;
+    static constexpr int CI = C2, SRC_PIX = Geo::P2, P = Geo::P3, CO = C3, K = KW3, G = 1;
+    static constexpr bool SPLIT = true, ZERO_FILL = true, PIPE = false;
+    static constexpr int MASK_ELEMS = 0, NBUF = 1;
+    static constexpr int PSB = C2 * 2 + 32;
+    static constexpr int ROWB = PADW * PSB + pad_to_step(PADW * PSB, Geo::W3 * PSB);
+    static constexpr int IMG = PADH * ROWB;
+    __device__ static constexpr int dst_off(int p) {
+        return (p / Geo::W2 + Geo::PAD3) * ROWB + (p % Geo::W2 + Geo::PAD3) * PSB;
+    }
+    __device__ static constexpr int base_off(int pos) { return (pos / Geo::W3) * ROWB + (pos % Geo::W3) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return (t / K3) * ROWB + (t % K3) * PSB; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;
+        const float *bias;
+        __bf16 *out, *out_lo;
+        uint8_t *mask_out;     // sign bits of the output for the backward pass, or null
+        typedef float4 Lane;
+        __device__ __forceinline__ Lane lane(int n) const { return *reinterpret_cast<const float4 *>(bias + n); }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &b,
+                                              const uint8_t *) const {
+            const float r0 = fmaxf(v[0] + b.x, 0.f), r1 = fmaxf(v[1] + b.y, 0.f), r2 = fmaxf(v[2] + b.z, 0.f),
+                        r3 = fmaxf(v[3] + b.w, 0.f);
+            const size_t at = ((size_t)s * Geo::P3 + pos) * C3 + n;
+            store_bf16x4_split(out, out_lo, at, r0, r1, r2, r3);
+            if (mask_out) {
+                const int lg = (n >> 2) & 3;
+                const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
+                if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
+            }
+        }
+    };
+};
 
 // conv3 (3x3, stride 1, padding PAD3): d(pre3) [H3][W3][64] zero-padded by OFF = 2 - PAD3 on every side;
 // tap (ty,tx) reads padded (y+ty, x+tx) against W3[co][ci][2-ty][2-tx]; output d(pre2) [H2][W2][64].
