@@ -9,7 +9,6 @@
 #include <vector>
 
 #include "arn_gemm.h"
-#include "arn_generic.h"
 #include "arn_layout.h"
 #include "arn_problems.h"
 #include "arn_pv_head.h"
@@ -114,14 +113,15 @@ template <class C>
 void launch_resident(const char *name, const typename C::Args &a, int B, hipStream_t s) {
     ProfScope ps(name, s);
     const int groups = (B + C::G - 1) / C::G;
-    const int target = C::NBUF == 1 ? 512 : 256;                              // single-buffered kernels share a CU
+    constexpr int waves = ResWaves<C>::value;
+    const int target = C::NBUF == 1 && waves == 4 ? 512 : 256;               // single-buffered four-wavefront kernels share a CU
     const int spw = resident_spw(groups, target) * C::G;
     // with few sample groups, the position tiles of a group are dealt to several workgroups
     constexpr int tiles = (C::G * C::P + 15) / 16;
     const int wgs = (int)cdiv(B, spw);
     int parts = 128 / wgs;   // every extra workgroup repeats the weight fetch and the staging: measured to pay only up to about 128 workgroups
     parts = parts < 1 ? 1 : parts > tiles ? tiles : parts;
-    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(wgs, parts), dim3(RESC_THREADS), 0, s, a, B, spw);
+    hipLaunchKernelGGL(resident_conv_kernel<C>, dim3(wgs, parts), dim3(64 * waves), 0, s, a, B, spw);
 }
 
 template <class F>
@@ -193,9 +193,10 @@ void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const
     // policy/value and action-value heads: the caller launches pv_head_kernel on the fc partial sums
 }
 
-// Convolutions of geometry G as gathered contractions (three products; conv1's pixel operand is exact: two)
+// Forward pass of a padded geometry G: the sample-resident kernels instantiated for its map sizes (three
+// products; conv1's pixel operand is exact: two)
 template <class G>
-void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+void forward_padded(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                      float *z_out, int zstride, bool masks, hipStream_t s) {
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
@@ -206,10 +207,10 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
                            w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     {
-        Conv2FwdG<G> p;
-        p.in = a1; p.lo_off = a1l - a1; p.M = B * G::P2; p.w = w.w2; p.w_lo = w.w2l; p.bias = w.b2;
-        p.out = a2; p.out_lo = a2l; p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
-        launch_nt_split("conv2_fwd", p, p.M, 1, 1, s);
+        typename ResConv2FwdGeo<G>::Args p;
+        p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
+        p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
+        launch_resident<ResConv2FwdGeo<G>>("conv2_fwd", p, B, s);
     }
     {
         typename ResConv3FwdGeo<G>::Args p;
@@ -227,7 +228,7 @@ void forward_generic(const Dims &d, const Packed &w, const uint8_t *obs, int B, 
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                       float *z_out, int zstride, bool masks, hipStream_t s) {
     if (d.geom == ARN_GEOM_PAPER) {
-        forward_generic<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
+        forward_padded<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
         return;
     }
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
@@ -339,7 +340,7 @@ void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *w
 
 // The same for geometry G: the same kernels, instantiated for its map sizes and padding.
 template <class G>
-void backward_trunk_generic(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+void backward_trunk_padded(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                             const ParamOffsets &po, const Splits &sp, float *dW, Fork &fk) {
     hipStream_t s = fk.s, s2 = fk.s2;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
@@ -686,7 +687,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         launch_nt("head_dgrad", p, B, HID / HeadDgrad::BN, 1, s);
     }
     fk();   // d(pre_fc)
-    if (d.geom == ARN_GEOM_PAPER) backward_trunk_generic<GeoPaper>(w, batch->obs, B, ws, o, po, sp, dW, fk);
+    if (d.geom == ARN_GEOM_PAPER) backward_trunk_padded<GeoPaper>(w, batch->obs, B, ws, o, po, sp, dW, fk);
     else backward_trunk_resident(w, batch->obs, B, ws, o, po, sp, dW, fk);
     if (ss) {   // join: the caller's stream continues only after the side stream's work
         (void)hipEventRecord(ss->join, s2);

@@ -64,7 +64,6 @@ namespace arn {
 // Threads per workgroup of the sample-resident kernels.  resident_conv_kernel uses four wavefronts
 // (one per SIMD); each keeps its share of the weights in registers.
 constexpr int RES_THREADS = 512;    // conv1 forward
-constexpr int RESC_THREADS = 256;   // resident_conv_kernel
 
 // true if base_off advances by the pixel stride (mod 256 bytes) between all consecutive rows of a sample group
 template <class C>
@@ -79,8 +78,23 @@ constexpr bool layout_is_uniform() {
     return true;
 }
 
+// Configurations with a static member WAVES = 8 run eight wavefronts per workgroup and one workgroup per CU
+// (for images too large for two workgroups to share the LDS): wavefronts w and w + 4 own the same channel
+// group and take alternate position tiles.
+template <class C, class = void>
+struct ResWaves {
+    static constexpr int value = 4;
+};
 template <class C>
-__global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const typename C::Args a, int B, int spw) {
+struct ResWaves<C, decltype((void)C::WAVES)> {
+    static constexpr int value = C::WAVES;
+};
+
+template <class C>
+__global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 2 : 1) void resident_conv_kernel(
+    const typename C::Args a, int B, int spw) {
+    constexpr int RESC_THREADS = 64 * ResWaves<C>::value;
+    constexpr int WPARTS = ResWaves<C>::value / 4;       // wavefronts that share a channel group
     constexpr int CI = C::CI, PS = CI * 2 + 32, NCH = CI / 8;   // pixel stride = 32 mod 64 bytes: conflict-free 16-position x 4-chunk reads (measured)
     constexpr int IMG = C::IMG;                          // bytes of one sample's LDS image (rows padded, see below)
     constexpr int PARTS = C::SPLIT ? 2 : 1;              // hi (+ lo)
@@ -108,13 +122,14 @@ __global__ __launch_bounds__(RESC_THREADS, 2) void resident_conv_kernel(const ty
     uint8_t *const lds_mask = reinterpret_cast<uint8_t *>(lds_mask8);
     char *const lds_b = reinterpret_cast<char *>(lds);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3;
     const int li = lane & 15, lg = lane >> 4;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
     // small batches: gridDim.y workgroups share a sample group, each taking every gridDim.y-th position tile
-    const int t_first = blockIdx.y, t_step = gridDim.y;
+    // (and the wavefronts that share a channel group split those again)
+    const int t_first = blockIdx.y * WPARTS + (tid >> 8), t_step = gridDim.y * WPARTS;
 
     // weights of this wavefront's channels, all k, as A-operand fragments (loaded below, after the
     // first image loads have been issued, so that staging does not wait for them)
@@ -567,6 +582,58 @@ struct ResConv2Dgrad {
 // computed from the map sizes.
 
 constexpr int pad_to_step(int have, int want) { return (((want - have) % 256) + 256) % 256; }
+
+// conv2 forward (4x4, stride 2, padding PAD2 > 0): act1 [H1][W1][32] with a zero border, act2 [H2][W2][64];
+// three products.  As in ResConv2Fwd the bordered image keeps even and odd columns in separate planes (so that
+// the stride-2 windows of neighbouring positions are neighbouring LDS pixels) and two image rows form one
+// block of PAIR pixels; PAIR is the next size for which the first position of an output row follows the last
+// of the row before at one pixel stride modulo 256 bytes.  The image (hi and lo) fills most of a CU's LDS, so
+// one workgroup of eight wavefronts runs per CU.
+template <class Geo>
+struct ResConv2FwdGeo {
+    static_assert(Geo::PAD2 > 0, "the unpadded case has a layout of its own (ResConv2Fwd)");
+    static constexpr int PADH = Geo::H1 + 2 * Geo::PAD2, PADW = Geo::W1 + 2 * Geo::PAD2;
+    static constexpr int EVENW = (PADW + 1) / 2;                       // pixels in the even-column plane of a row
+    static constexpr int CI = C1, SRC_PIX = Geo::P1, P = Geo::P2, CO = C2, K = KW2, G = 1, WAVES = 8;
+    static constexpr bool SPLIT = true, ZERO_FILL = true, PIPE = false;
+    static constexpr int MASK_ELEMS = 0, NBUF = 1;
+    static constexpr int PSB = C1 * 2 + 32;
+    static constexpr int pair_pixels() {
+        int p = 2 * PADW;
+        while (((p - Geo::W2) * PSB) % 256 != 0) ++p;
+        return p;
+    }
+    static constexpr int PAIR = pair_pixels(), IMG = ((PADH + 1) / 2) * PAIR * PSB;
+    __device__ static constexpr int plane_pix(int y, int x) {
+        return (y >> 1) * PAIR + (y & 1) * PADW + (x & 1) * EVENW + (x >> 1);
+    }
+    __device__ static constexpr int dst_off(int p) {
+        return plane_pix(p / Geo::W1 + Geo::PAD2, p % Geo::W1 + Geo::PAD2) * PSB;
+    }
+    __device__ static constexpr int base_off(int pos) { return plane_pix(2 * (pos / Geo::W2), 2 * (pos % Geo::W2)) * PSB; }
+    __device__ static constexpr int tap_off(int t) { return plane_pix(t / K2, t % K2) * PSB; }
+    struct Args {
+        const __bf16 *in, *in_lo, *w, *w_lo;
+        const uint8_t *mask;
+        const float *bias;
+        __bf16 *out, *out_lo;
+        uint8_t *mask_out;     // sign bits of the output for the backward pass, or null
+        typedef float4 Lane;
+        __device__ __forceinline__ Lane lane(int n) const { return *reinterpret_cast<const float4 *>(bias + n); }
+        __device__ __forceinline__ void store(int s, int, int pos, int n, f32x4 v, const Lane &b,
+                                              const uint8_t *) const {
+            const float r0 = fmaxf(v[0] + b.x, 0.f), r1 = fmaxf(v[1] + b.y, 0.f), r2 = fmaxf(v[2] + b.z, 0.f),
+                        r3 = fmaxf(v[3] + b.w, 0.f);
+            const size_t at = ((size_t)s * Geo::P2 + pos) * C2 + n;
+            store_bf16x4_split(out, out_lo, at, r0, r1, r2, r3);
+            if (mask_out) {
+                const int lg = (n >> 2) & 3;
+                const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);
+                if (lg == 0) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
+            }
+        }
+    };
+};
 
 // conv3 forward (3x3, stride 1, padding PAD3 > 0): act2 [H2][W2][64] with a zero border of PAD3 pixels,
 // act3 [H3][W3][64]; three products.
