@@ -193,66 +193,62 @@ void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const
     // policy/value and action-value heads: the caller launches pv_head_kernel on the fc partial sums
 }
 
-// Forward pass of a padded geometry G: the sample-resident kernels instantiated for its map sizes (three
-// products; conv1's pixel operand is exact: two)
+// Which configurations of the sample-resident kernels a geometry uses: the 84x84 network has hand-laid LDS
+// images, any other geometry the ones whose padding is computed from its map sizes.
 template <class G>
-void forward_padded(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                     float *z_out, int zstride, bool masks, hipStream_t s) {
+struct ConvConfigs {
+    typedef ResConv2FwdGeo<G> Fwd2;
+    typedef ResConv3FwdGeo<G> Fwd3;
+    typedef ResConv3DgradGeo<G> Dgrad3;
+    typedef ResConv2DgradGeo<G> Dgrad2;
+    static int conv1_parts(int) { return 1; }
+};
+template <>
+struct ConvConfigs<Geo84> {
+    typedef ResConv2Fwd Fwd2;
+    typedef ResConv3Fwd Fwd3;
+    typedef ResConv3Dgrad Dgrad3;
+    typedef ResConv2Dgrad Dgrad2;
+    // few samples: three workgroups share one (one workgroup fits per CU)
+    static int conv1_parts(int B) { return 3 * B <= 256 ? 3 : 1; }
+};
+
+// Forward pass for geometry G in three-product bf16 precision (conv1's pixel operand is exact: two products).
+template <class G>
+void forward_trunk(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                   float *z_out, int zstride, bool masks, hipStream_t s) {
+    typedef ConvConfigs<G> Cfg;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
     {
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
-        hipLaunchKernelGGL(conv1_fwd_resident_kernel<G>, dim3(cdiv(B, spw), 1), dim3(RES_THREADS), 0, s, obs, w.w1,
-                           w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
+        hipLaunchKernelGGL(conv1_fwd_resident_kernel<G>, dim3(cdiv(B, spw), Cfg::conv1_parts(B)), dim3(RES_THREADS), 0, s,
+                           obs, w.w1, w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     {
-        typename ResConv2FwdGeo<G>::Args p;
+        typename Cfg::Fwd2::Args p;
         p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
         p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
-        launch_resident<ResConv2FwdGeo<G>>("conv2_fwd", p, B, s);
+        launch_resident<typename Cfg::Fwd2>("conv2_fwd", p, B, s);
     }
     {
-        typename ResConv3FwdGeo<G>::Args p;
+        typename Cfg::Fwd3::Args p;
         p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
         p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
-        launch_resident<ResConv3FwdGeo<G>>("conv3_fwd", p, B, s);
+        launch_resident<typename Cfg::Fwd3>("conv3_fwd", p, B, s);
     }
     fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, zstride, s);
 }
 
-// trunk + heads forward in three-product bf16 precision.  C51: z_out = atom logits, rows of zstride floats
-// (NH = dense, or NHP for the library's own buffers).
-// PV: stops after the fc GEMM, whose fp32 partial sums (o.fcp) the fused head kernel consumes.
-// masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on the online weights).
+// trunk + heads forward.  C51: z_out = atom logits, rows of zstride floats (NH = dense, or NHP for the
+// library's own buffers).  PV, Q, DUEL: stops after the fc GEMM, whose fp32 partial sums (o.fcp) the fused head
+// kernel consumes.  masks: also write the ReLU sign bits of act1..3 for the backward pass (training forward on
+// the online weights).
 void forward_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
                       float *z_out, int zstride, bool masks, hipStream_t s) {
-    if (d.geom == ARN_GEOM_PAPER) {
-        forward_padded<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
-        return;
-    }
-    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
-    __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
-    {
-        ProfScope ps("conv1_fwd", s);
-        const int spw = resident_spw(B, 256);
-        const int parts = 3 * B <= 256 ? 3 : 1;   // few samples: three workgroups share one (one workgroup fits per CU)
-        hipLaunchKernelGGL(conv1_fwd_resident_kernel<Geo84>, dim3(cdiv(B, spw), parts), dim3(RES_THREADS), 0, s, obs, w.w1,
-                           w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
-    }
-    {
-        ResConv2Fwd::Args p;
-        p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
-        p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
-        launch_resident<ResConv2Fwd>("conv2_fwd", p, B, s);
-    }
-    {
-        ResConv3Fwd::Args p;
-        p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
-        p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
-        launch_resident<ResConv3Fwd>("conv3_fwd", p, B, s);
-    }
-    fc_and_head_launches<FEAT>(d, w, B, ws, o, z_out, zstride, s);
+    if (d.geom == ARN_GEOM_PAPER) forward_trunk<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
+    else forward_trunk<Geo84>(d, w, obs, B, ws, o, z_out, zstride, masks, s);
 }
 
 // Events that let work queued on the side stream see everything queued on the caller's stream so far.
@@ -268,84 +264,20 @@ struct Fork {
     }
 };
 
-// Backward pass below d(pre_fc), 84x84 network: sample-resident kernels.  The input-gradient chain
-// (fc -> conv3 -> conv2, then conv1's weight gradient) runs on the caller's stream; every other weight
-// gradient and its reduction runs on the side stream as soon as the gradient it consumes exists.
-void backward_trunk_resident(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                             const ParamOffsets &po, const Splits &sp, float *dW, Fork &fk) {
-    hipStream_t s = fk.s, s2 = fk.s2;
-    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
-    __bf16 *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
-    __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
-    {
-        FcWgrad p;
-        p.in = a3; p.M = B; p.dy = dph;
-        float *part = (float *)(ws + o.pwfc);
-        launch_tn("fc_wgrad", p, part, B, HID, FEAT, sp.fc, s2);
-        {
-            ProfScope ps("fc_reduce", s2);
-            hipLaunchKernelGGL((fc_reduce_kernel<FEAT, P3>), dim3(HID + 1), dim3(256), 0, s2, part, dW, (long)po.wfc, (long)po.bfc,
-                               sp.fc);
-        }
-    }
-    {
-        FcDgrad p;
-        p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
-        launch_nt("fc_dgrad", p, B, FEAT / FcDgrad::BN, 1, s);
-    }
-    fk();   // d(pre3)
-    {
-        float *part = (float *)(ws + o.pw3);
-        {
-            ProfScope ps("conv3_wgrad", s2);
-            const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, H2, H2, K3, S3, 0, H3, H3, C3, CONV3_WG_G, 2>), dim3(sp.c3),
-                               dim3(CW_THREADS), 0, s2, a2, dp3, part, B, resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
-        }
-        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
-    }
-    {
-        ResConv3Dgrad::Args p;
-        p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
-        launch_resident<ResConv3Dgrad>("conv3_dgrad", p, B, s);
-    }
-    fk();   // d(pre2)
-    {
-        float *part = (float *)(ws + o.pw2);
-        {
-            ProfScope ps("conv2_wgrad", s2);
-            const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, H1, H1, K2, S2, 0, H2, H2, C2, CONV2_WG_G, 2>), dim3(sp.c2),
-                               dim3(CW_THREADS), 0, s2, a1, dp2, part, B, resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
-        }
-        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
-    }
-    {
-        ResConv2Dgrad::Args p;
-        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
-        launch_resident<ResConv2Dgrad>("conv2_dgrad", p, B, s);
-    }
-    // conv1: weight gradient only (the input is data)
-    {
-        float *part = (float *)(ws + o.pw1);
-        {
-            ProfScope ps("conv1_wgrad", s);
-            hipLaunchKernelGGL(conv1_wgrad_resident_kernel<Geo84>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part, B,
-                               resident_spw(B, 256));
-        }
-        // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
-        launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
-    }
-}
-
-// The same for geometry G: the same kernels, instantiated for its map sizes and padding.
+// Backward pass below d(pre_fc) for geometry G.  Everything that needs only d(pre_fc) -- the fc weight gradient
+// and its reduction, next to the head's -- runs on the side stream; the chain fc dgrad -> conv3 dgrad ->
+// conv2 dgrad, the convolutions' weight gradients and one reduction kernel for all three of them stay on the
+// caller's stream.  (Every cross-stream event costs the waiting and the recording stream about 6 us, and two
+// heavy kernels side by side mostly share the memory system, so more overlap than this measured slower.)
 template <class G>
-void backward_trunk_padded(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
-                            const ParamOffsets &po, const Splits &sp, float *dW, Fork &fk) {
+void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o, const ParamOffsets &po,
+                    const Splits &sp, float *dW, Fork &fk) {
+    typedef ConvConfigs<G> Cfg;
     hipStream_t s = fk.s, s2 = fk.s2;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
     __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
+    float *part1 = (float *)(ws + o.pw1), *part2 = (float *)(ws + o.pw2), *part3 = (float *)(ws + o.pw3);
     {
         typedef Wgrad<DenseGather<G::FEAT>, 128, 64, 2, HID, G::FEAT> FcW;
         FcW p;
@@ -361,50 +293,51 @@ void backward_trunk_padded(const Packed &w, const uint8_t *obs, int B, char *ws,
         p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
         launch_nt("fc_dgrad", p, B, G::FEAT / 64, 1, s);
     }
-    fk();   // d(pre3)
     {
-        float *part = (float *)(ws + o.pw3);
-        {
-            ProfScope ps("conv3_wgrad", s2);
-            const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, G::H2, G::W2, K3, S3, G::PAD3, G::H3, G::W3, C3, CONV3_WG_G, 2>),
-                               dim3(sp.c3), dim3(CW_THREADS), 0, s2, a2, dp3, part, B,
-                               resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
-        }
-        launch_reduce("conv3_reduce", UnmapConv<C2, K3, C3>{(long)po.w3, (long)po.b3}, part, dW, (long)C3 * KW3, C3, sp.c3, 1.f, s2);
-    }
-    {
-        typename ResConv3DgradGeo<G>::Args p;
+        typename Cfg::Dgrad3::Args p;
         p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
-        launch_resident<ResConv3DgradGeo<G>>("conv3_dgrad", p, B, s);
-    }
-    fk();   // d(pre2)
-    {
-        float *part = (float *)(ws + o.pw2);
-        {
-            ProfScope ps("conv2_wgrad", s2);
-            const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
-            hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, G::H1, G::W1, K2, S2, G::PAD2, G::H2, G::W2, C2, CONV2_WG_G, 2>),
-                               dim3(sp.c2), dim3(CW_THREADS), 0, s2, a1, dp2, part, B,
-                               resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
-        }
-        launch_reduce("conv2_reduce", UnmapConv<C1, K2, C2>{(long)po.w2, (long)po.b2}, part, dW, (long)C2 * KW2, C2, sp.c2, 1.f, s2);
+        launch_resident<typename Cfg::Dgrad3>("conv3_dgrad", p, B, s);
     }
     {
-        typename ResConv2DgradGeo<G>::Args p;
+        typename Cfg::Dgrad2::Args p;
         p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
-        launch_resident<ResConv2DgradGeo<G>>("conv2_dgrad", p, B, s);
+        launch_resident<typename Cfg::Dgrad2>("conv2_dgrad", p, B, s);
     }
-    // conv1: weight gradient only (the input is data)
+    {   // conv1: weight gradient only (the input is data)
+        ProfScope ps("conv1_wgrad", s);
+        hipLaunchKernelGGL(conv1_wgrad_resident_kernel<G>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part1, B,
+                           resident_spw(B, 256));
+    }
     {
-        float *part = (float *)(ws + o.pw1);
-        {
-            ProfScope ps("conv1_wgrad", s);
-            hipLaunchKernelGGL(conv1_wgrad_resident_kernel<G>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part, B,
-                               resident_spw(B, 256));
+        ProfScope ps("conv2_wgrad", s);
+        const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
+        hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, G::H1, G::W1, K2, S2, G::PAD2, G::H2, G::W2, C2, CONV2_WG_G, 2>),
+                           dim3(sp.c2), dim3(CW_THREADS), 0, s, a1, dp2, part2, B,
+                           resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
+    }
+    {
+        ProfScope ps("conv3_wgrad", s);
+        const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
+        hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, G::H2, G::W2, K3, S3, G::PAD3, G::H3, G::W3, C3, CONV3_WG_G, 2>),
+                           dim3(sp.c3), dim3(CW_THREADS), 0, s, a2, dp3, part3, B,
+                           resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
+    }
+    {
+        // one launch adds the partials of all three convolutions (x = u8/255: conv1's pixel scale comes out of
+        // the contraction and is applied here; bias gradients have no such factor)
+        ProfScope ps("conv_reduce", s);
+        ConvReducePlan pl;
+        pl.seg[0] = make_reduce_seg(part1, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f);
+        pl.seg[1] = make_reduce_seg(part2, (long)C2 * KW2, C2, sp.c2, 1.f);
+        pl.seg[2] = make_reduce_seg(part3, (long)C3 * KW3, C3, sp.c3, 1.f);
+        pl.w1 = (long)po.w1; pl.b1 = (long)po.b1; pl.w2 = (long)po.w2; pl.b2 = (long)po.b2;
+        pl.w3 = (long)po.w3; pl.b3 = (long)po.b3;
+        int blk = 0;
+        for (int k = 0; k < 3; ++k) {
+            pl.seg[k].first_block = blk;
+            blk += (int)cdiv(pl.seg[k].block, 256 / pl.seg[k].ng);
         }
-        // x = u8/255: the pixel scale comes out of the contraction; the bias gradient has no such factor
-        launch_reduce("conv1_reduce", UnmapConv1{(long)po.w1, (long)po.b1}, part, dW, (long)C1 * KW1, C1, sp.c1, 1.f / 255.f, s);
+        hipLaunchKernelGGL(conv_reduce_kernel, dim3(blk), dim3(256), 0, s, pl, dW);
     }
 }
 
@@ -686,9 +619,9 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         p.in = dz; p.M = B; p.K = d.NHP; p.w = w.whd; p.h = h; p.out = dph;
         launch_nt("head_dgrad", p, B, HID / HeadDgrad::BN, 1, s);
     }
-    fk();   // d(pre_fc)
-    if (d.geom == ARN_GEOM_PAPER) backward_trunk_padded<GeoPaper>(w, batch->obs, B, ws, o, po, sp, dW, fk);
-    else backward_trunk_resident(w, batch->obs, B, ws, o, po, sp, dW, fk);
+    if (d.head == ARN_HEAD_C51) fk();   // d(pre_fc) comes from the head's input-gradient GEMM above
+    if (d.geom == ARN_GEOM_PAPER) backward_trunk<GeoPaper>(w, batch->obs, B, ws, o, po, sp, dW, fk);
+    else backward_trunk<Geo84>(w, batch->obs, B, ws, o, po, sp, dW, fk);
     if (ss) {   // join: the caller's stream continues only after the side stream's work
         (void)hipEventRecord(ss->join, s2);
         (void)hipStreamWaitEvent(s, ss->join, 0);

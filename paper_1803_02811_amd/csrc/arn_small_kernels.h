@@ -139,6 +139,26 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(F f, const float *
         dW[dst] = i < wcount ? t * wscale : t;
     }
 }
+// The same reduction for the three convolutions in one launch: a block finds the layer its index falls in
+// (uniform per block) and applies that layer's index map.
+struct ReduceSeg {
+    const float *part;
+    long block, wcount;     // entries per partial ([N*K' + N]); how many of them are weights
+    int splits, ng, first_block;
+    float wscale;
+};
+inline ReduceSeg make_reduce_seg(const float *part, long wcount, long bcount, int splits, float wscale) {
+    ReduceSeg g;
+    g.part = part; g.block = wcount + bcount; g.wcount = wcount; g.splits = splits; g.wscale = wscale;
+    g.ng = splits >= 64 ? 8 : splits >= 16 ? 4 : splits >= 4 ? 2 : 1;
+    g.first_block = 0;
+    return g;
+}
+struct ConvReducePlan {
+    ReduceSeg seg[3];       // conv1, conv2, conv3
+    long w1, b1, w2, b2, w3, b3;
+};
+
 // The fc layer's partials are [n][pos*64 + c] while the canonical weight is [n][c*P3 + pos]: one workgroup
 // per output row n adds the splits with contiguous reads, permutes the row in LDS (stride 49 words at
 // 84x84: no bank conflicts) and writes it out contiguously.  Workgroup HID handles the bias gradient.
@@ -180,6 +200,39 @@ struct UnmapConv1 {
     long woff, boff;
     __device__ long operator()(long i) const { return i >= C1 * KW1 ? boff + (i - C1 * KW1) : woff + i; }
 };
+__global__ __launch_bounds__(256) void conv_reduce_kernel(ConvReducePlan pl, float *__restrict__ dW) {
+    __shared__ float red[256];
+    const int k = (int)blockIdx.x >= pl.seg[2].first_block ? 2 : ((int)blockIdx.x >= pl.seg[1].first_block ? 1 : 0);
+    // segment fields selected without dynamic indexing of the argument block
+    const ReduceSeg g = k == 2 ? pl.seg[2] : (k == 1 ? pl.seg[1] : pl.seg[0]);
+    const int opb = 256 / g.ng;
+    const int o = threadIdx.x % opb, q = threadIdx.x / opb;
+    const long i = (long)((int)blockIdx.x - g.first_block) * opb + o;
+    const int per = (g.splits + g.ng - 1) / g.ng;
+    const int k0 = q * per, k1 = k0 + per < g.splits ? k0 + per : g.splits;
+    float s = 0.f;
+    if (i < g.block) {
+        int z = k0;
+        for (; z + 8 <= k1; z += 8) {     // eight independent loads in flight, added in split order
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = g.part[(size_t)(z + j) * g.block + i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += v[j];
+        }
+        for (; z < k1; ++z) s += g.part[(size_t)z * g.block + i];
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (q == 0 && i < g.block) {
+        const long dst = k == 2 ? UnmapConv<C2, K3, C3>{pl.w3, pl.b3}(i)
+                                : (k == 1 ? UnmapConv<C1, K2, C2>{pl.w2, pl.b2}(i) : UnmapConv1{pl.w1, pl.b1}(i));
+        float t = red[o];
+        for (int j = 1; j < g.ng; ++j) t += red[j * opb + o];
+        dW[dst] = i < g.wcount ? t * g.wscale : t;
+    }
+}
+
 struct UnmapHead {
     MapHeadRow h;
     int NHP;
