@@ -136,6 +136,23 @@ def test_full_batch_gradient_is_mean_of_shards(gu):
     assert abs(lf[0] - 0.5 * (halves[0][1][0] + halves[1][1][0])) < 1e-5
 
 
+@pytest.mark.parametrize("geometry", ["84", "paper"])
+def test_outputs_do_not_depend_on_the_batch_they_are_in(gu, geometry):
+    """Small batches deal a sample's position tiles to several workgroups and cut the fc contraction
+    differently; a sample's outputs must not change with the batch it is computed in (beyond fp32 rounding
+    of the differently ordered fc sums)."""
+    A = 18
+    frame = wl.FRAME if geometry == "84" else wl.PAPER_FRAME
+    flat = wl.he_normal_params(A, "pv", 2002, bias_std=0.1, fc_inputs=wl.FC_INPUTS[frame])
+    obs = wl.rect_frames(300, 1002, frame=frame)
+    net = gu.GpuNet(A, "pv", flat, geometry=geometry)
+    full = net.forward(obs)
+    for B in (1, 5, 16, 64, 129):
+        part = net.forward(obs[:B])
+        np.testing.assert_allclose(part["logits"], full["logits"][:B], atol=2e-5, rtol=0)
+        np.testing.assert_allclose(part["value"], full["value"][:B], atol=2e-5, rtol=0)
+
+
 # ---------------------------------------------------------------------------
 # Full workload sizes, in the launch configuration the benchmark times.
 # The oracle needs a few seconds per case on the GPU box's host cores.
