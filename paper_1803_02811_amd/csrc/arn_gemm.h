@@ -1,17 +1,17 @@
 // MFMA building blocks for gfx950: two workgroup-level contraction kernels that
-// every layer of the network is an instance of.
+// the dense layers (fc, categorical head) are instances of.
 //
 //   gemm_nt_kernel : out[m][n] = sum_k act(m,k) * W[n][k]
-//       forward layers and input gradients.  `act` is gathered on the fly
-//       (implicit im2col); W is a packed bf16 matrix with k contiguous.
+//       forward layers and input gradients.  `act` is gathered on the fly by the
+//       problem struct; W is a packed bf16 matrix with k contiguous.
 //   gemm_tn_kernel : out[n][k] = sum_m dY[m][n] * act(m,k)
 //       weight gradients: the contraction runs over the batch/position index,
 //       which is the slow index of both operands in memory, so fragments are
 //       taken from LDS with the transposing read ds_read_b64_tr_b16.
 //
-// Both use v_mfma_f32_32x32x16_bf16 (fp32 accumulate), 256 threads = 4
-// wavefronts of 64 lanes, and 64-element k-tiles staged through LDS (two stages
-// in the NT kernel) with a register prefetch of the tile after next.
+// Both use v_mfma_f32_32x32x16_bf16 (fp32 accumulate), 4 (or, for the NT kernel, 8)
+// wavefronts of 64 lanes, and 64-element k-tiles staged through LDS (optionally two
+// stages in the NT kernel) with a register prefetch of the tile after next.
 //
 // MFMA operand layout used throughout (checked on hardware):
 //   A (32 x 16): lane l holds row l%32,  k = 8*(l/32) .. +7

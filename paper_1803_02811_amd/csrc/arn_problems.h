@@ -5,7 +5,9 @@
 //
 // Activations are NHWC bf16: act1 [B,20,20,32], act2 [B,9,9,64], act3 [B,7,7,64]
 // (= the fc input with index (y*7+x)*64 + c; the packed fc weights are permuted
-// to match), h [B,512].  Gradients at pre-activations use the same layouts.
+// to match), h [B,512]; with the 104x80 geometry [B,25,19,32], [B,12,9,64], [B,12,9,64].
+// Gradients at pre-activations use the same layouts.  The fc problems are templates on
+// the fc input size (3136 or 6912).
 #pragma once
 #include "arn_gemm.h"
 #include "arn_layout.h"
