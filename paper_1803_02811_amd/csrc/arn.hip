@@ -525,10 +525,8 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     const ParamOffsets po = param_offsets(d);
     const Splits sp = make_splits(d, B);
     float *z = (float *)(ws + o.z);
-    __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *h = (__bf16 *)(ws + o.h);
-    __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
-    __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
+    __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph);
     float *lossp = (float *)(ws + o.lossp);
     const int lblocks = loss_blocks(d, B);
 
