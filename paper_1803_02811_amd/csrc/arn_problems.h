@@ -151,7 +151,7 @@ struct HeadDgrad : DenseGatherRt {
 // d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][FEAT], NHWC index
 template <int FEAT_>
 struct FcDgradT : DenseGather<HID> {
-    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 2, FEAT = FEAT_;
+    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 1, FEAT = FEAT_;
     const __bf16 *w;          // [FEAT][512]
     const uint8_t *maskbits;  // sign bits of act3, bit e&7 of byte e>>3 for element e = m*FEAT + n
     __bf16 *out;
