@@ -41,6 +41,10 @@ __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const
     static_assert(OBS_BYTES % 16 == 0 && (P1 * C1 * 2) % 16 == 0, "samples are copied in 16-byte words");
     __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][IN_H][IN_W]
     __shared__ u32x4 s_dy[RPAD * C1 * 2 / 16];    // bf16 [RPAD][32]
+    // With 80 positions (five k-steps) a whole number of output rows, the compiler turns the row/column
+    // arithmetic of the unrolled k loop into constant increments; otherwise the window origins are tabulated.
+    constexpr bool TABLE = 80 % W1 != 0;
+    __shared__ int s_win[TABLE ? RPAD : 1];       // byte offset of the window origin of output position m in s_img
     static_assert((NT / 4) * C1 * 4 <= RPAD * C1 * 2, "bias-gradient scratch");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -48,6 +52,13 @@ __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if constexpr (RPAD > P1)
         for (int i = DY_U4 + tid; i < RPAD * C1 * 2 / 16; i += NT) s_dy[i] = zero_u4();
+    auto window = [&](int m) __attribute__((always_inline)) {
+        const int mm = RPAD > P1 && m >= P1 ? P1 - 1 : m;   // rows past the last position (their dY is zero) take its window
+        const int oy = mm / W1, ox = mm - oy * W1;
+        return (S1 * oy * IN_W + S1 * ox) * 2;
+    };
+    if constexpr (TABLE)
+        for (int m = tid; m < RPAD; m += NT) s_win[m] = window(m);
 
     u32x4 rimg[NI], rdy[ND];
     auto gload = [&](int s) __attribute__((always_inline)) {
@@ -109,10 +120,7 @@ __global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const
 #pragma unroll 5
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const int ma = 16 * ks + row_in_step, mb = ma + 4;
-            // rows past the last position (their dY is zero) take the last position's window
-            const int wa = RPAD > P1 && ma >= P1 ? P1 - 1 : ma, wb = RPAD > P1 && mb >= P1 ? P1 - 1 : mb;
-            const int oya = wa / W1, oxa = wa - oya * W1, oyb = wb / W1, oxb = wb - oyb * W1;
-            const int pa = (S1 * oya * IN_W + S1 * oxa) * 2, pb = (S1 * oyb * IN_W + S1 * oxb) * 2;
+            const int pa = TABLE ? s_win[ma] : window(ma), pb = TABLE ? s_win[mb] : window(mb);
             const bf16x8 fy = tr_pair(dyl, ma * (C1 * 2) + ycol_off, mb * (C1 * 2) + ycol_off);
             const bf16x8 fx = tr_pair(img, pa + xoff, pb + xoff);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc, 0, 0, 0);
@@ -168,13 +176,20 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
 
     __shared__ u32x4 s_x[G * PIXP * PS / 16];
     __shared__ u32x4 s_dy[RPAD * YS / 16];
-    static_assert((G * PIXP * PS + RPAD * YS) <= 160 * 1024, "LDS budget");
+    __shared__ int s_win[RPAD];     // byte offset of the window origin of contraction row m in s_x
+    static_assert((G * PIXP * PS + RPAD * YS + RPAD * 4) <= 160 * 1024, "LDS budget");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wy = wave % WAVES_Y, wx = wave / WAVES_Y;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
 
+    // window origins do not depend on the sample: tabulated once instead of two divisions per row and k-step
+    for (int m = tid; m < RPAD; m += NT) {
+        const int mm = m < R ? m : R - 1;                    // padded rows: any in-range window (their dY is zero)
+        const int g = mm / P, rem = mm - g * P, oy = rem / WOUT, ox = rem - oy * WOUT;
+        s_win[m] = (g * PIXP + STRIDE * oy * WP + STRIDE * ox) * PS;
+    }
     // rows R..RPAD of dY stay zero for the whole kernel, and so does the border of the images
     for (int i = tid; i < (RPAD - R) * YS / 16; i += NT) s_dy[R * YS / 16 + i] = zero_u4();
     if constexpr (PAD > 0)
@@ -250,14 +265,7 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
 #pragma unroll 1
         for (int ks = 0; ks < KSTEPS; ++ks) {
             const int ma = 16 * ks + row_in_step, mb = ma + 4;
-            int base[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                int m = h ? mb : ma;
-                m = m < R ? m : R - 1;                       // padded rows: any in-range window (their dY is zero)
-                const int g = m / P, rem = m - g * P, oy = rem / WOUT, ox = rem - oy * WOUT;
-                base[h] = (g * PIXP + STRIDE * oy * WP + STRIDE * ox) * PS + col_lane;   // window origin in the bordered image
-            }
+            const int base[2] = {s_win[ma] + col_lane, s_win[mb] + col_lane};   // window origins in the bordered image
             bf16x8 fy[TY];
 #pragma unroll
             for (int a = 0; a < TY; ++a) {
