@@ -68,6 +68,41 @@ def test_forward_first_layer_against_explicit_window():
     assert np.isclose(c["act1"][0, co, oy, ox], max(want, 0.0), atol=1e-12)
 
 
+def test_paper_geometry_forward_against_explicit_windows():
+    """Appendix "Atari Frame Processing": 104x80 frames, no padding on the first layer, padding 1 on the second
+    and third: the feature maps are 25x19, 12x9, 12x9 and border outputs see zeros outside the map.  One
+    corner and one interior output of conv2 and conv3 and one hidden unit are rebuilt with explicit loops."""
+    spec = orc.NetSpec(6, "pv", geometry=orc.PAPER_104x80)
+    fc_in = wl.FC_INPUTS[wl.PAPER_FRAME]
+    params = orc.unflatten(wl.he_normal_params(6, "pv", seed=5, bias_std=0.1, fc_inputs=fc_in), spec)
+    obs = wl.uniform_frames(1, seed=6, frame=wl.PAPER_FRAME)
+    c = orc.forward(params, obs, spec)
+    assert c["act1"].shape == (1, 32, 25, 19) and c["act2"].shape == (1, 64, 12, 9) and c["act3"].shape == (1, 64, 12, 9)
+    assert c["h"].shape == (1, 512) and params["fc.W"].shape == (512, 6912)
+
+    def window_sum(inp, W, b, k, stride, pad, co, oy, ox):
+        acc = b[co]
+        for ci in range(inp.shape[0]):
+            for ky in range(k):
+                for kx in range(k):
+                    y, x = oy * stride - pad + ky, ox * stride - pad + kx
+                    if 0 <= y < inp.shape[1] and 0 <= x < inp.shape[2]:
+                        acc += W[co, ci, ky, kx] * inp[ci, y, x]
+        return acc
+
+    for (oy, ox) in [(0, 0), (11, 8), (5, 4)]:
+        want2 = window_sum(c["act1"][0], params["conv2.W"], params["conv2.b"], 4, 2, 1, 7, oy, ox)
+        assert np.isclose(c["pre2"][0, 7, oy, ox], want2, atol=1e-12)
+        want3 = window_sum(c["act2"][0], params["conv3.W"], params["conv3.b"], 3, 1, 1, 9, oy, ox)
+        assert np.isclose(c["pre3"][0, 9, oy, ox], want3, atol=1e-12)
+    acc = params["fc.b"][3]
+    for ch in range(64):
+        for y in range(12):
+            for x in range(9):
+                acc += params["fc.W"][3, ch * 108 + y * 9 + x] * c["act3"][0, ch, y, x]
+    assert np.isclose(c["pre_fc"][0, 3], acc, atol=1e-12)
+
+
 def _total_loss(flat, spec, batch, kind, tflat=None):
     params = orc.unflatten(flat, spec)
     c = orc.forward(params, batch["obs"], spec)
