@@ -4,7 +4,8 @@
 A step is one pass of the whole training hot path (forward, objective,
 backward, ordered gradient reduction) over one synthetic batch that is already
 resident in HBM: the A2C gradient step at B=2048 (256 envs x 8-step rollouts).
-Prints ONE JSON line; see the design doc for how each field is derived.
+Prints ONE JSON line: whole-step throughput, the roofline of the longest kernel (event-timed in this run, HBM
+traffic from the stored counter profile) and the CPU oracle's rate on a bounded sample.
 """
 import argparse
 import json
@@ -26,6 +27,7 @@ KERNEL_FLOPS = {  # per sample, by instrumented kernel name
     "fc_wgrad": 2 * MACS["fc"], "head_wgrad": 2 * MACS["head_pv"],
     "conv2_dgrad": 2 * MACS["conv2"], "conv3_dgrad": 2 * MACS["conv3"], "fc_dgrad": 2 * MACS["fc"],
     "head_dgrad": 2 * MACS["head_pv"],
+    "conv1_bwd": 2 * MACS["conv2"] + 2 * MACS["conv1"],   # conv2 input gradient + conv1 weight gradient, one kernel
 }
 # algorithmic HBM bytes per sample: every bf16 activation / gradient tensor written once and read once,
 # observations read as uint8 (weights and the flat gradient are per-launch constants, added below)
@@ -37,12 +39,13 @@ KERNEL_BYTES = {
     "fc_wgrad": ACT["a3"] + ACT["h"], "head_wgrad": ACT["h"] + ACT["z"],
     "conv2_dgrad": ACT["a2"] + 2 * ACT["a1"], "conv3_dgrad": ACT["a3"] + 2 * ACT["a2"],
     "fc_dgrad": ACT["h"] + 2 * ACT["a3"], "head_dgrad": ACT["z"] + 2 * ACT["h"],
+    "conv1_bwd": ACT["a2"] + ACT["obs"],                  # d(pre1) stays on chip
 }
 KERNEL_BYTES_PER_LAUNCH = {  # bf16 weights read (forward / input gradient) or fp32 gradient written (weight gradient)
     "conv1_fwd": 2 * 8192, "conv2_fwd": 2 * 32768, "conv3_fwd": 2 * 36864, "fc_fwd": 2 * 1605632, "head_fwd": 2 * 9728,
     "conv2_dgrad": 2 * 32768, "conv3_dgrad": 2 * 36864, "fc_dgrad": 2 * 1605632, "head_dgrad": 2 * 9728,
     "conv1_wgrad": 4 * 8192, "conv2_wgrad": 4 * 32768, "conv3_wgrad": 4 * 36864, "fc_wgrad": 4 * 1605632,
-    "head_wgrad": 4 * 9728,
+    "head_wgrad": 4 * 9728, "conv1_bwd": 2 * 32768 + 4 * 8192,
 }
 # whole step, per sample: the forward's bytes, then observations again, saved activations once, and every
 # activation gradient written and read once
@@ -92,7 +95,8 @@ def main():
     ap.add_argument("--cpu-samples", type=int, default=0, help="oracle sample size (0 = auto, ~10-30 s)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (see DESIGN.md, sharding)" % args.gpus,
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by sample; "
+              "one gradient all-reduce per step would follow)" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
 

@@ -14,6 +14,7 @@
 #include "arn_pv_head.h"
 #include "arn_resident.h"
 #include "arn_resident_conv.h"
+#include "arn_conv1_bwd.h"
 #include "arn_small_kernels.h"
 #include "arn_update.h"
 
@@ -298,6 +299,8 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
         p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
         launch_resident<typename Cfg::Dgrad3>("conv3_dgrad", p, B, s);
     }
+    static const bool unfused = getenv("ARN_UNFUSED_CONV1_BWD") != nullptr;
+    if (unfused) {
     {
         typename Cfg::Dgrad2::Args p;
         p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
@@ -307,6 +310,26 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
         ProfScope ps("conv1_wgrad", s);
         hipLaunchKernelGGL(conv1_wgrad_resident_kernel<G>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part1, B,
                            resident_spw(B, 256));
+    }
+    } else {
+        // conv2's input gradient feeds only conv1's weight gradient (conv1's input is data): one kernel, d(pre1) stays in LDS
+        ProfScope ps("conv1_bwd", s);
+        static const int shape = getenv("ARN_C1B_SHAPE") ? atoi(getenv("ARN_C1B_SHAPE")) : 1;
+        const uint8_t *m1 = (const uint8_t *)(ws + o.m1);
+        const int spw = resident_spw(B, 256);
+        if (shape == 1) {
+            typedef Conv1BwdShape<4, 2, 4> S;
+            hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
+                               dp2, w.w2d, m1, part1, B, spw);
+        } else if (shape == 2) {
+            typedef Conv1BwdShape<4, 2, 8> S;
+            hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
+                               dp2, w.w2d, m1, part1, B, spw);
+        } else {
+            typedef Conv1BwdShape<8, 1, 4> S;
+            hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
+                               dp2, w.w2d, m1, part1, B, spw);
+        }
     }
     {
         ProfScope ps("conv2_wgrad", s);

@@ -1,0 +1,375 @@
+// conv2's input gradient and conv1's weight gradient in one kernel.
+//
+// d(pre1) -- the largest tensor of the backward pass -- has a single consumer, conv1's weight gradient
+// (conv1's input is data, so there is no input gradient below it).  Here a workgroup produces a sample's
+// d(pre1) into LDS and contracts it there against the sample's frame: d(pre1) never goes to HBM, and one
+// kernel boundary is saved.
+//
+// The wavefronts of a workgroup have two roles.  The "producer" wavefronts compute d(pre1) of sample s+1: the
+// stride-2 input gradient as one 2x2 stride-1 correlation with 4 x 32 phase channels (one phase per wavefront,
+// all k of its weights in registers, fragments read from the zero-bordered d(pre2) image as in
+// resident_conv_kernel), masked by the sign bits of act1, written as bf16 rows into one of two LDS buffers.
+// Meanwhile the "consumer" wavefronts contract d(pre1) of sample s (the other buffer) against the bf16 image of
+// the frame with transposing LDS reads that address the 8x8 windows directly, as in the weight-gradient
+// kernels.  The producers are bound by the MFMA pipe, the consumers by the LDS issue rate of the transposing
+// reads, so the two roles fill each other's gaps on a SIMD.
+//
+// Each workgroup owns a fixed, contiguous range of samples and accumulates dW1 in registers; partial results
+// go to part[workgroup][32*256 + 32] and are summed in workgroup order by the reduction kernel.
+#pragma once
+#include "arn_resident.h"
+#include "arn_resident_conv.h"
+
+namespace arn {
+
+// Consumer layout: NWW wavefronts, each owning TX of the eight 32-column tiles of dW1 [32][256]; if NWW * TX
+// is 16, two wavefronts share a tile group and take alternate contraction steps (added at the end, fixed order).
+// Producer layout: NWD = 4 or 8 wavefronts; with 8, two share a phase and take alternate position tiles.
+template <int NWW_, int TX_, int NWD_>
+struct Conv1BwdShape {
+    static constexpr int NWW = NWW_, TX = TX_, NWD = NWD_, THREADS = 64 * (NWW + NWD);
+    static constexpr int KSPLIT = NWW * TX / 8, DPARTS = NWD / 4;
+    static_assert(NWW * TX == 8 || NWW * TX == 16, "one or two wavefronts per column-tile group");
+    static_assert(NWD == 4 || NWD == 8, "one or two wavefronts per phase");
+};
+
+// LDS layout of a d(pre1) buffer: rows of 32 bf16 (64 bytes); inside every 256-byte block of four rows the
+// eight 32-byte granules are rotated by the block index.  A producer writes 16 positions two pixels apart
+// (32 bytes each) per instruction: unrotated they would share two of the eight granule slots (an eight-way bank
+// conflict, measured as the kernel's bottleneck); rotated they cover all eight.  The consumers' transposing
+// reads take four consecutive rows of one block and stay conflict free.
+__device__ __forceinline__ constexpr int dy1_offset(int row, int byte) {
+    return (row >> 2) * 256 + ((((row & 3) * 2 + (byte >> 5) + (row >> 2)) & 7) << 5) + (byte & 31);
+}
+
+// Geo: frame geometry; D: the conv2 input-gradient configuration (ResConv2Dgrad / ResConv2DgradGeo), used with
+// one sample per iteration.  obs u8 [B][4][IN_H][IN_W]; dy2 = d(pre2) bf16 [B][P2][64]; w2d: the packed
+// input-gradient weights [phase*32 + ci][(ty*2 + tx)*64 + co]; mask1: sign bits of act1 (P1*32/8 bytes per sample).
+template <class Geo, class D, class S>
+__global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8_t *__restrict__ obs,
+                                                                     const __bf16 *__restrict__ dy2,
+                                                                     const __bf16 *__restrict__ w2d,
+                                                                     const uint8_t *__restrict__ mask1,
+                                                                     float *__restrict__ part, int B, int spw) {
+    constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
+    constexpr int NT = S::THREADS, NWW = S::NWW, TX = S::TX, KSPLIT = S::KSPLIT;
+    // consumer side (as conv1_wgrad_resident_kernel)
+    constexpr int IMG_U4 = OBS_BYTES / 16;
+    constexpr int KSTEPS = (P1 + 15) / 16, RPAD = KSTEPS * 16;   // contraction steps; d(pre1) rows P1..RPAD stay zero
+    constexpr int DYB = RPAD * C1 * 2;                           // bytes of one d(pre1) buffer
+    constexpr int NI = (IMG_U4 + NT - 1) / NT;
+    constexpr bool TABLE = 80 % W1 != 0;
+    // producer side (as resident_conv_kernel<D> with one sample)
+    constexpr int CI = D::CI, NCH = CI / 8, KS = D::K / 32, CT = D::CO / 64;
+    constexpr int NQ = D::SRC_PIX * NCH, NG = (NQ + NT - 1) / NT;
+    constexpr int DT = (D::P + 15) / 16;                         // position tiles of the 2x2 correlation
+    constexpr int MWORDS = P1 * C1 / 32;                         // 4-byte words of act1 sign bits per sample
+    static_assert(OBS_BYTES % 16 == 0, "a frame is copied in 16-byte words");
+    static_assert(D::CO == 4 * C1 && CT == 2 && D::PSB == CI * 2 + 32, "four phases of 32 channels, one phase per producer");
+    static_assert(MWORDS <= NT && (P1 * C1) % 32 == 0, "one mask word per thread");
+    static_assert(!D::SPLIT && D::ZERO_FILL, "single-product input gradient over a zero-bordered image");
+
+    __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][IN_H][IN_W]
+    __shared__ u32x4 s_dy[2 * DYB / 16];          // d(pre1), bf16 [2][RPAD][32]
+    __shared__ u32x4 s_g[D::IMG / 16];            // bordered d(pre2) image
+    __shared__ uint32_t s_mask[MWORDS];
+    __shared__ int s_win[TABLE ? RPAD : 1];       // byte offset of the window origin of output position m in s_img
+    static_assert(sizeof(u32x4) * 2 * IMG_U4 + 2 * DYB + D::IMG + 4 * MWORDS + 4 * (TABLE ? RPAD : 1) <= 160 * 1024,
+                  "LDS budget");
+    static_assert(8 * 16 * 64 * 4 * (KSPLIT - 1) <= (int)sizeof(u32x4) * 2 * IMG_U4, "scratch for the split contraction");
+    static_assert(S::NWD * 16 * C1 * 4 <= DYB, "bias-gradient scratch");
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, lg = lane >> 4;
+    const bool producer = wave >= NWW;
+    const int s_begin = blockIdx.x * spw;
+    const int s_end = s_begin + spw < B ? s_begin + spw : B;
+    if (s_begin >= s_end) return;
+
+    for (int i = tid; i < D::IMG / 16; i += NT) s_g[i] = zero_u4();
+    if constexpr (RPAD > P1) {
+        // rows P1..RPAD of both buffers stay zero: the blocks that hold them are cleared whole (their valid rows
+        // are rewritten for every sample)
+        constexpr int Z0 = (P1 & ~3) * C1 * 2 / 16, ZN = DYB / 16 - Z0;
+        for (int i = tid; i < 2 * ZN; i += NT) s_dy[(i / ZN) * (DYB / 16) + Z0 + i % ZN] = zero_u4();
+    }
+    auto window = [&](int m) __attribute__((always_inline)) {
+        const int mm = RPAD > P1 && m >= P1 ? P1 - 1 : m;   // rows past the last position (their dY is zero) take its window
+        const int oy = mm / W1, ox = mm - oy * W1;
+        return (S1 * oy * IN_W + S1 * ox) * 2;
+    };
+    if constexpr (TABLE)
+        for (int m = tid; m < RPAD; m += NT) s_win[m] = window(m);
+
+    // Prefetch registers and one persistent pointer per load (advanced by a sample after every use): the loads
+    // of consecutive samples need no address arithmetic in registers that an earlier load may still be filling.
+    u32x4 rimg[NI], rg[NG];
+    uint32_t rm = 0;
+    const u32x4 *pimg[NI], *pg[NG];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int idx = tid + NT * i;
+        pimg[i] = reinterpret_cast<const u32x4 *>(obs + (size_t)s_begin * OBS_BYTES) + (idx < IMG_U4 ? idx : IMG_U4 - 1);
+    }
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+        const int idx = tid + NT * i;
+        pg[i] = reinterpret_cast<const u32x4 *>(dy2 + (size_t)s_begin * D::SRC_PIX * CI) + (idx < NQ ? idx : NQ - 1);
+    }
+    const uint32_t *pm = reinterpret_cast<const uint32_t *>(mask1 + (size_t)s_begin * (MWORDS * 4)) + (tid < MWORDS ? tid : MWORDS - 1);
+    auto gload_img = [&]() __attribute__((always_inline)) {     // the next frame in sequence
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            rimg[i] = *pimg[i];
+            pimg[i] += OBS_BYTES / 16;
+        }
+    };
+    auto gload_g = [&]() __attribute__((always_inline)) {       // the next sample's d(pre2) and mask words
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            rg[i] = *pg[i];
+            pg[i] += D::SRC_PIX * CI * 2 / 16;
+        }
+        rm = *pm;
+        pm += MWORDS;
+    };
+    char *const img = reinterpret_cast<char *>(s_img);
+    char *const dyl = reinterpret_cast<char *>(s_dy);
+    char *const gl = reinterpret_cast<char *>(s_g);
+    const uint8_t *const mbytes = reinterpret_cast<const uint8_t *>(s_mask);
+    auto stage_img = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = tid + NT * i;
+            if (idx < IMG_U4) {
+                s_img[2 * idx] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
+                s_img[2 * idx + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
+            }
+        }
+    };
+    auto stage_g = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int q = tid + NT * i;
+            if (q < NQ) {
+                const int p = q / NCH, c = q - p * NCH;
+                *reinterpret_cast<u32x4 *>(gl + D::dst_off(p) + c * 16) = rg[i];
+            }
+        }
+        if (tid < MWORDS) s_mask[tid] = rm;
+    };
+
+    gload_g();
+    gload_img();
+
+    // Both roles run the same sequence of barriers: the prologue's two, two per sample (next function), and
+    // the three of the epilogue.
+    auto next_sample = [&](int s) __attribute__((always_inline)) {
+        // d(pre1) of s is complete in its buffer; the contraction of s-1 has read s_img and the other buffer;
+        // the producers are done with the d(pre2) image of s
+        __syncthreads();
+        stage_img();
+        if (s + 1 < s_end) stage_g();
+        __syncthreads();
+        if (s + 1 < s_end) gload_img();
+        if (s + 2 < s_end) gload_g();
+    };
+    float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
+    float *xch = reinterpret_cast<float *>(s_img);     // epilogue scratch
+    float *red = reinterpret_cast<float *>(s_dy);
+
+    if (producer) {
+        // phase = (wavefront - NWW) % 4: 32 channels, all k of their weights as A-operand fragments
+        const int phase = (wave - NWW) & 3, dpart = (wave - NWW) >> 2;
+        bf16x8 wd[CT][KS];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const size_t row = (size_t)(phase * 32 + ct * 16 + li) * D::K + 8 * lg;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) wd[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w2d + row + 32 * ks));
+        }
+        wait_global_loads();
+        // bias gradient: what this lane writes into d(pre1), channels ct*16 + 4*lg + r, added in fp32
+        float bs[CT][4];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bs[ct][r] = 0.f;
+
+        // This wavefront's position tiles t = dpart + j * DPARTS (the last may not exist): per-lane addresses that do
+        // not depend on the sample -- fragment base in the d(pre2) image, where channels ct*16 + 4*lg .. + 3 of the
+        // lane's position land in a d(pre1) buffer (-1: padded row or outside the map), and the byte of mask bits.
+        constexpr int NTW = (DT + S::DPARTS - 1) / S::DPARTS, KH = KS / 2;
+        int t_base[NTW], t_dst[NTW][CT], t_mask[NTW];
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) {
+            const int t = dpart + j * S::DPARTS < DT ? dpart + j * S::DPARTS : DT - 1;
+            int row = t * 16 + li;
+            const bool valid = row < D::P && dpart + j * S::DPARTS < DT;
+            row = row < D::P ? row : D::P - 1;            // padded rows recompute the last one; never stored
+            const int pix = valid ? D::out_pixel(row, phase) : -1;
+            t_base[j] = D::base_off(row) + 16 * lg;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) t_dst[j][ct] = pix < 0 ? -1 : dy1_offset(pix, (ct * 16 + 4 * lg) * 2);
+            t_mask[j] = ((pix < 0 ? 0 : pix) * C1 + 4 * lg) >> 3;   // channel group ct: + 2 bytes; bits 4*(lg&1) .. + 3
+        }
+        // The fragment reads are pipelined by half-tiles: the second half of a tile's k-steps is in flight during
+        // the MFMAs of the first, the first half of the next tile (and its mask bytes) during those of the second.
+        auto load_half = [&](int base, int half, bf16x8 (&f)[KH]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int jk = 0; jk < KH; ++jk) {
+                const int ks = half * KH + jk;
+                const int tap = (32 * ks) / CI, ci0 = (32 * ks) % CI;
+                f[jk] = as_bf16x8(*reinterpret_cast<const u32x4 *>(gl + base + D::tap_off(tap) + ci0 * 2));
+            }
+        };
+        auto mfma_half = [&](int half, const bf16x8 (&f)[KH], f32x4 (&da)[CT]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int jk = 0; jk < KH; ++jk)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    da[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wd[ct][half * KH + jk], f[jk], da[ct], 0, 0, 0);
+        };
+        // d(pre1) of the sample whose d(pre2) image and mask are staged, into dst
+        auto produce = [&](char *dst) __attribute__((always_inline)) {
+            bf16x8 fa[KH], fb[KH];
+            uint32_t mk[CT], mk_next[CT];
+            load_half(t_base[0], 0, fa);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) mk[ct] = mbytes[t_mask[0] + 2 * ct];
+#pragma unroll
+            for (int j = 0; j < NTW; ++j) {
+                if (dpart + j * S::DPARTS < DT) {             // wavefront-uniform
+                    const int jn = j + 1 < NTW ? j + 1 : j;   // a tile that does not exist repeats the last one's reads
+                    f32x4 da[CT];
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) da[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    load_half(t_base[j], 1, fb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_half(0, fa, da);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_half(t_base[jn], 0, fa);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) mk_next[ct] = mbytes[t_mask[jn] + 2 * ct];
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_half(1, fb, da);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (t_dst[j][0] >= 0) {
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct) {
+                            const int m = (int)(mk[ct] >> (4 * (lg & 1)));
+                            float v[4];
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {     // bit r of m set: keep the value (all-ones mask), else zero
+                                const float x = da[ct][r];
+                                v[r] = __int_as_float(__float_as_int(x) & -((m >> r) & 1));
+                                bs[ct][r] += v[r];
+                            }
+                            *reinterpret_cast<u32x2 *>(dst + t_dst[j][ct]) = pack_bf16x4(v[0], v[1], v[2], v[3]);
+                        }
+                    }
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) mk[ct] = mk_next[ct];
+                }
+            }
+        };
+
+        __syncthreads();                              // zero fill done
+        stage_g();
+        __syncthreads();
+        if (s_begin + 1 < s_end) gload_g();
+        produce(dyl);                                 // first sample: its d(pre1) before the loop
+        int cur = 0;
+        for (int s = s_begin; s < s_end; ++s) {
+            next_sample(s);
+            if (s + 1 < s_end) produce(dyl + (cur ^ 1) * DYB);
+            cur ^= 1;
+        }
+        __syncthreads();
+        if constexpr (KSPLIT == 2) __syncthreads();
+        // bias gradient: channel c = ct*16 + 4*lg + r is held by lanes (li = 0..15, lg) of all producers
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[((wave - NWW) * 16 + li) * C1 + ct * 16 + 4 * lg + r] = bs[ct][r];
+        __syncthreads();
+    } else {
+        // wavefront w owns column tiles (w % (8/TX)) * TX .. + TX - 1 and contraction steps w / (8/TX) + KSPLIT * j
+        f32x16 acc[TX];
+#pragma unroll
+        for (int b = 0; b < TX; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+        const int tile0 = (wave % (8 / TX)) * TX, kpart = wave / (8 / TX);
+        const int o = lane & 15, Gq = lane >> 4;
+        const int row_in_step = 8 * (Gq >> 1) + (o >> 2);          // + 4 for the second read
+        const int ycol_off = (16 * (Gq & 1) + 4 * (o & 3)) * 2;    // byte offset inside a d(pre1) row
+        // rows 16 ks + row_in_step (+ 4): a step of 16 rows is four blocks, so the rotation alternates between
+        // two values with the parity of ks -- granule index + 4, i.e. bit 7 of the byte offset flipped
+        const int ya = dy1_offset(row_in_step, ycol_off), yb = dy1_offset(row_in_step + 4, ycol_off);
+        const int ky_lane = 2 * (Gq & 1) + ((o & 3) >> 1), kx0 = 4 * (o & 1);
+        // byte offset of (ci, ky, kx0) for column tile t = ci*2 + upper/lower four kernel rows
+        int xoff[TX];
+#pragma unroll
+        for (int b = 0; b < TX; ++b) {
+            const int t = tile0 + b;
+            xoff[b] = (((t >> 1) * IN_H + (t & 1) * 4 + ky_lane) * IN_W + kx0) * 2;
+        }
+        __syncthreads();                              // zero fill done
+        stage_g();
+        __syncthreads();
+        if (s_begin + 1 < s_end) gload_g();
+        int cur = 0;
+        for (int s = s_begin; s < s_end; ++s) {
+            next_sample(s);
+            const char *src = dyl + cur * DYB;
+#pragma unroll 5
+            for (int ks = kpart; ks < KSTEPS; ks += KSPLIT) {
+                const int ma = 16 * ks + row_in_step, mb = ma + 4;
+                const int pa = TABLE ? s_win[ma] : window(ma), pb = TABLE ? s_win[mb] : window(mb);
+                const int flip = (ks & 1) << 7;
+                const bf16x8 fy = tr_pair(src, ks * (16 * C1 * 2) + (ya ^ flip), ks * (16 * C1 * 2) + (yb ^ flip));
+#pragma unroll
+                for (int b = 0; b < TX; ++b) {
+                    const bf16x8 fx = tr_pair(img, pa + xoff[b], pb + xoff[b]);
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc[b], 0, 0, 0);
+                }
+            }
+            cur ^= 1;
+        }
+        __syncthreads();
+        // two wavefronts per tile group: the second hands its sums over through LDS
+        if constexpr (KSPLIT == 2) {
+            if (kpart == 1) {
+#pragma unroll
+                for (int b = 0; b < TX; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) xch[((tile0 + b) * 16 + r) * 64 + lane] = acc[b][r];
+            }
+            __syncthreads();
+        }
+        if (kpart == 0) {
+            const int fr = lane & 31, fg = lane >> 5;
+#pragma unroll
+            for (int b = 0; b < TX; ++b) {
+                const int k = (tile0 + b) * 32 + fr;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int n = 8 * (r >> 2) + 4 * fg + (r & 3);
+                    float v = acc[b][r];
+                    if constexpr (KSPLIT == 2) v += xch[((tile0 + b) * 16 + r) * 64 + lane];
+                    out[n * KW1 + k] = v;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // bias gradient: the producers' lane sums, added in a fixed order
+    if (tid < C1) {
+        float t = red[tid];
+        for (int g = 1; g < S::NWD * 16; ++g) t += red[g * C1 + tid];
+        out[C1 * KW1 + tid] = t;
+    }
+}
+
+}  // namespace arn

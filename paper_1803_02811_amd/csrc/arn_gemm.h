@@ -90,6 +90,12 @@ __device__ __forceinline__ u32x4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
 
 __device__ __forceinline__ u32x4 zero_u4() { return u32x4{0u, 0u, 0u, 0u}; }
 
+// Waits until every global load of this wavefront has returned (s_waitcnt vmcnt(0), other counters unchanged).
+// Kernels that keep weights in registers call it once after loading them: otherwise the compiler places the
+// wait for those loads at their first use inside the sample loop, where it cannot tell them from the prefetch
+// of the next sample issued just before -- and every iteration would wait for its own prefetch.
+__device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // v if keep else 0, through a mask the optimiser cannot see through: a gather
 // written as `ok ? *p : 0` is compiled to a branch around the load with a wait
 // right behind it, which serialises the loads of one k-tile.  With the mask the

@@ -250,6 +250,7 @@ __global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 
             if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + 32 * ks));
         }
     }
+    wait_global_loads();
     int buf = 0;
     for (int s = s_begin; s < s_end; s += C::G) {
         stage(buf);
@@ -382,6 +383,7 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + wrow + 32 * ks));
         wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + wrow + 32 * ks));
     }
+    wait_global_loads();
     int buf = 0;
     for (int s = s_begin; s < s_end; ++s) {
 #pragma unroll
@@ -557,6 +559,10 @@ struct ResConv2Dgrad {
     __device__ static constexpr int dst_off(int p) { return (p / H2 + 1) * ROWB + (p % H2 + 1) * PSB; }
     __device__ static constexpr int base_off(int pos) { return (pos / 10) * ROWB + (pos % 10) * PSB; }
     __device__ static constexpr int tap_off(int t) { return (t / 2) * ROWB + (t % 2) * PSB; }
+    // act1 pixel that channel group `phase` of position pos lands on (always inside the map here)
+    __device__ static constexpr int out_pixel(int pos, int phase) {
+        return (2 * (pos / 10) + (phase >> 1)) * H1 + 2 * (pos % 10) + (phase & 1);
+    }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
         const uint8_t *mask;   // sign bits of act1
@@ -565,9 +571,7 @@ struct ResConv2Dgrad {
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
         __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
                                               const uint8_t *mbits) const {
-            const int phase = n >> 5, ci = n & 31, u = pos / 10, vv = pos - u * 10;
-            const int y = 2 * u + (phase >> 1), x = 2 * vv + (phase & 1);
-            const int pix = y * H1 + x;
+            const int ci = n & 31, pix = out_pixel(pos, n >> 5);
             const int e = (g * P1 + pix) * C1 + ci;
             const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
             *reinterpret_cast<u32x2 *>(out + ((size_t)s * P1 + pix) * C1 + ci) =
@@ -727,6 +731,11 @@ struct ResConv2DgradGeo {
     __device__ static constexpr int dst_off(int p) { return (p / Geo::W2 + 1) * ROWB + (p % Geo::W2 + 1) * PSB; }
     __device__ static constexpr int base_off(int pos) { return (pos / V) * ROWB + (pos % V) * PSB; }
     __device__ static constexpr int tap_off(int t) { return (t / 2) * ROWB + (t % 2) * PSB; }
+    // act1 pixel that channel group `phase` of position pos lands on, or -1 if that is outside the map
+    __device__ static constexpr int out_pixel(int pos, int phase) {
+        const int y = 2 * (pos / V) + (phase >> 1) - Geo::PAD2, x = 2 * (pos % V) + (phase & 1) - Geo::PAD2;
+        return (unsigned)y < (unsigned)Geo::H1 && (unsigned)x < (unsigned)Geo::W1 ? y * Geo::W1 + x : -1;
+    }
     struct Args {
         const __bf16 *in, *in_lo, *w, *w_lo;
         const uint8_t *mask;   // sign bits of act1
@@ -735,10 +744,8 @@ struct ResConv2DgradGeo {
         __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
         __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
                                               const uint8_t *mbits) const {
-            const int phase = n >> 5, ci = n & 31, u = pos / V, vv = pos - u * V;
-            const int y = 2 * u + (phase >> 1) - Geo::PAD2, x = 2 * vv + (phase & 1) - Geo::PAD2;
-            if ((unsigned)y >= (unsigned)Geo::H1 || (unsigned)x >= (unsigned)Geo::W1) return;
-            const int pix = y * Geo::W1 + x;
+            const int ci = n & 31, pix = out_pixel(pos, n >> 5);
+            if (pix < 0) return;
             const int e = (g * Geo::P1 + pix) * C1 + ci;
             const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
             *reinterpret_cast<u32x2 *>(out + ((size_t)s * Geo::P1 + pix) * C1 + ci) =
