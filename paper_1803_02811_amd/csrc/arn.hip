@@ -267,8 +267,8 @@ struct Fork {
 
 // Backward pass below d(pre_fc) for geometry G.  Everything that needs only d(pre_fc) -- the fc weight gradient
 // and its reduction, next to the head's -- runs on the side stream; the chain fc dgrad -> conv3 dgrad ->
-// conv2 dgrad, the convolutions' weight gradients and one reduction kernel for all three of them stay on the
-// caller's stream.  (Every cross-stream event costs the waiting and the recording stream about 6 us, and two
+// conv2 dgrad (fused with conv1's weight gradient), the other convolutions' weight gradients and one reduction
+// kernel for all three of them stay on the caller's stream.  (Every cross-stream event costs the waiting and the recording stream about 6 us, and two
 // heavy kernels side by side mostly share the memory system, so more overlap than this measured slower.)
 template <class G>
 void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o, const ParamOffsets &po,
@@ -277,7 +277,7 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
     hipStream_t s = fk.s, s2 = fk.s2;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *dph = (__bf16 *)(ws + o.dph), *dp3 = (__bf16 *)(ws + o.dp3);
-    __bf16 *dp2 = (__bf16 *)(ws + o.dp2), *dp1 = (__bf16 *)(ws + o.dp1);
+    __bf16 *dp2 = (__bf16 *)(ws + o.dp2);
     float *part1 = (float *)(ws + o.pw1), *part2 = (float *)(ws + o.pw2), *part3 = (float *)(ws + o.pw3);
     {
         typedef Wgrad<DenseGather<G::FEAT>, 128, 64, 2, HID, G::FEAT> FcW;
@@ -299,37 +299,14 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
         p.in = dp3; p.in_lo = nullptr; p.w = w.w3d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m2); p.out = dp2;
         launch_resident<typename Cfg::Dgrad3>("conv3_dgrad", p, B, s);
     }
-    static const bool unfused = getenv("ARN_UNFUSED_CONV1_BWD") != nullptr;
-    if (unfused) {
     {
-        typename Cfg::Dgrad2::Args p;
-        p.in = dp2; p.in_lo = nullptr; p.w = w.w2d; p.w_lo = nullptr; p.mask = (const uint8_t *)(ws + o.m1); p.out = dp1;
-        launch_resident<typename Cfg::Dgrad2>("conv2_dgrad", p, B, s);
-    }
-    {   // conv1: weight gradient only (the input is data)
-        ProfScope ps("conv1_wgrad", s);
-        hipLaunchKernelGGL(conv1_wgrad_resident_kernel<G>, dim3(sp.c1), dim3(C1W_THREADS), 0, s, obs, dp1, part1, B,
-                           resident_spw(B, 256));
-    }
-    } else {
-        // conv2's input gradient feeds only conv1's weight gradient (conv1's input is data): one kernel, d(pre1) stays in LDS
+        // conv2's input gradient feeds only conv1's weight gradient (conv1's input is data): one kernel, in which
+        // d(pre1) stays in LDS.  Four consumer wavefronts with two column tiles each and four producers: the shape
+        // that measured best (twelve-wavefront shapes spill or gain nothing).
         ProfScope ps("conv1_bwd", s);
-        static const int shape = getenv("ARN_C1B_SHAPE") ? atoi(getenv("ARN_C1B_SHAPE")) : 1;
-        const uint8_t *m1 = (const uint8_t *)(ws + o.m1);
-        const int spw = resident_spw(B, 256);
-        if (shape == 1) {
-            typedef Conv1BwdShape<4, 2, 4> S;
-            hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
-                               dp2, w.w2d, m1, part1, B, spw);
-        } else if (shape == 2) {
-            typedef Conv1BwdShape<4, 2, 8> S;
-            hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
-                               dp2, w.w2d, m1, part1, B, spw);
-        } else {
-            typedef Conv1BwdShape<8, 1, 4> S;
-            hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
-                               dp2, w.w2d, m1, part1, B, spw);
-        }
+        typedef Conv1BwdShape<4, 2, 4> S;
+        hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
+                           dp2, w.w2d, (const uint8_t *)(ws + o.m1), part1, B, resident_spw(B, 256));
     }
     {
         ProfScope ps("conv2_wgrad", s);

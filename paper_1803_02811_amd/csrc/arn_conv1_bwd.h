@@ -67,7 +67,8 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
     static_assert(OBS_BYTES % 16 == 0, "a frame is copied in 16-byte words");
     static_assert(D::CO == 4 * C1 && CT == 2 && D::PSB == CI * 2 + 32, "four phases of 32 channels, one phase per producer");
     static_assert(MWORDS <= NT && (P1 * C1) % 32 == 0, "one mask word per thread");
-    static_assert(!D::SPLIT && D::ZERO_FILL, "single-product input gradient over a zero-bordered image");
+    static_assert(!D::SPLIT && D::ZERO_FILL && D::G == 1, "single-product input gradient over a zero-bordered image, one sample");
+    static_assert(layout_is_uniform<D>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
 
     __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][IN_H][IN_W]
     __shared__ u32x4 s_dy[2 * DYB / 16];          // d(pre1), bf16 [2][RPAD][32]

@@ -214,7 +214,7 @@ struct Workspace {
     size_t ztgt, m;                     // C51: target-net atom logits, projected target
     size_t qt, astar;                   // DQN: target-net Q(s',.) fp32 [B][A]; Double-DQN: online greedy action on s' int32 [B]
     size_t m1, m2, m3;                  // ReLU sign bits of act1..3 (bit e&7 of byte e>>3, NHWC element e), written by the forward
-    size_t dz, dph, dp3, dp2, dp1;      // bf16 gradients at pre-activations
+    size_t dz, dph, dp3, dp2;           // bf16 gradients at pre-activations (d(pre1) never leaves the chip)
     size_t lossp;                       // fp32 [blocks][4] partial loss sums
     size_t pw1, pw2, pw3, pwfc, pwh;    // fp32 weight-gradient partials [split][N*K' + N]
     size_t total;
@@ -258,7 +258,6 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
         w.dph = take(b * HID * 2);
         w.dp3 = take(b * feat * 2);
         w.dp2 = take(b * p2 * C2 * 2);
-        w.dp1 = take(b * p1 * C1 * 2);
         w.lossp = take((size_t)loss_blocks(d, B) * 4 * 4);
         const Splits s = make_splits(d, B);
         w.pw1 = take((size_t)s.c1 * ((size_t)C1 * KW1 + C1) * 4);

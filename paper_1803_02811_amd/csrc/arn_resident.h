@@ -24,131 +24,6 @@ __device__ __forceinline__ bf16x8 tr_pair(const char *lds_base, int off_a, int o
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// conv1: x = uint8 observation [4][IN_H][IN_W] of geometry Geo (k' = ci*64 + ky*8 + kx, window at
-// (4oy, 4ox)), dY = d(pre1) [P1][32] (P1 = 400 at 84x84).  part[wg] = [32][256] then [32] bias sums.
-// The 1/255 pixel scale is applied by the reduction.
-constexpr int C1W_THREADS = 512;   // eight wavefronts: one 32-column tile of dW1 each, two per SIMD
-template <class Geo>
-__global__ __launch_bounds__(C1W_THREADS) void conv1_wgrad_resident_kernel(const uint8_t *__restrict__ obs,
-                                                                   const __bf16 *__restrict__ dy,
-                                                                   float *__restrict__ part, int B, int spw) {
-    constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
-    constexpr int IMG_U4 = OBS_BYTES / 16;        // sixteen-pixel groups per sample (1764 at 84x84)
-    constexpr int DY_U4 = P1 * C1 * 2 / 16;       // 1600 at 84x84
-    constexpr int KSTEPS = (P1 + 15) / 16, RPAD = KSTEPS * 16;   // contraction steps; dY rows P1..RPAD stay zero
-    constexpr int NT = C1W_THREADS;
-    constexpr int NI = (IMG_U4 + NT - 1) / NT, ND = (DY_U4 + NT - 1) / NT;   // 4, 4
-    static_assert(OBS_BYTES % 16 == 0 && (P1 * C1 * 2) % 16 == 0, "samples are copied in 16-byte words");
-    __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][IN_H][IN_W]
-    __shared__ u32x4 s_dy[RPAD * C1 * 2 / 16];    // bf16 [RPAD][32]
-    // With 80 positions (five k-steps) a whole number of output rows, the compiler turns the row/column
-    // arithmetic of the unrolled k loop into constant increments; otherwise the window origins are tabulated.
-    constexpr bool TABLE = 80 % W1 != 0;
-    __shared__ int s_win[TABLE ? RPAD : 1];       // byte offset of the window origin of output position m in s_img
-    static_assert((NT / 4) * C1 * 4 <= RPAD * C1 * 2, "bias-gradient scratch");
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int s_begin = blockIdx.x * spw;
-    const int s_end = s_begin + spw < B ? s_begin + spw : B;
-    if constexpr (RPAD > P1)
-        for (int i = DY_U4 + tid; i < RPAD * C1 * 2 / 16; i += NT) s_dy[i] = zero_u4();
-    auto window = [&](int m) __attribute__((always_inline)) {
-        const int mm = RPAD > P1 && m >= P1 ? P1 - 1 : m;   // rows past the last position (their dY is zero) take its window
-        const int oy = mm / W1, ox = mm - oy * W1;
-        return (S1 * oy * IN_W + S1 * ox) * 2;
-    };
-    if constexpr (TABLE)
-        for (int m = tid; m < RPAD; m += NT) s_win[m] = window(m);
-
-    u32x4 rimg[NI], rdy[ND];
-    auto gload = [&](int s) __attribute__((always_inline)) {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(obs + (size_t)s * OBS_BYTES);
-        const u32x4 *dsrc = reinterpret_cast<const u32x4 *>(dy + (size_t)s * P1 * C1);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int idx = tid + NT * i;
-            rimg[i] = src[idx < IMG_U4 ? idx : IMG_U4 - 1];
-        }
-#pragma unroll
-        for (int i = 0; i < ND; ++i) {
-            const int idx = tid + NT * i;
-            rdy[i] = dsrc[idx < DY_U4 ? idx : DY_U4 - 1];
-        }
-    };
-
-    f32x16 acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    // bias gradient: a thread always stages the same eight dY channels (chunk tid % 4 of a row), so it
-    // adds what it stages, in fp32; the 128 threads of a chunk are added in thread order at the end
-    float bs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-    // per-lane constants of the transposing reads
-    const int o = lane & 15, G = lane >> 4;
-    const int row_in_step = 8 * (G >> 1) + (o >> 2);          // + 4 for the second read
-    const int ycol_off = (16 * (G & 1) + 4 * (o & 3)) * 2;    // byte offset inside a dY row
-    const int ky_lane = 2 * (G & 1) + ((o & 3) >> 1), kx0 = 4 * (o & 1);
-    // byte offset of (ci, ky, kx0) for the wavefront's column tile (tile t = ci*2 + upper/lower four kernel rows)
-    const int xoff = (((wave >> 1) * IN_H + (wave & 1) * 4 + ky_lane) * IN_W + kx0) * 2;
-
-    if (s_begin < s_end) gload(s_begin);
-    for (int s = s_begin; s < s_end; ++s) {
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int idx = tid + NT * i;
-            if (idx < IMG_U4) {
-                s_img[2 * idx] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
-                s_img[2 * idx + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < ND; ++i) {
-            const int idx = tid + NT * i;
-            if (idx < DY_U4) {
-                s_dy[idx] = rdy[i];
-                const bf16x8 f = as_bf16x8(rdy[i]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bs[e] += (float)f[e];
-            }
-        }
-        __syncthreads();
-        if (s + 1 < s_end) gload(s + 1);
-
-        const char *img = reinterpret_cast<const char *>(s_img);
-        const char *dyl = reinterpret_cast<const char *>(s_dy);
-#pragma unroll 5
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            const int ma = 16 * ks + row_in_step, mb = ma + 4;
-            const int pa = TABLE ? s_win[ma] : window(ma), pb = TABLE ? s_win[mb] : window(mb);
-            const bf16x8 fy = tr_pair(dyl, ma * (C1 * 2) + ycol_off, mb * (C1 * 2) + ycol_off);
-            const bf16x8 fx = tr_pair(img, pa + xoff, pb + xoff);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc, 0, 0, 0);
-        }
-    }
-
-    float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
-    const int fr = lane & 31, fg = lane >> 5;
-    {
-        const int k = wave * 32 + fr;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int n = 8 * (r >> 2) + 4 * fg + (r & 3);
-            out[n * KW1 + k] = acc[r];
-        }
-    }
-    __syncthreads();
-    float *red = reinterpret_cast<float *>(s_dy);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) red[(tid >> 2) * C1 + (tid & 3) * 8 + e] = bs[e];
-    __syncthreads();
-    if (tid < C1) {
-        float t = red[tid];
-        for (int g = 1; g < NT / 4; ++g) t += red[g * C1 + tid];
-        out[C1 * KW1 + tid] = t;
-    }
-}
-
 // conv2 / conv3: x = NHWC bf16 activations [HIN][WIN][CIN] of G samples per
 // iteration (k' = (ky*KS + kx)*CIN + ci), dY = d(pre) rows [G*HOUT*WOUT][COUT].
 // With PAD > 0 the LDS image of a sample has a zero border of PAD pixels (cleared once; only the

@@ -548,13 +548,13 @@ struct ResConv3Dgrad {
 // The four output phases (y%2, x%2) share their activation fragments, so they
 // are the 4 x 32 "channels" of one 2x2 stride-1 convolution over the padded
 // image with 10x10 positions (u,v); channel n = phase*32 + ci lands at act1
-// pixel (2u + phase/2, 2v + phase%2).  Output d(pre1) masked by act1 > 0.
+// pixel (2u + phase/2, 2v + phase%2).  This is the image description only: the kernel that uses it
+// (conv1_bwd_fused_kernel) feeds d(pre1) straight into conv1's weight gradient, one sample per iteration.
 struct ResConv2Dgrad {
     static constexpr int PADW = H2 + 2;   // 11
-    static constexpr int CI = C2, SRC_PIX = P2, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 2;
-    static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
-    static constexpr int MASK_ELEMS = P1 * C1, NBUF = 1;
-    // row and image padding as in the forward kernels (10 positions per output row over 11-pixel rows)
+    static constexpr int CI = C2, SRC_PIX = P2, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 1;
+    static constexpr bool SPLIT = false, ZERO_FILL = true;
+    // row padding as in the forward kernels (10 positions per output row over 11-pixel rows)
     static constexpr int PSB = C2 * 2 + 32, ROWB = PADW * PSB + 96, IMG = 20608;
     __device__ static constexpr int dst_off(int p) { return (p / H2 + 1) * ROWB + (p % H2 + 1) * PSB; }
     __device__ static constexpr int base_off(int pos) { return (pos / 10) * ROWB + (pos % 10) * PSB; }
@@ -563,21 +563,6 @@ struct ResConv2Dgrad {
     __device__ static constexpr int out_pixel(int pos, int phase) {
         return (2 * (pos / 10) + (phase >> 1)) * H1 + 2 * (pos % 10) + (phase & 1);
     }
-    struct Args {
-        const __bf16 *in, *in_lo, *w, *w_lo;
-        const uint8_t *mask;   // sign bits of act1
-        __bf16 *out;
-        struct Lane {};
-        __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
-        __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
-                                              const uint8_t *mbits) const {
-            const int ci = n & 31, pix = out_pixel(pos, n >> 5);
-            const int e = (g * P1 + pix) * C1 + ci;
-            const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
-            *reinterpret_cast<u32x2 *>(out + ((size_t)s * P1 + pix) * C1 + ci) =
-                pack_bf16x4(m & 1 ? v[0] : 0.f, m & 2 ? v[1] : 0.f, m & 4 ? v[2] : 0.f, m & 8 ? v[3] : 0.f);
-        }
-    };
 };
 
 // ---------------------------------------------------------------------------
@@ -715,19 +700,18 @@ struct ResConv3DgradGeo {
 // conv2 (4x4, stride 2, padding PAD2): d(pre2) [H2][W2][64] zero-padded by 1.  In coordinates of the padded
 // input, (y + PAD2, x + PAD2) = (2u + py, 2v + px); the four phases (py,px) share their fragments, so they are
 // the 4 x 32 channels of one 2x2 stride-1 correlation over positions (u,v); channel n = phase*32 + ci lands at
-// act1 pixel (2u + py - PAD2, 2v + px - PAD2) if that is inside the map.
+// act1 pixel (2u + py - PAD2, 2v + px - PAD2) if that is inside the map.  Image description for
+// conv1_bwd_fused_kernel, as ResConv2Dgrad.
 template <class Geo>
 struct ResConv2DgradGeo {
     static constexpr int U = ((Geo::H1 - 1 + Geo::PAD2) >> 1) + 1, V = ((Geo::W1 - 1 + Geo::PAD2) >> 1) + 1;
     static constexpr int PADH = Geo::H2 + 2, PADW = Geo::W2 + 2;
     static_assert(U <= PADH - 1 && V <= PADW - 1, "every 2x2 window lies inside the padded gradient");
-    static constexpr int CI = C2, SRC_PIX = Geo::P2, P = U * V, CO = 4 * C1, K = 4 * C2, G = 2;
-    static constexpr bool SPLIT = false, ZERO_FILL = true, PIPE = true;
-    static constexpr int MASK_ELEMS = Geo::P1 * C1, NBUF = 1;
+    static constexpr int CI = C2, SRC_PIX = Geo::P2, P = U * V, CO = 4 * C1, K = 4 * C2, G = 1;
+    static constexpr bool SPLIT = false, ZERO_FILL = true;
     static constexpr int PSB = C2 * 2 + 32;
     static constexpr int ROWB = PADW * PSB + pad_to_step(PADW * PSB, V * PSB);
-    static constexpr int LAST = (U - 1) * ROWB + (V - 1) * PSB;
-    static constexpr int IMG = PADH * ROWB + pad_to_step(PADH * ROWB, LAST + PSB);
+    static constexpr int IMG = (PADH * ROWB + 15) / 16 * 16;
     __device__ static constexpr int dst_off(int p) { return (p / Geo::W2 + 1) * ROWB + (p % Geo::W2 + 1) * PSB; }
     __device__ static constexpr int base_off(int pos) { return (pos / V) * ROWB + (pos % V) * PSB; }
     __device__ static constexpr int tap_off(int t) { return (t / 2) * ROWB + (t % 2) * PSB; }
@@ -736,22 +720,6 @@ struct ResConv2DgradGeo {
         const int y = 2 * (pos / V) + (phase >> 1) - Geo::PAD2, x = 2 * (pos % V) + (phase & 1) - Geo::PAD2;
         return (unsigned)y < (unsigned)Geo::H1 && (unsigned)x < (unsigned)Geo::W1 ? y * Geo::W1 + x : -1;
     }
-    struct Args {
-        const __bf16 *in, *in_lo, *w, *w_lo;
-        const uint8_t *mask;   // sign bits of act1
-        __bf16 *out;
-        struct Lane {};
-        __device__ __forceinline__ Lane lane(int) const { return Lane{}; }
-        __device__ __forceinline__ void store(int s, int g, int pos, int n, f32x4 v, const Lane &,
-                                              const uint8_t *mbits) const {
-            const int ci = n & 31, pix = out_pixel(pos, n >> 5);
-            if (pix < 0) return;
-            const int e = (g * Geo::P1 + pix) * C1 + ci;
-            const uint32_t m = (uint32_t)mbits[e >> 3] >> (e & 7);
-            *reinterpret_cast<u32x2 *>(out + ((size_t)s * Geo::P1 + pix) * C1 + ci) =
-                pack_bf16x4(m & 1 ? v[0] : 0.f, m & 2 ? v[1] : 0.f, m & 4 ? v[2] : 0.f, m & 8 ? v[3] : 0.f);
-        }
-    };
 };
 
 }  // namespace arn
