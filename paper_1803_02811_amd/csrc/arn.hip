@@ -302,7 +302,8 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
     {
         // conv2's input gradient feeds only conv1's weight gradient (conv1's input is data): one kernel, in which
         // d(pre1) stays in LDS.  Four consumer wavefronts with two column tiles each and four producers: the shape
-        // that measured best (twelve-wavefront shapes spill or gain nothing).
+        // that measured best (eight producers or eight consumers in twelve wavefronts, or four column tiles per
+        // consumer with the contraction split in two, were all within 3 % or spilled registers).
         ProfScope ps("conv1_bwd", s);
         typedef Conv1BwdShape<4, 2, 4> S;
         hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,

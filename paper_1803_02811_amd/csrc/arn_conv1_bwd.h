@@ -11,8 +11,8 @@
 // resident_conv_kernel), masked by the sign bits of act1, written as bf16 rows into one of two LDS buffers.
 // Meanwhile the "consumer" wavefronts contract d(pre1) of sample s (the other buffer) against the bf16 image of
 // the frame with transposing LDS reads that address the 8x8 windows directly, as in the weight-gradient
-// kernels.  The producers are bound by the MFMA pipe, the consumers by the LDS issue rate of the transposing
-// reads, so the two roles fill each other's gaps on a SIMD.
+// kernels.  The producers mostly use the MFMA pipe and VALU, the consumers the LDS, so the two roles fill each
+// other's gaps on a SIMD; their code sits in two branches so that registers are allocated for one role only.
 //
 // Each workgroup owns a fixed, contiguous range of samples and accumulates dW1 in registers; partial results
 // go to part[workgroup][32*256 + 32] and are summed in workgroup order by the reduction kernel.
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
                                                                      float *__restrict__ part, int B, int spw) {
     constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
     constexpr int NT = S::THREADS, NWW = S::NWW, TX = S::TX, KSPLIT = S::KSPLIT;
-    // consumer side (as conv1_wgrad_resident_kernel)
+    // consumer side (a weight-gradient contraction over the P1 positions, as in conv_wgrad_resident_kernel)
     constexpr int IMG_U4 = OBS_BYTES / 16;
     constexpr int KSTEPS = (P1 + 15) / 16, RPAD = KSTEPS * 16;   // contraction steps; d(pre1) rows P1..RPAD stay zero
     constexpr int DYB = RPAD * C1 * 2;                           // bytes of one d(pre1) buffer
@@ -137,7 +137,6 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
     char *const img = reinterpret_cast<char *>(s_img);
     char *const dyl = reinterpret_cast<char *>(s_dy);
     char *const gl = reinterpret_cast<char *>(s_g);
-    const uint8_t *const mbytes = reinterpret_cast<const uint8_t *>(s_mask);
     auto stage_img = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -212,7 +211,7 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
             t_base[j] = D::base_off(row) + 16 * lg;
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) t_dst[j][ct] = pix < 0 ? -1 : dy1_offset(pix, (ct * 16 + 4 * lg) * 2);
-            t_mask[j] = ((pix < 0 ? 0 : pix) * C1 + 4 * lg) >> 3;   // channel group ct: + 2 bytes; bits 4*(lg&1) .. + 3
+            t_mask[j] = pix < 0 ? 0 : pix;                // the position's 32 sign bits are one word of s_mask
         }
         // The fragment reads are pipelined by half-tiles: the second half of a tile's k-steps is in flight during
         // the MFMAs of the first, the first half of the next tile (and its mask bytes) during those of the second.
@@ -234,10 +233,9 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
         // d(pre1) of the sample whose d(pre2) image and mask are staged, into dst
         auto produce = [&](char *dst) __attribute__((always_inline)) {
             bf16x8 fa[KH], fb[KH];
-            uint32_t mk[CT], mk_next[CT];
+            uint32_t mk, mk_next;
             load_half(t_base[0], 0, fa);
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) mk[ct] = mbytes[t_mask[0] + 2 * ct];
+            mk = s_mask[t_mask[0]];
 #pragma unroll
             for (int j = 0; j < NTW; ++j) {
                 if (dpart + j * S::DPARTS < DT) {             // wavefront-uniform
@@ -250,15 +248,14 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
                     mfma_half(0, fa, da);
                     __builtin_amdgcn_sched_barrier(0);
                     load_half(t_base[jn], 0, fa);
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) mk_next[ct] = mbytes[t_mask[jn] + 2 * ct];
+                    mk_next = s_mask[t_mask[jn]];
                     __builtin_amdgcn_sched_barrier(0);
                     mfma_half(1, fb, da);
                     __builtin_amdgcn_sched_barrier(0);
                     if (t_dst[j][0] >= 0) {
 #pragma unroll
                         for (int ct = 0; ct < CT; ++ct) {
-                            const int m = (int)(mk[ct] >> (4 * (lg & 1)));
+                            const int m = (int)(mk >> (ct * 16 + 4 * lg));   // bit r: channel ct*16 + 4*lg + r
                             float v[4];
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {     // bit r of m set: keep the value (all-ones mask), else zero
@@ -269,8 +266,7 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
                             *reinterpret_cast<u32x2 *>(dst + t_dst[j][ct]) = pack_bf16x4(v[0], v[1], v[2], v[3]);
                         }
                     }
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) mk[ct] = mk_next[ct];
+                    mk = mk_next;
                 }
             }
         };

@@ -1,4 +1,5 @@
-// Weight-gradient kernels that keep one sample's operands resident in LDS.
+// Weight-gradient kernel (conv2, conv3) that keeps a few samples' operands resident in LDS; conv1's weight
+// gradient uses the same contraction inside conv1_bwd_fused_kernel.
 //
 // dW[co][k'] = sum over samples and output positions m of dY[m][co] * x(m,k').
 // The contraction index m is the slow index of both operands in memory, so both
