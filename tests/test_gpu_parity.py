@@ -267,6 +267,25 @@ def test_black_frames_exact_zero_preactivations(gu):
     _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
 
 
+@pytest.mark.parametrize("geometry,B", [("84", 515), ("paper", 515), ("84", 1), ("paper", 1), ("84", 257)])
+def test_gradients_with_short_and_single_sample_workgroups(gu, geometry, B):
+    """The sample-resident backward kernels give each workgroup a contiguous range of samples: 515 = 171 x 3 + 2
+    leaves the last workgroup short (and makes the fused conv1 backward pipeline three samples per workgroup),
+    257 gives ranges of two with a single sample at the end, 1 is one workgroup with nothing to prefetch."""
+    A = 18
+    frame = wl.FRAME if geometry == "84" else wl.PAPER_FRAME
+    fc_in = wl.FC_INPUTS[frame]
+    flat = wl.he_normal_params(A, "pv", 2011, bias_std=0.1, fc_inputs=fc_in)
+    batch = wl.actor_critic_batch(3, B=B, frame=frame)
+    spec = orc.NetSpec(A, "pv") if geometry == "84" else orc.NetSpec(A, "pv", geometry=orc.PAPER_104x80)
+    ref = orc.train_step_grads(flat, batch, "a2c", spec)
+    dW, loss = gu.GpuNet(A, "pv", flat, geometry=geometry).train(batch, "a2c")
+    got, want = gu.per_tensor(dW, A, "pv", fc_inputs=fc_in), gu.per_tensor(ref["flat"], A, "pv", fc_inputs=fc_in)
+    for name in want:
+        gu.tol_check(got[name], want[name], name)
+    gu.tol_check(loss[:1], np.array([ref["loss"]["total"]]), "loss.total")
+
+
 def test_saturated_frames_and_large_batch_tail(gu):
     """All-255 frames (largest pixel sums) and a batch that leaves ragged tails in every kernel."""
     A, B = 18, 259
