@@ -301,12 +301,9 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
     }
     {
         // conv2's input gradient feeds only conv1's weight gradient (conv1's input is data): one kernel, in which
-        // d(pre1) stays in LDS.  Four consumer wavefronts with two column tiles each and four producers: the shape
-        // that measured best (eight producers or eight consumers in twelve wavefronts, or four column tiles per
-        // consumer with the contraction split in two, were all within 3 % or spilled registers).
+        // d(pre1) stays in LDS
         ProfScope ps("conv1_bwd", s);
-        typedef Conv1BwdShape<4, 2, 4> S;
-        hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2, S>), dim3(sp.c1), dim3(S::THREADS), 0, s, obs,
+        hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2>), dim3(sp.c1), dim3(C1B_THREADS), 0, s, obs,
                            dp2, w.w2d, (const uint8_t *)(ws + o.m1), part1, B, resident_spw(B, 256));
     }
     {

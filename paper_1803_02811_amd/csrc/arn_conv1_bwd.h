@@ -5,14 +5,17 @@
 // d(pre1) into LDS and contracts it there against the sample's frame: d(pre1) never goes to HBM, and one
 // kernel boundary is saved.
 //
-// The wavefronts of a workgroup have two roles.  The "producer" wavefronts compute d(pre1) of sample s+1: the
+// The eight wavefronts of a workgroup have two roles.  Four "producers" compute d(pre1) of sample s+1: the
 // stride-2 input gradient as one 2x2 stride-1 correlation with 4 x 32 phase channels (one phase per wavefront,
 // all k of its weights in registers, fragments read from the zero-bordered d(pre2) image as in
 // resident_conv_kernel), masked by the sign bits of act1, written as bf16 rows into one of two LDS buffers.
-// Meanwhile the "consumer" wavefronts contract d(pre1) of sample s (the other buffer) against the bf16 image of
-// the frame with transposing LDS reads that address the 8x8 windows directly, as in the weight-gradient
-// kernels.  The producers mostly use the MFMA pipe and VALU, the consumers the LDS, so the two roles fill each
-// other's gaps on a SIMD; their code sits in two branches so that registers are allocated for one role only.
+// Meanwhile four "consumers" contract d(pre1) of sample s (the other buffer) against the bf16 image of the
+// frame with transposing LDS reads that address the 8x8 windows directly, as in the weight-gradient kernels.
+// Consumer w owns the two 32-column tiles of dW1 that belong to input channel w, so it is the only reader of
+// that channel's plane of the image: it loads, converts and stores the plane itself, after its own contraction,
+// with no barrier.  The producers stage d(pre2) and the mask words, which all four of them read.  The producers
+// mostly use the MFMA pipe and VALU, the consumers the LDS, so the two roles fill each other's gaps on a SIMD;
+// their code sits in two branches that execute the same barriers, so registers are allocated for one role only.
 //
 // Each workgroup owns a fixed, contiguous range of samples and accumulates dW1 in registers; partial results
 // go to part[workgroup][32*256 + 32] and are summed in workgroup order by the reduction kernel.
@@ -22,67 +25,58 @@
 
 namespace arn {
 
-// Consumer layout: NWW wavefronts, each owning TX of the eight 32-column tiles of dW1 [32][256]; if NWW * TX
-// is 16, two wavefronts share a tile group and take alternate contraction steps (added at the end, fixed order).
-// Producer layout: NWD = 4 or 8 wavefronts; with 8, two share a phase and take alternate position tiles.
-template <int NWW_, int TX_, int NWD_>
-struct Conv1BwdShape {
-    static constexpr int NWW = NWW_, TX = TX_, NWD = NWD_, THREADS = 64 * (NWW + NWD);
-    static constexpr int KSPLIT = NWW * TX / 8, DPARTS = NWD / 4;
-    static_assert(NWW * TX == 8 || NWW * TX == 16, "one or two wavefronts per column-tile group");
-    static_assert(NWD == 4 || NWD == 8, "one or two wavefronts per phase");
-};
+constexpr int C1B_THREADS = 512;   // four consumer wavefronts (0-3), four producers (4-7); one workgroup per CU
 
 // LDS layout of a d(pre1) buffer: rows of 32 bf16 (64 bytes); inside every 256-byte block of four rows the
 // eight 32-byte granules are rotated by the block index.  A producer writes 16 positions two pixels apart
 // (32 bytes each) per instruction: unrotated they would share two of the eight granule slots (an eight-way bank
-// conflict, measured as the kernel's bottleneck); rotated they cover all eight.  The consumers' transposing
-// reads take four consecutive rows of one block and stay conflict free.
+// conflict, measured as a bottleneck); rotated they cover all eight.  The consumers' transposing reads take
+// four consecutive rows of one block and stay conflict free.
 __device__ __forceinline__ constexpr int dy1_offset(int row, int byte) {
     return (row >> 2) * 256 + ((((row & 3) * 2 + (byte >> 5) + (row >> 2)) & 7) << 5) + (byte & 31);
 }
 
-// Geo: frame geometry; D: the conv2 input-gradient configuration (ResConv2Dgrad / ResConv2DgradGeo), used with
-// one sample per iteration.  obs u8 [B][4][IN_H][IN_W]; dy2 = d(pre2) bf16 [B][P2][64]; w2d: the packed
+// Geo: frame geometry; D: the description of conv2's input gradient (ResConv2Dgrad / ResConv2DgradGeo: the
+// d(pre2) image of one sample).  obs u8 [B][4][IN_H][IN_W]; dy2 = d(pre2) bf16 [B][P2][64]; w2d: the packed
 // input-gradient weights [phase*32 + ci][(ty*2 + tx)*64 + co]; mask1: sign bits of act1 (P1*32/8 bytes per sample).
-template <class Geo, class D, class S>
-__global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8_t *__restrict__ obs,
-                                                                     const __bf16 *__restrict__ dy2,
-                                                                     const __bf16 *__restrict__ w2d,
-                                                                     const uint8_t *__restrict__ mask1,
-                                                                     float *__restrict__ part, int B, int spw) {
+template <class Geo, class D>
+__global__ __launch_bounds__(C1B_THREADS) void conv1_bwd_fused_kernel(const uint8_t *__restrict__ obs,
+                                                                      const __bf16 *__restrict__ dy2,
+                                                                      const __bf16 *__restrict__ w2d,
+                                                                      const uint8_t *__restrict__ mask1,
+                                                                      float *__restrict__ part, int B, int spw) {
     constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
-    constexpr int NT = S::THREADS, NWW = S::NWW, TX = S::TX, KSPLIT = S::KSPLIT;
+    constexpr int NT = C1B_THREADS, NR = NT / 2;                 // threads in all, and per role
     // consumer side (a weight-gradient contraction over the P1 positions, as in conv_wgrad_resident_kernel)
-    constexpr int IMG_U4 = OBS_BYTES / 16;
+    constexpr int PLANE_U4 = IN_H * IN_W / 16;                   // one input channel of the frame, 16 pixels per word
+    constexpr int NI = (PLANE_U4 + 63) / 64;                     // words per lane of the wavefront that owns the plane
     constexpr int KSTEPS = (P1 + 15) / 16, RPAD = KSTEPS * 16;   // contraction steps; d(pre1) rows P1..RPAD stay zero
     constexpr int DYB = RPAD * C1 * 2;                           // bytes of one d(pre1) buffer
-    constexpr int NI = (IMG_U4 + NT - 1) / NT;
+    constexpr int TX = 2;                                        // column tiles of dW1 per consumer: one input channel
     constexpr bool TABLE = 80 % W1 != 0;
     // producer side (as resident_conv_kernel<D> with one sample)
-    constexpr int CI = D::CI, NCH = CI / 8, KS = D::K / 32, CT = D::CO / 64;
-    constexpr int NQ = D::SRC_PIX * NCH, NG = (NQ + NT - 1) / NT;
+    constexpr int CI = D::CI, NCH = CI / 8, KS = D::K / 32, KH = KS / 2, CT = D::CO / 64;
+    constexpr int NQ = D::SRC_PIX * NCH, NG = (NQ + NR - 1) / NR;
     constexpr int DT = (D::P + 15) / 16;                         // position tiles of the 2x2 correlation
-    constexpr int MWORDS = P1 * C1 / 32;                         // 4-byte words of act1 sign bits per sample
-    static_assert(OBS_BYTES % 16 == 0, "a frame is copied in 16-byte words");
+    constexpr int MWORDS = P1 * C1 / 32, NM = (MWORDS + NR - 1) / NR;   // 4-byte words of act1 sign bits per sample
+    static_assert((IN_H * IN_W) % 16 == 0 && OBS_BYTES == 4 * IN_H * IN_W, "a channel plane is copied in 16-byte words");
     static_assert(D::CO == 4 * C1 && CT == 2 && D::PSB == CI * 2 + 32, "four phases of 32 channels, one phase per producer");
-    static_assert(MWORDS <= NT && (P1 * C1) % 32 == 0, "one mask word per thread");
+    static_assert((P1 * C1) % 32 == 0, "whole mask words per sample");
     static_assert(!D::SPLIT && D::ZERO_FILL && D::G == 1, "single-product input gradient over a zero-bordered image, one sample");
     static_assert(layout_is_uniform<D>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
 
-    __shared__ u32x4 s_img[2 * IMG_U4];           // bf16 [4][IN_H][IN_W]
-    __shared__ u32x4 s_dy[2 * DYB / 16];          // d(pre1), bf16 [2][RPAD][32]
+    __shared__ u32x4 s_img[8 * PLANE_U4];         // bf16 [4][IN_H][IN_W]
+    __shared__ u32x4 s_dy[2 * DYB / 16];          // d(pre1), bf16 [2][RPAD][32], rows laid out by dy1_offset
     __shared__ u32x4 s_g[D::IMG / 16];            // bordered d(pre2) image
-    __shared__ uint32_t s_mask[MWORDS];
+    __shared__ uint32_t s_mask[MWORDS];           // word p: the 32 sign bits of act1 at position p
     __shared__ int s_win[TABLE ? RPAD : 1];       // byte offset of the window origin of output position m in s_img
-    static_assert(sizeof(u32x4) * 2 * IMG_U4 + 2 * DYB + D::IMG + 4 * MWORDS + 4 * (TABLE ? RPAD : 1) <= 160 * 1024,
+    static_assert(sizeof(u32x4) * 8 * PLANE_U4 + 2 * DYB + D::IMG + 4 * MWORDS + 4 * (TABLE ? RPAD : 1) <= 160 * 1024,
                   "LDS budget");
-    static_assert(8 * 16 * 64 * 4 * (KSPLIT - 1) <= (int)sizeof(u32x4) * 2 * IMG_U4, "scratch for the split contraction");
-    static_assert(S::NWD * 16 * C1 * 4 <= DYB, "bias-gradient scratch");
+    static_assert(4 * 16 * C1 * 4 <= DYB, "bias-gradient scratch");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    const bool producer = wave >= NWW;
+    const bool producer = wave >= 4;
     const int s_begin = blockIdx.x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
@@ -102,85 +96,19 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
     if constexpr (TABLE)
         for (int m = tid; m < RPAD; m += NT) s_win[m] = window(m);
 
-    // Prefetch registers and one persistent pointer per load (advanced by a sample after every use): the loads
-    // of consecutive samples need no address arithmetic in registers that an earlier load may still be filling.
-    u32x4 rimg[NI], rg[NG];
-    uint32_t rm = 0;
-    const u32x4 *pimg[NI], *pg[NG];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int idx = tid + NT * i;
-        pimg[i] = reinterpret_cast<const u32x4 *>(obs + (size_t)s_begin * OBS_BYTES) + (idx < IMG_U4 ? idx : IMG_U4 - 1);
-    }
-#pragma unroll
-    for (int i = 0; i < NG; ++i) {
-        const int idx = tid + NT * i;
-        pg[i] = reinterpret_cast<const u32x4 *>(dy2 + (size_t)s_begin * D::SRC_PIX * CI) + (idx < NQ ? idx : NQ - 1);
-    }
-    const uint32_t *pm = reinterpret_cast<const uint32_t *>(mask1 + (size_t)s_begin * (MWORDS * 4)) + (tid < MWORDS ? tid : MWORDS - 1);
-    auto gload_img = [&]() __attribute__((always_inline)) {     // the next frame in sequence
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            rimg[i] = *pimg[i];
-            pimg[i] += OBS_BYTES / 16;
-        }
-    };
-    auto gload_g = [&]() __attribute__((always_inline)) {       // the next sample's d(pre2) and mask words
-#pragma unroll
-        for (int i = 0; i < NG; ++i) {
-            rg[i] = *pg[i];
-            pg[i] += D::SRC_PIX * CI * 2 / 16;
-        }
-        rm = *pm;
-        pm += MWORDS;
-    };
     char *const img = reinterpret_cast<char *>(s_img);
     char *const dyl = reinterpret_cast<char *>(s_dy);
     char *const gl = reinterpret_cast<char *>(s_g);
-    auto stage_img = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int idx = tid + NT * i;
-            if (idx < IMG_U4) {
-                s_img[2 * idx] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
-                s_img[2 * idx + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
-            }
-        }
-    };
-    auto stage_g = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < NG; ++i) {
-            const int q = tid + NT * i;
-            if (q < NQ) {
-                const int p = q / NCH, c = q - p * NCH;
-                *reinterpret_cast<u32x4 *>(gl + D::dst_off(p) + c * 16) = rg[i];
-            }
-        }
-        if (tid < MWORDS) s_mask[tid] = rm;
-    };
-
-    gload_g();
-    gload_img();
-
-    // Both roles run the same sequence of barriers: the prologue's two, two per sample (next function), and
-    // the three of the epilogue.
-    auto next_sample = [&](int s) __attribute__((always_inline)) {
-        // d(pre1) of s is complete in its buffer; the contraction of s-1 has read s_img and the other buffer;
-        // the producers are done with the d(pre2) image of s
-        __syncthreads();
-        stage_img();
-        if (s + 1 < s_end) stage_g();
-        __syncthreads();
-        if (s + 1 < s_end) gload_img();
-        if (s + 2 < s_end) gload_g();
-    };
     float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
-    float *xch = reinterpret_cast<float *>(s_img);     // epilogue scratch
-    float *red = reinterpret_cast<float *>(s_dy);
+    float *red = reinterpret_cast<float *>(s_dy);      // epilogue scratch
 
+    // Both roles run the same sequence of barriers: two in the prologue, two per sample, two in the epilogue.
+    // Every global load of the sample loop has a persistent pointer, advanced by a sample after each use, so that
+    // the prefetch needs no address arithmetic in registers that an earlier load may still be filling.
     if (producer) {
-        // phase = (wavefront - NWW) % 4: 32 channels, all k of their weights as A-operand fragments
-        const int phase = (wave - NWW) & 3, dpart = (wave - NWW) >> 2;
+        const int ptid = tid - NR;
+        // phase = (wavefront - 4): 32 channels, all k of their weights as A-operand fragments
+        const int phase = wave - 4;
         bf16x8 wd[CT][KS];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
@@ -188,6 +116,49 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) wd[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w2d + row + 32 * ks));
         }
+        // d(pre2) and mask words of consecutive samples
+        u32x4 rg[NG];
+        uint32_t rm[NM];
+        const u32x4 *pg[NG];
+        const uint32_t *pm[NM];
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+            const int idx = ptid + NR * i;
+            pg[i] = reinterpret_cast<const u32x4 *>(dy2 + (size_t)s_begin * D::SRC_PIX * CI) + (idx < NQ ? idx : NQ - 1);
+        }
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            const int idx = ptid + NR * i;
+            pm[i] = reinterpret_cast<const uint32_t *>(mask1 + (size_t)s_begin * (MWORDS * 4)) + (idx < MWORDS ? idx : MWORDS - 1);
+        }
+        auto gload_g = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < NG; ++i) {
+                rg[i] = *pg[i];
+                pg[i] += D::SRC_PIX * CI * 2 / 16;
+            }
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                rm[i] = *pm[i];
+                pm[i] += MWORDS;
+            }
+        };
+        auto stage_g = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < NG; ++i) {
+                const int q = ptid + NR * i;
+                if (q < NQ) {
+                    const int p = q / NCH, c = q - p * NCH;
+                    *reinterpret_cast<u32x4 *>(gl + D::dst_off(p) + c * 16) = rg[i];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                const int q = ptid + NR * i;
+                if (q < MWORDS) s_mask[q] = rm[i];
+            }
+        };
+        gload_g();
         wait_global_loads();
         // bias gradient: what this lane writes into d(pre1), channels ct*16 + 4*lg + r, added in fp32
         float bs[CT][4];
@@ -196,25 +167,23 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
 #pragma unroll
             for (int r = 0; r < 4; ++r) bs[ct][r] = 0.f;
 
-        // This wavefront's position tiles t = dpart + j * DPARTS (the last may not exist): per-lane addresses that do
-        // not depend on the sample -- fragment base in the d(pre2) image, where channels ct*16 + 4*lg .. + 3 of the
-        // lane's position land in a d(pre1) buffer (-1: padded row or outside the map), and the byte of mask bits.
-        constexpr int NTW = (DT + S::DPARTS - 1) / S::DPARTS, KH = KS / 2;
-        int t_base[NTW], t_dst[NTW][CT], t_mask[NTW];
+        // Per-lane addresses of the position tiles, which do not depend on the sample: fragment base in the d(pre2)
+        // image, where channels ct*16 + 4*lg .. + 3 of the lane's position land in a d(pre1) buffer (-1: padded row
+        // or outside the map), and the position's mask word.
+        int t_base[DT], t_dst[DT][CT], t_mask[DT];
 #pragma unroll
-        for (int j = 0; j < NTW; ++j) {
-            const int t = dpart + j * S::DPARTS < DT ? dpart + j * S::DPARTS : DT - 1;
+        for (int t = 0; t < DT; ++t) {
             int row = t * 16 + li;
-            const bool valid = row < D::P && dpart + j * S::DPARTS < DT;
-            row = row < D::P ? row : D::P - 1;            // padded rows recompute the last one; never stored
+            const bool valid = row < D::P;
+            row = valid ? row : D::P - 1;                 // padded rows recompute the last one; never stored
             const int pix = valid ? D::out_pixel(row, phase) : -1;
-            t_base[j] = D::base_off(row) + 16 * lg;
+            t_base[t] = D::base_off(row) + 16 * lg;
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) t_dst[j][ct] = pix < 0 ? -1 : dy1_offset(pix, (ct * 16 + 4 * lg) * 2);
-            t_mask[j] = pix < 0 ? 0 : pix;                // the position's 32 sign bits are one word of s_mask
+            for (int ct = 0; ct < CT; ++ct) t_dst[t][ct] = pix < 0 ? -1 : dy1_offset(pix, (ct * 16 + 4 * lg) * 2);
+            t_mask[t] = pix < 0 ? 0 : pix;
         }
         // The fragment reads are pipelined by half-tiles: the second half of a tile's k-steps is in flight during
-        // the MFMAs of the first, the first half of the next tile (and its mask bytes) during those of the second.
+        // the MFMAs of the first, the first half of the next tile (and its mask word) during those of the second.
         auto load_half = [&](int base, int half, bf16x8 (&f)[KH]) __attribute__((always_inline)) {
 #pragma unroll
             for (int jk = 0; jk < KH; ++jk) {
@@ -237,37 +206,35 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
             load_half(t_base[0], 0, fa);
             mk = s_mask[t_mask[0]];
 #pragma unroll
-            for (int j = 0; j < NTW; ++j) {
-                if (dpart + j * S::DPARTS < DT) {             // wavefront-uniform
-                    const int jn = j + 1 < NTW ? j + 1 : j;   // a tile that does not exist repeats the last one's reads
-                    f32x4 da[CT];
+            for (int t = 0; t < DT; ++t) {
+                const int tn = t + 1 < DT ? t + 1 : t;        // the last tile repeats its own reads
+                f32x4 da[CT];
 #pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) da[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    load_half(t_base[j], 1, fb);
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfma_half(0, fa, da);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_half(t_base[jn], 0, fa);
-                    mk_next = s_mask[t_mask[jn]];
-                    __builtin_amdgcn_sched_barrier(0);
-                    mfma_half(1, fb, da);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (t_dst[j][0] >= 0) {
+                for (int ct = 0; ct < CT; ++ct) da[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                load_half(t_base[t], 1, fb);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_half(0, fa, da);
+                __builtin_amdgcn_sched_barrier(0);
+                load_half(t_base[tn], 0, fa);
+                mk_next = s_mask[t_mask[tn]];
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_half(1, fb, da);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t_dst[t][0] >= 0) {
 #pragma unroll
-                        for (int ct = 0; ct < CT; ++ct) {
-                            const int m = (int)(mk >> (ct * 16 + 4 * lg));   // bit r: channel ct*16 + 4*lg + r
-                            float v[4];
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const int m = (int)(mk >> (ct * 16 + 4 * lg));   // bit r: channel ct*16 + 4*lg + r
+                        float v[4];
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) {     // bit r of m set: keep the value (all-ones mask), else zero
-                                const float x = da[ct][r];
-                                v[r] = __int_as_float(__float_as_int(x) & -((m >> r) & 1));
-                                bs[ct][r] += v[r];
-                            }
-                            *reinterpret_cast<u32x2 *>(dst + t_dst[j][ct]) = pack_bf16x4(v[0], v[1], v[2], v[3]);
+                        for (int r = 0; r < 4; ++r) {         // bit r set: keep the value (AND with all ones), else zero
+                            const float x = da[ct][r];
+                            v[r] = __int_as_float(__float_as_int(x) & -((m >> r) & 1));
+                            bs[ct][r] += v[r];
                         }
+                        *reinterpret_cast<u32x2 *>(dst + t_dst[t][ct]) = pack_bf16x4(v[0], v[1], v[2], v[3]);
                     }
-                    mk = mk_next;
                 }
+                mk = mk_next;
             }
         };
 
@@ -278,26 +245,56 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
         produce(dyl);                                 // first sample: its d(pre1) before the loop
         int cur = 0;
         for (int s = s_begin; s < s_end; ++s) {
-            next_sample(s);
+            // d(pre1) of s is complete in buffer cur; the contraction of s-1 has read the other buffer; all producers
+            // are done with the d(pre2) image of s
+            __syncthreads();
+            if (s + 1 < s_end) stage_g();
+            __syncthreads();
+            if (s + 2 < s_end) gload_g();
             if (s + 1 < s_end) produce(dyl + (cur ^ 1) * DYB);
             cur ^= 1;
         }
         __syncthreads();
-        if constexpr (KSPLIT == 2) __syncthreads();
         // bias gradient: channel c = ct*16 + 4*lg + r is held by lanes (li = 0..15, lg) of all producers
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[((wave - NWW) * 16 + li) * C1 + ct * 16 + 4 * lg + r] = bs[ct][r];
+            for (int r = 0; r < 4; ++r) red[(phase * 16 + li) * C1 + ct * 16 + 4 * lg + r] = bs[ct][r];
         __syncthreads();
     } else {
-        // wavefront w owns column tiles (w % (8/TX)) * TX .. + TX - 1 and contraction steps w / (8/TX) + KSPLIT * j
+        // wavefront w: input channel w, i.e. column tiles 2w (kernel rows 0-3) and 2w+1 (rows 4-7) of dW1, and the
+        // channel's plane of the image
         f32x16 acc[TX];
 #pragma unroll
         for (int b = 0; b < TX; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
-        const int tile0 = (wave % (8 / TX)) * TX, kpart = wave / (8 / TX);
+        u32x4 rimg[NI];
+        const u32x4 *pimg[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int idx = lane + 64 * i;
+            pimg[i] = reinterpret_cast<const u32x4 *>(obs + (size_t)s_begin * OBS_BYTES) + wave * PLANE_U4 +
+                      (idx < PLANE_U4 ? idx : PLANE_U4 - 1);
+        }
+        auto gload_plane = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                rimg[i] = *pimg[i];
+                pimg[i] += OBS_BYTES / 16;
+            }
+        };
+        auto stage_plane = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int idx = lane + 64 * i;
+                if (idx < PLANE_U4) {
+                    s_img[2 * (wave * PLANE_U4 + idx)] = u8x8_to_bf16x8(rimg[i].x, rimg[i].y);
+                    s_img[2 * (wave * PLANE_U4 + idx) + 1] = u8x8_to_bf16x8(rimg[i].z, rimg[i].w);
+                }
+            }
+        };
+        gload_plane();
         const int o = lane & 15, Gq = lane >> 4;
         const int row_in_step = 8 * (Gq >> 1) + (o >> 2);          // + 4 for the second read
         const int ycol_off = (16 * (Gq & 1) + 4 * (o & 3)) * 2;    // byte offset inside a d(pre1) row
@@ -308,20 +305,19 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
         // byte offset of (ci, ky, kx0) for column tile t = ci*2 + upper/lower four kernel rows
         int xoff[TX];
 #pragma unroll
-        for (int b = 0; b < TX; ++b) {
-            const int t = tile0 + b;
-            xoff[b] = (((t >> 1) * IN_H + (t & 1) * 4 + ky_lane) * IN_W + kx0) * 2;
-        }
-        __syncthreads();                              // zero fill done
-        stage_g();
+        for (int b = 0; b < TX; ++b) xoff[b] = ((wave * IN_H + b * 4 + ky_lane) * IN_W + kx0) * 2;
+
+        __syncthreads();                              // zero fill and window table done
+        stage_plane();                                // nobody else touches this plane
         __syncthreads();
-        if (s_begin + 1 < s_end) gload_g();
+        if (s_begin + 1 < s_end) gload_plane();
         int cur = 0;
         for (int s = s_begin; s < s_end; ++s) {
-            next_sample(s);
+            __syncthreads();                          // d(pre1) of s is complete
+            __syncthreads();                          // (the producers' staging barrier)
             const char *src = dyl + cur * DYB;
 #pragma unroll 5
-            for (int ks = kpart; ks < KSTEPS; ks += KSPLIT) {
+            for (int ks = 0; ks < KSTEPS; ++ks) {
                 const int ma = 16 * ks + row_in_step, mb = ma + 4;
                 const int pa = TABLE ? s_win[ma] : window(ma), pb = TABLE ? s_win[mb] : window(mb);
                 const int flip = (ks & 1) << 7;
@@ -332,31 +328,19 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
                     acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy, fx, acc[b], 0, 0, 0);
                 }
             }
+            if (s + 1 < s_end) stage_plane();         // the plane of s+1: this wavefront's reads of s are done
+            if (s + 2 < s_end) gload_plane();
             cur ^= 1;
         }
         __syncthreads();
-        // two wavefronts per tile group: the second hands its sums over through LDS
-        if constexpr (KSPLIT == 2) {
-            if (kpart == 1) {
+        const int fr = lane & 31, fg = lane >> 5;
 #pragma unroll
-                for (int b = 0; b < TX; ++b)
+        for (int b = 0; b < TX; ++b) {
+            const int k = (wave * TX + b) * 32 + fr;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) xch[((tile0 + b) * 16 + r) * 64 + lane] = acc[b][r];
-            }
-            __syncthreads();
-        }
-        if (kpart == 0) {
-            const int fr = lane & 31, fg = lane >> 5;
-#pragma unroll
-            for (int b = 0; b < TX; ++b) {
-                const int k = (tile0 + b) * 32 + fr;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int n = 8 * (r >> 2) + 4 * fg + (r & 3);
-                    float v = acc[b][r];
-                    if constexpr (KSPLIT == 2) v += xch[((tile0 + b) * 16 + r) * 64 + lane];
-                    out[n * KW1 + k] = v;
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int n = 8 * (r >> 2) + 4 * fg + (r & 3);
+                out[n * KW1 + k] = acc[b][r];
             }
         }
         __syncthreads();
@@ -364,7 +348,7 @@ __global__ __launch_bounds__(S::THREADS) void conv1_bwd_fused_kernel(const uint8
     // bias gradient: the producers' lane sums, added in a fixed order
     if (tid < C1) {
         float t = red[tid];
-        for (int g = 1; g < S::NWD * 16; ++g) t += red[g * C1 + tid];
+        for (int g = 1; g < 4 * 16; ++g) t += red[g * C1 + tid];
         out[C1 * KW1 + tid] = t;
     }
 }
