@@ -27,7 +27,8 @@ KERNEL_FLOPS = {  # per sample, by instrumented kernel name
     "fc_wgrad": 2 * MACS["fc"], "head_wgrad": 2 * MACS["head_pv"],
     "conv2_dgrad": 2 * MACS["conv2"], "conv3_dgrad": 2 * MACS["conv3"], "fc_dgrad": 2 * MACS["fc"],
     "head_dgrad": 2 * MACS["head_pv"],
-    "conv1_bwd": 2 * MACS["conv2"] + 2 * MACS["conv1"],   # conv2 input gradient + conv1 weight gradient, one kernel
+    # conv2 input gradient + conv1 weight gradient + conv2 and conv3 weight gradients, one launch
+    "conv_bwd": 2 * MACS["conv2"] + 2 * MACS["conv1"] + 2 * MACS["conv2"] + 2 * MACS["conv3"],
 }
 # algorithmic HBM bytes per sample: every bf16 activation / gradient tensor written once and read once,
 # observations read as uint8 (weights and the flat gradient are per-launch constants, added below)
@@ -39,13 +40,14 @@ KERNEL_BYTES = {
     "fc_wgrad": ACT["a3"] + ACT["h"], "head_wgrad": ACT["h"] + ACT["z"],
     "conv2_dgrad": ACT["a2"] + 2 * ACT["a1"], "conv3_dgrad": ACT["a3"] + 2 * ACT["a2"],
     "fc_dgrad": ACT["h"] + 2 * ACT["a3"], "head_dgrad": ACT["z"] + 2 * ACT["h"],
-    "conv1_bwd": ACT["a2"] + ACT["obs"],                  # d(pre1) stays on chip
+    # d(pre1) stays on chip; d(pre2) is read by two of the three parts
+    "conv_bwd": ACT["a2"] + ACT["obs"] + ACT["a1"] + ACT["a2"] + ACT["a2"] + ACT["a3"],
 }
 KERNEL_BYTES_PER_LAUNCH = {  # bf16 weights read (forward / input gradient) or fp32 gradient written (weight gradient)
     "conv1_fwd": 2 * 8192, "conv2_fwd": 2 * 32768, "conv3_fwd": 2 * 36864, "fc_fwd": 2 * 1605632, "head_fwd": 2 * 9728,
     "conv2_dgrad": 2 * 32768, "conv3_dgrad": 2 * 36864, "fc_dgrad": 2 * 1605632, "head_dgrad": 2 * 9728,
     "conv1_wgrad": 4 * 8192, "conv2_wgrad": 4 * 32768, "conv3_wgrad": 4 * 36864, "fc_wgrad": 4 * 1605632,
-    "head_wgrad": 4 * 9728, "conv1_bwd": 2 * 32768 + 4 * 8192,
+    "head_wgrad": 4 * 9728, "conv_bwd": 2 * 32768 + 4 * 8192 + 4 * 32768 + 4 * 36864,
 }
 # whole step, per sample: the forward's bytes, then observations again, saved activations once, and every
 # activation gradient written and read once

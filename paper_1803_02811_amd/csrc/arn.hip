@@ -14,7 +14,7 @@
 #include "arn_pv_head.h"
 #include "arn_resident.h"
 #include "arn_resident_conv.h"
-#include "arn_conv1_bwd.h"
+#include "arn_conv_bwd.h"
 #include "arn_small_kernels.h"
 #include "arn_update.h"
 
@@ -300,25 +300,19 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
         launch_resident<typename Cfg::Dgrad3>("conv3_dgrad", p, B, s);
     }
     {
-        // conv2's input gradient feeds only conv1's weight gradient (conv1's input is data): one kernel, in which
-        // d(pre1) stays in LDS
-        ProfScope ps("conv1_bwd", s);
-        hipLaunchKernelGGL((conv1_bwd_fused_kernel<G, typename Cfg::Dgrad2>), dim3(sp.c1), dim3(C1B_THREADS), 0, s, obs,
-                           dp2, w.w2d, (const uint8_t *)(ws + o.m1), part1, B, resident_spw(B, 256));
-    }
-    {
-        ProfScope ps("conv2_wgrad", s);
-        const int groups = (B + CONV2_WG_G - 1) / CONV2_WG_G;
-        hipLaunchKernelGGL((conv_wgrad_resident_kernel<C1, G::H1, G::W1, K2, S2, G::PAD2, G::H2, G::W2, C2, CONV2_WG_G, 2>),
-                           dim3(sp.c2), dim3(CW_THREADS), 0, s, a1, dp2, part2, B,
-                           resident_spw(groups, WGRAD_WGS) * CONV2_WG_G);
-    }
-    {
-        ProfScope ps("conv3_wgrad", s);
-        const int groups = (B + CONV3_WG_G - 1) / CONV3_WG_G;
-        hipLaunchKernelGGL((conv_wgrad_resident_kernel<C2, G::H2, G::W2, K3, S3, G::PAD3, G::H3, G::W3, C3, CONV3_WG_G, 2>),
-                           dim3(sp.c3), dim3(CW_THREADS), 0, s, a2, dp3, part3, B,
-                           resident_spw(groups, WGRAD_WGS) * CONV3_WG_G);
+        // One launch for everything that is left once d(pre2) exists: conv2's input gradient fused with conv1's
+        // weight gradient (conv1's input is data, so d(pre1) has this one consumer and stays in LDS), and the
+        // weight gradients of conv2 and conv3 -- three ranges of workgroups, longest first.
+        ProfScope ps("conv_bwd", s);
+        ConvBackwardArgs p;
+        p.obs = obs; p.dp2 = dp2; p.w2d = w.w2d; p.mask1 = (const uint8_t *)(ws + o.m1); p.part1 = part1;
+        p.a1 = a1; p.a2 = a2; p.dp3 = dp3; p.part2 = part2; p.part3 = part3;
+        p.B = B; p.n1 = sp.c1; p.n2 = sp.c2;
+        p.spw1 = resident_spw(B, 256);
+        p.spw2 = resident_spw((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS) * CONV2_WG_G;
+        p.spw3 = resident_spw((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS) * CONV3_WG_G;
+        hipLaunchKernelGGL((conv_backward_kernel<G, typename Cfg::Dgrad2>), dim3(sp.c1 + sp.c2 + sp.c3),
+                           dim3(ConvBackward<G, typename Cfg::Dgrad2>::THREADS), 0, s, p);
     }
     {
         // one launch adds the partials of all three convolutions (x = u8/255: conv1's pixel scale comes out of

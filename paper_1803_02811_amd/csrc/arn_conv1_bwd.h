@@ -36,18 +36,25 @@ __device__ __forceinline__ constexpr int dy1_offset(int row, int byte) {
     return (row >> 2) * 256 + ((((row & 3) * 2 + (byte >> 5) + (row >> 2)) & 7) << 5) + (byte & 31);
 }
 
+// LDS bytes of conv1_bwd_fused_body<Geo, D>
+template <class Geo, class D>
+constexpr int conv1_bwd_lds_bytes() {
+    constexpr int RPAD = (Geo::P1 + 15) / 16 * 16;
+    return 8 * Geo::IN_H * Geo::IN_W + 2 * RPAD * C1 * 2 + D::IMG + Geo::P1 * C1 / 8 + (80 % Geo::W1 != 0 ? RPAD : 4) * 4;
+}
+
+// The work of workgroup `block` (of C1B_THREADS threads) in the caller's LDS buffer `lds`.
 // Geo: frame geometry; D: the description of conv2's input gradient (ResConv2Dgrad / ResConv2DgradGeo: the
 // d(pre2) image of one sample).  obs u8 [B][4][IN_H][IN_W]; dy2 = d(pre2) bf16 [B][P2][64]; w2d: the packed
 // input-gradient weights [phase*32 + ci][(ty*2 + tx)*64 + co]; mask1: sign bits of act1 (P1*32/8 bytes per sample).
 template <class Geo, class D>
-__global__ __launch_bounds__(C1B_THREADS) void conv1_bwd_fused_kernel(const uint8_t *__restrict__ obs,
-                                                                      const __bf16 *__restrict__ dy2,
-                                                                      const __bf16 *__restrict__ w2d,
-                                                                      const uint8_t *__restrict__ mask1,
-                                                                      float *__restrict__ part, int B, int spw) {
+__device__ __forceinline__ void conv1_bwd_fused_body(u32x4 *lds, int block, const uint8_t *__restrict__ obs,
+                                                     const __bf16 *__restrict__ dy2, const __bf16 *__restrict__ w2d,
+                                                     const uint8_t *__restrict__ mask1, float *__restrict__ part, int B,
+                                                     int spw) {
     constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
     constexpr int NT = C1B_THREADS, NR = NT / 2;                 // threads in all, and per role
-    // consumer side (a weight-gradient contraction over the P1 positions, as in conv_wgrad_resident_kernel)
+    // consumer side (a weight-gradient contraction over the P1 positions, as in conv_wgrad_resident_body)
     constexpr int PLANE_U4 = IN_H * IN_W / 16;                   // one input channel of the frame, 16 pixels per word
     constexpr int NI = (PLANE_U4 + 63) / 64;                     // words per lane of the wavefront that owns the plane
     constexpr int KSTEPS = (P1 + 15) / 16, RPAD = KSTEPS * 16;   // contraction steps; d(pre1) rows P1..RPAD stay zero
@@ -64,20 +71,21 @@ __global__ __launch_bounds__(C1B_THREADS) void conv1_bwd_fused_kernel(const uint
     static_assert((P1 * C1) % 32 == 0, "whole mask words per sample");
     static_assert(!D::SPLIT && D::ZERO_FILL && D::G == 1, "single-product input gradient over a zero-bordered image, one sample");
     static_assert(layout_is_uniform<D>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
-
-    __shared__ u32x4 s_img[8 * PLANE_U4];         // bf16 [4][IN_H][IN_W]
-    __shared__ u32x4 s_dy[2 * DYB / 16];          // d(pre1), bf16 [2][RPAD][32], rows laid out by dy1_offset
-    __shared__ u32x4 s_g[D::IMG / 16];            // bordered d(pre2) image
-    __shared__ uint32_t s_mask[MWORDS];           // word p: the 32 sign bits of act1 at position p
-    __shared__ int s_win[TABLE ? RPAD : 1];       // byte offset of the window origin of output position m in s_img
-    static_assert(sizeof(u32x4) * 8 * PLANE_U4 + 2 * DYB + D::IMG + 4 * MWORDS + 4 * (TABLE ? RPAD : 1) <= 160 * 1024,
-                  "LDS budget");
+    static_assert(D::IMG % 16 == 0 && DYB % 16 == 0, "16-byte aligned LDS regions");
+    static_assert(conv1_bwd_lds_bytes<Geo, D>() == 8 * PLANE_U4 * 16 + 2 * DYB + D::IMG + 4 * MWORDS + 4 * (TABLE ? RPAD : 4) &&
+                      conv1_bwd_lds_bytes<Geo, D>() <= 160 * 1024, "LDS budget");
     static_assert(4 * 16 * C1 * 4 <= DYB, "bias-gradient scratch");
+
+    u32x4 *const s_img = lds;                                    // bf16 [4][IN_H][IN_W]
+    u32x4 *const s_dy = s_img + 8 * PLANE_U4;                    // d(pre1), bf16 [2][RPAD][32], rows laid out by dy1_offset
+    u32x4 *const s_g = s_dy + 2 * DYB / 16;                      // bordered d(pre2) image
+    uint32_t *const s_mask = reinterpret_cast<uint32_t *>(s_g + D::IMG / 16);   // word p: the 32 sign bits of act1 at position p
+    int *const s_win = reinterpret_cast<int *>(s_mask + MWORDS); // byte offset of the window origin of output position m in s_img
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
     const bool producer = wave >= 4;
-    const int s_begin = blockIdx.x * spw;
+    const int s_begin = block * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
 
@@ -99,7 +107,7 @@ __global__ __launch_bounds__(C1B_THREADS) void conv1_bwd_fused_kernel(const uint
     char *const img = reinterpret_cast<char *>(s_img);
     char *const dyl = reinterpret_cast<char *>(s_dy);
     char *const gl = reinterpret_cast<char *>(s_g);
-    float *out = part + (size_t)blockIdx.x * (C1 * KW1 + C1);
+    float *out = part + (size_t)block * (C1 * KW1 + C1);
     float *red = reinterpret_cast<float *>(s_dy);      // epilogue scratch
 
     // Both roles run the same sequence of barriers: two in the prologue, two per sample, two in the epilogue.

@@ -33,10 +33,19 @@ __device__ __forceinline__ bf16x8 tr_pair(const char *lds_base, int off_a, int o
 // by one transposing read fall into different banks.  WAVES_Y wavefronts split
 // the COUT/32 row tiles, the others split the column tiles.
 constexpr int CW_THREADS = 512;   // eight wavefronts, two per SIMD: one hides the other's LDS latency
+
+// LDS bytes of conv_wgrad_resident_body with the same parameters
+template <int CIN, int HIN, int WIN, int KS, int STRIDE, int PAD, int HOUT, int WOUT, int COUT, int G>
+constexpr int conv_wgrad_lds_bytes() {
+    constexpr int RPAD = (G * HOUT * WOUT + 15) / 16 * 16;
+    return G * (HIN + 2 * PAD) * (WIN + 2 * PAD) * (CIN * 2 + 16) + RPAD * (COUT * 2 + 16) + RPAD * 4;
+}
+
+// The work of workgroup `block` (of 512 threads) in the caller's LDS buffer `lds`.
 template <int CIN, int HIN, int WIN, int KS, int STRIDE, int PAD, int HOUT, int WOUT, int COUT, int G, int WAVES_Y>
-__global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const __bf16 *__restrict__ x,
-                                                                  const __bf16 *__restrict__ dy,
-                                                                  float *__restrict__ part, int B, int spw) {
+__device__ __forceinline__ void conv_wgrad_resident_body(u32x4 *lds, int block, const __bf16 *__restrict__ x,
+                                                         const __bf16 *__restrict__ dy, float *__restrict__ part, int B,
+                                                         int spw) {
     constexpr int PIX = HIN * WIN, P = HOUT * WOUT, KP = KS * KS * CIN;
     constexpr int HP = HIN + 2 * PAD, WP = WIN + 2 * PAD, PIXP = HP * WP;   // LDS image with its zero border
     constexpr int PS = CIN * 2 + 16, YS = COUT * 2 + 16;            // padded strides in bytes
@@ -49,15 +58,17 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
     constexpr int TY = NY / WAVES_Y, TX = (NX + WAVES_X - 1) / WAVES_X;   // the last wavefront along x may own fewer column tiles
     static_assert(NY % WAVES_Y == 0, "tile split");
     static_assert(NT % YCH == 0 && (NT / YCH) * COUT * 4 <= RPAD * YS, "bias-gradient scratch");
+    static_assert((G * PIXP * PS) % 16 == 0 && (RPAD * YS) % 16 == 0, "16-byte aligned LDS regions");
+    static_assert(conv_wgrad_lds_bytes<CIN, HIN, WIN, KS, STRIDE, PAD, HOUT, WOUT, COUT, G>() == G * PIXP * PS + RPAD * YS + RPAD * 4 &&
+                      G * PIXP * PS + RPAD * YS + RPAD * 4 <= 160 * 1024, "LDS budget");
 
-    __shared__ u32x4 s_x[G * PIXP * PS / 16];
-    __shared__ u32x4 s_dy[RPAD * YS / 16];
-    __shared__ int s_win[RPAD];     // byte offset of the window origin of contraction row m in s_x
-    static_assert((G * PIXP * PS + RPAD * YS + RPAD * 4) <= 160 * 1024, "LDS budget");
+    u32x4 *const s_x = lds;                              // [G * PIXP] pixels of PS bytes
+    u32x4 *const s_dy = lds + G * PIXP * PS / 16;        // [RPAD] rows of YS bytes
+    int *const s_win = reinterpret_cast<int *>(lds + (G * PIXP * PS + RPAD * YS) / 16);   // [RPAD]: byte offset of the window origin of contraction row m in s_x
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wy = wave % WAVES_Y, wx = wave / WAVES_Y;
-    const int s_begin = blockIdx.x * spw;
+    const int s_begin = block * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
 
     // window origins do not depend on the sample: tabulated once instead of two divisions per row and k-step
@@ -162,7 +173,7 @@ __global__ __launch_bounds__(CW_THREADS) void conv_wgrad_resident_kernel(const _
         }
     }
 
-    float *out = part + (size_t)blockIdx.x * (COUT * KP + COUT);
+    float *out = part + (size_t)block * (COUT * KP + COUT);
     const int fr = lane & 31, fg = lane >> 5;
 #pragma unroll
     for (int a = 0; a < TY; ++a)
