@@ -1,5 +1,5 @@
-// Weight-gradient kernel (conv2, conv3) that keeps a few samples' operands resident in LDS; conv1's weight
-// gradient uses the same contraction inside conv1_bwd_fused_kernel.
+// Weight gradient of conv2 / conv3 with a few samples' operands resident in LDS (a workgroup body, launched by
+// conv_backward_kernel); conv1's weight gradient uses the same contraction inside conv1_bwd_fused_body.
 //
 // dW[co][k'] = sum over samples and output positions m of dY[m][co] * x(m,k').
 // The contraction index m is the slow index of both operands in memory, so both
@@ -9,7 +9,7 @@
 // transposing reads address the overlapping windows inside that image directly.
 // Each workgroup owns a fixed, contiguous range of samples and accumulates in
 // registers; partial results go to part[workgroup][...] and are summed in
-// workgroup order by reduce_partials_kernel, so dW is bit-reproducible.
+// workgroup order by conv_reduce_kernel, so dW is bit-reproducible.
 #pragma once
 #include "arn_gemm.h"
 #include "arn_layout.h"

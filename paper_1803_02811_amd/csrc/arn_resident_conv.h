@@ -549,7 +549,7 @@ struct ResConv3Dgrad {
 // are the 4 x 32 "channels" of one 2x2 stride-1 convolution over the padded
 // image with 10x10 positions (u,v); channel n = phase*32 + ci lands at act1
 // pixel (2u + phase/2, 2v + phase%2).  This is the image description only: the kernel that uses it
-// (conv1_bwd_fused_kernel) feeds d(pre1) straight into conv1's weight gradient, one sample per iteration.
+// (conv1_bwd_fused_body) feeds d(pre1) straight into conv1's weight gradient, one sample per iteration.
 struct ResConv2Dgrad {
     static constexpr int PADW = H2 + 2;   // 11
     static constexpr int CI = C2, SRC_PIX = P2, P = 100, HO = 10, CO = 4 * C1, K = 4 * C2, G = 1;
@@ -701,7 +701,7 @@ struct ResConv3DgradGeo {
 // input, (y + PAD2, x + PAD2) = (2u + py, 2v + px); the four phases (py,px) share their fragments, so they are
 // the 4 x 32 channels of one 2x2 stride-1 correlation over positions (u,v); channel n = phase*32 + ci lands at
 // act1 pixel (2u + py - PAD2, 2v + px - PAD2) if that is inside the map.  Image description for
-// conv1_bwd_fused_kernel, as ResConv2Dgrad.
+// conv1_bwd_fused_body, as ResConv2Dgrad.
 template <class Geo>
 struct ResConv2DgradGeo {
     static constexpr int U = ((Geo::H1 - 1 + Geo::PAD2) >> 1) + 1, V = ((Geo::W1 - 1 + Geo::PAD2) >> 1) + 1;
