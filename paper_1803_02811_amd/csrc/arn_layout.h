@@ -163,9 +163,10 @@ inline int pick_split(long rows, int tiles, int target_wgs) {
     if (s > iters) s = iters;
     return (int)s;
 }
-// workgroups of the conv2 / conv3 weight-gradient kernels: each writes a full fp32 partial of dW, so fewer
-// workgroups mean less partial traffic; they run on the side stream next to the input-gradient kernels
-constexpr int WGRAD_WGS = 256;
+// workgroups of the conv2 / conv3 weight gradients: each writes a full fp32 partial of dW, so fewer workgroups
+// mean less partial traffic (and a cheaper reduction).  The two are ranges of one grid (conv_backward_kernel) and
+// run side by side, so 128 + 128 workgroups of one per CU fill the 256 CUs.
+constexpr int WGRAD_WGS = 128;
 constexpr int CONV2_WG_G = 2, CONV3_WG_G = 4;   // samples staged per iteration by the conv2 / conv3 weight-gradient kernels
 // sample-resident weight-gradient kernels: samples per workgroup and number of workgroups
 inline int resident_spw(int B, int target_wgs) { return (B + target_wgs - 1) / target_wgs; }
