@@ -15,6 +15,7 @@
 #include "arn_resident.h"
 #include "arn_resident_conv.h"
 #include "arn_conv_bwd.h"
+#include "arn_conv23_fwd.h"
 #include "arn_small_kernels.h"
 #include "arn_update.h"
 
@@ -203,6 +204,9 @@ struct ConvConfigs {
     typedef ResConv3DgradGeo<G> Dgrad3;
     typedef ResConv2DgradGeo<G> Dgrad2;
     static int conv1_parts(int) { return 1; }
+    // conv2 -> conv3 through LDS needs both layers' images in one CU's LDS: not with the bordered images of this geometry
+    static bool fused_conv23(int) { return false; }
+    static void launch_conv23(const Conv23Args &, int, int, hipStream_t) {}
 };
 template <>
 struct ConvConfigs<Geo84> {
@@ -212,6 +216,12 @@ struct ConvConfigs<Geo84> {
     typedef ResConv2Dgrad Dgrad2;
     // few samples: three workgroups share one (one workgroup fits per CU)
     static int conv1_parts(int B) { return 3 * B <= 256 ? 3 : 1; }
+    // one workgroup per sample range and no tile splitting: for batches that give every CU at least a sample
+    static bool fused_conv23(int B) { return B >= 256; }
+    static void launch_conv23(const Conv23Args &p, int B, int spw, hipStream_t s) {
+        hipLaunchKernelGGL((conv23_fwd_fused_kernel<ResConv2Fwd, ResConv3Fwd>), dim3((B + spw - 1) / spw), dim3(C23_THREADS), 0,
+                           s, p, B, spw);
+    }
 };
 
 // Forward pass for geometry G in three-product bf16 precision (conv1's pixel operand is exact: two products).
@@ -227,17 +237,29 @@ void forward_trunk(const Dims &d, const Packed &w, const uint8_t *obs, int B, ch
         hipLaunchKernelGGL(conv1_fwd_resident_kernel<G>, dim3(cdiv(B, spw), Cfg::conv1_parts(B)), dim3(RES_THREADS), 0, s,
                            obs, w.w1, w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
-    {
-        typename Cfg::Fwd2::Args p;
-        p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
-        p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
-        launch_resident<typename Cfg::Fwd2>("conv2_fwd", p, B, s);
-    }
-    {
-        typename Cfg::Fwd3::Args p;
-        p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
-        p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
-        launch_resident<typename Cfg::Fwd3>("conv3_fwd", p, B, s);
+    static const bool unfused23 = getenv("ARN_UNFUSED_CONV23") != nullptr;
+    if (Cfg::fused_conv23(B) && !unfused23) {
+        // conv2 and conv3 in one kernel: act2 passes through LDS
+        ProfScope ps("conv23_fwd", s);
+        Conv23Args p;
+        p.a1 = a1; p.a1_lo = a1l; p.w2 = w.w2; p.w2_lo = w.w2l; p.w3 = w.w3; p.w3_lo = w.w3l; p.b2 = w.b2; p.b3 = w.b3;
+        p.a2 = masks ? a2 : nullptr; p.a3 = a3; p.a3_lo = a3l;
+        p.m2 = masks ? (uint8_t *)(ws + o.m2) : nullptr; p.m3 = masks ? (uint8_t *)(ws + o.m3) : nullptr;
+        const int spw = resident_spw(B, 256);
+        Cfg::launch_conv23(p, B, spw, s);
+    } else {
+        {
+            typename Cfg::Fwd2::Args p;
+            p.in = a1; p.in_lo = a1l; p.w = w.w2; p.w_lo = w.w2l; p.mask = nullptr; p.bias = w.b2; p.out = a2; p.out_lo = a2l;
+            p.mask_out = masks ? (uint8_t *)(ws + o.m2) : nullptr;
+            launch_resident<typename Cfg::Fwd2>("conv2_fwd", p, B, s);
+        }
+        {
+            typename Cfg::Fwd3::Args p;
+            p.in = a2; p.in_lo = a2l; p.w = w.w3; p.w_lo = w.w3l; p.mask = nullptr; p.bias = w.b3; p.out = a3; p.out_lo = a3l;
+            p.mask_out = masks ? (uint8_t *)(ws + o.m3) : nullptr;
+            launch_resident<typename Cfg::Fwd3>("conv3_fwd", p, B, s);
+        }
     }
     fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, zstride, s);
 }
