@@ -28,17 +28,18 @@ struct Conv23Args {
 // P2, P3: the LDS image descriptions of conv2 forward (one sample per iteration) and conv3 forward.
 template <class P2, class P3>
 __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Conv23Args a, int B, int spw) {
-    constexpr int NR = C23_THREADS / 2;                          // threads per role
     // conv2 (producers)
-    constexpr int CI2 = P2::CI, NCH2 = CI2 / 8, IMG2 = P2::IMG, KS2 = P2::K / 32, KH2 = KS2 / 4;   // k-steps in four parts: 32 fragment registers
+    constexpr int CI2 = P2::CI, NCH2 = CI2 / 8, IMG2 = P2::IMG, KS2 = P2::K / 32;
+    constexpr int PARTS2 = 8, KH2 = KS2 / PARTS2;                // a tile's k-steps in eight parts: two sets of 16 fragment registers
     constexpr int R2 = P2::P, NT2 = (R2 + 15) / 16;
-    constexpr int NQ2 = P2::SRC_PIX * NCH2, NL2 = (NQ2 + NR - 1) / NR;   // 16-byte chunks of a sample's act1, per part
+    constexpr int NQ2 = P2::SRC_PIX * NCH2, NL2 = (NQ2 + C23_THREADS - 1) / C23_THREADS;   // 16-byte chunks of a sample's act1, per part and per thread
     // conv3 (consumers), one sample per iteration
-    constexpr int CI3 = P3::CI, IMG3 = P3::IMG, KS3 = P3::K / 32, KH3 = KS3 / 2;
+    constexpr int CI3 = P3::CI, IMG3 = P3::IMG, KS3 = P3::K / 32;
+    constexpr int PARTS3 = 2, KH3 = KS3 / PARTS3;                // two halves of nine k-steps
     constexpr int R3 = P3::P, NT3 = (R3 + 15) / 16;
     static_assert(P2::G == 1 && P2::SPLIT && P3::SPLIT && !P2::ZERO_FILL && !P3::ZERO_FILL, "three-product layers without borders");
     static_assert(P2::CO == 64 && P3::CO == 64 && P2::CO == CI3 && P2::P == P3::SRC_PIX, "conv2's output is conv3's input");
-    static_assert(KS2 % 4 == 0 && KS3 % 2 == 0 && P2::PSB == CI2 * 2 + 32 && P3::PSB == CI3 * 2 + 32, "k-steps in two halves");
+    static_assert(KS2 % PARTS2 == 0 && PARTS2 % 2 == 0 && KS3 % PARTS3 == 0 && PARTS3 % 2 == 0 && P2::PSB == CI2 * 2 + 32 && P3::PSB == CI3 * 2 + 32, "k-steps in an even number of parts");
     static_assert(layout_is_uniform<P2>() && layout_is_uniform<P3>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
     static_assert(2 * IMG2 + 4 * IMG3 <= 160 * 1024 && IMG2 % 16 == 0 && IMG3 % 16 == 0, "LDS budget");
 
@@ -53,9 +54,41 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
 
+    // act1 of consecutive samples is prefetched and staged by all eight wavefronts: one persistent pointer per load,
+    // advanced by a sample after each use; the lo tensor is at a fixed distance from the hi tensor
+    u32x4 rh[NL2], rl[NL2];
+    const u32x4 *ph[NL2];
+    const ptrdiff_t lo_at = reinterpret_cast<const u32x4 *>(a.a1_lo) - reinterpret_cast<const u32x4 *>(a.a1);
+#pragma unroll
+    for (int i = 0; i < NL2; ++i) {
+        const int q = tid + C23_THREADS * i;
+        ph[i] = reinterpret_cast<const u32x4 *>(a.a1 + (size_t)s_begin * (NQ2 * 8) + (size_t)(q < NQ2 ? q : NQ2 - 1) * 8);
+    }
+    auto gload = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NL2; ++i) {
+            rh[i] = *ph[i];
+            rl[i] = *(ph[i] + lo_at);
+            ph[i] += NQ2;
+        }
+    };
+    auto stage = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NL2; ++i) {
+            const int q = tid + C23_THREADS * i;
+            if (q < NQ2) {
+                const int p = q / NCH2, c = q - p * NCH2;
+                const int off = P2::dst_off(p) + c * 16;
+                *reinterpret_cast<u32x4 *>(a1l + off) = rh[i];
+                *reinterpret_cast<u32x4 *>(a1l + IMG2 + off) = rl[i];
+            }
+        }
+    };
+    gload();
+
     // Both roles run the same sequence of barriers: one in the prologue and two per sample.
     if (producer) {
-        const int pw = wave - 4, ptid = tid - NR;
+        const int pw = wave - 4;
         const int n0 = pw * 16 + 4 * lg;                         // this lane's four output channels
         bf16x8 wh[KS2], wl[KS2];
         {
@@ -67,36 +100,6 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
             }
         }
         const float4 bias = *reinterpret_cast<const float4 *>(a.b2 + n0);
-        // act1 of consecutive samples: one persistent pointer per load, advanced by a sample after each use
-        u32x4 rh[NL2], rl[NL2];
-        const u32x4 *ph[NL2];
-        const ptrdiff_t lo_at = reinterpret_cast<const u32x4 *>(a.a1_lo) - reinterpret_cast<const u32x4 *>(a.a1);   // the lo tensor, relative to hi
-#pragma unroll
-        for (int i = 0; i < NL2; ++i) {
-            const int q = ptid + NR * i;
-            ph[i] = reinterpret_cast<const u32x4 *>(a.a1 + (size_t)s_begin * (NQ2 * 8) + (size_t)(q < NQ2 ? q : NQ2 - 1) * 8);
-        }
-        auto gload = [&]() __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < NL2; ++i) {
-                rh[i] = *ph[i];
-                rl[i] = *(ph[i] + lo_at);
-                ph[i] += NQ2;
-            }
-        };
-        auto stage = [&]() __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < NL2; ++i) {
-                const int q = ptid + NR * i;
-                if (q < NQ2) {
-                    const int p = q / NCH2, c = q - p * NCH2;
-                    const int off = P2::dst_off(p) + c * 16;
-                    *reinterpret_cast<u32x4 *>(a1l + off) = rh[i];
-                    *reinterpret_cast<u32x4 *>(a1l + IMG2 + off) = rl[i];
-                }
-            }
-        };
-        gload();
         wait_global_loads();
         // per-lane addresses of the position tiles: fragment base in the act1 image, and where the lane's four
         // channels of its position go in an act2 image (-1: padded row)
@@ -128,14 +131,21 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
         };
         // act2 of sample s (its act1 image is staged) into the LDS image dst, and what the backward pass needs of it
         auto produce = [&](char *dst, int s) __attribute__((always_inline)) {
+            // the fragments of the next part (an eighth of a tile's k-steps) are read while the MFMAs of the current
+            // one run: two register sets, statically alternated (an even number of parts per tile)
+            bf16x8 fh[2][KH2], fl[2][KH2];
+            load_half(t_base[0], 0, fh[0], fl[0]);
 #pragma unroll
             for (int t = 0; t < NT2; ++t) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                bf16x8 fh[KH2], fl[KH2];
 #pragma unroll
-                for (int part = 0; part < KS2 / KH2; ++part) {
-                    load_half(t_base[t], part, fh, fl);
-                    mfma_half(part, fh, fl, acc);
+                for (int part = 0; part < PARTS2; ++part) {
+                    const bool last = part + 1 == PARTS2;
+                    const int tn = last ? (t + 1 < NT2 ? t + 1 : t) : t;     // the last tile repeats its own first reads
+                    load_half(t_base[tn], last ? 0 : part + 1, fh[(part + 1) & 1], fl[(part + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_half(part, fh[part & 1], fl[part & 1], acc);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 const float r0 = fmaxf(acc[0] + bias.x, 0.f), r1 = fmaxf(acc[1] + bias.y, 0.f);
                 const float r2 = fmaxf(acc[2] + bias.z, 0.f), r3 = fmaxf(acc[3] + bias.w, 0.f);
@@ -209,20 +219,25 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[half * KH3 + j], fh[j], acc, 0, 0, 0);
             }
         };
+        stage();
         __syncthreads();
+        if (s_begin + 1 < s_end) gload();
         int cur = 0;
         for (int s = s_begin; s < s_end; ++s) {
-            __syncthreads();                          // act2 of s is complete
-            __syncthreads();                          // (the producers' staging barrier)
+            __syncthreads();                          // act2 of s is complete; the producers are done with act1 of s
+            if (s + 1 < s_end) stage();
+            __syncthreads();
+            if (s + 2 < s_end) gload();
             const char *src = reinterpret_cast<const char *>(s_a2[cur]);
 #pragma unroll
             for (int t = 0; t < NT3; ++t) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                 bf16x8 fh[KH3], fl[KH3];
-                load_half(src, t_base[t], 0, fh, fl);
-                mfma_half(0, fh, fl, acc);
-                load_half(src, t_base[t], 1, fh, fl);
-                mfma_half(1, fh, fl, acc);
+#pragma unroll
+                for (int part = 0; part < PARTS3; ++part) {
+                    load_half(src, t_base[t], part, fh, fl);
+                    mfma_half(part, fh, fl, acc);
+                }
                 const float r0 = fmaxf(acc[0] + bias.x, 0.f), r1 = fmaxf(acc[1] + bias.y, 0.f);
                 const float r2 = fmaxf(acc[2] + bias.z, 0.f), r3 = fmaxf(acc[3] + bias.w, 0.f);
                 const int pos = t * 16 + li;
