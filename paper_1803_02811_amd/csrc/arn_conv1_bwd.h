@@ -1,9 +1,8 @@
-// conv2's input gradient and conv1's weight gradient in one kernel.
+// conv2's input gradient and conv1's weight gradient in one workgroup body (a range of conv_backward_kernel).
 //
 // d(pre1) -- the largest tensor of the backward pass -- has a single consumer, conv1's weight gradient
 // (conv1's input is data, so there is no input gradient below it).  Here a workgroup produces a sample's
-// d(pre1) into LDS and contracts it there against the sample's frame: d(pre1) never goes to HBM, and one
-// kernel boundary is saved.
+// d(pre1) into LDS and contracts it there against the sample's frame: d(pre1) never goes to HBM.
 //
 // The eight wavefronts of a workgroup have two roles.  Four "producers" compute d(pre1) of sample s+1: the
 // stride-2 input gradient as one 2x2 stride-1 correlation with 4 x 32 phase channels (one phase per wavefront,
