@@ -24,6 +24,7 @@ KERNEL_FLOPS = {  # per sample, by instrumented kernel name
     "conv1_fwd": 2 * MACS["conv1"], "conv2_fwd": 2 * MACS["conv2"], "conv3_fwd": 2 * MACS["conv3"],
     "fc_fwd": 2 * MACS["fc"], "head_fwd": 2 * MACS["head_pv"],
     "conv23_fwd": 2 * MACS["conv2"] + 2 * MACS["conv3"],   # conv2 and conv3 forward, one kernel (act2 through LDS)
+    "conv123_fwd": 2 * MACS["conv1"] + 2 * MACS["conv2"] + 2 * MACS["conv3"],   # ... with conv1 ahead of them in each workgroup
     "conv1_wgrad": 2 * MACS["conv1"], "conv2_wgrad": 2 * MACS["conv2"], "conv3_wgrad": 2 * MACS["conv3"],
     "fc_wgrad": 2 * MACS["fc"], "head_wgrad": 2 * MACS["head_pv"],
     "conv2_dgrad": 2 * MACS["conv2"], "conv3_dgrad": 2 * MACS["conv3"], "fc_dgrad": 2 * MACS["fc"],
@@ -38,6 +39,7 @@ KERNEL_BYTES = {
     "conv1_fwd": ACT["obs"] + ACT["a1"], "conv2_fwd": ACT["a1"] + ACT["a2"], "conv3_fwd": ACT["a2"] + ACT["a3"],
     "fc_fwd": ACT["a3"] + ACT["h"], "head_fwd": ACT["h"] + ACT["z"],
     "conv23_fwd": ACT["a1"] + ACT["a2"] + ACT["a3"],       # act2 is written once, for the backward pass
+    "conv123_fwd": ACT["obs"] + 2 * ACT["a1"] + ACT["a2"] + ACT["a3"],
     "conv1_wgrad": ACT["obs"] + ACT["a1"], "conv2_wgrad": ACT["a1"] + ACT["a2"], "conv3_wgrad": ACT["a2"] + ACT["a3"],
     "fc_wgrad": ACT["a3"] + ACT["h"], "head_wgrad": ACT["h"] + ACT["z"],
     "conv2_dgrad": ACT["a2"] + 2 * ACT["a1"], "conv3_dgrad": ACT["a3"] + 2 * ACT["a2"],
@@ -46,7 +48,7 @@ KERNEL_BYTES = {
     "conv_bwd": ACT["a2"] + ACT["obs"] + ACT["a1"] + ACT["a2"] + ACT["a2"] + ACT["a3"],
 }
 KERNEL_BYTES_PER_LAUNCH = {  # bf16 weights read (forward / input gradient) or fp32 gradient written (weight gradient)
-    "conv1_fwd": 2 * 8192, "conv2_fwd": 2 * 32768, "conv3_fwd": 2 * 36864, "conv23_fwd": 2 * 32768 + 2 * 36864, "fc_fwd": 2 * 1605632, "head_fwd": 2 * 9728,
+    "conv1_fwd": 2 * 8192, "conv2_fwd": 2 * 32768, "conv3_fwd": 2 * 36864, "conv23_fwd": 2 * 32768 + 2 * 36864, "conv123_fwd": 2 * 8192 + 2 * 32768 + 2 * 36864, "fc_fwd": 2 * 1605632, "head_fwd": 2 * 9728,
     "conv2_dgrad": 2 * 32768, "conv3_dgrad": 2 * 36864, "fc_dgrad": 2 * 1605632, "head_dgrad": 2 * 9728,
     "conv1_wgrad": 4 * 8192, "conv2_wgrad": 4 * 32768, "conv3_wgrad": 4 * 36864, "fc_wgrad": 4 * 1605632,
     "head_wgrad": 4 * 9728, "conv_bwd": 2 * 32768 + 4 * 8192 + 4 * 32768 + 4 * 36864,

@@ -207,6 +207,8 @@ struct ConvConfigs {
     // conv2 -> conv3 through LDS needs both layers' images in one CU's LDS: not with the bordered images of this geometry
     static bool fused_conv23(int) { return false; }
     static void launch_conv23(const Conv23Args &, int, int, hipStream_t) {}
+    static void launch_conv123(const uint8_t *, const __bf16 *, const __bf16 *, const float *, uint8_t *, const Conv23Args &, int,
+                               int, hipStream_t) {}
 };
 template <>
 struct ConvConfigs<Geo84> {
@@ -222,6 +224,11 @@ struct ConvConfigs<Geo84> {
         hipLaunchKernelGGL((conv23_fwd_fused_kernel<ResConv2Fwd, ResConv3Fwd>), dim3((B + spw - 1) / spw), dim3(C23_THREADS), 0,
                            s, p, B, spw);
     }
+    static void launch_conv123(const uint8_t *obs, const __bf16 *w1, const __bf16 *w1l, const float *b1, uint8_t *m1,
+                               const Conv23Args &p, int B, int spw, hipStream_t s) {
+        hipLaunchKernelGGL((conv123_fwd_kernel<Geo84, ResConv2Fwd, ResConv3Fwd>), dim3((B + spw - 1) / spw), dim3(C23_THREADS),
+                           0, s, obs, w1, w1l, b1, m1, p, B, spw);
+    }
 };
 
 // Forward pass for geometry G in three-product bf16 precision (conv1's pixel operand is exact: two products).
@@ -231,21 +238,24 @@ void forward_trunk(const Dims &d, const Packed &w, const uint8_t *obs, int B, ch
     typedef ConvConfigs<G> Cfg;
     __bf16 *a1 = (__bf16 *)(ws + o.a1), *a2 = (__bf16 *)(ws + o.a2), *a3 = (__bf16 *)(ws + o.a3);
     __bf16 *a1l = (__bf16 *)(ws + o.a1l), *a2l = (__bf16 *)(ws + o.a2l), *a3l = (__bf16 *)(ws + o.a3l);
-    {
+    const bool chained = Cfg::fused_conv23(B) && Cfg::conv1_parts(B) == 1;
+    if (!chained) {
         ProfScope ps("conv1_fwd", s);
         const int spw = resident_spw(B, 256);
         hipLaunchKernelGGL(conv1_fwd_resident_kernel<G>, dim3(cdiv(B, spw), Cfg::conv1_parts(B)), dim3(RES_THREADS), 0, s,
                            obs, w.w1, w.w1l, w.b1, a1, a1l, masks ? (uint8_t *)(ws + o.m1) : nullptr, B, spw);
     }
     if (Cfg::fused_conv23(B)) {
-        // conv2 and conv3 in one kernel: act2 passes through LDS
-        ProfScope ps("conv23_fwd", s);
+        // conv2 and conv3 in one kernel: act2 passes through LDS; with one workgroup per sample range in conv1 too,
+        // conv1 runs in the same launch, ahead of them in every workgroup
+        ProfScope ps(chained ? "conv123_fwd" : "conv23_fwd", s);
         Conv23Args p;
         p.a1 = a1; p.a1_lo = a1l; p.w2 = w.w2; p.w2_lo = w.w2l; p.w3 = w.w3; p.w3_lo = w.w3l; p.b2 = w.b2; p.b3 = w.b3;
         p.a2 = masks ? a2 : nullptr; p.a3 = a3; p.a3_lo = a3l;
         p.m2 = masks ? (uint8_t *)(ws + o.m2) : nullptr; p.m3 = masks ? (uint8_t *)(ws + o.m3) : nullptr;
         const int spw = resident_spw(B, 256);
-        Cfg::launch_conv23(p, B, spw, s);
+        if (chained) Cfg::launch_conv123(obs, w.w1, w.w1l, w.b1, masks ? (uint8_t *)(ws + o.m1) : nullptr, p, B, spw, s);
+        else Cfg::launch_conv23(p, B, spw, s);
     } else {
         {
             typename Cfg::Fwd2::Args p;

@@ -25,9 +25,14 @@ struct Conv23Args {
     uint8_t *m2, *m3;                // sign bits of act2 / act3 for the backward pass, or null
 };
 
+// LDS bytes of conv23_fwd_fused_body<P2, P3>: conv2's input image and two of conv3's, hi and lo parts each
+template <class P2, class P3>
+constexpr int conv23_fwd_lds_bytes() { return 2 * P2::IMG + 4 * P3::IMG; }
+
+// The work of workgroup `block` (of C23_THREADS threads) in the caller's LDS buffer.
 // P2, P3: the LDS image descriptions of conv2 forward (one sample per iteration) and conv3 forward.
 template <class P2, class P3>
-__global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Conv23Args a, int B, int spw) {
+__device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, const Conv23Args &a, int B, int spw) {
     // conv2 (producers)
     constexpr int CI2 = P2::CI, NCH2 = CI2 / 8, IMG2 = P2::IMG, KS2 = P2::K / 32;
     constexpr int PARTS2 = 8, KH2 = KS2 / PARTS2;                // a tile's k-steps in eight parts: two sets of 16 fragment registers
@@ -41,16 +46,15 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
     static_assert(P2::CO == 64 && P3::CO == 64 && P2::CO == CI3 && P2::P == P3::SRC_PIX, "conv2's output is conv3's input");
     static_assert(KS2 % PARTS2 == 0 && PARTS2 % 2 == 0 && KS3 % PARTS3 == 0 && PARTS3 % 2 == 0 && P2::PSB == CI2 * 2 + 32 && P3::PSB == CI3 * 2 + 32, "k-steps in an even number of parts");
     static_assert(layout_is_uniform<P2>() && layout_is_uniform<P3>(), "fragment rows must advance by one pixel stride modulo 256 bytes");
-    static_assert(2 * IMG2 + 4 * IMG3 <= 160 * 1024 && IMG2 % 16 == 0 && IMG3 % 16 == 0, "LDS budget");
+    static_assert(conv23_fwd_lds_bytes<P2, P3>() <= 160 * 1024 && IMG2 % 16 == 0 && IMG3 % 16 == 0, "LDS budget");
 
-    __shared__ u32x4 s_a1[2 * IMG2 / 16];         // act1 image of one sample, hi then lo
-    __shared__ u32x4 s_a2[2][2 * IMG3 / 16];      // act2 images (hi then lo), double buffered
-    char *const a1l = reinterpret_cast<char *>(s_a1);
+    char *const a1l = reinterpret_cast<char *>(lds);                 // act1 image of one sample, hi then lo
+    char *const a2l = a1l + 2 * IMG2;                                // two act2 images (hi then lo each): double buffered
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
     const bool producer = wave >= 4;
-    const int s_begin = blockIdx.x * spw;
+    const int s_begin = block * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
 
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
         stage();
         __syncthreads();
         if (s_begin + 1 < s_end) gload();
-        produce(reinterpret_cast<char *>(s_a2[0]), s_begin);     // first sample: its act2 before the loop
+        produce(a2l, s_begin);     // first sample: its act2 before the loop
         int cur = 0;
         for (int s = s_begin; s < s_end; ++s) {
             // act2 of s is complete in buffer cur; conv3 of s-1 has read the other buffer; all producers are done
@@ -179,7 +183,7 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
             if (s + 1 < s_end) stage();
             __syncthreads();
             if (s + 2 < s_end) gload();
-            if (s + 1 < s_end) produce(reinterpret_cast<char *>(s_a2[cur ^ 1]), s + 1);
+            if (s + 1 < s_end) produce(a2l + (cur ^ 1) * (2 * IMG3), s + 1);
             cur ^= 1;
         }
     } else {
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
             if (s + 1 < s_end) stage();
             __syncthreads();
             if (s + 2 < s_end) gload();
-            const char *src = reinterpret_cast<const char *>(s_a2[cur]);
+            const char *src = a2l + cur * (2 * IMG3);
 #pragma unroll
             for (int t = 0; t < NT3; ++t) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -252,6 +256,33 @@ __global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Con
             cur ^= 1;
         }
     }
+}
+
+template <class P2, class P3>
+__global__ __launch_bounds__(C23_THREADS) void conv23_fwd_fused_kernel(const Conv23Args a, int B, int spw) {
+    __shared__ u32x4 lds[conv23_fwd_lds_bytes<P2, P3>() / 16];
+    conv23_fwd_fused_body<P2, P3>(lds, blockIdx.x, a, B, spw);
+}
+
+// conv1, conv2 and conv3 forward of a workgroup's sample range, one layer pair after the other, in one launch: the
+// three layers are independent across samples, so a workgroup only waits for its own act1 (a barrier)
+// instead of for the whole grid, and the launch boundary between conv1 and the fused conv2/conv3 kernel is gone.
+// act1 still goes through global memory (the backward pass needs it, and the layers' LDS images do not fit side by
+// side).  Both bodies use the same sample ranges (spw per workgroup) and 512 threads.
+template <class Geo, class P2, class P3>
+__global__ __launch_bounds__(C23_THREADS) void conv123_fwd_kernel(const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w1,
+                                                                  const __bf16 *__restrict__ w1_lo, const float *__restrict__ b1,
+                                                                  uint8_t *__restrict__ m1, const Conv23Args a, int B, int spw) {
+    static_assert(RES_THREADS == C23_THREADS, "one block size for both bodies");
+    constexpr int L1 = conv1_fwd_lds_bytes<Geo>(), L23 = conv23_fwd_lds_bytes<P2, P3>();
+    __shared__ u32x4 lds[(L1 > L23 ? L1 : L23) / 16];
+    conv1_fwd_resident_body<Geo>(lds, blockIdx.x, 0, 1, obs, w1, w1_lo, b1, const_cast<__bf16 *>(a.a1), const_cast<__bf16 *>(a.a1_lo),
+                                 m1, B, spw);
+    // The barrier orders this workgroup's act1 stores before its own reads (a workgroup's wavefronts share the CU's
+    // vector cache).  A device-wide fence here is ruinous: it writes back and invalidates the whole L2 of the XCD,
+    // once per workgroup (measured: 186 instead of 97 us).
+    __syncthreads();
+    conv23_fwd_fused_body<P2, P3>(lds, blockIdx.x, a, B, spw);
 }
 
 }  // namespace arn

@@ -306,11 +306,16 @@ __global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 
 // the position tiles of a sample (25 at 84x84; the last one may be ragged) are dealt round-robin to the four
 // wavefront pairs.  Three-product precision with an exact activation operand needs
 // two MFMAs per fragment (W_hi x, W_lo x).
+// The work of workgroup (block_x, block_y) of a grid with grid_y workgroups per sample range, in the caller's LDS
+// buffer of conv1_fwd_lds_bytes<Geo>() bytes.
 template <class Geo>
-__global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
-    const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w, const __bf16 *__restrict__ w_lo,
-    const float *__restrict__ bias, __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo,
-    uint8_t *__restrict__ mask_out, int B, int spw) {
+constexpr int conv1_fwd_lds_bytes() { return 4 * Geo::OBS_BYTES; }   // two bf16 images
+
+template <class Geo>
+__device__ __forceinline__ void conv1_fwd_resident_body(
+    u32x4 *lds, int block_x, int block_y, int grid_y, const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w,
+    const __bf16 *__restrict__ w_lo, const float *__restrict__ bias, __bf16 *__restrict__ out,
+    __bf16 *__restrict__ out_lo, uint8_t *__restrict__ mask_out, int B, int spw) {
     constexpr int IN_H = Geo::IN_H, IN_W = Geo::IN_W, W1 = Geo::W1, P1 = Geo::P1, OBS_BYTES = Geo::OBS_BYTES;
     static_assert(OBS_BYTES % 16 == 0, "a sample is copied in 16-byte words");
     constexpr int IMG_U4 = OBS_BYTES / 16;                           // sixteen-pixel groups (1764 at 84x84)
@@ -318,12 +323,12 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
     constexpr int KS = KW1 / 32;                                     // 8
     constexpr int NT = (P1 + 15) / 16;                               // position tiles (25 at 84x84, no remainder)
     constexpr bool RAGGED = P1 % 16 != 0;
-    __shared__ u32x4 s_img[2][2 * IMG_U4];                           // bf16 [4][IN_H][IN_W], double buffered
-    static_assert(sizeof(u32x4) * 4 * IMG_U4 <= 160 * 1024, "LDS budget");
+    u32x4(*const s_img)[2 * IMG_U4] = reinterpret_cast<u32x4(*)[2 * IMG_U4]>(lds);   // bf16 [4][IN_H][IN_W], double buffered
+    static_assert(sizeof(u32x4) * 4 * IMG_U4 == conv1_fwd_lds_bytes<Geo>() && conv1_fwd_lds_bytes<Geo>() <= 160 * 1024, "LDS budget");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    const int s_begin = blockIdx.x * spw;
+    const int s_begin = block_x * spw;
     const int s_end = s_begin + spw < B ? s_begin + spw : B;
     if (s_begin >= s_end) return;
 
@@ -414,7 +419,7 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
                 unit(s, t0 + 4 * (j + 1), fb);
             }
             if (j < nj) unit(s, t0 + 4 * j, fa);
-        } else if (gridDim.y == 1) {
+        } else if (grid_y == 1) {
             frag_load(img, t0, fa);
 #pragma unroll
             for (int j = 0; j < 6; j += 2) {
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         } else {
             // small batches: three workgroups per sample, each taking one pair of this wavefront's tiles
             // (the last one also tile 24)
-            const int j = 2 * (int)blockIdx.y;
+            const int j = 2 * block_y;
             const bool tail = j == 4 && t0 == 0;
             frag_load(img, t0 + 4 * j, fa);
             frag_load(img, t0 + 4 * (j + 1), fb);
@@ -438,6 +443,15 @@ __global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
         }
         buf ^= 1;
     }
+}
+
+template <class Geo>
+__global__ __launch_bounds__(RES_THREADS) void conv1_fwd_resident_kernel(
+    const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w, const __bf16 *__restrict__ w_lo,
+    const float *__restrict__ bias, __bf16 *__restrict__ out, __bf16 *__restrict__ out_lo,
+    uint8_t *__restrict__ mask_out, int B, int spw) {
+    __shared__ u32x4 lds[conv1_fwd_lds_bytes<Geo>() / 16];
+    conv1_fwd_resident_body<Geo>(lds, blockIdx.x, blockIdx.y, gridDim.y, obs, w, w_lo, bias, out, out_lo, mask_out, B, spw);
 }
 
 // ---------------------------------------------------------------------------
