@@ -23,7 +23,7 @@ def _oracle_forward(flat, obs, A, head):
     return orc.forward(orc.unflatten(flat, spec), obs, spec), spec
 
 
-@pytest.mark.parametrize("B", [1, 16, 37, 64, 130])
+@pytest.mark.parametrize("B", [1, 16, 37, 64, 85, 86, 130])
 def test_forward_uniform_frames(gu, B):
     """Workload 1 (B=16, A=6, uniform frames) plus ragged and single-sample batches."""
     flat = wl.he_normal_params(6, "pv", 2001, bias_std=0.0 if B == 16 else 0.1)
