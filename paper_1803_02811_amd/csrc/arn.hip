@@ -582,7 +582,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                 ProfScope ps("q_target", s);
                 PvHeadArgs p = pv_head_args(d, *wt, B, ws, o);
                 p.logits = (float *)(ws + o.qt);
-                p.rpb = LOSS_BLOCK;
+                p.rpb = loss_block(B);
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
             if (cfg->double_q) {
@@ -590,7 +590,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
                 ProfScope ps("q_select", s);
                 PvHeadArgs p = pv_head_args(d, w, B, ws, o);
                 p.greedy = (int32_t *)(ws + o.astar);
-                p.rpb = LOSS_BLOCK;
+                p.rpb = loss_block(B);
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
         }
@@ -607,6 +607,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             p.reward = batch->reward; p.done = batch->done; p.gamma = cfg->gamma;
         }
         p.whd = w.whd; p.h = h; p.dz = dz; p.dph = dph; p.lossp = lossp;
+        p.rpb = loss_block(B);
         hipLaunchKernelGGL(pv_head_kernel<true>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
     }
 

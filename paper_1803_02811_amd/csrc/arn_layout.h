@@ -203,7 +203,9 @@ inline int fc_ksplit(int B) {
     return ks;
 }
 
-constexpr int LOSS_BLOCK = 8;     // samples per workgroup of the fused policy/value head kernel in the gradient step (at most 16)
+// Samples per workgroup of the fused policy/value head kernel in the gradient step (at most 16): eight keep all
+// CUs busy at a few thousand samples; above that sixteen fill the MFMA's 16 sample columns and halve the workgroups.
+inline int loss_block(int B) { return B >= 4096 ? 16 : 8; }
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
 // byte offsets into the workspace
@@ -221,7 +223,7 @@ struct Workspace {
     size_t total;
 };
 inline int loss_blocks(const Dims &d, int B) {
-    return d.small ? (B + LOSS_BLOCK - 1) / LOSS_BLOCK : (B + C51_WAVES - 1) / C51_WAVES;
+    return d.small ? (B + loss_block(B) - 1) / loss_block(B) : (B + C51_WAVES - 1) / C51_WAVES;
 }
 inline Workspace make_workspace(const Dims &d, int B, int mode) {
     Workspace w{};

@@ -39,7 +39,7 @@ struct PvHeadArgs {
     const __bf16 *wh, *whl; // head weights [64][512] hi / lo; rows A+1.. are zero
     const float *bh;        // [64] head bias (policy rows then the value row)
     int B, A;
-    int rpb;                // inference: samples per workgroup (1..16; 0 = 16).  Small batches spread over more
+    int rpb;                // samples per workgroup (1..16; 0 = 16).  Small batches spread over more
                             // workgroups, because one CU's L1 rate bounds the addition of the fc partial sums
     int qmode;              // 0: policy logits + value row; 1: scalar Q rows; 2: advantage rows + value row -> Q
     // inference outputs (each may be null)
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
     __shared__ float sRed[3][PVH_ROWS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rpb = TRAIN ? LOSS_BLOCK : (p.rpb <= 0 ? PVH_ROWS : p.rpb);
+    const int rpb = p.rpb <= 0 ? PVH_ROWS : p.rpb;
     const int n0 = blockIdx.x * rpb;
     const int srow = tid >> 4, c = tid & 15;              // sample within the block, lane within its group of 16
     const int n = n0 + srow;
