@@ -532,6 +532,24 @@ def paper_geometry_report(args, arn, wl, np, torch):
         "kernel_us": {n: round(v * 1e3, 2) for n, v in sorted(avg_ms.items(), key=lambda kv: -kv[1])}}))
 
 
+def kernel_times_us(arn, torch, step, steps, stream):
+    """Average duration per launch site (microseconds, event-pair overhead subtracted) over `steps` more steps;
+    sites that launch several times per step (the forward kernels of a step with a target network) are summed."""
+    arn.profile_enable(True)
+    for _ in range(steps):
+        step()
+        arn.profile_null(stream)
+    torch.cuda.synchronize()
+    per = {}
+    for name, ms in arn.profile_collect(cap=96 * steps + 64):
+        tot, cnt = per.get(name, (0.0, 0))
+        per[name] = (tot + ms, cnt + 1)
+    arn.profile_enable(False)
+    null_ms = per.pop("null")[0] / steps
+    us = {n: max(t - c * null_ms, 0.0) / steps * 1e3 for n, (t, c) in per.items()}
+    return {n: round(v, 2) for n, v in sorted(us.items(), key=lambda kv: -kv[1])}
+
+
 def other_workload(args, arn, wl, np, torch):
     """Secondary report lines for the other workloads (same JSON shape, no per-kernel roofline)."""
     dev, k = "cuda:0", args.workload
@@ -594,7 +612,8 @@ def other_workload(args, arn, wl, np, torch):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s (workload %d)" % (w["name"], k), "global_batch": B, "parallelism": "single-gpu"},
         "mfma_frac_whole_step": round(B / sec * flops / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "algorithmic_flops_per_sample": flops}))
+        "algorithmic_flops_per_sample": flops,
+        "kernel_us_per_step": kernel_times_us(arn, torch, step, min(args.steps, 50), stream)}))
 
 
 if __name__ == "__main__":
