@@ -67,7 +67,7 @@ extern "C" {
 
 typedef enum {
     ARN_OK = 0,
-    ARN_EINVAL = -1,     /* null or misaligned pointer, B <= 0 */
+    ARN_EINVAL = -1,     /* null or misaligned pointer, B <= 0 or B > 2^20 (1,048,576 samples per call) */
     ARN_ESHAPE = -2,     /* unsupported num_actions / num_atoms / head for this call */
     ARN_EKIND = -3,      /* unknown head_kind / loss_kind / mode */
     ARN_EWORKSPACE = -4, /* workspace smaller than arn_workspace_bytes() */

@@ -407,7 +407,7 @@ extern "C" {
 const char *arn_status_string(int status) {
     switch (status) {
         case ARN_OK: return "ok";
-        case ARN_EINVAL: return "invalid argument (null or misaligned pointer, or B <= 0)";
+        case ARN_EINVAL: return "invalid argument (null or misaligned pointer, B <= 0 or B > 2^20)";
         case ARN_ESHAPE: return "unsupported shape (num_actions, num_atoms or head for this call)";
         case ARN_EKIND: return "unknown head_kind, loss_kind or mode";
         case ARN_EWORKSPACE: return "workspace too small";

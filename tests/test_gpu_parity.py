@@ -172,6 +172,42 @@ def test_full_size_a2c_b2048(gu):
         assert np.abs(got[name] - want[name]).max() <= 2e-2 * np.abs(want[name]).max(), name
 
 
+@pytest.mark.parametrize("copies", [4096, 16384])
+def test_largest_batches(gu, copies):
+    """B = 2^18 and B = 2^20 (the largest batch the library accepts): element and byte offsets into every
+    activation tensor pass 2^31 and 2^32.  The batch is `copies` copies of 64 distinct samples (tiled on the
+    device), so every copy's forward outputs must repeat the first copy's bits, the first copy must match the
+    oracle, and the batch-mean gradient must be the oracle's gradient of the 64."""
+    import torch
+    import paper_1803_02811_amd as arn
+    A, base = 18, 64
+    B = base * copies
+    flat = wl.he_normal_params(A, "pv", 2003, bias_std=0.05)
+    small = wl.actor_critic_batch(3, B=base)
+    spec = orc.NetSpec(A, "pv")
+    ref = orc.train_step_grads(flat, small, "a2c", spec)
+    net = gu.GpuNet(A, "pv", flat)
+    dev = net.device_batch(small)
+    big = {k: v.repeat(copies, *([1] * (v.dim() - 1))).contiguous() for k, v in dev.items()}
+    assert big["obs"].shape == (B, 4, 84, 84) and big["obs"].numel() > 2 ** 31
+    logits = torch.empty(B, A, dtype=torch.float32, device=gu.DEV)
+    value = torch.empty(B, dtype=torch.float32, device=gu.DEV)
+    arn.policy_forward(net.cfg, net.packed, big["obs"], logits, value, None, None,
+                       workspace=net.workspace(B, arn.ARN_MODE_FORWARD))
+    torch.cuda.synchronize()
+    lg, vl = logits.view(copies, base, A), value.view(copies, base)
+    assert bool((lg == lg[:1]).all()) and bool((vl == vl[:1]).all())
+    gu.tol_check(lg[0].cpu().numpy(), ref["cache"]["logits"], "logits")
+    gu.tol_check(vl[0].cpu().numpy(), ref["cache"]["value"], "value")
+    del logits, value, lg, vl
+    net._ws.clear()
+    dW, loss = net.train(None, "a2c", dev_batch=big)
+    _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
+    net._ws.clear()
+    del big
+    torch.cuda.empty_cache()
+
+
 def test_full_size_ppo_b4096(gu):
     """Workload 4: B=4096 PPO-clip step on uniform frames, old log-probs from perturbed oracle logits."""
     A, B = 18, 4096
