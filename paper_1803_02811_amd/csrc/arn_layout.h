@@ -204,8 +204,9 @@ inline int fc_ksplit(int B) {
 }
 
 // Samples per workgroup of the fused policy/value head kernel in the gradient step (at most 16): eight keep all
-// CUs busy at a few thousand samples; above that sixteen fill the MFMA's 16 sample columns and halve the workgroups.
-inline int loss_block(int B) { return B >= 4096 ? 16 : 8; }
+// CUs busy at a few thousand samples; above that sixteen fill the MFMA's 16 sample columns and halve the workgroups;
+// small batches are spread over more CUs, four samples each (one CU's L1 rate bounds the addition of the fc partials).
+inline int loss_block(int B) { return B >= 4096 ? 16 : B <= 512 ? 4 : 8; }
 constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
 
 // byte offsets into the workspace
