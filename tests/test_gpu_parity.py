@@ -303,11 +303,12 @@ def test_black_frames_exact_zero_preactivations(gu):
     _compare_grads(gu, dW, ref["flat"], A, "pv", loss, ref["loss"], ["total", "policy", "value", "entropy"])
 
 
-@pytest.mark.parametrize("geometry,B", [("84", 515), ("paper", 515), ("84", 1), ("paper", 1), ("84", 257)])
+@pytest.mark.parametrize("geometry,B", [("84", 515), ("paper", 515), ("84", 1), ("paper", 1), ("84", 257), ("84", 4099)])
 def test_gradients_with_short_and_single_sample_workgroups(gu, geometry, B):
     """The sample-resident backward kernels give each workgroup a contiguous range of samples: 515 = 171 x 3 + 2
     leaves the last workgroup short (and makes the fused conv1 backward pipeline three samples per workgroup),
-    257 gives ranges of two with a single sample at the end, 1 is one workgroup with nothing to prefetch."""
+    257 gives ranges of two with a single sample at the end, 1 is one workgroup with nothing to prefetch; 4099 is
+    past the size from which the head kernel takes sixteen samples per workgroup, with three in its last one."""
     A = 18
     frame = wl.FRAME if geometry == "84" else wl.PAPER_FRAME
     fc_in = wl.FC_INPUTS[frame]
