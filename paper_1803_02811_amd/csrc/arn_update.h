@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "arn_gemm.h"
 #include "arn_layout.h"
 #include "arn_small_kernels.h"
 
@@ -136,8 +137,20 @@ struct PackSeg {
     long n;
     void *out, *out_lo;
 };
+// The fc matrix (95 % of the parameters) is laid out by tile blocks instead: elementwise maps would read it with
+// a stride of one row (input-gradient layout) or of P3 floats (forward layout).  A tile is PACK_FC_ROWS hidden
+// units x PACK_FC_CH conv3 channels x all P3 positions -- contiguous runs of PACK_FC_CH * P3 floats in the flat
+// vector -- staged in LDS and written out as 16-byte words of eight channels (forward layout, hi and lo) and of
+// eight hidden units (input-gradient layout).  Eight rows per tile measured best (12.2 us for the whole launch
+// against 13.1 with sixteen and 16 with thirty-two; the elementwise maps took 18.3).
+constexpr int PACK_FC_ROWS = 8, PACK_FC_CH = 8;
+constexpr int PACK_FC_MAX_P3 = 108;   // 12 x 9 positions after conv3 on 104 x 80 frames
+static_assert(P3 <= PACK_FC_MAX_P3 && GeoPaper::P3 <= PACK_FC_MAX_P3, "fc tile buffer");
+static_assert(HID % PACK_FC_ROWS == 0 && C3 % PACK_FC_CH == 0 && PACK_FC_CH == 8 && PACK_FC_ROWS % 8 == 0, "fc tile shape");
 struct PackPlan {
     PackSeg seg[PK_COUNT];
+    int fc_first_block;                      // blocks from here on are fc tiles
+    __bf16 *fc_hi, *fc_lo, *fc_dgrad;
     long w1, w2, w3, wfc, b1, b2, b3, bfc;   // offsets in the flat vector
     MapHeadRow hr;
     int NHP;
@@ -164,7 +177,7 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     set(PK_W1, (long)C1 * KW1, o.w1, o.w1l, true);
     set(PK_W2, (long)C2 * KW2, o.w2, o.w2l, true);
     set(PK_W3, (long)C3 * KW3, o.w3, o.w3l, true);
-    set(PK_WFC, (long)HID * d.feat, o.wfc, o.wfcl, true);
+    set(PK_WFC, 0, o.wfc, o.wfcl, true);          // by tile blocks, below
     set(PK_WH, (long)d.NHP * HID, o.wh, o.whl, true);
     set(PK_B1, C1, o.b1, 0, false);
     set(PK_B2, C2, o.b2, 0, false);
@@ -172,7 +185,8 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     set(PK_BFC, HID, o.bfc, 0, false);
     set(PK_BH, d.NHP, o.bh, 0, false);
     set(PK_WHD, (long)HID * d.NHP, o.whd, 0, false);
-    set(PK_WFCD, (long)d.feat * HID, o.wfcd, 0, false);
+    set(PK_WFCD, 0, o.wfcd, 0, false);            // by tile blocks, below
+    pl.fc_hi = (__bf16 *)(b + o.wfc); pl.fc_lo = (__bf16 *)(b + o.wfcl); pl.fc_dgrad = (__bf16 *)(b + o.wfcd);
     set(PK_W3D, (long)C2 * KW3, o.w3d, 0, false);
     set(PK_W2D, (long)4 * C1 * 256, o.w2d, 0, false);
     int blk = 0;
@@ -180,11 +194,68 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
         pl.seg[k].first_block = blk;
         blk += (int)((pl.seg[k].n + 255) / 256);
     }
-    pl.blocks = blk;
+    pl.fc_first_block = blk;
+    pl.blocks = blk + (HID / PACK_FC_ROWS) * (C3 / PACK_FC_CH);
     return pl;
 }
 
+// One fc tile: hidden units n0 .. n0 + PACK_FC_ROWS - 1, conv3 channels c0 .. c0 + PACK_FC_CH - 1.
+// Flat order Wfc[n][c * P3 + pos]; forward layout [n][pos * 64 + c]; input-gradient layout [pos * 64 + c][n].
+template <int P3_>
+__device__ __forceinline__ void pack_fc_tile(const PackPlan &pl, const float *__restrict__ w, int tile,
+                                             float (&s_t)[PACK_FC_ROWS][PACK_FC_CH * PACK_FC_MAX_P3]) {
+    constexpr int p3 = P3_, feat = C3 * P3_, run = PACK_FC_CH * p3;
+    constexpr int NL = (PACK_FC_ROWS * run + 255) / 256;
+    const int n0 = (tile / (C3 / PACK_FC_CH)) * PACK_FC_ROWS, c0 = (tile % (C3 / PACK_FC_CH)) * PACK_FC_CH;
+    const int tid = threadIdx.x;
+    float v_in[NL];   // all loads of the tile in flight before the first is used
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        int i = tid + 256 * j;
+        i = i < PACK_FC_ROWS * run ? i : PACK_FC_ROWS * run - 1;
+        const int r = i / run, e = i - r * run;
+        v_in[j] = w[pl.wfc + (long)(n0 + r) * feat + (long)c0 * p3 + e];
+    }
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+        const int i = tid + 256 * j;
+        if (i < PACK_FC_ROWS * run) s_t[i / run][i % run] = v_in[j];
+    }
+    __syncthreads();
+    // forward layout: one 16-byte word = channels c0 .. c0+7 of (row r, position pos)
+    for (int i = tid; i < PACK_FC_ROWS * p3; i += 256) {
+        const int r = i / p3, pos = i - r * p3;
+        float v[PACK_FC_CH];
+#pragma unroll
+        for (int c = 0; c < PACK_FC_CH; ++c) v[c] = s_t[r][c * p3 + pos];
+        bf16x8 hi, lo;
+#pragma unroll
+        for (int c = 0; c < PACK_FC_CH; ++c) {
+            hi[c] = (__bf16)v[c];
+            lo[c] = (__bf16)(v[c] - (float)hi[c]);
+        }
+        const size_t at = (size_t)(n0 + r) * feat + (size_t)pos * C3 + c0;
+        *reinterpret_cast<bf16x8 *>(pl.fc_hi + at) = hi;
+        *reinterpret_cast<bf16x8 *>(pl.fc_lo + at) = lo;
+    }
+    // input-gradient layout: one 16-byte word = hidden units n0 + 8h .. + 7 of (position pos, channel c)  (h = 0 with eight rows)
+    for (int i = tid; i < (PACK_FC_ROWS / 8) * run; i += 256) {
+        const int h = i / run, e = i - h * run, c = e / p3, pos = e - c * p3;
+        bf16x8 hi;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) hi[r] = (__bf16)s_t[8 * h + r][e];
+        *reinterpret_cast<bf16x8 *>(pl.fc_dgrad + ((size_t)pos * C3 + c0 + c) * HID + n0 + 8 * h) = hi;
+    }
+}
+
 __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float *__restrict__ w) {
+    if ((int)blockIdx.x >= pl.fc_first_block) {
+        __shared__ float s_t[PACK_FC_ROWS][PACK_FC_CH * PACK_FC_MAX_P3];
+        const int tile = (int)blockIdx.x - pl.fc_first_block;
+        if (pl.p3 == P3) pack_fc_tile<P3>(pl, w, tile, s_t);
+        else pack_fc_tile<GeoPaper::P3>(pl, w, tile, s_t);
+        return;
+    }
     int k = 0;
 #pragma unroll
     for (int j = 1; j < PK_COUNT; ++j) k = (int)blockIdx.x >= pl.seg[j].first_block ? j : k;
