@@ -176,10 +176,31 @@ __global__ __launch_bounds__(256) void fc_reduce_kernel(const float *__restrict_
         }
         return;
     }
-    for (int k = tid; k < FEAT; k += 256) {
-        float s = 0.f;
-        for (int q = 0; q < splits; ++q) s += part[(size_t)q * block + (long)n * FEAT + k];
-        row[(k & 63) * P3 + (k >> 6)] = s;
+    // four consecutive k per thread and pass (same position, channels c .. c+3); all loads of a split are issued
+    // before the first is added, and the splits are added in order
+    static_assert(FEAT % 4 == 0 && ((long)HID * FEAT + HID) % 4 == 0, "16-byte loads of the partials");
+    constexpr int NV = (FEAT / 4 + 255) / 256;
+    float4 acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int q = 0; q < splits; ++q) {
+        const float4 *src = reinterpret_cast<const float4 *>(part + (size_t)q * block + (long)n * FEAT);
+        float4 v[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int k4 = tid + 256 * j;
+            v[j] = src[k4 < FEAT / 4 ? k4 : FEAT / 4 - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) { acc[j].x += v[j].x; acc[j].y += v[j].y; acc[j].z += v[j].z; acc[j].w += v[j].w; }
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int k = 4 * (tid + 256 * j);
+        if (k < FEAT) {
+            const int at = (k & 63) * P3 + (k >> 6);
+            row[at] = acc[j].x; row[at + P3] = acc[j].y; row[at + 2 * P3] = acc[j].z; row[at + 3 * P3] = acc[j].w;
+        }
     }
     __syncthreads();
     for (int i = tid; i < FEAT; i += 256) dW[woff + (long)n * FEAT + i] = row[i];
