@@ -188,6 +188,13 @@ __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, con
         }
     } else {
         const int n0 = wave * 16 + 4 * lg;
+        // The first act1 image goes to LDS before this role's weights are asked for: the producers cannot start
+        // before it is there (prologue barrier) and before their own weights are, while conv3's weights are not
+        // needed until the producers have finished the first sample -- fetched now they would only compete with
+        // the producers' for the L2.
+        stage();
+        __syncthreads();
+        if (s_begin + 1 < s_end) gload();
         bf16x8 wh[KS3], wl[KS3];
         {
             const size_t row = (size_t)(wave * 16 + li) * P3::K + 8 * lg;
@@ -223,9 +230,6 @@ __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, con
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wh[half * KH3 + j], fh[j], acc, 0, 0, 0);
             }
         };
-        stage();
-        __syncthreads();
-        if (s_begin + 1 < s_end) gload();
         int cur = 0;
         for (int s = s_begin; s < s_end; ++s) {
             __syncthreads();                          // act2 of s is complete; the producers are done with act1 of s
