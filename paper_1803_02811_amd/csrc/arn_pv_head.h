@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "arn_gemm.h"
 #include "arn_lanes.h"
 #include "arn_layout.h"
@@ -113,9 +115,6 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
     int a = 0;
     float ad = 0.f, rt = 0.f, olp = 0.f;
     if constexpr (TRAIN) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t)
-            wd[t] = *reinterpret_cast<const u32x4 *>(p.whd + (size_t)((wave * 8 + t) * 16 + fi) * 64 + fg * 8);
         if (live) {
             a = min(max(p.action[n], 0), p.A - 1);
             if (p.objective == 2) {
@@ -138,31 +137,26 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (live) {   // rows past the batch (or past this block's share) load nothing
+            // the k ranges are added in order; four ranges (32 loads), then two, then one are in flight at a time
+            auto add_planes = [&](int z, auto count) __attribute__((always_inline)) {
+                constexpr int Q = decltype(count)::value;
+                float4 v[Q][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = *reinterpret_cast<const float4 *>(src + 64 * j);
-        // the k ranges are added in order; four ranges (32 loads) are in flight at a time
-        int z = 1;
-        for (; z + 4 <= p.ks; z += 4) {
-            float4 v[4][8];
+                for (int q = 0; q < Q; ++q)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+                    for (int j = 0; j < 8; ++j)
+                        v[q][j] = *reinterpret_cast<const float4 *>(src + (size_t)(z + q) * plane + 64 * j);
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    v[q][j] = *reinterpret_cast<const float4 *>(src + (size_t)(z + q) * plane + 64 * j);
+                for (int q = 0; q < Q; ++q)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    acc[j].x += v[q][j].x; acc[j].y += v[q][j].y; acc[j].z += v[q][j].z; acc[j].w += v[q][j].w;
-                }
-        }
-        for (; z < p.ks; ++z) {
-            float4 v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const float4 *>(src + (size_t)z * plane + 64 * j);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) { acc[j].x += v[j].x; acc[j].y += v[j].y; acc[j].z += v[j].z; acc[j].w += v[j].w; }
-        }
+                    for (int j = 0; j < 8; ++j) {
+                        acc[j].x += v[q][j].x; acc[j].y += v[q][j].y; acc[j].z += v[q][j].z; acc[j].w += v[q][j].w;
+                    }
+            };
+            int z = 0;
+            for (; z + 4 <= p.ks; z += 4) add_planes(z, std::integral_constant<int, 4>());
+            if (z + 2 <= p.ks) { add_planes(z, std::integral_constant<int, 2>()); z += 2; }
+            if (z < p.ks) add_planes(z, std::integral_constant<int, 1>());
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -180,6 +174,13 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         }
     }
     __syncthreads();
+    // the weights of step 4 are asked for only now: fetched with the others they would compete with the fc partial
+    // sums of step 1 for the L2, and steps 2 and 3 are long enough to cover them
+    if constexpr (TRAIN) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            wd[t] = *reinterpret_cast<const u32x4 *>(p.whd + (size_t)((wave * 8 + t) * 16 + fi) * 64 + fg * 8);
+    }
 
     // ---- 2. head GEMM: wave w takes k = 128 w .. 128 w + 127 for both 16-row tiles ----
     {
