@@ -135,11 +135,6 @@ __global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 
     // first image loads have been issued, so that staging does not wait for them)
     bf16x8 wh[CT][KS], wl[C::SPLIT ? CT : 1][C::SPLIT ? KS : 1];
 
-    if constexpr (C::ZERO_FILL) {
-        for (int i = tid; i < NBUF * BUF / 16; i += RESC_THREADS) lds[i] = zero_u4();
-        __syncthreads();
-    }
-
     typename C::Args::Lane lane_state[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) lane_state[ct] = a.lane(wave * (16 * CT) + ct * 16 + 4 * lg);
@@ -249,6 +244,10 @@ __global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 
             wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w + row + 32 * ks));
             if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + 32 * ks));
         }
+    }
+    if constexpr (C::ZERO_FILL) {   // the zero border is written while the first image and the weights are on their way
+        for (int i = tid; i < NBUF * BUF / 16; i += RESC_THREADS) lds[i] = zero_u4();
+        __syncthreads();
     }
     wait_global_loads();
     int buf = 0;
