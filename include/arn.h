@@ -141,12 +141,12 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
                    size_t workspace_bytes, void *stream);
 
 typedef struct {
-    const uint8_t *obs;        /* [B,4,84,84] */
+    const uint8_t *obs;        /* [B,4,84,84] ([B,4,104,80] with ARN_GEOM_PAPER) */
     const int32_t *action;     /* [B], 0 <= a < A (values outside are clamped into range, not reported) */
     const float *adv;          /* [B]  a2c, ppo: advantage estimates (constants) */
     const float *ret;          /* [B]  a2c, ppo: value regression targets */
     const float *old_logp;     /* [B]  ppo: log pi_old(a|s) */
-    const uint8_t *next_obs;   /* [B,4,84,84]  c51, dqn */
+    const uint8_t *next_obs;   /* same shape as obs;  c51, dqn */
     const float *reward;       /* [B]  c51, dqn */
     const uint8_t *done;       /* [B]  c51, dqn: 1 = terminal transition */
     const void *w_target_packed; /* c51, dqn: packed target-network parameters */

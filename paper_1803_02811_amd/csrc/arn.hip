@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "arn_gemm.h"
@@ -23,6 +24,8 @@ using namespace arn;
 
 namespace {
 
+std::mutex g_lazy_mutex;   // guards the lazily filled per-device tables below (first calls from several host threads)
+
 inline bool aligned(const void *p, size_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline bool known_head(int k) { return k == ARN_HEAD_PV || k == ARN_HEAD_C51 || k == ARN_HEAD_Q || k == ARN_HEAD_DUEL; }
 
@@ -32,6 +35,7 @@ int check_arch() {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return ARN_EHIP;
     if (dev < 0 || dev >= 64) return ARN_EHIP;
+    std::lock_guard<std::mutex> lock(g_lazy_mutex);
     if (cached[dev] == 0) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) cached[dev] = -2;
@@ -79,6 +83,7 @@ SideStream *side_stream() {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
     SideStream &ss = per_dev[dev];
+    std::lock_guard<std::mutex> lock(g_lazy_mutex);
     if (ss.state == 0) {
         const char *off = getenv("ARN_SINGLE_STREAM");
         bool ok = !(off && off[0] == '1');
@@ -445,28 +450,32 @@ int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_pack
     return launched();
 }
 
-int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, float *logits,
-                       float *value, float *probs, int32_t *greedy, void *workspace, size_t workspace_bytes,
-                       void *stream) {
+namespace {
+// Argument checks of arn_policy_forward; fills *d_out.
+int check_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, float *logits,
+                         float *value, float *probs, int32_t *greedy, Dims *d_out) {
     if (!cfg || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
     if (!known_head(cfg->head_kind)) return ARN_EKIND;
     const Dims d = make_dims(cfg);
     if (!d.ok) return ARN_ESHAPE;
-    if (!aligned(w_packed, 256) || !aligned(obs, 16) || !aligned(logits, 16) || !aligned(workspace, 256))
-        return ARN_EINVAL;
+    if (!aligned(w_packed, 256) || !aligned(obs, 16) || !aligned(logits, 16)) return ARN_EINVAL;
     if (d.small && !aligned(value, 16)) return ARN_EINVAL;
     if ((value && !aligned(value, 16)) || (probs && !aligned(probs, 16)) || (greedy && !aligned(greedy, 16)))
         return ARN_EINVAL;
     if (d.qhead && probs) return ARN_ESHAPE;
-    const Workspace o = make_workspace(d, B, ARN_MODE_FORWARD);
-    if (workspace_bytes < o.total) return ARN_EWORKSPACE;
-    if (int e = check_arch()) return e;
-    hipStream_t s = (hipStream_t)stream;
+    *d_out = d;
+    return ARN_OK;
+}
+
+// The launches of one inference call; `ws` holds make_workspace(d, B, ARN_MODE_FORWARD).total bytes.
+int policy_forward_launches(const arn_config *cfg, const Dims &d, const Workspace &o, const void *w_packed,
+                            const uint8_t *obs, int B, float *logits, float *value, float *probs, int32_t *greedy,
+                            char *ws, hipStream_t s) {
     const Packed w = view_packed(w_packed, d);
-    forward_launches(d, w, obs, B, (char *)workspace, o, logits, d.NH, false, s);
+    forward_launches(d, w, obs, B, ws, o, logits, d.NH, false, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
-        PvHeadArgs p = pv_head_args(d, w, B, (char *)workspace, o);
+        PvHeadArgs p = pv_head_args(d, w, B, ws, o);
         p.logits = logits; p.value = value; p.probs = probs; p.greedy = greedy;
         p.rpb = infer_rows_per_block(B);
         hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
@@ -477,6 +486,20 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
                            (const uint8_t *)nullptr, probs, value, greedy, (float *)nullptr);
     }
     return launched();
+}
+}  // namespace
+
+int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, float *logits,
+                       float *value, float *probs, int32_t *greedy, void *workspace, size_t workspace_bytes,
+                       void *stream) {
+    Dims d;
+    if (int e = check_policy_forward(cfg, w_packed, obs, B, logits, value, probs, greedy, &d)) return e;
+    if (!aligned(workspace, 256)) return ARN_EINVAL;
+    const Workspace o = make_workspace(d, B, ARN_MODE_FORWARD);
+    if (workspace_bytes < o.total) return ARN_EWORKSPACE;
+    if (int e = check_arch()) return e;
+    return policy_forward_launches(cfg, d, o, w_packed, obs, B, logits, value, probs, greedy, (char *)workspace,
+                                   (hipStream_t)stream);
 }
 
 int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, const float *u,
@@ -550,7 +573,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     float *z = (float *)(ws + o.z);
     __bf16 *h = (__bf16 *)(ws + o.h);
     __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph);
-    float *lossp = (float *)(ws + o.lossp);
+    float *lossp = (float *)(ws + o.lossp), *hbp = (float *)(ws + o.hbp);
     const int lblocks = loss_blocks(d, B);
 
     // ---- forward and objective ----
@@ -568,7 +591,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         forward_launches(d, w, batch->obs, B, ws, o, z, d.NHP, true, s);
         ProfScope ps("loss", s);
         hipLaunchKernelGGL(c51_loss_kernel, dim3(lblocks), dim3(64 * C51_WAVES), 0, s, z, d.NHP, m, batch->action, B, d.A,
-                           d.atoms, d.NHP, dz, lossp);
+                           d.atoms, d.NHP, c51_loss_spw(B), dz, lossp, hbp);
     } else {
         const Packed *wt = nullptr;
         Packed wt_view;
@@ -606,7 +629,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             p.a_star = cfg->double_q ? (const int32_t *)(ws + o.astar) : nullptr;
             p.reward = batch->reward; p.done = batch->done; p.gamma = cfg->gamma;
         }
-        p.whd = w.whd; p.h = h; p.dz = dz; p.dph = dph; p.lossp = lossp;
+        p.whd = w.whd; p.h = h; p.dz = dz; p.dph = dph; p.lossp = lossp; p.hbp = hbp;
         p.rpb = loss_block(B);
         hipLaunchKernelGGL(pv_head_kernel<true>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
     }
@@ -635,6 +658,8 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         float *part = (float *)(ws + o.pwh);
         launch_tn("head_wgrad", p, part, B, d.NHP, HID, sp.hd, s2);
         launch_reduce("head_reduce", UnmapHead{head_rows(d, po), d.NHP}, part, dW, (long)d.NHP * HID, d.NHP, sp.hd, 1.f, s2);
+        // the head's bias gradient: the loss kernel's fp32 block partials, added in block order
+        launch_reduce("head_bias", UnmapHeadBias{head_rows(d, po)}, hbp, dW, 0, d.small ? 32 : d.NHP, lblocks, 1.f, s2);
     }
     if (d.head == ARN_HEAD_C51) {
         HeadDgrad p;

@@ -207,7 +207,10 @@ inline int fc_ksplit(int B) {
 // CUs busy at a few thousand samples; above that sixteen fill the MFMA's 16 sample columns and halve the workgroups;
 // small batches are spread over more CUs, four samples each (one CU's L1 rate bounds the addition of the fc partials).
 inline int loss_block(int B) { return B >= 4096 ? 16 : B <= 512 ? 4 : 8; }
-constexpr int C51_WAVES = 4;      // samples (one per wavefront) per block in the C51 kernels
+constexpr int C51_WAVES = 4;      // wavefronts per block in the C51 kernels (one sample per wavefront at a time)
+// Samples each wavefront of c51_loss_kernel takes one after the other: a block also writes one fp32 partial of the
+// head's bias gradient, so large batches use fewer, longer blocks.
+inline int c51_loss_spw(int B) { return B <= 2048 ? 1 : 8; }
 
 // byte offsets into the workspace
 struct Workspace {
@@ -220,11 +223,13 @@ struct Workspace {
     size_t m1, m2, m3;                  // ReLU sign bits of act1..3 (bit e&7 of byte e>>3, NHWC element e), written by the forward
     size_t dz, dph, dp3, dp2;           // bf16 gradients at pre-activations (d(pre1) never leaves the chip)
     size_t lossp;                       // fp32 [blocks][4] partial loss sums
+    size_t hbp;                         // fp32 [blocks][32 or NHP] partial sums of the head's bias gradient
     size_t pw1, pw2, pw3, pwfc, pwh;    // fp32 weight-gradient partials [split][N*K' + N]
     size_t total;
 };
 inline int loss_blocks(const Dims &d, int B) {
-    return d.small ? (B + loss_block(B) - 1) / loss_block(B) : (B + C51_WAVES - 1) / C51_WAVES;
+    const int per = d.small ? loss_block(B) : C51_WAVES * c51_loss_spw(B);
+    return (B + per - 1) / per;
 }
 inline Workspace make_workspace(const Dims &d, int B, int mode) {
     Workspace w{};
@@ -263,6 +268,7 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
         w.dp3 = take(b * feat * 2);
         w.dp2 = take(b * p2 * C2 * 2);
         w.lossp = take((size_t)loss_blocks(d, B) * 4 * 4);
+        w.hbp = take((size_t)loss_blocks(d, B) * (d.small ? 32 : d.NHP) * 4);
         const Splits s = make_splits(d, B);
         w.pw1 = take((size_t)s.c1 * ((size_t)C1 * KW1 + C1) * 4);
         w.pw2 = take((size_t)s.c2 * ((size_t)C2 * KW2 + C2) * 4);

@@ -71,6 +71,7 @@ struct PvHeadArgs {
     __bf16 *dz;             // [B][64]
     __bf16 *dph;            // [B][512] d(pre_fc)
     float *lossp;           // [blocks][4] partial sums {policy, value, entropy}
+    float *hbp;             // [blocks][32] this block's sum of dz per head row, from the fp32 values (the bias gradient)
 };
 
 __device__ __forceinline__ float group16_sum(float v) { return row16_sum(v); }   // same bits in all 16 lanes of the group
@@ -92,6 +93,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
     __shared__ float sZ[4][32][PVH_ROWS];                 // per-wave partial head outputs [wave][row][sample]
     __shared__ __attribute__((aligned(16))) __bf16 sDz[PVH_ROWS * PVH_DZS];
     __shared__ float sRed[3][PVH_ROWS];
+    __shared__ float sG[TRAIN ? PVH_ROWS : 1][32];        // fp32 dz, for the bias gradient
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rpb = p.rpb <= 0 ? PVH_ROWS : p.rpb;
@@ -332,6 +334,8 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
         if (!live) g0 = g1 = 0.f;
         sDz[srow * PVH_DZS + c] = (__bf16)g0;
         sDz[srow * PVH_DZS + c + 16] = (__bf16)g1;
+        sG[srow][c] = g0;
+        sG[srow][c + 16] = g1;
         if (c == 0) {
             sRed[0][srow] = live ? t0 : 0.f;
             sRed[1][srow] = live ? t1 : 0.f;
@@ -343,6 +347,16 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
 #pragma unroll
             for (int i = 0; i < PVH_ROWS; ++i) t += sRed[tid][i];
             p.lossp[blockIdx.x * 4 + tid] = t;
+        }
+        // The head's bias gradient is the sum of dz over the batch.  It is taken from the fp32 values, in sample
+        // order: a sum of bf16-rounded terms is off by about 2^-9 of its largest terms, which is most of the
+        // result when the terms happen to cancel -- and these are tensors of one to a few dozen entries.
+        if (tid >= 64 && tid < 96) {
+            const int r = tid - 64;
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < PVH_ROWS; ++i) t += sG[i][r];
+            p.hbp[blockIdx.x * 32 + r] = t;
         }
         if (tid < PVH_ROWS * 8) {   // dz rows [64] as eight 16-byte words; columns 32.. are zero
             const int r = tid >> 3, q = tid & 7;

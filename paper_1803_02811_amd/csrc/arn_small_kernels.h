@@ -254,11 +254,15 @@ __global__ __launch_bounds__(256) void conv_reduce_kernel(ConvReducePlan pl, flo
     }
 }
 
-struct UnmapHead {
+struct UnmapHeadBias {   // index = head row -> its bias entry in the flat gradient (or -1)
+    MapHeadRow h;
+    __device__ long operator()(long i) const { return h.brow((int)i); }
+};
+struct UnmapHead {       // the weight-gradient GEMM's partial block; its bias sums (of bf16 values) are not used
     MapHeadRow h;
     int NHP;
     __device__ long operator()(long i) const {
-        if (i >= (long)NHP * HID) return h.brow((int)(i - (long)NHP * HID));
+        if (i >= (long)NHP * HID) return -1;
         const long b = h.wrow((int)(i / HID));
         return b < 0 ? -1 : b + i % HID;
     }
@@ -366,14 +370,24 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
 
 // Categorical cross-entropy against the projected target and its gradient:
 // L_n = -sum_i m_i log p_i(s_n, a_n);  d/dlogit[a_n][i] = (p_i sum(m) - m_i)/B, other rows 0.
-// One wavefront per sample writes the whole bf16 gradient row [NHP].
+// A wavefront takes `spw` consecutive samples one after the other and writes each one's whole bf16 gradient
+// row [NHP].  The head's bias gradient (the sum of those rows over the batch) is accumulated from the fp32
+// values -- per wavefront in LDS, in sample order, then over the block's wavefronts in order -- and written as
+// one partial per block; a sum of the bf16-rounded rows would be off by about 2^-9 of its largest terms, which
+// is most of the result when they cancel.
+constexpr int C51_MAX_NHP = 18 * 64;
 __global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
     const float *__restrict__ z, int zstride, const float *__restrict__ m_in, const int32_t *__restrict__ action,
-    int B, int A, int atoms, int NHP, __bf16 *__restrict__ dz, float *__restrict__ lossp) {
+    int B, int A, int atoms, int NHP, int spw, __bf16 *__restrict__ dz, float *__restrict__ lossp,
+    float *__restrict__ hbp) {
     __shared__ float red[C51_WAVES];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, n = blockIdx.x * C51_WAVES + wv;
+    __shared__ float sb[C51_WAVES][C51_MAX_NHP];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int c = lane; c < NHP; c += 64) sb[wv][c] = 0.f;
     float ce = 0.f;
-    if (n < B) {
+    for (int i = 0; i < spw; ++i) {
+        const int n = (blockIdx.x * C51_WAVES + wv) * spw + i;    // wavefront-uniform
+        if (n >= B) break;
         const int a = min(max(action[n], 0), A - 1);   // an out-of-range action must not become an out-of-range read
         const bool on = lane < atoms;
         const float x = on ? z[(size_t)n * zstride + a * atoms + lane] : -INFINITY;
@@ -382,10 +396,11 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
         const float s = wave_sum(e);
         const float lp = x - mx - logf(s);
         const float m = on ? m_in[(size_t)n * atoms + lane] : 0.f;
-        ce = -wave_sum(on ? m * lp : 0.f);
+        ce += -wave_sum(on ? m * lp : 0.f);
         const float msum = wave_sum(m);
         const float g = on ? (e / s * msum - m) / (float)B : 0.f;
         const int lo = a * atoms;
+        if (on) sb[wv][lo + lane] += g;                 // this wavefront's own row of LDS: no other writer
         __bf16 *row = dz + (size_t)n * NHP;
         for (int c0 = 0; c0 < NHP; c0 += 64) {
             const int c = c0 + lane, src = c - lo;
@@ -395,6 +410,12 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
     }
     if (lane == 0) red[wv] = ce;
     __syncthreads();
+    for (int c = threadIdx.x; c < NHP; c += 64 * C51_WAVES) {
+        float t = sb[0][c];
+#pragma unroll
+        for (int w = 1; w < C51_WAVES; ++w) t += sb[w][c];
+        hbp[(size_t)blockIdx.x * NHP + c] = t;
+    }
     if (threadIdx.x == 0) {
         float s = 0.f;
         for (int i = 0; i < C51_WAVES; ++i) s += red[i];

@@ -20,6 +20,34 @@ def tol_check(got, ref, name, rel=1e-2, abs_=1e-3):
     return err, bound
 
 
+REL_BAR = 2e-2      # purely relative bar per gradient tensor: max|err| <= REL_BAR * max|ref|
+REL_FLOOR = 1e-7    # tensors whose reference is zero up to round-off are held to this absolute figure instead
+
+
+def check_grads(got: dict, ref: dict, title=""):
+    """Every gradient tensor against the oracle's: the stated bar (1e-2 max|ref| + 1e-3) AND a purely relative
+    one (max|err| <= 2e-2 max|ref|), because for small-magnitude tensors (large batches, the categorical head)
+    the absolute term of the stated bar would carry the comparison alone.  Prints err / max|ref| per tensor."""
+    assert set(got) == set(ref), (sorted(got), sorted(ref))
+    rows, bad = [], []
+    for name in ref:
+        g = np.asarray(got[name], dtype=np.float64)
+        r = np.asarray(ref[name], dtype=np.float64)
+        assert g.shape == r.shape, (name, g.shape, r.shape)
+        assert np.isfinite(g).all(), name
+        err = float(np.abs(g - r).max()) if g.size else 0.0
+        mx = float(np.abs(r).max()) if r.size else 0.0
+        ratio = err / mx if mx > 0 else (0.0 if err == 0 else float("inf"))
+        rows.append((name, err, mx, ratio))
+        if err > 1e-2 * mx + 1e-3 or err > max(REL_BAR * mx, REL_FLOOR):
+            bad.append(name)
+    print("\n  gradient parity %s: err / max|ref| per tensor" % title)
+    for name, err, mx, ratio in rows:
+        print("    %-8s max|err| %.3e  max|ref| %.3e  ratio %.2e%s" % (name, err, mx, ratio, "  <-- FAIL" if name in bad else ""))
+    assert not bad, "gradient tensors outside the bar (stated or 2e-2 relative): %s" % ", ".join(bad)
+    return {name: ratio for name, _, _, ratio in rows}
+
+
 class GpuNet:
     """Packed weights + workspace for one config; thin wrapper over the binding."""
 

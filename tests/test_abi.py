@@ -170,3 +170,4 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".h", ".hip", ".cpp")):
                 text = open(os.path.join(root, f)).read()
                 assert "oracle" not in text, f
+

@@ -4,7 +4,7 @@ import pytest
 
 import workloads as wl
 from oracle import nature_cnn as orc
-from tests.gpu_util import GpuNet, per_tensor, tol_check
+from tests.gpu_util import GpuNet, check_grads, per_tensor, tol_check
 
 pytestmark = pytest.mark.gpu
 
@@ -41,8 +41,7 @@ def test_dqn_gradients(head, double_q, B):
     net = GpuNet(A, head, flat, double_q=double_q)
     dW, loss = net.train(batch, "dqn", target_packed=net.pack(tflat))
     got, want = per_tensor(dW, A, head), per_tensor(ref["flat"], A, head)
-    for name in want:
-        tol_check(got[name], want[name], name)
+    check_grads(got, want, "dqn %s double=%d B=%d" % (head, double_q, B))
     assert abs(loss[0] - ref["loss"]["total"]) <= 1e-2 * abs(ref["loss"]["total"]) + 1e-3
     assert loss[1] == pytest.approx(loss[0]) and loss[2] == 0 and loss[3] == 0
     # the bootstrapped action is a discrete choice: where the selecting network's top-2 gap is below the bar a

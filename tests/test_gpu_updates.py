@@ -13,7 +13,7 @@ import paper_1803_02811_amd as arn
 import workloads as wl
 from oracle import nature_cnn as orc
 from oracle import update_rules as up
-from tests.gpu_util import DEV, GpuNet, per_tensor, tol_check
+from tests.gpu_util import DEV, GpuNet, check_grads, per_tensor, tol_check
 
 pytestmark = pytest.mark.gpu
 
@@ -130,14 +130,26 @@ def test_update_with_repack_matches_separate_prepare(head):
     n = flat.size
     inp = wl.update_rule_inputs(n, 1, seed=400)
     g = _dev(inp["grads"][0] * 100.0)
-    for rule in ("rmsprop", "adam"):
+    for rule in ("rmsprop", "adam", "adam_local", "adam_merge"):
         th = _dev(flat)
         packed = torch.zeros(arn.packed_bytes(net.cfg), dtype=torch.uint8, device=DEV)
-        s1, s2 = (torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(2))
+        s1, s2, a1, a2, a3 = (torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(5))
         if rule == "rmsprop":
             arn.rmsprop_update(th, g, s1, lr=1e-3, rho=0.99, eps=1e-6, cfg=net.cfg, w_packed=packed)
-        else:
+        elif rule == "adam":
             arn.adam_update(th, g, s1, s2, t=1, r=1e-3, beta1=0.9, beta2=0.999, eps=1e-5, cfg=net.cfg, w_packed=packed)
+        elif rule == "adam_local":
+            arn.async_adam_local_step(th, g, s1, s2, a1, a2, a3, t=1, r=1e-3, beta1=0.9, beta2=0.999, eps=1e-5,
+                                      cfg=net.cfg, w_packed=packed)
+        else:
+            # a local step without the re-pack, then the merge re-packs the learner's new theta (= the new central one)
+            arn.async_adam_local_step(th, g, s1, s2, a1, a2, a3, t=1, r=1e-3, beta1=0.9, beta2=0.999, eps=1e-5)
+            th_c = _dev(flat)
+            m_c, v_c = (torch.zeros(n, dtype=torch.float32, device=DEV) for _ in range(2))
+            arn.async_adam_merge(th_c, m_c, v_c, th, s1, s2, a1, a2, a3, n_local=1, beta1=0.9, beta2=0.999,
+                                 cfg=net.cfg, w_packed=packed)
+            torch.cuda.synchronize()
+            assert torch.equal(th, th_c) and not a1.any() and not a3.any()
         torch.cuda.synchronize()
         assert not torch.equal(th, _dev(flat))
         want = torch.zeros_like(packed)
@@ -184,6 +196,5 @@ def test_one_learner_iteration_gradient_update_gradient():
     dW1, loss1 = net.train(batch, "a2c")
     assert np.abs(g1["flat"] - g0["flat"]).max() > 0.2 * np.abs(g0["flat"]).max()     # a different gradient
     got, want = per_tensor(dW1, A, "pv"), per_tensor(g1["flat"], A, "pv")
-    for name in want:
-        tol_check(got[name], want[name], "gradient after the update: " + name)
+    check_grads(got, want, "gradient after the update")
     assert abs(loss1[0] - g1["loss"]["total"]) < 1e-2 * abs(g1["loss"]["total"]) + 1e-3
