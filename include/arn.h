@@ -72,7 +72,8 @@ typedef enum {
     ARN_EKIND = -3,      /* unknown head_kind / loss_kind / mode */
     ARN_EWORKSPACE = -4, /* workspace smaller than arn_workspace_bytes() */
     ARN_EARCH = -5,      /* current device is not gfx950 */
-    ARN_EHIP = -6        /* a HIP runtime call or launch failed */
+    ARN_EHIP = -6,       /* a HIP runtime call or launch failed */
+    ARN_ESTATIC = -7     /* arn_policy_forward_static: the call needs more scratch memory than ARN_STATIC_SCRATCH_BYTES */
 } arn_status;
 
 enum { ARN_HEAD_PV = 0, ARN_HEAD_C51 = 1, ARN_HEAD_Q = 2, ARN_HEAD_DUEL = 3 };
@@ -126,6 +127,21 @@ int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_pack
 int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B,
                        float *logits, float *value, float *probs, int32_t *greedy,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* arn_policy_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and kernels as
+ * arn_policy_forward, but the scratch memory is a buffer of ARN_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (one copy per GPU, held until the process ends); the call allocates and frees nothing.
+ *   - Accepted iff arn_workspace_bytes(cfg, B, ARN_MODE_FORWARD) <= ARN_STATIC_SCRATCH_BYTES (for example every
+ *     policy/value, Q or dueling head on 84x84 frames up to B = 256); otherwise ARN_ESTATIC and nothing is launched.
+ *   - All calls on one GPU share that buffer and it keeps the last call's contents (every call rewrites what it
+ *     reads): calls that overlap in time on one GPU -- from two streams or two host threads -- race; order them
+ *     on one stream or with events.
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress); make that call outside
+ *     graph capture. */
+#define ARN_STATIC_SCRATCH_BYTES (32u << 20)
+int arn_policy_forward_static(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B,
+                              float *logits, float *value, float *probs, int32_t *greedy, void *stream);
 
 /* Inference that returns actions, as the paper's sampler does (section "Synchronized Sampling": the
  * simulator processes receive actions, not logits).  The random numbers are inputs:

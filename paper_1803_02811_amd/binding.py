@@ -68,6 +68,8 @@ def load_library():
         lib.arn_weights_prepare.argtypes = [cp, vp, vp, vp]
         lib.arn_policy_forward.restype = ctypes.c_int
         lib.arn_policy_forward.argtypes = [cp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.arn_policy_forward_static.restype = ctypes.c_int
+        lib.arn_policy_forward_static.argtypes = [cp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp]
         lib.arn_policy_act.restype = ctypes.c_int
         lib.arn_policy_act.argtypes = [cp, vp, vp, ctypes.c_int, vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
         lib.arn_train_step_grads.restype = ctypes.c_int
@@ -135,6 +137,16 @@ def policy_forward(cfg: Config, w_packed, obs, logits, value=None, probs=None, g
     _check(load_library().arn_policy_forward(
         ctypes.byref(cfg), _ptr(w_packed), _ptr(obs), B, _ptr(logits), _ptr(value), _ptr(probs), _ptr(greedy),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)), "arn_policy_forward")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20   # ARN_STATIC_SCRATCH_BYTES of the header
+
+
+def policy_forward_static(cfg: Config, w_packed, obs, logits, value=None, probs=None, greedy=None, *, stream=None) -> None:
+    B = int(obs.shape[0])
+    _check(load_library().arn_policy_forward_static(
+        ctypes.byref(cfg), _ptr(w_packed), _ptr(obs), B, _ptr(logits), _ptr(value), _ptr(probs), _ptr(greedy),
+        _stream(stream)), "arn_policy_forward_static")
 
 
 def policy_act(cfg: Config, w_packed, obs, u, u2, action, logp=None, *, epsilon=0.0, workspace, stream=None) -> None:

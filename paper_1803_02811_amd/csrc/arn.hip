@@ -22,6 +22,11 @@
 
 using namespace arn;
 
+// Scratch memory of arn_policy_forward_static, the entry point for callers that cannot allocate: one copy per
+// GPU the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress (static_scratch_ptr below); kernels receive the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[ARN_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 std::mutex g_lazy_mutex;   // guards the lazily filled per-device tables below (first calls from several host threads)
@@ -93,6 +98,20 @@ SideStream *side_stream() {
         ss.state = ok ? 1 : -1;
     }
     return ss.state == 1 ? &ss : nullptr;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+void *static_scratch_ptr() {
+    static void *per_dev[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_lazy_mutex);
+    if (!per_dev[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        per_dev[dev] = ptr;
+    }
+    return per_dev[dev];
 }
 
 template <class P>
@@ -418,6 +437,7 @@ const char *arn_status_string(int status) {
         case ARN_EWORKSPACE: return "workspace too small";
         case ARN_EARCH: return "device is not gfx950";
         case ARN_EHIP: return "HIP runtime error";
+        case ARN_ESTATIC: return "batch too large for the library's static scratch buffer (arn_policy_forward_static)";
         default: return "unknown status";
     }
 }
@@ -451,7 +471,7 @@ int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_pack
 }
 
 namespace {
-// Argument checks of arn_policy_forward; fills *d_out.
+// Argument checks shared by arn_policy_forward and arn_policy_forward_static; fills *d_out.
 int check_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, float *logits,
                          float *value, float *probs, int32_t *greedy, Dims *d_out) {
     if (!cfg || B <= 0 || B > (1 << 20)) return ARN_EINVAL;
@@ -499,6 +519,19 @@ int arn_policy_forward(const arn_config *cfg, const void *w_packed, const uint8_
     if (workspace_bytes < o.total) return ARN_EWORKSPACE;
     if (int e = check_arch()) return e;
     return policy_forward_launches(cfg, d, o, w_packed, obs, B, logits, value, probs, greedy, (char *)workspace,
+                                   (hipStream_t)stream);
+}
+
+int arn_policy_forward_static(const arn_config *cfg, const void *w_packed, const uint8_t *obs, int B, float *logits,
+                              float *value, float *probs, int32_t *greedy, void *stream) {
+    Dims d;
+    if (int e = check_policy_forward(cfg, w_packed, obs, B, logits, value, probs, greedy, &d)) return e;
+    const Workspace o = make_workspace(d, B, ARN_MODE_FORWARD);
+    if (o.total > (size_t)ARN_STATIC_SCRATCH_BYTES) return ARN_ESTATIC;
+    if (int e = check_arch()) return e;
+    void *ptr = static_scratch_ptr();
+    if (!ptr) return ARN_EHIP;
+    return policy_forward_launches(cfg, d, o, w_packed, obs, B, logits, value, probs, greedy, (char *)ptr,
                                    (hipStream_t)stream);
 }
 

@@ -171,3 +171,24 @@ def test_product_path_does_not_import_the_oracle():
                 text = open(os.path.join(root, f)).read()
                 assert "oracle" not in text, f
 
+
+def test_static_scratch_entry_point_rejects_on_the_host(lib):
+    """arn_policy_forward_static: same argument checks as arn_policy_forward, and a batch whose forward workspace
+    exceeds the library's static buffer is refused (ARN_ESTATIC) before anything is launched."""
+    header = open(os.path.join(ROOT, "include", "arn.h")).read()
+    m = re.search(r"#define ARN_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == arn.STATIC_SCRATCH_BYTES
+    cfg = arn.Config(18, arn.ARN_HEAD_PV)
+    c = ctypes.byref(cfg)
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1001)
+    fn = lib.arn_policy_forward_static
+    assert fn(None, fake, fake, 4, fake, fake, None, None, None) == -1
+    assert fn(c, fake, fake, 0, fake, fake, None, None, None) == -1
+    assert fn(c, fake, odd, 4, fake, fake, None, None, None) == -1
+    assert fn(c, fake, fake, 4, fake, None, None, None, None) == -1          # the policy/value head needs `value`
+    assert arn.workspace_bytes(cfg, 256, arn.ARN_MODE_FORWARD) <= arn.STATIC_SCRATCH_BYTES      # the documented example
+    too_big = 256
+    while arn.workspace_bytes(cfg, too_big, arn.ARN_MODE_FORWARD) <= arn.STATIC_SCRATCH_BYTES:
+        too_big *= 2
+    assert fn(c, fake, fake, too_big, fake, fake, None, None, None) == -7
+    assert b"static" in lib.arn_status_string(-7)
