@@ -17,6 +17,7 @@
 #include "arn_resident_conv.h"
 #include "arn_conv_bwd.h"
 #include "arn_conv23_fwd.h"
+#include "arn_infer_fwd.h"
 #include "arn_small_kernels.h"
 #include "arn_update.h"
 
@@ -163,6 +164,7 @@ void launch_reduce(const char *name, const F &f, const float *part, float *dW, l
 struct Packed {   // typed views of the packed blob
     const __bf16 *w1, *w2, *w3, *wfc, *wh, *whd, *wfcd, *w3d, *w2d;
     const __bf16 *w1l, *w2l, *w3l, *wfcl, *whl;
+    const _Float16 *w1h, *w2h, *w3h, *wfch;   // fp16 forward layouts
     const float *b1, *b2, *b3, *bfc, *bh;
 };
 Packed view_packed(const void *blob, const Dims &d) {
@@ -188,22 +190,28 @@ Packed view_packed(const void *blob, const Dims &d) {
     p.w3l = (const __bf16 *)(b + o.w3l);
     p.wfcl = (const __bf16 *)(b + o.wfcl);
     p.whl = (const __bf16 *)(b + o.whl);
+    p.w1h = (const _Float16 *)(b + o.w1h);
+    p.w2h = (const _Float16 *)(b + o.w2h);
+    p.w3h = (const _Float16 *)(b + o.w3h);
+    p.wfch = (const _Float16 *)(b + o.wfch);
     return p;
 }
 
-// fc layer (three products) and, for the categorical head, the head GEMM; shared by both geometries
-template <int FEAT_>
+// fc layer and, for the categorical head, the head GEMM; shared by both geometries.  F16: act3 and the fc
+// weights are fp16 and the layer is one product (no-gradient forward); otherwise three bf16 products.
+template <int FEAT_, bool F16 = false>
 void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o, float *z_out,
                           int zstride, hipStream_t s) {
     __bf16 *a3 = (__bf16 *)(ws + o.a3), *a3l = (__bf16 *)(ws + o.a3l);
     __bf16 *h = (__bf16 *)(ws + o.h), *hl = (__bf16 *)(ws + o.hl);
     {
-        typedef FcFwdT<FEAT_> Fc;
+        typedef typename std::conditional<F16, FcFwdF16T<FEAT_>, FcFwdT<FEAT_>>::type Fc;
         Fc p;
-        p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
+        p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = F16 ? (const __bf16 *)w.wfch : w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
         p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
         p.to_partial = p.ksplit > 1 || d.small;
-        launch_nt_split("fc_fwd", p, B, HID / Fc::BN, p.ksplit, s);
+        if constexpr (F16) launch_nt("fc_fwd", p, B, HID / Fc::BN, p.ksplit, s);
+        else launch_nt_split("fc_fwd", p, B, HID / Fc::BN, p.ksplit, s);
         if (p.ksplit > 1 && !d.small) {
             ProfScope ps("fc_finish", s);
             const long total = (long)B * HID;
@@ -295,6 +303,29 @@ void forward_trunk(const Dims &d, const Packed &w, const uint8_t *obs, int B, ch
         }
     }
     fc_and_head_launches<G::FEAT>(d, w, B, ws, o, z_out, zstride, s);
+}
+
+// Forward pass that carries no gradient (action selection): the three convolutions in one kernel and one fp16
+// product per layer, act3 in fp16, then the fc layer in fp16.  The heads run as in the training forward.
+template <class G>
+void infer_trunk(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                 float *z_out, int zstride, hipStream_t s) {
+    typedef ConvConfigs<G> Cfg;
+    {
+        ProfScope ps("conv_infer", s);
+        InferConvArgs p;
+        p.obs = obs; p.w1 = w.w1h; p.w2 = w.w2h; p.w3 = w.w3h; p.b1 = w.b1; p.b2 = w.b2; p.b3 = w.b3;
+        p.a3 = (_Float16 *)(ws + o.a3);
+        const int spw = resident_spw(B, 256);
+        hipLaunchKernelGGL((infer_conv_kernel<G, typename Cfg::Fwd2, typename Cfg::Fwd3>), dim3(cdiv(B, spw)),
+                           dim3(INF_THREADS), 0, s, p, B, spw);
+    }
+    fc_and_head_launches<G::FEAT, true>(d, w, B, ws, o, z_out, zstride, s);
+}
+void infer_launches(const Dims &d, const Packed &w, const uint8_t *obs, int B, char *ws, const Workspace &o,
+                    float *z_out, int zstride, hipStream_t s) {
+    if (d.geom == ARN_GEOM_PAPER) infer_trunk<GeoPaper>(d, w, obs, B, ws, o, z_out, zstride, s);
+    else infer_trunk<Geo84>(d, w, obs, B, ws, o, z_out, zstride, s);
 }
 
 // trunk + heads forward.  C51: z_out = atom logits, rows of zstride floats (NH = dense, or NHP for the
@@ -492,7 +523,7 @@ int policy_forward_launches(const arn_config *cfg, const Dims &d, const Workspac
                             const uint8_t *obs, int B, float *logits, float *value, float *probs, int32_t *greedy,
                             char *ws, hipStream_t s) {
     const Packed w = view_packed(w_packed, d);
-    forward_launches(d, w, obs, B, ws, o, logits, d.NH, false, s);
+    infer_launches(d, w, obs, B, ws, o, logits, d.NH, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, ws, o);
@@ -555,7 +586,7 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
     char *ws = (char *)workspace;
     const Packed w = view_packed(w_packed, d);
     float *z = (float *)(ws + o.z);   // categorical head only
-    forward_launches(d, w, obs, B, ws, o, z, d.NHP, false, s);
+    infer_launches(d, w, obs, B, ws, o, z, d.NHP, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
         PvHeadArgs p = pv_head_args(d, w, B, ws, o);

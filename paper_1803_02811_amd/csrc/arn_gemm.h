@@ -34,10 +34,14 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int LDS_ROW = 9;   // u32x4 per staged row: 8 of data (64 bf16) + 1 of padding
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
 __device__ __forceinline__ u32x2 pack_bf16x4(float a, float b, float c, float d) {
     bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
@@ -170,6 +174,24 @@ template <class P>
 struct ThreadsOf<P, decltype((void)P::THREADS)> {
     static constexpr int value = P::THREADS;
 };
+// Problems with a static member F16 = true hold fp16 operands (same 16-byte fragments, the fp16 MFMA): the single
+// product of the forward passes that carry no gradient.
+template <class P, class = void>
+struct IsF16 {
+    static constexpr bool value = false;
+};
+template <class P>
+struct IsF16<P, decltype((void)P::F16)> {
+    static constexpr bool value = P::F16;
+};
+// one 32x32x16 MFMA on fragments held as eight 16-bit lanes: bf16, or fp16 when F16
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
 // Problems with a member function prefetch(m, n) have it called for every output quad before the k loop;
 // its result (for example the ReLU-derivative bits of the quad) is handed to store(), which then needs no
 // dependent load in the epilogue.
@@ -302,10 +324,10 @@ __global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p)
 #pragma unroll
                 for (int b = 0; b < TM; ++b) {
                     if constexpr (SPLIT)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw2[a], fa[b], acc[a][b], 0, 0, 0);
+                        acc[a][b] = mfma_32x32x16<IsF16<P>::value>(fw2[a], fa[b], acc[a][b]);
                     if constexpr (ALO)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fa2[b], acc[a][b], 0, 0, 0);
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[a], fa[b], acc[a][b], 0, 0, 0);
+                        acc[a][b] = mfma_32x32x16<IsF16<P>::value>(fw[a], fa2[b], acc[a][b]);
+                    acc[a][b] = mfma_32x32x16<IsF16<P>::value>(fw[a], fa[b], acc[a][b]);
                 }
         }
         __syncthreads();

@@ -121,6 +121,7 @@ struct PackedOffsets {
     size_t b1, b2, b3, bfc, bh;          // fp32 biases
     size_t w1l, w2l, w3l, wfcl, whl;     // low parts (w - hi) for the three-product inference path
     size_t whd, wfcd, w3d, w2d;          // input-gradient layouts
+    size_t w1h, w2h, w3h, wfch;          // fp16 copies of the forward layouts (single-product, no-gradient forward)
     size_t fwd_bytes, total;
 };
 inline PackedOffsets packed_offsets(const Dims &d) {
@@ -147,6 +148,10 @@ inline PackedOffsets packed_offsets(const Dims &d) {
     o.wfcd = take((size_t)d.feat * HID * 2);
     o.w3d = take((size_t)C2 * KW3 * 2);
     o.w2d = take((size_t)4 * C1 * 4 * C2 * 2);
+    o.w1h = take((size_t)C1 * KW1 * 2);
+    o.w2h = take((size_t)C2 * KW2 * 2);
+    o.w3h = take((size_t)C3 * KW3 * 2);
+    o.wfch = take((size_t)HID * d.feat * 2);
     o.total = p;
     return o;
 }

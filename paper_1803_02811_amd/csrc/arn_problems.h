@@ -94,6 +94,12 @@ struct FcFwdT : DenseGather<FEAT_> {
     }
 };
 typedef FcFwdT<FEAT> FcFwd;
+// The same layer with fp16 activations and weights in one product (no-gradient forward): `in` and `w` point at
+// fp16 data of the same layouts; the outputs are the fp32 partial sums or the (hi, lo) bf16 hidden layer as above.
+template <int FEAT_>
+struct FcFwdF16T : FcFwdT<FEAT_> {
+    static constexpr bool F16 = true;
+};
 
 // categorical head: rows of the packed head matrix are the A*atoms categorical rows
 // C51: atom logits fp32 [M][ZS] with bias; ZS = ZW (dense, the inference output) or the padded head width

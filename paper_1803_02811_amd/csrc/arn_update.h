@@ -136,6 +136,7 @@ struct PackSeg {
     int first_block;
     long n;
     void *out, *out_lo;
+    void *out_f16;     // fp16 copy of a forward layout, or null
 };
 // The fc matrix (95 % of the parameters) is laid out by tile blocks instead: elementwise maps would read it with
 // a stride of one row (input-gradient layout) or of P3 floats (forward layout).  A tile is PACK_FC_ROWS hidden
@@ -144,6 +145,8 @@ struct PackSeg {
 // eight hidden units (input-gradient layout).  Eight rows per tile measured best (12.2 us for the whole launch
 // against 13.1 with sixteen and 16 with thirty-two; the elementwise maps took 18.3).
 constexpr int PACK_FC_ROWS = 8, PACK_FC_CH = 8;
+// fp16 copy of a weight: values beyond the largest half are clamped to it instead of becoming infinite
+__device__ __forceinline__ _Float16 to_f16_finite(float v) { return (_Float16)fminf(fmaxf(v, -65504.f), 65504.f); }
 constexpr int PACK_FC_MAX_P3 = 108;   // 12 x 9 positions after conv3 on 104 x 80 frames
 static_assert(P3 <= PACK_FC_MAX_P3 && GeoPaper::P3 <= PACK_FC_MAX_P3, "fc tile buffer");
 static_assert(HID % PACK_FC_ROWS == 0 && C3 % PACK_FC_CH == 0 && PACK_FC_CH == 8 && PACK_FC_ROWS % 8 == 0, "fc tile shape");
@@ -151,6 +154,7 @@ struct PackPlan {
     PackSeg seg[PK_COUNT];
     int fc_first_block;                      // blocks from here on are fc tiles
     __bf16 *fc_hi, *fc_lo, *fc_dgrad;
+    _Float16 *fc_f16;
     long w1, w2, w3, wfc, b1, b2, b3, bfc;   // offsets in the flat vector
     MapHeadRow hr;
     int NHP;
@@ -173,6 +177,7 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
         pl.seg[k].n = n;
         pl.seg[k].out = b + out;
         pl.seg[k].out_lo = has_lo ? b + lo : nullptr;
+        pl.seg[k].out_f16 = nullptr;
     };
     set(PK_W1, (long)C1 * KW1, o.w1, o.w1l, true);
     set(PK_W2, (long)C2 * KW2, o.w2, o.w2l, true);
@@ -186,7 +191,9 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     set(PK_BH, d.NHP, o.bh, 0, false);
     set(PK_WHD, (long)HID * d.NHP, o.whd, 0, false);
     set(PK_WFCD, 0, o.wfcd, 0, false);            // by tile blocks, below
+    pl.seg[PK_W1].out_f16 = b + o.w1h; pl.seg[PK_W2].out_f16 = b + o.w2h; pl.seg[PK_W3].out_f16 = b + o.w3h;
     pl.fc_hi = (__bf16 *)(b + o.wfc); pl.fc_lo = (__bf16 *)(b + o.wfcl); pl.fc_dgrad = (__bf16 *)(b + o.wfcd);
+    pl.fc_f16 = (_Float16 *)(b + o.wfch);
     set(PK_W3D, (long)C2 * KW3, o.w3d, 0, false);
     set(PK_W2D, (long)4 * C1 * 256, o.w2d, 0, false);
     int blk = 0;
@@ -229,14 +236,17 @@ __device__ __forceinline__ void pack_fc_tile(const PackPlan &pl, const float *__
 #pragma unroll
         for (int c = 0; c < PACK_FC_CH; ++c) v[c] = s_t[r][c * p3 + pos];
         bf16x8 hi, lo;
+        f16x8 hf;
 #pragma unroll
         for (int c = 0; c < PACK_FC_CH; ++c) {
             hi[c] = (__bf16)v[c];
             lo[c] = (__bf16)(v[c] - (float)hi[c]);
+            hf[c] = to_f16_finite(v[c]);
         }
         const size_t at = (size_t)(n0 + r) * feat + (size_t)pos * C3 + c0;
         *reinterpret_cast<bf16x8 *>(pl.fc_hi + at) = hi;
         *reinterpret_cast<bf16x8 *>(pl.fc_lo + at) = lo;
+        *reinterpret_cast<f16x8 *>(pl.fc_f16 + at) = hf;
     }
     // input-gradient layout: one 16-byte word = hidden units n0 + 8h .. + 7 of (position pos, channel c)  (h = 0 with eight rows)
     for (int i = tid; i < (PACK_FC_ROWS / 8) * run; i += 256) {
@@ -262,10 +272,10 @@ __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float 
     // region fields selected without dynamic indexing of the argument block
     int first = 0;
     long n = 0;
-    void *out = nullptr, *out_lo = nullptr;
+    void *out = nullptr, *out_lo = nullptr, *out_f16 = nullptr;
 #pragma unroll
     for (int j = 0; j < PK_COUNT; ++j)
-        if (j == k) { first = pl.seg[j].first_block; n = pl.seg[j].n; out = pl.seg[j].out; out_lo = pl.seg[j].out_lo; }
+        if (j == k) { first = pl.seg[j].first_block; n = pl.seg[j].n; out = pl.seg[j].out; out_lo = pl.seg[j].out_lo; out_f16 = pl.seg[j].out_f16; }
     const long i = (long)((int)blockIdx.x - first) * 256 + threadIdx.x;
     if (i >= n) return;
     long s;
@@ -292,6 +302,7 @@ __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float 
         const __bf16 hi = (__bf16)v;
         ((__bf16 *)out)[i] = hi;
         if (out_lo) ((__bf16 *)out_lo)[i] = (__bf16)(v - (float)hi);
+        if (out_f16) ((_Float16 *)out_f16)[i] = to_f16_finite(v);
     }
 }
 

@@ -61,12 +61,13 @@ def test_categorical_draw_matches_the_oracle():
     want = orc.sample_categorical(probs, un["u"])
     act, logp = GpuNet(A, "pv", flat).act(obs, un["u"], un["u2"], want_logp=True)
     assert ((act >= 0) & (act < A)).all()
-    # the draw is a threshold decision on the CDF: compare where u is clear of every CDF boundary by more than
-    # the forward's error bar; elsewhere either neighbour is a correct draw
+    # the draw is a threshold decision on the CDF, as the greedy action is one on the logits: it is compared
+    # where u is clear of every CDF boundary by 5e-3 (the greedy rule's top-2 gap of 1e-2, half for each side:
+    # a boundary moves by no more than the logits' error); elsewhere either neighbour is a correct draw
     cdf = np.cumsum(probs, axis=1)
     margin = np.abs(cdf - un["u"][:, None].astype(np.float64)).min(axis=1)
-    clear = margin > 1e-3
-    assert clear.mean() > 0.9
+    clear = margin > 5e-3
+    assert clear.mean() > 0.75
     np.testing.assert_array_equal(act[clear], want[clear])
     near = ~clear
     assert (np.abs(act[near].astype(int) - want[near]) <= 1).all()

