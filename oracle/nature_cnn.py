@@ -157,6 +157,11 @@ class Geometry:
 NATURE_84 = Geometry()
 # the paper's own frame size and padding (appendix "Atari Frame Processing")
 PAPER_104x80 = Geometry(in_h=104, in_w=80, convs=((32, 8, 4, 0), (64, 4, 2, 1), (64, 3, 1, 1)))
+# the 2-convolutional-layer network the same appendix names for the policy-gradient runs.  The paper gives no filter
+# counts; they are those of the publication it cites for that network (the asynchronous actor-critic paper):
+# 16 filters 8x8 stride 4, 32 filters 4x4 stride 2, 256 hidden units.  On 104x80 frames the first layer gives 25x19
+# and the second, padded by 1 as the appendix says, the 12x9 map it states.
+A3C_104x80 = Geometry(in_h=104, in_w=80, convs=((16, 8, 4, 0), (32, 4, 2, 1)), hidden=256)
 
 
 @dataclass(frozen=True)

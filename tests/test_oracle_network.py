@@ -11,6 +11,10 @@ SMALL = orc.Geometry(in_ch=2, in_h=20, in_w=20, convs=((3, 4, 2, 0), (4, 3, 1, 0
 SMALL_PADDED = orc.Geometry(in_ch=2, in_h=22, in_w=18, convs=((3, 4, 2, 0), (4, 4, 2, 1), (4, 3, 1, 1)), hidden=6)
 
 
+# a small 2-convolution stack shaped like the policy-gradient network of the same appendix (second layer padded by 1)
+SMALL_TWO_CONV = orc.Geometry(in_ch=2, in_h=22, in_w=18, convs=((3, 4, 2, 0), (5, 4, 2, 1)), hidden=7)
+
+
 def _rand_params(spec, seed, bias=True):
     r = np.random.default_rng(seed)
     out = {}
@@ -103,6 +107,41 @@ def test_paper_geometry_forward_against_explicit_windows():
     assert np.isclose(c["pre_fc"][0, 3], acc, atol=1e-12)
 
 
+def test_two_convolution_network_sizes_and_forward_against_explicit_loops():
+    """The policy-gradient network of appendix "Atari Frame Processing": 104x80 frames, first layer 25x19, second
+    layer padded by 1 -> the 12x9 map the appendix states; outputs rebuilt with explicit window sums."""
+    g = orc.A3C_104x80
+    assert g.feature_shape() == (32, 12, 9) and wl.A3C_FC_INPUTS == 32 * 12 * 9
+    assert orc.out_size(104, 8, 4) == 25 and orc.out_size(80, 8, 4) == 19
+    assert orc.out_size(25, 4, 2, 1) == 12 and orc.out_size(19, 4, 2, 1) == 9
+    spec = orc.NetSpec(6, "pv", geometry=g)
+    assert orc.param_layout(spec) == wl.param_shapes(6, "pv", net="a3c")
+    assert orc.param_count(spec) == 16 * 256 + 16 + 32 * 256 + 32 + 256 * 3456 + 256 + 7 * 256 + 7
+    params = orc.unflatten(wl.he_normal_params(6, "pv", seed=5, bias_std=0.1, net="a3c"), spec)
+    obs = wl.uniform_frames(1, seed=6, frame=wl.PAPER_FRAME)
+    c = orc.forward(params, obs, spec)
+    assert c["act1"].shape == (1, 16, 25, 19) and c["act2"].shape == (1, 32, 12, 9) and "act3" not in c
+    assert c["h"].shape == (1, 256)
+    x = obs[0].astype(np.float64) / 255.0
+    # conv1, one output: window rows 4 oy .. 4 oy + 7
+    oy, ox, co = 24, 18, 9
+    want = (x[:, 4 * oy:4 * oy + 8, 4 * ox:4 * ox + 8] * params["conv1.W"][co]).sum() + params["conv1.b"][co]
+    assert np.isclose(c["pre1"][0, co, oy, ox], want, atol=1e-12)
+    # conv2 at a corner and at an edge: taps that fall into the padding contribute nothing
+    a1 = np.zeros((16, 27, 21))
+    a1[:, 1:26, 1:20] = c["act1"][0]
+    for (oy, ox, co) in [(0, 0, 3), (11, 8, 31), (5, 0, 17)]:
+        want = (a1[:, 2 * oy:2 * oy + 4, 2 * ox:2 * ox + 4] * params["conv2.W"][co]).sum() + params["conv2.b"][co]
+        assert np.isclose(c["pre2"][0, co, oy, ox], want, atol=1e-12)
+    # fc input index is c*108 + y*9 + x over the second layer's map
+    acc = params["fc.b"][5]
+    for ch in range(32):
+        for y in range(12):
+            for xx in range(9):
+                acc += params["fc.W"][5, ch * 108 + y * 9 + xx] * c["act2"][0, ch, y, xx]
+    assert np.isclose(c["pre_fc"][0, 5], acc, atol=1e-12)
+
+
 def _total_loss(flat, spec, batch, kind, tflat=None):
     params = orc.unflatten(flat, spec)
     c = orc.forward(params, batch["obs"], spec)
@@ -117,7 +156,7 @@ def _total_loss(flat, spec, batch, kind, tflat=None):
 
 
 @pytest.mark.parametrize("kind,geometry", [("a2c", SMALL), ("ppo", SMALL), ("c51", SMALL), ("a2c", SMALL_PADDED),
-                                           ("c51", SMALL_PADDED)])
+                                           ("c51", SMALL_PADDED), ("a2c", SMALL_TWO_CONV), ("ppo", SMALL_TWO_CONV)])
 def test_whole_backward_by_finite_differences(kind, geometry):
     """Central differences of the scalar loss on a sample of coordinates of every
     tensor, small geometries (one of them padded and non-square), non-zero biases, B = 3."""

@@ -78,33 +78,48 @@ def _shift(img: np.ndarray, dy: int, dx: int) -> np.ndarray:
     return out
 
 
+# fc inputs of the 2-convolution policy-gradient network on 104x80 frames (32 channels x 12 x 9)
+A3C_FC_INPUTS = 32 * 12 * 9
+
+
 def param_shapes(num_actions: int, head: str, num_atoms: int = 51,
-                 fc_inputs: int = FC_INPUTS[FRAME]) -> List[Tuple[str, Tuple[int, ...]]]:
-    """Canonical flat order of the parameter vector (interface, fixed by the C header)."""
-    out = [("conv1.W", (32, 4, 8, 8)), ("conv1.b", (32,)),
-           ("conv2.W", (64, 32, 4, 4)), ("conv2.b", (64,)),
-           ("conv3.W", (64, 64, 3, 3)), ("conv3.b", (64,)),
-           ("fc.W", (512, fc_inputs)), ("fc.b", (512,))]
+                 fc_inputs: int = FC_INPUTS[FRAME], net: str = "nature") -> List[Tuple[str, Tuple[int, ...]]]:
+    """Canonical flat order of the parameter vector (interface, fixed by the C header).  net = "nature": the
+    3-convolution network (fc_inputs selects the frame size); net = "a3c": the 2-convolution network on 104x80
+    frames (16 and 32 filters, 256 hidden units)."""
+    if net == "a3c":
+        hid = 256
+        out = [("conv1.W", (16, 4, 8, 8)), ("conv1.b", (16,)),
+               ("conv2.W", (32, 16, 4, 4)), ("conv2.b", (32,)),
+               ("fc.W", (hid, A3C_FC_INPUTS)), ("fc.b", (hid,))]
+    elif net == "nature":
+        hid = 512
+        out = [("conv1.W", (32, 4, 8, 8)), ("conv1.b", (32,)),
+               ("conv2.W", (64, 32, 4, 4)), ("conv2.b", (64,)),
+               ("conv3.W", (64, 64, 3, 3)), ("conv3.b", (64,)),
+               ("fc.W", (hid, fc_inputs)), ("fc.b", (hid,))]
+    else:
+        raise ValueError(net)
     if head == "pv":
-        out += [("pi.W", (num_actions, 512)), ("pi.b", (num_actions,)), ("v.W", (1, 512)), ("v.b", (1,))]
+        out += [("pi.W", (num_actions, hid)), ("pi.b", (num_actions,)), ("v.W", (1, hid)), ("v.b", (1,))]
     elif head == "c51":
-        out += [("c51.W", (num_actions * num_atoms, 512)), ("c51.b", (num_actions * num_atoms,))]
+        out += [("c51.W", (num_actions * num_atoms, hid)), ("c51.b", (num_actions * num_atoms,))]
     elif head == "q":
-        out += [("q.W", (num_actions, 512)), ("q.b", (num_actions,))]
+        out += [("q.W", (num_actions, hid)), ("q.b", (num_actions,))]
     elif head == "duel":
-        out += [("adv.W", (num_actions, 512)), ("adv.b", (num_actions,)), ("val.W", (1, 512)), ("val.b", (1,))]
+        out += [("adv.W", (num_actions, hid)), ("adv.b", (num_actions,)), ("val.W", (1, hid)), ("val.b", (1,))]
     else:
         raise ValueError(head)
     return out
 
 
 def he_normal_params(num_actions: int, head: str, seed: int, num_atoms: int = 51,
-                     bias_std: float = 0.0, fc_inputs: int = FC_INPUTS[FRAME]) -> np.ndarray:
+                     bias_std: float = 0.0, fc_inputs: int = FC_INPUTS[FRAME], net: str = "nature") -> np.ndarray:
     """Flat fp32 vector: every weight tensor ~ N(0, 2/fan_in); biases 0, or
     N(0, bias_std^2) when a test wants the bias paths exercised."""
     g = rng(seed)
     parts = []
-    for name, shp in param_shapes(num_actions, head, num_atoms, fc_inputs):
+    for name, shp in param_shapes(num_actions, head, num_atoms, fc_inputs, net):
         if name.endswith(".W"):
             fan_in = int(np.prod(shp[1:]))
             parts.append(g.standard_normal(shp).reshape(-1) * np.sqrt(2.0 / fan_in))
@@ -114,9 +129,9 @@ def he_normal_params(num_actions: int, head: str, seed: int, num_atoms: int = 51
 
 
 def split_params(flat: np.ndarray, num_actions: int, head: str, num_atoms: int = 51,
-                 fc_inputs: int = FC_INPUTS[FRAME]) -> Dict[str, np.ndarray]:
+                 fc_inputs: int = FC_INPUTS[FRAME], net: str = "nature") -> Dict[str, np.ndarray]:
     out, o = {}, 0
-    for name, shp in param_shapes(num_actions, head, num_atoms, fc_inputs):
+    for name, shp in param_shapes(num_actions, head, num_atoms, fc_inputs, net):
         n = int(np.prod(shp))
         out[name] = flat[o:o + n].reshape(shp)
         o += n
