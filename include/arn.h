@@ -54,6 +54,11 @@
  *   C51: c51.W[A*atoms,512] (row a*atoms+j) c51.b[A*atoms]
  *   Q  : q.W[A,512] q.b[A]
  *   DUEL: adv.W[A,512] adv.b[A] val.W[1,512] val.b[1]        (same shape as PV)
+ * ARN_GEOM_A3C: conv1.W[16,4,8,8] conv1.b[16] conv2.W[32,16,4,4] conv2.b[32] fc.W[256,3456] (input index
+ *   c*108 + y*9 + x) fc.b[256], then the heads as above with 256 in place of 512.  This network runs on the
+ *   kernels of the 104x80 three-convolution network, embedded in it with zero filters and an identity third
+ *   layer (exact: the embedded network computes the same function and the same gradients); it is supported for
+ *   completeness of the paper's networks, not tuned.
  */
 #ifndef ARN_H
 #define ARN_H
@@ -81,7 +86,10 @@ enum { ARN_LOSS_A2C = 0, ARN_LOSS_PPO = 1, ARN_LOSS_C51 = 2, ARN_LOSS_DQN = 3 };
 enum { ARN_MODE_FORWARD = 0, ARN_MODE_TRAIN = 1 };
 /* frame size and padding of the convolution stack (appendix "Atari Frame Processing") */
 enum { ARN_GEOM_84 = 0,      /* 84x84 frames, no padding: 20x20 -> 9x9 -> 7x7, fc input 3136 */
-       ARN_GEOM_PAPER = 1 }; /* 104x80 frames, padding 1 on conv2/conv3: 25x19 -> 12x9 -> 12x9, fc input 6912 */
+       ARN_GEOM_PAPER = 1,   /* 104x80 frames, padding 1 on conv2/conv3: 25x19 -> 12x9 -> 12x9, fc input 6912 */
+       ARN_GEOM_A3C = 2 };   /* the 2-convolution policy-gradient network of the same appendix on 104x80 frames:
+                                conv 8x8/4 x16 -> conv 4x4/2 x32 (padding 1) -> fc 3456 -> 256; maps 25x19 -> 12x9.
+                                (Filter counts: those of the publication the appendix cites for this network.) */
 
 typedef struct {
     int32_t num_actions;   /* 1..31 for PV, Q, DUEL; 1..18 for C51 */
@@ -93,7 +101,7 @@ typedef struct {
     float value_coef;      /* weight of mean((V-ret)^2) (0.5) */
     float entropy_coef;    /* weight of the mean-entropy bonus (0.01) */
     int32_t double_q;      /* DQN: 1 = the online network picks the next action (Double-DQN), 0 = the target network */
-    int32_t geometry;      /* ARN_GEOM_84 (0) or ARN_GEOM_PAPER; anything else is ARN_ESHAPE */
+    int32_t geometry;      /* ARN_GEOM_84 (0), ARN_GEOM_PAPER or ARN_GEOM_A3C; anything else is ARN_ESHAPE */
 } arn_config;
 
 /* Number of fp32 entries of the flat parameter vector; 0 on a bad config. */
@@ -116,7 +124,7 @@ size_t arn_workspace_bytes(const arn_config *cfg, int B, int mode);
 int arn_weights_prepare(const arn_config *cfg, const float *w_fp32, void *w_packed, void *stream);
 
 /* Batched action-selection inference (section "Synchronized Sampling").
- *   obs    : uint8 [B,4,84,84] (NCHW; [B,4,104,80] with ARN_GEOM_PAPER), read only
+ *   obs    : uint8 [B,4,84,84] (NCHW; [B,4,104,80] with ARN_GEOM_PAPER and ARN_GEOM_A3C), read only
  *   logits : PV: fp32 [B,A]; C51: fp32 [B,A,atoms]; Q, DUEL: the action values Q [B,A].  Required.
  *   value  : PV: fp32 [B], required.  C51: expected action values Q [B,A], or NULL.
  *            Q, DUEL: max_a Q [B], required.

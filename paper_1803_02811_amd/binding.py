@@ -9,10 +9,10 @@ from typing import Optional
 ARN_HEAD_PV, ARN_HEAD_C51, ARN_HEAD_Q, ARN_HEAD_DUEL = 0, 1, 2, 3
 ARN_LOSS_A2C, ARN_LOSS_PPO, ARN_LOSS_C51, ARN_LOSS_DQN = 0, 1, 2, 3
 ARN_MODE_FORWARD, ARN_MODE_TRAIN = 0, 1
-ARN_GEOM_84, ARN_GEOM_PAPER = 0, 1
+ARN_GEOM_84, ARN_GEOM_PAPER, ARN_GEOM_A3C = 0, 1, 2
 LOSS_KINDS = {"a2c": ARN_LOSS_A2C, "ppo": ARN_LOSS_PPO, "c51": ARN_LOSS_C51, "dqn": ARN_LOSS_DQN}
 HEAD_KINDS = {"pv": ARN_HEAD_PV, "c51": ARN_HEAD_C51, "q": ARN_HEAD_Q, "duel": ARN_HEAD_DUEL}
-GEOMETRIES = {"84": ARN_GEOM_84, "paper": ARN_GEOM_PAPER}
+GEOMETRIES = {"84": ARN_GEOM_84, "paper": ARN_GEOM_PAPER, "a3c": ARN_GEOM_A3C}
 
 
 class Config(ctypes.Structure):

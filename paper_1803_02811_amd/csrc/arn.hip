@@ -433,6 +433,17 @@ PvHeadArgs pv_head_args(const Dims &d, const Packed &w, int B, char *ws, const W
 
 // Lays the flat fp32 parameters out in every packed form, one launch.
 void launch_pack_all(const Dims &d, const float *w_fp32, void *w_packed, hipStream_t s) {
+    if (d.a3c) {
+        // the 2-convolution network: its parameters are first laid into the embedding network's flat vector, kept
+        // in the tail of the packed blob, and that vector is packed
+        ProfScope ps("a3c_embed", s);
+        float *big = (float *)((char *)w_packed + packed_offsets(d).a3c_flat);
+        const A3cMap m = make_a3c_map(d);
+        const long total = (long)m.e.total;
+        hipLaunchKernelGGL(a3c_fill_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, big, total, (long)m.e.w3);
+        hipLaunchKernelGGL(a3c_scatter_kernel, dim3(cdiv(m.total, 256)), dim3(256), 0, s, m, w_fp32, big);
+        w_fp32 = big;
+    }
     ProfScope ps("pack_all", s);
     const PackPlan pl = make_pack_plan(d, w_packed);
     hipLaunchKernelGGL(pack_all_kernel, dim3(pl.blocks), dim3(256), 0, s, pl, w_fp32);
@@ -447,7 +458,7 @@ int check_update(size_t n, const arn_config *cfg, const void *w_packed, bool *re
         if (!known_head(cfg->head_kind)) return ARN_EKIND;
         *d_out = make_dims(cfg);
         if (!d_out->ok) return ARN_ESHAPE;
-        if (n != param_offsets(*d_out).total) return ARN_ESHAPE;
+        if (n != public_param_count(*d_out)) return ARN_ESHAPE;
         if (!aligned(w_packed, 256)) return ARN_EINVAL;
     }
     return ARN_OK;
@@ -475,7 +486,7 @@ const char *arn_status_string(int status) {
 
 size_t arn_param_count(const arn_config *cfg) {
     const Dims d = make_dims(cfg);
-    return d.ok ? param_offsets(d).total : 0;
+    return d.ok ? public_param_count(d) : 0;
 }
 
 size_t arn_packed_bytes(const arn_config *cfg) {
@@ -634,6 +645,8 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     const Packed w = view_packed(w_packed, d);
     const ParamOffsets po = param_offsets(d);
     const Splits sp = make_splits(d, B);
+    float *const dW_out = dW;
+    if (d.a3c) dW = (float *)(ws + o.a3c_dw);   // the embedding network's gradient; the caller's entries are gathered from it at the end
     float *z = (float *)(ws + o.z);
     __bf16 *h = (__bf16 *)(ws + o.h);
     __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph);
@@ -736,6 +749,11 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     if (ss) {   // join: the caller's stream continues only after the side stream's work
         (void)hipEventRecord(ss->join, s2);
         (void)hipStreamWaitEvent(s, ss->join, 0);
+    }
+    if (d.a3c) {
+        ProfScope ps("a3c_gather", s);
+        const A3cMap m = make_a3c_map(d);
+        hipLaunchKernelGGL(a3c_gather_kernel, dim3(cdiv(m.total, 256)), dim3(256), 0, s, m, dW, dW_out);
     }
     return launched();
 }

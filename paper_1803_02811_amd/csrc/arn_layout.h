@@ -49,7 +49,8 @@ struct Dims {
     bool small = false;   // at most 32 head rows: the fused head kernel follows the fc GEMM (PV, Q, DUEL)
     bool vrow = false;    // the row after the A action rows is a state value (PV, DUEL)
     bool qhead = false;   // the head outputs are action values (Q, DUEL)
-    int geom = ARN_GEOM_84;
+    int geom = ARN_GEOM_84;   // geometry of the kernels that run: ARN_GEOM_84 or ARN_GEOM_PAPER
+    bool a3c = false;         // the 2-convolution network, embedded in the ARN_GEOM_PAPER network
     int p1 = P1, p2 = P2, p3 = P3, feat = FEAT, obs_bytes = OBS_BYTES;   // positions per sample after conv1..3, fc inputs, bytes per observation
     bool ok = false;
 };
@@ -60,6 +61,10 @@ inline Dims make_dims(const arn_config *c) {
     d.A = c->num_actions;
     d.head = c->head_kind;
     d.geom = c->geometry;
+    if (d.geom == ARN_GEOM_A3C) {
+        d.a3c = true;
+        d.geom = ARN_GEOM_PAPER;
+    }
     if (d.geom == ARN_GEOM_PAPER) {
         d.p1 = GeoPaper::P1; d.p2 = GeoPaper::P2; d.p3 = GeoPaper::P3;
         d.feat = GeoPaper::FEAT; d.obs_bytes = GeoPaper::OBS_BYTES;
@@ -115,6 +120,62 @@ inline ParamOffsets param_offsets(const Dims &d) {
     return o;
 }
 
+// The 2-convolution network (16 and 32 filters, 256 hidden units, 104x80 frames) as a sub-network of the
+// three-convolution one: its filters, hidden units and head columns are the leading ones, everything else is
+// zero and conv3 is the identity (centre tap 1 on the diagonal, zero bias).  ReLU of a non-negative map is that
+// map, and the sign bits of act3 equal those of act2, so function and gradients are those of the small network.
+constexpr int A3C_C1 = 16, A3C_C2 = 32, A3C_HID = 256, A3C_FEAT = A3C_C2 * 12 * 9;
+struct A3cMap {   // index of the small network's flat vector -> index of the embedding network's
+    long w1, b1, w2, b2, wfc, bfc, wh, bh, wv, bv, total;   // offsets in the small vector
+    ParamOffsets e;                                         // offsets in the embedding vector
+    int feat;                                               // fc inputs of the embedding network
+#if defined(__HIPCC__)
+    __host__ __device__
+#endif
+    long operator()(long i) const {
+        if (i < b1) return (long)e.w1 + i;                                   // filters 0..15: the leading rows
+        if (i < w2) return (long)e.b1 + (i - b1);
+        if (i < b2) {
+            const long j = i - w2, co = j / (A3C_C1 * 16), r = j % (A3C_C1 * 16);
+            return (long)e.w2 + co * (C1 * 16) + r;                          // [co][ci][4][4]: ci < 16 of 32
+        }
+        if (i < wfc) return (long)e.b2 + (i - b2);
+        if (i < bfc) {
+            const long j = i - wfc, n = j / A3C_FEAT, k = j % A3C_FEAT;
+            return (long)e.wfc + n * feat + k;                               // input index c*108 + pos, c < 32
+        }
+        if (i < wh) return (long)e.bfc + (i - bfc);
+        if (i < bh) {
+            const long j = i - wh;
+            return (long)e.wh + (j / A3C_HID) * HID + j % A3C_HID;
+        }
+        if (i < wv) return (long)e.bh + (i - bh);
+        if (i < bv) return (long)e.wv + (i - wv);
+        return (long)e.bv + (i - bv);
+    }
+};
+inline A3cMap make_a3c_map(const Dims &d) {
+    A3cMap m{};
+    long p = 0;
+    m.w1 = p; p += (long)A3C_C1 * KW1;
+    m.b1 = p; p += A3C_C1;
+    m.w2 = p; p += (long)A3C_C2 * A3C_C1 * 16;
+    m.b2 = p; p += A3C_C2;
+    m.wfc = p; p += (long)A3C_HID * A3C_FEAT;
+    m.bfc = p; p += A3C_HID;
+    const int rows = d.vrow ? d.A : d.NH;
+    m.wh = p; p += (long)rows * A3C_HID;
+    m.bh = p; p += rows;
+    m.wv = p; p += d.vrow ? A3C_HID : 0;
+    m.bv = p; p += d.vrow ? 1 : 0;
+    m.total = p;
+    m.e = param_offsets(d);
+    m.feat = d.feat;
+    return m;
+}
+// entries of the flat parameter / gradient vector at the interface
+inline size_t public_param_count(const Dims &d) { return d.a3c ? (size_t)make_a3c_map(d).total : param_offsets(d).total; }
+
 // byte offsets into the packed blob
 struct PackedOffsets {
     size_t w1, w2, w3, wfc, wh;          // forward layouts  [N][K'] bf16 (high parts)
@@ -122,6 +183,7 @@ struct PackedOffsets {
     size_t w1l, w2l, w3l, wfcl, whl;     // low parts (w - hi) for the three-product inference path
     size_t whd, wfcd, w3d, w2d;          // input-gradient layouts
     size_t w1h, w2h, w3h, wfch;          // fp16 copies of the forward layouts (single-product, no-gradient forward)
+    size_t a3c_flat;                     // the embedding network's flat fp32 vector (2-convolution network only)
     size_t fwd_bytes, total;
 };
 inline PackedOffsets packed_offsets(const Dims &d) {
@@ -152,6 +214,7 @@ inline PackedOffsets packed_offsets(const Dims &d) {
     o.w2h = take((size_t)C2 * KW2 * 2);
     o.w3h = take((size_t)C3 * KW3 * 2);
     o.wfch = take((size_t)HID * d.feat * 2);
+    o.a3c_flat = take(d.a3c ? param_offsets(d).total * 4 : 0);
     o.total = p;
     return o;
 }
@@ -230,6 +293,7 @@ struct Workspace {
     size_t lossp;                       // fp32 [blocks][4] partial loss sums
     size_t hbp;                         // fp32 [blocks][32 or NHP] partial sums of the head's bias gradient
     size_t pw1, pw2, pw3, pwfc, pwh;    // fp32 weight-gradient partials [split][N*K' + N]
+    size_t a3c_dw;                      // gradient of the embedding network (2-convolution network only)
     size_t total;
 };
 inline int loss_blocks(const Dims &d, int B) {
@@ -280,6 +344,7 @@ inline Workspace make_workspace(const Dims &d, int B, int mode) {
         w.pw3 = take((size_t)s.c3 * ((size_t)C3 * KW3 + C3) * 4);
         w.pwfc = take((size_t)s.fc * ((size_t)HID * feat + HID) * 4);
         w.pwh = take((size_t)s.hd * ((size_t)d.NHP * HID + d.NHP) * 4);
+        w.a3c_dw = take(d.a3c ? param_offsets(d).total * 4 : 0);
     }
     w.total = p;
     return w;

@@ -258,6 +258,29 @@ __device__ __forceinline__ void pack_fc_tile(const PackPlan &pl, const float *__
     }
 }
 
+// ---- the 2-convolution network inside the three-convolution one (A3cMap, arn_layout.h) ----
+// fill: zeros everywhere, ones on conv3's identity taps W3[c][c][1][1]
+__global__ __launch_bounds__(256) void a3c_fill_kernel(float *__restrict__ big, long total, long w3) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    float v = 0.f;
+    const long j = i - w3;
+    if (j >= 0 && j < (long)C3 * KW3) {
+        const long co = j / KW3, r = j % KW3, ci = r / (K3 * K3), t = r % (K3 * K3);
+        v = (co == ci && t == (K3 * K3) / 2) ? 1.f : 0.f;
+    }
+    big[i] = v;
+}
+// scatter the small network's parameters into the embedding vector / gather its gradient out of it
+__global__ __launch_bounds__(256) void a3c_scatter_kernel(A3cMap m, const float *__restrict__ small, float *__restrict__ big) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < m.total) big[m(i)] = small[i];
+}
+__global__ __launch_bounds__(256) void a3c_gather_kernel(A3cMap m, const float *__restrict__ big, float *__restrict__ small) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < m.total) small[i] = big[m(i)];
+}
+
 __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float *__restrict__ w) {
     if ((int)blockIdx.x >= pl.fc_first_block) {
         __shared__ float s_t[PACK_FC_ROWS][PACK_FC_CH * PACK_FC_MAX_P3];

@@ -47,11 +47,25 @@ def test_paper_geometry_sizes(lib):
     assert arn.param_count(cfg) == 1_693_875 + 512 * (6912 - 3136)
     assert arn.packed_bytes(cfg) > arn.packed_bytes(arn.Config(18))
     assert arn.workspace_bytes(cfg, 64, arn.ARN_MODE_TRAIN) > arn.workspace_bytes(arn.Config(18), 64, arn.ARN_MODE_TRAIN)
-    bad = arn.Config(18, geometry=2)
+    bad = arn.Config(18, geometry=3)
     assert arn.param_count(bad) == 0 and arn.packed_bytes(bad) == 0
     assert arn.workspace_bytes(bad, 64, arn.ARN_MODE_FORWARD) == 0
     fake = ctypes.c_void_p(1 << 20)
     assert lib.arn_weights_prepare(ctypes.byref(bad), fake, fake, None) == -2
+
+
+def test_two_convolution_network_sizes(lib):
+    """ARN_GEOM_A3C: the flat vector is the small network's own (oracle layout), whatever the kernels embed it in."""
+    for A, head, okind in [(18, arn.ARN_HEAD_PV, "pv"), (6, arn.ARN_HEAD_PV, "pv"), (18, arn.ARN_HEAD_C51, "c51"),
+                           (4, arn.ARN_HEAD_Q, "q"), (9, arn.ARN_HEAD_DUEL, "duel")]:
+        cfg = arn.Config(A, head, geometry=arn.ARN_GEOM_A3C)
+        assert arn.param_count(cfg) == orc.param_count(orc.NetSpec(A, okind, geometry=orc.A3C_104x80))
+    cfg = arn.Config(18, geometry=arn.ARN_GEOM_A3C)
+    assert arn.param_count(cfg) == 897_328 + 18 * 256 + 18 + 256 + 1
+    big = arn.Config(18, geometry=arn.ARN_GEOM_PAPER)
+    assert arn.packed_bytes(cfg) >= arn.packed_bytes(big) + 4 * arn.param_count(big)
+    assert arn.workspace_bytes(cfg, 64, arn.ARN_MODE_TRAIN) >= arn.workspace_bytes(big, 64, arn.ARN_MODE_TRAIN) + 4 * arn.param_count(big)
+    assert arn.workspace_bytes(cfg, 64, arn.ARN_MODE_FORWARD) == arn.workspace_bytes(big, 64, arn.ARN_MODE_FORWARD)
 
 
 def test_sizes_and_bad_configs(lib):

@@ -151,5 +151,5 @@ def test_constant_frames(gu, fill):
 
 def test_bad_geometry_is_rejected(gu):
     import paper_1803_02811_amd as arn
-    cfg = arn.Config(18, geometry=2)
+    cfg = arn.Config(18, geometry=3)
     assert arn.param_count(cfg) == 0 and arn.workspace_bytes(cfg, 16, arn.ARN_MODE_FORWARD) == 0
