@@ -59,20 +59,126 @@ FWDBWD_BYTES = sum(KERNEL_BYTES[k] for k in ("conv1_fwd", "conv2_fwd", "conv3_fw
     + ACT["obs"] + (ACT["a1"] + ACT["a2"] + ACT["a3"] + ACT["h"]) + 2 * (ACT["a1"] + ACT["a2"] + ACT["a3"] + ACT["h"])
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+SETTLE_S = 0.25             # seconds the device is driven before the timed steps (see workload_report)
 
 
-def measured_traffic(kernel, B):
-    """HBM bytes per launch of `kernel` from the committed counter summary (FETCH_SIZE + WRITE_SIZE, each
-    scaled by what the same counter reads for a plain copy of known size); None if it covers another batch."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "a2c_b2048_traffic.json")
+def per_step_event_ms(torch, fn, steps):
+    """Duration of each of `steps` calls, from an event pair around every call on the current stream (the calls
+    are issued back to back; a call's duration is the time from the previous call's end to its own)."""
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(steps):
+        fn()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    return [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+
+
+def wall_ms(torch, fn, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def kernel_profile(arn, torch, step, steps):
+    """(average us per launch, launches per step) by instrumented kernel name over `steps` more steps, with the
+    event pair's own contribution (a pair around nothing, once per step) subtracted."""
+    stream = torch.cuda.current_stream()
+    arn.profile_enable(True)
+    for _ in range(steps):
+        step()
+        arn.profile_null(stream)
+    torch.cuda.synchronize()
+    per = {}
+    for name, ms in arn.profile_collect(cap=128 * steps + 64):
+        tot, cnt = per.get(name, (0.0, 0))
+        per[name] = (tot + ms, cnt + 1)
+    arn.profile_enable(False)
+    null_ms = per.pop("null")[0] / steps
+    avg_us = {n: max(t / c - null_ms, 0.0) * 1e3 for n, (t, c) in per.items()}
+    calls = {n: c / steps for n, (t, c) in per.items()}
+    return avg_us, calls, null_ms * 1e3
+
+
+def roofline_of(avg_us, B, kernel_flops, kernel_bytes, bytes_per_launch, tag):
+    """Roofline of the kernel with the largest average launch duration among those with a byte / flop model:
+    algorithmic bytes (or flops) per launch over its event-timed duration, against the published peak of the
+    resource whose time at peak is larger."""
+    known = [n for n in avg_us if n in kernel_flops]
+    dominant = max(known, key=avg_us.get)
+    dom_s = avg_us[dominant] * 1e-6
+    dom_flops = kernel_flops[dominant] * B
+    dom_bytes = kernel_bytes[dominant] * B + bytes_per_launch[dominant]
+    if dom_bytes / (PEAK_HBM_GBS * 1e9) >= dom_flops / (PEAK_BF16_TFLOPS * 1e12):
+        achieved = dom_bytes / dom_s / 1e9
+        r = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": round(achieved / PEAK_HBM_GBS, 4)}
+    else:
+        achieved = dom_flops / dom_s / 1e12
+        r = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+             "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4)}
+    r["traffic"] = measured_traffic(dominant, tag)
+    r["traffic_source"] = "profiles/%s_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see its .md)" % tag \
+        if r["traffic"] is not None else None
+    r["avg_launch_us"] = round(avg_us[dominant], 2)
+    r["algorithmic_bytes_per_launch"] = dom_bytes
+    r["algorithmic_flops_per_launch"] = dom_flops
+    return r
+
+
+def measured_traffic(kernel, tag):
+    """HBM bytes per launch of `kernel` from the committed counter summary of this workload (written by
+    `bench.py --summarise-counters`): FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a
+    plain copy of known size; None if no summary covers the workload or the kernel."""
+    path = os.path.join(ROOT, "profiles", "%s_traffic.json" % tag)
     try:
         with open(path) as f:
             prof = json.load(f)
     except (OSError, ValueError):
         return None
-    if prof.get("batch") != B:
-        return None
     return prof.get("hbm_bytes_per_launch", {}).get(kernel)
+
+
+def head_macs(A, head):
+    return (A * 51 if head == "c51" else A + 1) * 512
+
+
+def flop_models(A, head):
+    """Algorithmic flops and HBM bytes per sample (and bytes per launch) by instrumented kernel name."""
+    hm = head_macs(A, head)
+    flops = dict(KERNEL_FLOPS)
+    flops.update({"head_fwd": 2 * hm, "head_wgrad": 2 * hm, "head_dgrad": 2 * hm,
+                  "conv_infer": 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"])})
+    z = 4 * (A * 51 if head == "c51" else A + 1)
+    kb = dict(KERNEL_BYTES)
+    kb.update({"head_fwd": ACT["h"] + z, "head_wgrad": ACT["h"] + z // 2, "head_dgrad": z // 2 + 2 * ACT["h"],
+               "conv_infer": ACT["obs"] + ACT["a3"]})          # frames in, act3 (fp16) out: nothing else leaves the chip
+    per_launch = dict(KERNEL_BYTES_PER_LAUNCH)
+    per_launch.update({"head_fwd": 2 * hm, "head_dgrad": 2 * hm, "head_wgrad": 4 * hm,
+                       "conv_infer": 2 * 8192 + 2 * 32768 + 2 * 36864})
+    return flops, kb, per_launch
+
+
+def oracle_baseline(np, fn, n, what, budget_s=12.0, max_reps=50):
+    """The oracle as it stands on the host cores, repeated for about 10-30 s on a bounded slice of the workload."""
+    from oracle import nature_cnn as orc
+    reps, t_total = 0, 0.0
+    while reps < 1 or (t_total < budget_s and reps < max_reps):
+        t0 = time.perf_counter()
+        fn()
+        t_total += time.perf_counter() - t0
+        reps += 1
+    return {"value": round(n * reps / t_total, 1), "unit": "samples/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "%s, %d repetitions, %.1f s (rate scales linearly to the full batch)" % (what, reps, t_total)}
+
+
+def stats_ms(np, xs):
+    a = np.asarray(xs, dtype=np.float64)
+    return {"mean": round(float(a.mean()), 4), "median": round(float(np.median(a)), 4), "min": round(float(a.min()), 4)}
 
 
 def main():
@@ -89,7 +195,9 @@ def main():
                          "(secondary line)")
     ap.add_argument("--paper-geometry", action="store_true",
                     help="secondary report: the A2C gradient step and inference on the paper's own 104x80 frames with "
-                         "padded conv2/conv3 (gathered-contraction kernels), per-kernel times included")
+                         "padded conv2/conv3, per-kernel times included")
+    ap.add_argument("--a3c-net", action="store_true",
+                    help="secondary report: the same on the 2-convolution policy-gradient network (104x80 frames)")
     ap.add_argument("--update-rules", action="store_true",
                     help="report the parameter-update kernels instead (secondary line)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
@@ -98,6 +206,15 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB mebibytes a few times (reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--summarise-counters", metavar="DIR",
+                    help="no GPU needed: turn the rocprofv3 CSV output under DIR (runs made as profiles/*_traffic.md "
+                         "says) into profiles/<tag>_traffic.json/.md, or with --sq into profiles/<tag>_sq_counters.md")
+    ap.add_argument("--summarise-stats", metavar="DIR",
+                    help="no GPU needed: turn rocprofv3 --kernel-trace --stats output under DIR (bench_kernel_stats.csv and "
+                         "log.txt with the bench line) into profiles/<tag>_kernel_stats.md; --cmd gives the command to quote")
+    ap.add_argument("--cmd", default="", help="--summarise-stats: the profiled command, quoted in the summary")
+    ap.add_argument("--tag", default="", help="workload tag of --summarise-counters output (default: from --workload)")
+    ap.add_argument("--sq", action="store_true", help="--summarise-counters: shader-core counters instead of traffic")
     ap.add_argument("--cpu-samples", type=int, default=0, help="oracle sample size (0 = auto, ~10-30 s)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -105,6 +222,14 @@ def main():
               "one gradient all-reduce per step would follow)" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
+    if args.summarise_stats:
+        summarise_stats(args.summarise_stats, args.tag, args.cmd)
+        return
+    if args.summarise_counters:
+        import workloads as wl
+        tag = args.tag or wl.WORKLOADS[args.workload]["name"]
+        summarise_counters(args.summarise_counters, tag, args.sq)
+        return
 
     import numpy as np
     import torch
@@ -132,131 +257,320 @@ def main():
     if args.alternating:
         alternating_report(args, arn, wl, np, torch)
         return
-    if args.paper_geometry:
-        paper_geometry_report(args, arn, wl, np, torch)
+    if args.paper_geometry or args.a3c_net:
+        paper_geometry_report(args, arn, wl, np, torch, "a3c" if args.a3c_net else "nature")
         return
-    if args.workload != 3:
-        other_workload(args, arn, wl, np, torch)
-        return
-    A, B, k = 18, args.batch or 2048, 3
-    cfg = arn.Config(A, arn.ARN_HEAD_PV)
-    flat = wl.he_normal_params(A, "pv", 2000 + k)
-    w = torch.from_numpy(flat).to(dev)
+    workload_report(args, arn, wl, np, torch)
+
+
+def workload_report(args, arn, wl, np, torch):
+    """One JSON line for workload k: whole-step throughput (wall clock over exactly K steps after W warm-ups),
+    per-step median / min, per-kernel event times, the roofline of the longest kernel, and the oracle's rate."""
+    dev, k = "cuda:0", args.workload
+    w = wl.WORKLOADS[k]
+    A, B, head, kind = w["A"], args.batch or w["B"], w["head"], w["kind"]
+    cfg = arn.Config(A, arn.ARN_HEAD_PV if head == "pv" else arn.ARN_HEAD_C51)
+    flat = wl.he_normal_params(A, head, 2000 + k)
     packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
-    arn.weights_prepare(cfg, w, packed)
-    batch_np = wl.actor_critic_batch(k, B=B)
-    batch = {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for n, v in batch_np.items()}
-    ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
-    dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
-    loss = torch.empty(4, dtype=torch.float32, device=dev)
-    stream = torch.cuda.current_stream()
-
-    def step():
-        arn.train_step_grads(cfg, packed, batch, "a2c", dW, loss, workspace=ws, stream=torch.cuda.current_stream())
-
-    def timed(fn, steps):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
-
-    for _ in range(args.warmup):
-        step()
-    sec = timed(step, args.steps)
-    value = B / sec
-
-    # forward-only (action-selection inference) rate on the same batch, for the report
+    arn.weights_prepare(cfg, torch.from_numpy(flat).to(dev), packed)
+    stream = None   # the binding then takes the stream that is current at call time (it differs under graph capture)
+    to_dev = lambda d: {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for n, v in d.items()}
+    conv_macs = MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"]
+    fwd_flops = 2 * (conv_macs + head_macs(A, head))
+    tflat = None
     wsf = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
-    logits = torch.empty(B, A, dtype=torch.float32, device=dev)
-    val = torch.empty(B, dtype=torch.float32, device=dev)
-
-    def fwd():
-        arn.policy_forward(cfg, packed, batch["obs"], logits, val, workspace=wsf, stream=torch.cuda.current_stream())
-
-    for _ in range(args.warmup):
-        fwd()
-    sec_fwd = timed(fwd, args.steps)
-
-    # the same calls captured once into HIP graphs and replayed (what a tight training / serving loop would do)
-    def graph_time(fn):
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            fn()
-        for _ in range(args.warmup):
-            g.replay()
-        return timed(g.replay, args.steps)
-
-    sec_graph, sec_fwd_graph = graph_time(step), graph_time(fwd)
-
-    # per-kernel durations: the same K steps again with a HIP event pair around every launch
-    arn.profile_enable(True)
-    for _ in range(args.steps):
-        step()
-        arn.profile_null(torch.cuda.current_stream())
-    torch.cuda.synchronize()
-    recs = arn.profile_collect(cap=64 * args.steps + 64)
-    arn.profile_enable(False)
-    per = {}
-    for name, ms in recs:
-        tot, cnt = per.get(name, (0.0, 0))
-        per[name] = (tot + ms, cnt + 1)
-    # an event pair around nothing measures what the pair itself adds; it is subtracted from every kernel
-    null_ms = per.pop("null")[0] / args.steps
-    avg_ms = {n: max(t / c - null_ms, 0.0) for n, (t, c) in per.items()}
-    dominant = max((n for n in avg_ms if n in KERNEL_FLOPS), key=avg_ms.get)
-    dom_s = avg_ms[dominant] * 1e-3
-    dom_flops = KERNEL_FLOPS[dominant] * B
-    dom_bytes = KERNEL_BYTES[dominant] * B + KERNEL_BYTES_PER_LAUNCH[dominant]
-    # the binding resource is the one whose time at peak is larger
-    if dom_bytes / (PEAK_HBM_GBS * 1e9) >= dom_flops / (PEAK_BF16_TFLOPS * 1e12):
-        achieved = dom_bytes / dom_s / 1e9
-        roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    if kind == "forward":
+        batch_np = {"obs": wl.frames_for(k, B)}
+        obs = torch.from_numpy(batch_np["obs"]).to(dev)
+        logits = torch.empty(B, A, dtype=torch.float32, device=dev)
+        value = torch.empty(B, dtype=torch.float32, device=dev)
+        probs = torch.empty(B, A, dtype=torch.float32, device=dev)
+        greedy = torch.empty(B, dtype=torch.int32, device=dev)
+        step = lambda: arn.policy_forward(cfg, packed, obs, logits, value, probs, greedy, workspace=wsf, stream=stream)
+        flops, bytes_alg, name, dtype = fwd_flops, ACT["obs"] + 4 * (2 * A + 2), "policy_forward", "f16"
+        bytes_launch = 2 * (8192 + 32768 + 36864 + 1605632 + head_macs(A, head))      # one fp16 copy of every weight matrix
     else:
-        achieved = dom_flops / dom_s / 1e12
-        roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
-    roofline["traffic"] = measured_traffic(dominant, B)
-    roofline["avg_launch_us"] = round(avg_ms[dominant] * 1e3, 2)
-    roofline["event_pair_overhead_us"] = round(null_ms * 1e3, 2)
-    roofline["algorithmic_bytes_per_launch"] = dom_bytes
-    roofline["algorithmic_flops_per_launch"] = dom_flops
+        ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
+        dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
+        loss = torch.empty(4, dtype=torch.float32, device=dev)
+        tgt_flops = 0
+        if kind == "c51":
+            batch_np = wl.c51_batch(k, B=B)
+            batch = to_dev(batch_np)
+            tflat = wl.he_normal_params(A, head, 3000 + k)
+            tpacked = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
+            arn.weights_prepare(cfg, torch.from_numpy(tflat).to(dev), tpacked)
+            batch["w_target_packed"] = tpacked
+            tgt_flops = fwd_flops
+        else:
+            batch_np = wl.actor_critic_batch(k, B=B, normalise_adv=(kind == "ppo"))
+            batch = to_dev(batch_np)
+            if kind == "ppo":
+                # sampling-policy log-probs: the current logits (from this library) perturbed by N(0, 0.05^2)
+                logits = torch.empty(B, A, dtype=torch.float32, device=dev)
+                value = torch.empty(B, dtype=torch.float32, device=dev)
+                arn.policy_forward(cfg, packed, batch["obs"], logits, value, workspace=wsf, stream=stream)
+                noisy = logits + torch.from_numpy(wl.logit_noise(k, B, A).astype(np.float32)).to(dev)
+                batch["old_logp"] = torch.log_softmax(noisy, dim=1).gather(1, batch["action"].long()[:, None])[:, 0].contiguous()
+                batch_np["old_logp"] = batch["old_logp"].cpu().numpy()
+        step = lambda: arn.train_step_grads(cfg, packed, batch, kind, dW, loss, workspace=ws, stream=stream)
+        flops = 3 * fwd_flops - 2 * MACS["conv1"] + tgt_flops
+        bytes_alg = FWDBWD_BYTES + (sum(KERNEL_BYTES[q] for q in ("conv1_fwd", "conv2_fwd", "conv3_fwd", "fc_fwd")) if kind == "c51" else 0)
+        bytes_launch, name, dtype = 0, "train_step_grads:" + kind, "bf16"
+
+    # A process that has just started runs its first few hundred steps 5-10 % slower than it does from then on
+    # (every kernel alike: the GPU leaves its idle clocks).  The figure of interest is the rate of a training job,
+    # so the device is first driven for SETTLE_S seconds; the rate of the K steps right after the W warm-ups of a
+    # fresh process is measured before that and printed too (startup_ms_per_step).
+    for _ in range(args.warmup):
+        step()
+    startup_ms = wall_ms(torch, step, args.steps)
+    t0, preroll = time.perf_counter(), 0
+    while time.perf_counter() - t0 < SETTLE_S:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        preroll += 20
+    # ---- the contract: W untimed warm-up steps, then exactly K timed steps ----
+    for _ in range(args.warmup):
+        step()
+    ms = wall_ms(torch, step, args.steps)
+    value_sps = B / (ms * 1e-3)
+    # the same K steps again, each with its own event pair: spread of the step time
+    per_step = per_step_event_ms(torch, step, args.steps)
+
+    avg_us, calls, null_us = kernel_profile(arn, torch, step, min(args.steps, 50))
+    kflops, kbytes, klaunch = flop_models(A, head)
+    roofline = roofline_of(avg_us, B, kflops, kbytes, klaunch, w["name"] if not args.batch else "none")
+    roofline["event_pair_overhead_us"] = round(null_us, 2)
 
     out = {
-        "metric": "Nature-CNN samples/sec (fwd+bwd) at B=%d on 1 GPU" % B,
-        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "a2c_grad_step_B%d_A18 (256 envs x 8 steps, rectangle frames)" % B,
-                   "global_batch": B, "parallelism": "single-gpu"},
-        "mfma_frac_whole_step": round(value * FWDBWD_FLOPS / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "hbm_frac_whole_step": round(value * FWDBWD_BYTES / 1e9 / PEAK_HBM_GBS, 4),
-        "forward_samples_per_s": round(B / sec_fwd, 1),
-        "forward_ms": round(sec_fwd * 1e3, 4),
-        "graph_replay_ms_per_step": round(sec_graph * 1e3, 4),
-        "graph_replay_forward_ms": round(sec_fwd_graph * 1e3, 4),
-        "kernel_us": {n: round(v * 1e3, 2) for n, v in sorted(avg_ms.items(), key=lambda kv: -kv[1])},
+        "metric": "Nature-CNN samples/sec (%s) at B=%d on 1 GPU" % ("fwd+bwd" if kind != "forward" else "fwd", B),
+        "value": round(value_sps, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s (workload %d: %s, A=%d)" % (w["name"], k, name, A), "global_batch": B,
+                   "parallelism": "single-gpu"},
+        "step_ms": stats_ms(np, per_step),
+        "startup_ms_per_step": round(startup_ms, 4), "settle_steps_before_timing": preroll,
+        "mfma_frac_whole_step": round(value_sps * flops / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "hbm_frac_whole_step": round((bytes_alg * B + bytes_launch) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "algorithmic_flops_per_sample": flops,
+        "kernel_us": {n: round(v, 2) for n, v in sorted(avg_us.items(), key=lambda kv: -kv[1])},
+        "kernel_launches_per_step": {n: round(c, 2) for n, c in calls.items() if c != 1.0},
         "roofline": roofline,
     }
 
+    if kind == "forward":
+        # cold figure: a 512 MiB buffer is rewritten between calls, which evicts the L2s and the 256 MiB memory-side
+        # cache, so weights and frames come from HBM; each call is timed on its own (warm figure: step_ms above)
+        junk = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        cold = []
+        for i in range(min(args.steps, 30)):
+            junk.fill_(i & 0xff)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step()
+            e1.record()
+            torch.cuda.synchronize()
+            cold.append(e0.elapsed_time(e1))
+        out["cold_cache_call_ms"] = stats_ms(np, cold)
+        out["hbm_frac_cold"] = round((bytes_alg * B + bytes_launch) / (float(np.median(cold)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+        del junk
+    else:
+        # forward-only (action-selection inference, the fp16 single-product path) on the same frames, for the report
+        lg = torch.empty(B, A * (51 if head == "c51" else 1), dtype=torch.float32, device=dev)
+        vl = torch.empty(B, A if head == "c51" else 1, dtype=torch.float32, device=dev)
+        fwd = lambda: arn.policy_forward(cfg, packed, batch["obs"], lg, vl, workspace=wsf, stream=stream)
+        for _ in range(args.warmup):
+            fwd()
+        f_ms = wall_ms(torch, fwd, args.steps)
+        out["forward_ms"] = round(f_ms, 4)
+        out["forward_samples_per_s"] = round(B / (f_ms * 1e-3), 1)
+        if k == 3:
+            # the same calls captured once into HIP graphs and replayed
+            def graph_time(fn):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    fn()
+                for _ in range(args.warmup):
+                    g.replay()
+                return wall_ms(torch, g.replay, args.steps)
+            out["graph_replay_ms_per_step"] = round(graph_time(step), 4)
+            out["graph_replay_forward_ms"] = round(graph_time(fwd), 4)
+
     if not args.no_cpu_baseline:
         from oracle import nature_cnn as orc
-        spec = orc.NetSpec(A, "pv")
-        n = args.cpu_samples or min(B, 2048)
-        sub = {kk: v[:n] for kk, v in batch_np.items()}
-        reps, t_total = 0, 0.0
-        while reps < 1 or (t_total < 12.0 and reps < 20):     # about 10-30 s of CPU work
-            t0 = time.perf_counter()
-            orc.train_step_grads(flat, sub, "a2c", spec)
-            t_total += time.perf_counter() - t0
-            reps += 1
-        out["cpu_baseline"] = {"value": round(n * reps / t_total, 1), "unit": "samples/s", "cores": orc.num_threads(),
-                               "kind": "oracle",
-                               "sample": "first %d samples of the same batch, fwd+loss+bwd, %d repetitions, %.1f s"
-                                         % (n, reps, t_total)}
+        spec = orc.NetSpec(A, head)
+        if kind == "forward":
+            n = args.cpu_samples or B
+            params = orc.unflatten(flat, spec)
+            sub = batch_np["obs"][:n]
+            out["cpu_baseline"] = oracle_baseline(np, lambda: orc.forward(params, sub, spec), n,
+                                                  "forward of the first %d samples of the same batch" % n)
+        else:
+            n = args.cpu_samples or min(B, 2048 if kind != "c51" else 1024)
+            sub = {kk: v[:n] for kk, v in batch_np.items()}
+            fn = lambda: orc.train_step_grads(flat, sub, kind, spec, flat_target_params=tflat)
+            what = "first %d samples of the same batch, %sforward + objective + backward" % (
+                n, "target-network forward + " if kind == "c51" else "")
+            out["cpu_baseline"] = oracle_baseline(np, fn, n, what)
     print(json.dumps(out))
+
+
+# ---------------------------------------------------------------------------
+# rocprofv3 counter CSVs -> committed summaries (no GPU needed)
+# ---------------------------------------------------------------------------
+KERNEL_NAME_PATTERNS = [   # first match wins: mangled or demangled rocprofv3 kernel name -> instrumented launch name
+    (r"conv123_fwd_kernel", "conv123_fwd"), (r"conv23_fwd_fused", "conv23_fwd"), (r"infer_conv_kernel", "conv_infer"),
+    (r"conv_backward_kernel", "conv_bwd"), (r"conv1_fwd_resident", "conv1_fwd"), (r"ResConv2Fwd", "conv2_fwd"),
+    (r"ResConv3Fwd", "conv3_fwd"), (r"ResConv3Dgrad", "conv3_dgrad"), (r"FcFwd", "fc_fwd"), (r"FcDgrad", "fc_dgrad"),
+    (r"pv_head_kernel<true>|pv_head_kernelILb1", "pv_head"), (r"pv_head_kernel<false>|pv_head_kernelILb0", "pv_head_infer"),
+    (r"HeadWgrad", "head_wgrad"), (r"HeadFwdC51", "head_fwd"), (r"HeadDgrad", "head_dgrad"),
+    (r"UnmapHeadBias", "head_bias"), (r"UnmapHead", "head_reduce"),
+    (r"gemm_tn_kernel.*DenseGather", "fc_wgrad"), (r"fc_reduce", "fc_reduce"), (r"fc_finish", "fc_finish"),
+    (r"conv_reduce_kernel", "conv_reduce"), (r"loss_finalize", "loss_finalize"), (r"c51_dist", "c51_dist"),
+    (r"c51_loss", "loss"), (r"pack_all", "pack_all"), (r"__amd_rocclr_copyBuffer", "copy"),
+]
+
+
+def summarise_stats(root, tag, cmd):
+    """rocprofv3's per-kernel statistics of one profiled bench run as a table, with the same run's bench line."""
+    import csv
+    import glob
+    import re
+    src = glob.glob(os.path.join(root, "**", "*_kernel_stats.csv"), recursive=True)
+    if not src or not tag:
+        raise SystemExit("need --tag and a *_kernel_stats.csv under " + root)
+
+    def short(n):
+        n = re.sub(r"void |arn::", "", n)
+        n = re.sub(r"\(.*$", "", n)
+        return re.sub(r"^_ZN3arn\d+", "", n)[:100]
+    md = ["# %s: kernel trace" % tag, "", "Command (on one MI355X, from the repository root):", "", "    " + cmd, "",
+          "    python3 bench.py --summarise-stats DIR --tag %s --cmd '...'" % tag, "",
+          "Per-kernel summary from rocprofv3's `*_kernel_stats.csv` (durations in microseconds).", "",
+          "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
+    with open(src[0]) as f:
+        for r in csv.DictReader(f):
+            if float(r["Percentage"]) >= 0.05:
+                md.append("| `%s` | %s | %.2f | %.2f | %.2f | %.2f |" % (
+                    short(r["Name"]), r["Calls"], float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3,
+                    float(r["MaxNs"]) / 1e3, float(r["Percentage"])))
+    log = os.path.join(root, "log.txt")
+    if os.path.exists(log):
+        lines = [x for x in open(log) if x.startswith("{")]
+        if lines:
+            j = json.loads(lines[-1])
+            ku = j.get("kernel_us") or {}
+            md += ["", "The same run's bench line (profiler attached): %.1f us per step; its HIP-event durations per launch "
+                       "(event-pair overhead subtracted), for comparison with the averages above:" % (j["ms_per_step"] * 1e3), "",
+                   ", ".join("%s %.1f" % (n, v) for n, v in ku.items()) + "."]
+    path = os.path.join(ROOT, "profiles", "%s_kernel_stats.md" % tag)
+    with open(path, "w") as f:
+        f.write("\n".join(md) + "\n")
+    print("wrote", path)
+
+
+def _short_kernel_name(k):
+    import re
+    for pat, n in KERNEL_NAME_PATTERNS:
+        if re.search(pat, k):
+            return n
+    return None
+
+
+def _counter_means(path):
+    """{short kernel name: {counter: mean value per dispatch}} of one rocprofv3 *_counter_collection.csv."""
+    import collections
+    import csv
+    acc = collections.defaultdict(lambda: collections.defaultdict(float))
+    cnt = collections.defaultdict(lambda: collections.defaultdict(int))
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            n = _short_kernel_name(r["Kernel_Name"])
+            if n is None:
+                continue
+            acc[n][r["Counter_Name"]] += float(r["Counter_Value"])
+            cnt[n][r["Counter_Name"]] += 1
+    return {n: {c: acc[n][c] / cnt[n][c] for c in acc[n]} for n in acc}
+
+
+def _find_csv(root, sub, prefix):
+    import glob
+    g = glob.glob(os.path.join(root, sub, "**", "%s_counter_collection.csv" % prefix), recursive=True)
+    if not g:
+        raise SystemExit("no %s_counter_collection.csv under %s/%s" % (prefix, root, sub))
+    return g[0]
+
+
+def summarise_counters(root, tag, sq):
+    """DIR layout (what the commands quoted in the written .md produce):
+         DIR/FETCH_SIZE/{bench,copy}_counter_collection.csv, DIR/WRITE_SIZE/{bench,copy}_counter_collection.csv
+       or, with --sq, DIR/sq_a and DIR/sq_b with pmc_counter_collection.csv."""
+    prof = os.path.join(ROOT, "profiles")
+    if sq:
+        a = _counter_means(_find_csv(root, "sq_a", "pmc"))
+        b = _counter_means(_find_csv(root, "sq_b", "pmc"))
+        md = ["# %s: shader-core counters per kernel" % tag, "",
+              "Commands (one MI355X, repository root; one pass of eight SQ counters each; weight gradients kept on the "
+              "caller's stream so that dispatches do not overlap):", "",
+              "    ARN_SINGLE_STREAM=1 rocprofv3 --pmc SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAIT_INST_ANY SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE -d DIR/sq_a -o pmc --output-format csv -- python3 bench.py <workload flags> --steps 3 --warmup 1 --no-cpu-baseline",
+              "    ARN_SINGLE_STREAM=1 rocprofv3 --pmc SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_ACTIVE_INST_ANY SQ_INSTS_LDS SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_INST_LEVEL_LDS -d DIR/sq_b -o pmc --output-format csv -- python3 bench.py <workload flags> --steps 3 --warmup 1 --no-cpu-baseline",
+              "    python3 bench.py --summarise-counters DIR --sq --tag %s" % tag, "",
+              "Per-dispatch averages. SQ_BUSY_CYCLES sums the 32 shader engines, SQ_VALU_MFMA_BUSY_CYCLES the 1024 SIMDs, "
+              "SQ_LDS_IDX_ACTIVE the 256 CUs; shares of the wavefronts' resident cycles (SQ_WAVE_CYCLES): waiting at an "
+              "s_waitcnt, waiting to issue, issuing. Executed MFMA work = SQ_INSTS_VALU_MFMA_MOPS_BF16 x 512 flop.", "",
+              "| kernel | busy cycles (per SE) | MFMA pipe busy % | LDS busy % | bank-conflict cycles / LDS active % | s_waitcnt % | wait to issue % | issuing % | executed MFMA GFLOP |",
+              "|---|---|---|---|---|---|---|---|---|"]
+        rows = []
+        for n, c in a.items():
+            busy = c.get("SQ_BUSY_CYCLES", 0.0) / 32
+            if busy < 100 or n in ("copy", "pack_all"):
+                continue
+            d = b.get(n, {})
+            wc = d.get("SQ_WAVE_CYCLES", 0.0) or float("nan")
+            rows.append((busy, "| %s | %s | %.0f | %.0f | %.0f | %.0f | %.0f | %.0f | %.1f |" % (
+                n, format(int(busy), ","), c["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024 / busy * 100,
+                c["SQ_LDS_IDX_ACTIVE"] / 256 / busy * 100, c["SQ_LDS_BANK_CONFLICT"] / max(c["SQ_LDS_IDX_ACTIVE"], 1) * 100,
+                d.get("SQ_WAIT_ANY", 0) / wc * 100, d.get("SQ_WAIT_INST_ANY", 0) / wc * 100,
+                d.get("SQ_ACTIVE_INST_ANY", 0) / wc * 100, d.get("SQ_INSTS_VALU_MFMA_MOPS_BF16", 0) * 512 / 1e9)))
+        md += [r for _, r in sorted(rows, reverse=True)]
+        path = os.path.join(prof, "%s_sq_counters.md" % tag)
+        with open(path, "w") as f:
+            f.write("\n".join(md) + "\n")
+        print("wrote", path)
+        return
+    fb = _counter_means(_find_csv(root, "FETCH_SIZE", "bench"))
+    fc = _counter_means(_find_csv(root, "FETCH_SIZE", "copy"))
+    wb = _counter_means(_find_csv(root, "WRITE_SIZE", "bench"))
+    wc = _counter_means(_find_csv(root, "WRITE_SIZE", "copy"))
+    copy_kib = 256 * 1024
+    fs, ws = copy_kib / fc["copy"]["FETCH_SIZE"], copy_kib / wc["copy"]["WRITE_SIZE"]
+    rows = []
+    for n in fb:
+        if n in ("copy", "pack_all"):
+            continue
+        f_kib, w_kib = fb[n].get("FETCH_SIZE", 0.0), wb.get(n, {}).get("WRITE_SIZE", 0.0)
+        rows.append((n, f_kib, w_kib, (f_kib * fs + w_kib * ws) * 1024))
+    rows.sort(key=lambda r: -r[3])
+    md = ["# %s: HBM traffic per kernel launch" % tag, "",
+          "Commands (one MI355X, repository root; weight gradients kept on the caller's stream so that dispatches do not overlap):", "",
+          "    ARN_SINGLE_STREAM=1 rocprofv3 --pmc FETCH_SIZE -d DIR/FETCH_SIZE -o bench --output-format csv -- python3 bench.py <workload flags> --steps 3 --warmup 1 --no-cpu-baseline",
+          "    rocprofv3 --pmc FETCH_SIZE -d DIR/FETCH_SIZE -o copy --output-format csv -- python3 bench.py --calibrate-copy 256",
+          "    (the same two with WRITE_SIZE)",
+          "    python3 bench.py --summarise-counters DIR --tag %s" % tag, "",
+          "Calibration: a plain 256 MiB device copy reads FETCH_SIZE = %.0f KiB and WRITE_SIZE = %.0f KiB per dispatch, so the "
+          "counters are scaled by %.3f (fetch) and %.3f (write). Averages over all dispatches of the run." % (
+              fc["copy"]["FETCH_SIZE"], wc["copy"]["WRITE_SIZE"], fs, ws), "",
+          "| kernel | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled HBM bytes per launch |", "|---|---|---|---|"]
+    md += ["| %s | %.0f | %.0f | %s |" % (n, f_kib, w_kib, format(int(b), ",")) for n, f_kib, w_kib, b in rows]
+    with open(os.path.join(prof, "%s_traffic.md" % tag), "w") as f:
+        f.write("\n".join(md) + "\n")
+    with open(os.path.join(prof, "%s_traffic.json" % tag), "w") as f:
+        json.dump({"workload": tag, "fetch_scale": round(fs, 4), "write_scale": round(ws, 4),
+                   "hbm_bytes_per_launch": {n: int(b) for n, _, _, b in rows}}, f, indent=1)
+    print("wrote profiles/%s_traffic.json and .md" % tag)
 
 
 UPDATE_BYTES = {"rmsprop": 20, "adam": 28, "adam_local": 52, "adam_merge": 60}   # fp32 arrays read + written per parameter
@@ -472,17 +786,20 @@ def alternating_report(args, arn, wl, np, torch):
         "actions_valid": ok}))
 
 
-def paper_geometry_report(args, arn, wl, np, torch):
+def paper_geometry_report(args, arn, wl, np, torch, net="nature"):
     """A2C gradient step and action-selection inference on the frame size and padding of the paper's own runs
     (appendix "Atari Frame Processing"): 104x80 frames, 25x19 -> 12x9 -> 12x9 feature maps, fc 6912 -> 512."""
     dev, A, B, k = "cuda:0", 18, args.batch or 2048, 3
     frame, fc_in = wl.PAPER_FRAME, wl.FC_INPUTS[wl.PAPER_FRAME]
-    macs = {"conv1": 25 * 19 * 256 * 32, "conv2": 12 * 9 * 512 * 64, "conv3": 12 * 9 * 576 * 64, "fc": fc_in * 512,
-            "head": (A + 1) * 512}
+    if net == "a3c":   # 2-convolution network: its own algorithmic flops, whatever the embedding executes
+        macs = {"conv1": 25 * 19 * 256 * 16, "conv2": 12 * 9 * 256 * 32, "fc": wl.A3C_FC_INPUTS * 256, "head": (A + 1) * 256}
+    else:
+        macs = {"conv1": 25 * 19 * 256 * 32, "conv2": 12 * 9 * 512 * 64, "conv3": 12 * 9 * 576 * 64, "fc": fc_in * 512,
+                "head": (A + 1) * 512}
     fwd_flops = 2 * sum(macs.values())
     fwdbwd_flops = 3 * fwd_flops - 2 * macs["conv1"]
-    cfg = arn.Config(A, arn.ARN_HEAD_PV, geometry=arn.ARN_GEOM_PAPER)
-    flat = wl.he_normal_params(A, "pv", 2000 + k, fc_inputs=fc_in)
+    cfg = arn.Config(A, arn.ARN_HEAD_PV, geometry=arn.ARN_GEOM_A3C if net == "a3c" else arn.ARN_GEOM_PAPER)
+    flat = wl.he_normal_params(A, "pv", 2000 + k, fc_inputs=fc_in, net=net)
     packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
     arn.weights_prepare(cfg, torch.from_numpy(flat).to(dev), packed)
     batch = {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev)
@@ -520,100 +837,17 @@ def paper_geometry_report(args, arn, wl, np, torch):
     null_ms = per.pop("null")[0] / args.steps
     avg_ms = {n: max(t / c - null_ms, 0.0) for n, (t, c) in per.items()}
     print(json.dumps({
-        "metric": "Nature-CNN samples/sec (fwd+bwd, 104x80 frames, padded conv2/conv3) at B=%d on 1 GPU" % B,
+        "metric": "%s samples/sec (fwd+bwd, 104x80 frames) at B=%d on 1 GPU" % (
+            "2-convolution network" if net == "a3c" else "Nature-CNN, padded conv2/conv3,", B),
         "value": round(B / sec, 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "a2c_grad_step_B%d_A18 on 104x80 frames (25x19 -> 12x9 -> 12x9, fc 6912)" % B,
+        "config": {"workload": ("a2c_grad_step_B%d_A18 on 104x80 frames, " % B) + ("2 convolutions 16/32 filters (25x19 -> 12x9, fc 3456 -> 256)" if net == "a3c" else "25x19 -> 12x9 -> 12x9, fc 6912"),
                    "global_batch": B, "parallelism": "single-gpu"},
         "mfma_frac_whole_step": round(B / sec * fwdbwd_flops / 1e12 / PEAK_BF16_TFLOPS, 4),
         "forward_samples_per_s": round(B / sec_fwd, 1), "forward_ms": round(sec_fwd * 1e3, 4),
         "algorithmic_flops_per_sample": {"forward": fwd_flops, "forward_backward": fwdbwd_flops},
         "kernel_us": {n: round(v * 1e3, 2) for n, v in sorted(avg_ms.items(), key=lambda kv: -kv[1])}}))
-
-
-def kernel_times_us(arn, torch, step, steps, stream):
-    """Average duration per launch site (microseconds, event-pair overhead subtracted) over `steps` more steps;
-    sites that launch several times per step (the forward kernels of a step with a target network) are summed."""
-    arn.profile_enable(True)
-    for _ in range(steps):
-        step()
-        arn.profile_null(stream)
-    torch.cuda.synchronize()
-    per = {}
-    for name, ms in arn.profile_collect(cap=96 * steps + 64):
-        tot, cnt = per.get(name, (0.0, 0))
-        per[name] = (tot + ms, cnt + 1)
-    arn.profile_enable(False)
-    null_ms = per.pop("null")[0] / steps
-    us = {n: max(t - c * null_ms, 0.0) / steps * 1e3 for n, (t, c) in per.items()}
-    return {n: round(v, 2) for n, v in sorted(us.items(), key=lambda kv: -kv[1])}
-
-
-def other_workload(args, arn, wl, np, torch):
-    """Secondary report lines for the other workloads (same JSON shape, no per-kernel roofline)."""
-    dev, k = "cuda:0", args.workload
-    w = wl.WORKLOADS[k]
-    A, B, head = w["A"], args.batch or w["B"], w["head"]
-    cfg = arn.Config(A, arn.ARN_HEAD_PV if head == "pv" else arn.ARN_HEAD_C51)
-    flat = wl.he_normal_params(A, head, 2000 + k)
-    packed = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
-    arn.weights_prepare(cfg, torch.from_numpy(flat).to(dev), packed)
-    stream = torch.cuda.current_stream()
-    to_dev = lambda d: {n: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for n, v in d.items()}
-    if w["kind"] == "forward":
-        obs = torch.from_numpy(wl.frames_for(k, B)).to(dev)
-        ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
-        logits = torch.empty(B, A, dtype=torch.float32, device=dev)
-        value = torch.empty(B, dtype=torch.float32, device=dev)
-        probs = torch.empty(B, A, dtype=torch.float32, device=dev)
-        greedy = torch.empty(B, dtype=torch.int32, device=dev)
-        step = lambda: arn.policy_forward(cfg, packed, obs, logits, value, probs, greedy, workspace=ws, stream=stream)
-        flops = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + (A + 1) * 512)
-        name = "policy_forward"
-    else:
-        ws = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_TRAIN), dtype=torch.uint8, device=dev)
-        dW = torch.empty(arn.param_count(cfg), dtype=torch.float32, device=dev)
-        loss = torch.empty(4, dtype=torch.float32, device=dev)
-        if w["kind"] == "ppo":
-            batch = to_dev(wl.actor_critic_batch(k, B=B, normalise_adv=True))
-            # sampling-policy log-probs: the current logits (from this library) perturbed by N(0, 0.05^2)
-            wsf = torch.empty(arn.workspace_bytes(cfg, B, arn.ARN_MODE_FORWARD), dtype=torch.uint8, device=dev)
-            logits = torch.empty(B, A, dtype=torch.float32, device=dev)
-            value = torch.empty(B, dtype=torch.float32, device=dev)
-            arn.policy_forward(cfg, packed, batch["obs"], logits, value, workspace=wsf, stream=stream)
-            noisy = logits + torch.from_numpy(wl.logit_noise(k, B, A).astype(np.float32)).to(dev)
-            batch["old_logp"] = torch.log_softmax(noisy, dim=1).gather(1, batch["action"].long()[:, None])[:, 0].contiguous()
-            head_macs = (A + 1) * 512
-            tgt_flops = 0
-        else:
-            batch = to_dev(wl.c51_batch(k, B=B))
-            tpacked = torch.empty(arn.packed_bytes(cfg), dtype=torch.uint8, device=dev)
-            arn.weights_prepare(cfg, torch.from_numpy(wl.he_normal_params(A, head, 3000 + k)).to(dev), tpacked)
-            batch["w_target_packed"] = tpacked
-            head_macs = A * 51 * 512
-            tgt_flops = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + head_macs)
-        fwd = 2 * (MACS["conv1"] + MACS["conv2"] + MACS["conv3"] + MACS["fc"] + head_macs)
-        flops = 3 * fwd - 2 * MACS["conv1"] + tgt_flops
-        step = lambda: arn.train_step_grads(cfg, packed, batch, w["kind"], dW, loss, workspace=ws, stream=stream)
-        name = "train_step_grads:" + w["kind"]
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / args.steps
-    print(json.dumps({
-        "metric": "Nature-CNN samples/sec (%s) at B=%d on 1 GPU" % (name, B), "value": round(B / sec, 1),
-        "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s (workload %d)" % (w["name"], k), "global_batch": B, "parallelism": "single-gpu"},
-        "mfma_frac_whole_step": round(B / sec * flops / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "algorithmic_flops_per_sample": flops,
-        "kernel_us_per_step": kernel_times_us(arn, torch, step, min(args.steps, 50), stream)}))
 
 
 if __name__ == "__main__":
