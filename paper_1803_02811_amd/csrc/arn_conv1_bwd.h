@@ -119,9 +119,9 @@ __device__ __forceinline__ void conv1_bwd_fused_body(u32x4 *lds, int block, cons
         bf16x8 wd[CT][KS];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
-            const size_t row = (size_t)(phase * 32 + ct * 16 + li) * D::K + 8 * lg;
+            const size_t row = frag_base(phase * 2 + ct, D::K, lane);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) wd[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w2d + row + 32 * ks));
+            for (int ks = 0; ks < KS; ++ks) wd[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w2d + row + FRAG_STEP * ks));
         }
         // d(pre2) and mask words of consecutive samples
         u32x4 rg[NG];

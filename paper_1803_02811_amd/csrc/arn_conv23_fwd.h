@@ -96,11 +96,11 @@ __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, con
         const int n0 = pw * 16 + 4 * lg;                         // this lane's four output channels
         bf16x8 wh[KS2], wl[KS2];
         {
-            const size_t row = (size_t)(pw * 16 + li) * P2::K + 8 * lg;
+            const size_t row = frag_base(pw, P2::K, lane);
 #pragma unroll
             for (int ks = 0; ks < KS2; ++ks) {
-                wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w2 + row + 32 * ks));
-                wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w2_lo + row + 32 * ks));
+                wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w2 + row + FRAG_STEP * ks));
+                wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w2_lo + row + FRAG_STEP * ks));
             }
         }
         const float4 bias = *reinterpret_cast<const float4 *>(a.b2 + n0);
@@ -197,11 +197,11 @@ __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, con
         if (s_begin + 1 < s_end) gload();
         bf16x8 wh[KS3], wl[KS3];
         {
-            const size_t row = (size_t)(wave * 16 + li) * P3::K + 8 * lg;
+            const size_t row = frag_base(wave, P3::K, lane);
 #pragma unroll
             for (int ks = 0; ks < KS3; ++ks) {
-                wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w3 + row + 32 * ks));
-                wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w3_lo + row + 32 * ks));
+                wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w3 + row + FRAG_STEP * ks));
+                wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w3_lo + row + FRAG_STEP * ks));
             }
         }
         const float4 bias = *reinterpret_cast<const float4 *>(a.b3 + n0);

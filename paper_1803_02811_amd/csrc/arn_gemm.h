@@ -92,6 +92,18 @@ __device__ __forceinline__ u32x4 u8x8_to_bf16x8(uint32_t lo, uint32_t hi) {
     return r;
 }
 
+// Weights that a wavefront keeps in registers as MFMA A-operand fragments (16 rows x 32 k) are packed in fragment
+// order: the eight values of lane l for (16-row tile t, k-step ks) of a [rows][K] matrix are the 16 contiguous
+// bytes at element ((t * K/32 + ks) * 64 + l) * 8.  A wavefront's load of one fragment is then one contiguous
+// kilobyte; read from the row-major matrix it was sixteen 64-byte pieces a row apart, and a workgroup's
+// 300 KB of such loads took 8 us before the first MFMA (measured).  frag_base + FRAG_STEP * ks addresses it.
+constexpr int FRAG_STEP = 512;
+__device__ __forceinline__ size_t frag_base(int tile, int K, int lane) { return (size_t)tile * K * 16 + (size_t)lane * 8; }
+// the same index for the packing side: element (row, k) of the [rows][K] matrix
+__host__ __device__ constexpr long frag_index(long row, long k, long K) {
+    return ((row >> 4) * (K >> 5) + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (row & 15)) * 8 + (k & 7);
+}
+
 __device__ __forceinline__ u32x4 zero_u4() { return u32x4{0u, 0u, 0u, 0u}; }
 
 // Waits until every global load of this wavefront has returned (s_waitcnt vmcnt(0), other counters unchanged).

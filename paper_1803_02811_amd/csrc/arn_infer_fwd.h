@@ -45,7 +45,7 @@ __device__ __forceinline__ u32x2 relu_f16x4(float a, float b, float c, float d) 
 
 struct InferConvArgs {
     const uint8_t *obs;                 // [B][4][IN_H][IN_W]
-    const _Float16 *w1, *w2, *w3;       // forward layouts [co][k'] as in the bf16 copies
+    const _Float16 *w1, *w2, *w3;       // forward weights [co][k'] in fragment order (frag_index)
     const float *b1, *b2, *b3;
     _Float16 *a3;                       // [B][P3][64]
 };
@@ -107,18 +107,18 @@ __global__ __launch_bounds__(INF_THREADS) void infer_conv_kernel(const InferConv
     const int ct = wave & 3, t_first = wave >> 2;
     f16x8 w1[KS1];
     auto load_w1 = [&]() __attribute__((always_inline)) {
-        const size_t r1 = (size_t)(ct1 * 16 + li) * KW1 + 8 * lg;
+        const size_t r1 = frag_base(ct1, KW1, lane);
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) w1[ks] = as_f16x8(*reinterpret_cast<const u32x4 *>(a.w1 + r1 + 32 * ks));
+        for (int ks = 0; ks < KS1; ++ks) w1[ks] = as_f16x8(*reinterpret_cast<const u32x4 *>(a.w1 + r1 + FRAG_STEP * ks));
     };
     load_w1();
     f16x8 w2[KS2], w3[KS3];
     {
-        const size_t r2 = (size_t)(ct * 16 + li) * KW2 + 8 * lg, r3 = (size_t)(ct * 16 + li) * KW3 + 8 * lg;
+        const size_t r2 = frag_base(ct, KW2, lane), r3 = frag_base(ct, KW3, lane);
 #pragma unroll
-        for (int ks = 0; ks < KS2; ++ks) w2[ks] = as_f16x8(*reinterpret_cast<const u32x4 *>(a.w2 + r2 + 32 * ks));
+        for (int ks = 0; ks < KS2; ++ks) w2[ks] = as_f16x8(*reinterpret_cast<const u32x4 *>(a.w2 + r2 + FRAG_STEP * ks));
 #pragma unroll
-        for (int ks = 0; ks < KS3; ++ks) w3[ks] = as_f16x8(*reinterpret_cast<const u32x4 *>(a.w3 + r3 + 32 * ks));
+        for (int ks = 0; ks < KS3; ++ks) w3[ks] = as_f16x8(*reinterpret_cast<const u32x4 *>(a.w3 + r3 + FRAG_STEP * ks));
     }
     const float4 bias1 = *reinterpret_cast<const float4 *>(a.b1 + ct1 * 16 + 4 * lg);
     const float4 bias2 = *reinterpret_cast<const float4 *>(a.b2 + ct * 16 + 4 * lg);

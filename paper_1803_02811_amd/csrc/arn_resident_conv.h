@@ -238,11 +238,11 @@ __global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 
     gload(s_begin);
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-        const size_t row = (size_t)(wave * (16 * CT) + ct * 16 + li) * C::K + 8 * lg;
+        const size_t row = frag_base(wave * CT + ct, C::K, lane);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w + row + 32 * ks));
-            if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + 32 * ks));
+            wh[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w + row + FRAG_STEP * ks));
+            if constexpr (C::SPLIT) wl[ct][ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(a.w_lo + row + FRAG_STEP * ks));
         }
     }
     if constexpr (C::ZERO_FILL) {   // the zero border is written while the first image and the weights are on their way
@@ -381,11 +381,11 @@ __device__ __forceinline__ void conv1_fwd_resident_body(
     };
 
     gload(s_begin);
-    const size_t wrow = (size_t)(ct * 16 + li) * KW1 + 8 * lg;   // after the first image loads: staging does not wait for the weights
+    const size_t wrow = frag_base(ct, KW1, lane);   // after the first image loads: staging does not wait for the weights
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + wrow + 32 * ks));
-        wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + wrow + 32 * ks));
+        wh[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w + wrow + FRAG_STEP * ks));
+        wl[ks] = as_bf16x8(*reinterpret_cast<const u32x4 *>(w_lo + wrow + FRAG_STEP * ks));
     }
     wait_global_loads();
     int buf = 0;

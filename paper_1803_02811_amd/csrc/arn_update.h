@@ -322,10 +322,16 @@ __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float 
     if (k >= PK_B1 && k <= PK_BH) {
         ((float *)out)[i] = v;
     } else {
+        // the convolution weights live in registers as MFMA fragments: packed in fragment order (frag_index)
+        long o = i;
+        if (k == PK_W1) o = frag_index(i / KW1, i % KW1, KW1);
+        else if (k == PK_W2) o = frag_index(i / KW2, i % KW2, KW2);
+        else if (k == PK_W3 || k == PK_W3D) o = frag_index(i / KW3, i % KW3, KW3);
+        else if (k == PK_W2D) o = frag_index(i / 256, i % 256, 256);
         const __bf16 hi = (__bf16)v;
-        ((__bf16 *)out)[i] = hi;
-        if (out_lo) ((__bf16 *)out_lo)[i] = (__bf16)(v - (float)hi);
-        if (out_f16) ((_Float16 *)out_f16)[i] = to_f16_finite(v);
+        ((__bf16 *)out)[o] = hi;
+        if (out_lo) ((__bf16 *)out_lo)[o] = (__bf16)(v - (float)hi);
+        if (out_f16) ((_Float16 *)out_f16)[o] = to_f16_finite(v);
     }
 }
 
