@@ -38,7 +38,7 @@ struct PvHeadArgs {
     const float *partial;   // fp32 [ks][B][512] partial sums of the fc GEMM
     int ks;
     const float *bfc;       // [512]
-    const __bf16 *wh, *whl; // head weights [64][512] hi / lo; rows A+1.. are zero
+    const __bf16 *wh, *whl; // head weights [64][512] hi / lo in fragment order (frag_index); rows A+1.. are zero
     const float *bh;        // [64] head bias (policy rows then the value row)
     int B, A;
     int rpb;                // samples per workgroup (1..16; 0 = 16).  Small batches spread over more
@@ -65,7 +65,7 @@ struct PvHeadArgs {
     const uint8_t *done;
     float gamma;
     float clip_eps, value_coef, entropy_coef;
-    const __bf16 *whd;      // head weights for the input gradient [512][64] (k = head row contiguous)
+    const __bf16 *whd;      // head weights for the input gradient [512][64] (k = head row), in fragment order
     // training outputs
     __bf16 *h;              // [B][512] fc activations (bf16), read by the head's weight gradient
     __bf16 *dz;             // [B][64]
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
     for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const size_t at = (size_t)(16 * t + fi) * HID + (wave * 4 + s) * 32 + fg * 8;
+            const size_t at = frag_base(t, HID, lane) + FRAG_STEP * (wave * 4 + s);   // fragment order (frag_index)
             wa[s][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(p.wh + at));
             wl[s][t] = as_bf16x8(*reinterpret_cast<const u32x4 *>(p.whl + at));
         }
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(PVH_THREADS) void pv_head_kernel(const PvHeadArgs p
     if constexpr (TRAIN) {
 #pragma unroll
         for (int t = 0; t < 8; ++t)
-            wd[t] = *reinterpret_cast<const u32x4 *>(p.whd + (size_t)((wave * 8 + t) * 16 + fi) * 64 + fg * 8);
+            wd[t] = *reinterpret_cast<const u32x4 *>(p.whd + frag_base(wave * 8 + t, 64, lane));   // fragment order
     }
 
     // ---- 2. head GEMM: wave w takes k = 128 w .. 128 w + 127 for both 16-row tiles ----

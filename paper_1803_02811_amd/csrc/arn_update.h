@@ -158,6 +158,7 @@ struct PackPlan {
     long w1, w2, w3, wfc, b1, b2, b3, bfc;   // offsets in the flat vector
     MapHeadRow hr;
     int NHP;
+    int small_head; // the head's matrices are read by pv_head_kernel as register fragments: fragment order
     int feat, p3;   // fc inputs and positions after conv3
     int blocks;
 };
@@ -171,6 +172,7 @@ inline PackPlan make_pack_plan(const Dims &d, void *w_packed) {
     pl.b1 = (long)po.b1; pl.b2 = (long)po.b2; pl.b3 = (long)po.b3; pl.bfc = (long)po.bfc;
     pl.hr = head_rows(d, po);
     pl.NHP = d.NHP;
+    pl.small_head = d.small ? 1 : 0;
     pl.feat = d.feat;
     pl.p3 = d.p3;
     auto set = [&](int k, long n, size_t out, size_t lo, bool has_lo) {
@@ -328,6 +330,8 @@ __global__ __launch_bounds__(256) void pack_all_kernel(PackPlan pl, const float 
         else if (k == PK_W2) o = frag_index(i / KW2, i % KW2, KW2);
         else if (k == PK_W3 || k == PK_W3D) o = frag_index(i / KW3, i % KW3, KW3);
         else if (k == PK_W2D) o = frag_index(i / 256, i % 256, 256);
+        else if (k == PK_WH && pl.small_head) o = frag_index(i / HID, i % HID, HID);
+        else if (k == PK_WHD && pl.small_head) o = frag_index(i / 64, i % 64, 64);
         const __bf16 hi = (__bf16)v;
         ((__bf16 *)out)[o] = hi;
         if (out_lo) ((__bf16 *)out_lo)[o] = (__bf16)(v - (float)hi);
