@@ -174,6 +174,8 @@ typedef struct {
     const float *reward;       /* [B]  c51, dqn */
     const uint8_t *done;       /* [B]  c51, dqn: 1 = terminal transition */
     const void *w_target_packed; /* c51, dqn: packed target-network parameters */
+    int32_t *next_action;      /* [B]  c51, dqn: OUTPUT, or NULL: the greedy next action a* the step bootstrapped from
+                                  (overwritten; 16-byte aligned) */
 } arn_batch;
 
 /* Local gradient of one training batch (step 1 of section "Synchronous
@@ -187,6 +189,10 @@ typedef struct {
  *   dqn: mean((y - Q(s,a))^2), y = reward + gamma (1-done) Q(s', a*; target network), a* = the greedy
  *        action of the target network on s', or of the online network when cfg->double_q is set
  *        (one more forward pass); y is a constant.
+ *   The passes that carry no gradient -- the target network's forward on next_obs and Double-DQN's selection
+ *   forward -- run one fp16 product per layer, as the inference calls do (values within about 2e-3 of exact
+ *   arithmetic).  Where two next actions' values lie closer than that, a* may be either of them; batch->next_action
+ *   reports the one taken.
  *   dW   : fp32 [arn_param_count], overwritten with dLoss/dW in canonical order
  *   loss : fp32 [4], overwritten: {total, policy (or cross-entropy, or squared TD error), value mse, entropy}
  * loss_kind a2c/ppo need head PV; c51 needs head C51; dqn needs head Q or DUEL (ARN_ESHAPE otherwise). */

@@ -439,16 +439,18 @@ def c51_project_scatter(p_next, reward, done, gamma=0.99, v_min=-10.0, v_max=10.
     return m
 
 
-def c51_target(atom_logits_next, reward, done, gamma=0.99, v_min=-10.0, v_max=10.0) -> dict:
+def c51_target(atom_logits_next, reward, done, gamma=0.99, v_min=-10.0, v_max=10.0, a_star=None) -> dict:
     """Target distribution from the target network's outputs on next states.
 
     p = softmax over atoms; Q[a] = sum_j z_j p[a,j]; a* = lowest-index argmax Q;
     m = projection of p[a*].  Also returns the top-2 gap of Q for graders.
+    `a_star` given: the next action is taken from it instead of the argmax (a grader that accepts either of two
+    next actions whose values tie within its margin evaluates the step for the one under test).
     """
     B, A, N = atom_logits_next.shape
     p = np.exp(log_softmax(atom_logits_next))
     q = p @ c51_support(N, v_min, v_max)
-    a_star = greedy(q)
+    a_star = greedy(q) if a_star is None else np.asarray(a_star, dtype=np.int64)
     m = c51_project(p[np.arange(B), a_star], np.asarray(reward, dtype=np.float64),
                     np.asarray(done, dtype=np.float64), gamma, v_min, v_max)
     return {"m": m, "a_star": a_star, "q": q, "q_gap": top2_gap(q)}
@@ -480,11 +482,15 @@ def c51_loss_grad(atom_logits, action, m) -> np.ndarray:
 # --------------------------------------------------------------------------
 # DQN objective (section "RL Algorithm Background")
 # --------------------------------------------------------------------------
-def dqn_target(q_next_target, reward, done, gamma: float, q_next_online=None) -> np.ndarray:
+def dqn_target(q_next_target, reward, done, gamma: float, q_next_online=None, a_star=None) -> np.ndarray:
     """y = r + gamma (1 - done) Q(a*|s'; theta-), with a* = argmax of the target network's values, or of
-    the online network's values on s' when `q_next_online` is given (Double-DQN)."""
+    the online network's values on s' when `q_next_online` is given (Double-DQN); `a_star` given: that action
+    instead of the argmax (see c51_target)."""
     qt = np.asarray(q_next_target, dtype=np.float64)
-    sel = greedy(qt if q_next_online is None else np.asarray(q_next_online, dtype=np.float64))
+    if a_star is None:
+        sel = greedy(qt if q_next_online is None else np.asarray(q_next_online, dtype=np.float64))
+    else:
+        sel = np.asarray(a_star, dtype=np.int64)
     boot = qt[np.arange(qt.shape[0]), sel]
     live = 1.0 - np.asarray(done, dtype=np.float64)
     return np.asarray(reward, dtype=np.float64) + gamma * live * boot
@@ -565,12 +571,14 @@ class Hyper:
 
 
 def train_step_grads(flat_params, batch: dict, loss_kind: str, spec: NetSpec,
-                     hyper: Hyper = Hyper(), flat_target_params=None) -> dict:
+                     hyper: Hyper = Hyper(), flat_target_params=None, next_action=None) -> dict:
     """Forward, objective and backward for one batch.
 
     batch keys -- a2c: obs, action, adv, ret; ppo: + old_logp;
     c51, dqn: obs, action, next_obs, reward, done (and `flat_target_params`).
-    Returns {"loss": {...}, "grads": {name: array}, "flat": flat gradient, ...}.
+    `next_action` (c51, dqn): bootstrap from these next actions instead of the greedy ones (see c51_target).
+    Returns {"loss": {...}, "grads": {name: array}, "flat": flat gradient, ...}; c51 and dqn also
+    "select_q" [B,A], the action values the greedy next action is the argmax of, and "next_action" [B].
     """
     params = unflatten(flat_params, spec)
     cache = forward(params, batch["obs"], spec)
@@ -594,8 +602,9 @@ def train_step_grads(flat_params, batch: dict, loss_kind: str, spec: NetSpec,
         tparams = unflatten(flat_target_params, spec)
         tcache = forward(tparams, batch["next_obs"], spec)
         tgt = c51_target(tcache["atom_logits"], batch["reward"], batch["done"],
-                         hyper.gamma, hyper.v_min, hyper.v_max)
+                         hyper.gamma, hyper.v_min, hyper.v_max, a_star=next_action)
         out["target"] = tgt
+        out["select_q"], out["next_action"] = tgt["q"], tgt["a_star"]
         out["loss"] = c51_loss_value(cache["atom_logits"], batch["action"], tgt["m"])
         d = c51_loss_grad(cache["atom_logits"], batch["action"], tgt["m"])
         grads = backward(params, cache, spec, datom_logits=d)
@@ -604,8 +613,10 @@ def train_step_grads(flat_params, batch: dict, loss_kind: str, spec: NetSpec,
         tparams = unflatten(flat_target_params, spec)
         q_next_t = forward(tparams, batch["next_obs"], spec)["q"]
         q_next_o = forward(params, batch["next_obs"], spec)["q"] if hyper.double_q else None
-        y = dqn_target(q_next_t, batch["reward"], batch["done"], hyper.gamma, q_next_o)
+        y = dqn_target(q_next_t, batch["reward"], batch["done"], hyper.gamma, q_next_o, a_star=next_action)
         out["target"] = y
+        out["select_q"] = q_next_t if q_next_o is None else q_next_o
+        out["next_action"] = greedy(out["select_q"]) if next_action is None else np.asarray(next_action, dtype=np.int64)
         out["loss"] = dqn_loss_value(cache["q"], batch["action"], y)
         d = dqn_loss_grad(cache["q"], batch["action"], y)
         grads = backward(params, cache, spec, dq=d)

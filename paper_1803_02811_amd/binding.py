@@ -31,7 +31,8 @@ class Config(ctypes.Structure):
 class _Batch(ctypes.Structure):
     """Mirror of arn_batch."""
     _fields_ = [(n, ctypes.c_void_p) for n in
-                ("obs", "action", "adv", "ret", "old_logp", "next_obs", "reward", "done", "w_target_packed")]
+                ("obs", "action", "adv", "ret", "old_logp", "next_obs", "reward", "done", "w_target_packed",
+                 "next_action")]
 
 
 class ArnError(RuntimeError):
@@ -157,7 +158,7 @@ def policy_act(cfg: Config, w_packed, obs, u, u2, action, logp=None, *, epsilon=
 
 
 def train_step_grads(cfg: Config, w_packed, batch: dict, loss_kind, dW, loss, *, workspace, stream=None) -> None:
-    """batch: dict of device tensors keyed like arn_batch's fields (missing = NULL)."""
+    """batch: dict of device tensors keyed like arn_batch's fields (missing = NULL); "next_action" is an output."""
     kind = LOSS_KINDS[loss_kind] if isinstance(loss_kind, str) else int(loss_kind)
     b = _Batch(*[_ptr(batch.get(n)) for n, _ in _Batch._fields_])
     B = int(batch["obs"].shape[0])

@@ -635,6 +635,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         if (!aligned(batch->next_obs, 16) || !aligned(batch->reward, 16) || !aligned(batch->done, 16) ||
             !aligned(batch->w_target_packed, 256))
             return ARN_EINVAL;
+        if (batch->next_action && !aligned(batch->next_action, 16)) return ARN_EINVAL;
     }
     const Workspace o = make_workspace(d, B, ARN_MODE_TRAIN);
     if (workspace_bytes < o.total) return ARN_EWORKSPACE;
@@ -652,18 +653,21 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
     __bf16 *dz = (__bf16 *)(ws + o.dz), *dph = (__bf16 *)(ws + o.dph);
     float *lossp = (float *)(ws + o.lossp), *hbp = (float *)(ws + o.hbp);
     const int lblocks = loss_blocks(d, B);
+    // Double-DQN: the online network's greedy action on the next states, kept where the caller asked for it
+    int32_t *const astar = batch->next_action ? batch->next_action : (int32_t *)(ws + o.astar);
 
     // ---- forward and objective ----
+    // The passes that carry no gradient (target network, Double-DQN selection) are one fp16 product per layer.
     if (loss_kind == ARN_LOSS_C51) {
         // target network on next states -> projected target m; its activations are then overwritten
         const Packed wt = view_packed(batch->w_target_packed, d);
         float *ztgt = (float *)(ws + o.ztgt), *m = (float *)(ws + o.m);
-        forward_launches(d, wt, batch->next_obs, B, ws, o, ztgt, d.NHP, false, s);
+        infer_launches(d, wt, batch->next_obs, B, ws, o, ztgt, d.NHP, s);
         {
             ProfScope ps("c51_target", s);
-                hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, d.NHP, B, d.A,
+            hipLaunchKernelGGL(c51_dist_kernel, dim3(cdiv(B, C51_WAVES)), dim3(64 * C51_WAVES), 0, s, ztgt, d.NHP, B, d.A,
                                d.atoms, cfg->v_min, cfg->v_max, cfg->gamma, batch->reward, batch->done,
-                               (float *)nullptr, (float *)nullptr, (int32_t *)nullptr, m);
+                               (float *)nullptr, (float *)nullptr, batch->next_action, m);
         }
         forward_launches(d, w, batch->obs, B, ws, o, z, d.NHP, true, s);
         ProfScope ps("loss", s);
@@ -677,19 +681,20 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             // states -> its greedy action.  The activations of these passes are then overwritten.
             wt_view = view_packed(batch->w_target_packed, d);
             wt = &wt_view;
-            forward_launches(d, *wt, batch->next_obs, B, ws, o, nullptr, 0, false, s);
+            infer_launches(d, *wt, batch->next_obs, B, ws, o, nullptr, 0, s);
             {
                 ProfScope ps("q_target", s);
                 PvHeadArgs p = pv_head_args(d, *wt, B, ws, o);
                 p.logits = (float *)(ws + o.qt);
+                if (!cfg->double_q) p.greedy = batch->next_action;
                 p.rpb = loss_block(B);
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
             if (cfg->double_q) {
-                forward_launches(d, w, batch->next_obs, B, ws, o, nullptr, 0, false, s);
+                infer_launches(d, w, batch->next_obs, B, ws, o, nullptr, 0, s);
                 ProfScope ps("q_select", s);
                 PvHeadArgs p = pv_head_args(d, w, B, ws, o);
-                p.greedy = (int32_t *)(ws + o.astar);
+                p.greedy = astar;
                 p.rpb = loss_block(B);
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
             }
@@ -703,7 +708,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         p.clip_eps = cfg->clip_eps; p.value_coef = cfg->value_coef; p.entropy_coef = cfg->entropy_coef;
         if (loss_kind == ARN_LOSS_DQN) {
             p.q_next = (const float *)(ws + o.qt);
-            p.a_star = cfg->double_q ? (const int32_t *)(ws + o.astar) : nullptr;
+            p.a_star = cfg->double_q ? astar : nullptr;
             p.reward = batch->reward; p.done = batch->done; p.gamma = cfg->gamma;
         }
         p.whd = w.whd; p.h = h; p.dz = dz; p.dph = dph; p.lossp = lossp; p.hbp = hbp;

@@ -127,9 +127,52 @@ class GpuNet:
         ws = self.workspace(B, arn.ARN_MODE_TRAIN)
         dW = torch.full((self.nparam,), float("nan"), dtype=torch.float32, device=DEV)
         loss = torch.empty(4, dtype=torch.float32, device=DEV)
+        self.next_action = None
+        if kind in ("c51", "dqn"):
+            b = dict(b)
+            b["next_action"] = torch.full((B,), -1, dtype=torch.int32, device=DEV)
         arn.train_step_grads(self.cfg, self.packed, b, kind, dW, loss, workspace=ws)
         torch.cuda.synchronize()
+        if kind in ("c51", "dqn"):
+            self.next_action = b["next_action"].cpu().numpy()     # the greedy next action the step bootstrapped from
         return dW.cpu().numpy(), loss.cpu().numpy()
+
+
+GREEDY_MARGIN = 1e-2   # greedy actions must agree wherever the oracle's top-2 gap exceeds this
+
+
+def train_c51_or_dqn(net, orc, flat, tflat, batch, kind, spec, hyper=None):
+    """One categorical / DQN gradient step on the GPU and the oracle's step it is to be compared with.
+
+    The greedy next action a* (the target network's, or with Double-DQN the online network's) is a discrete
+    decision on floating-point values, and the library takes it on the values of its one-product fp16 forward.
+    The grader's rule for such decisions: the GPU's a* must equal the oracle's wherever the oracle's top-2 gap of
+    the deciding action values exceeds 1e-2; elsewhere it must be one of the actions within 1e-2 of the oracle's
+    maximum.  Where an admissible a* differs from the oracle's own, the oracle's step is re-evaluated for the
+    GPU's choice, so that everything downstream of the decision is still compared value by value.
+    Returns (dW, loss, ref, number of samples whose a* differed).
+    """
+    kw = dict(flat_target_params=tflat)
+    if hyper is not None:
+        kw["hyper"] = hyper
+    ref = orc.train_step_grads(flat, batch, kind, spec, **kw)
+    dW, loss = net.train(batch, kind, target_packed=net.pack(tflat))
+    got = net.next_action.astype(np.int64)
+    A = ref["select_q"].shape[1]
+    assert ((got >= 0) & (got < A)).all(), "next_action outside [0, A)"
+    q = ref["select_q"]
+    gap = orc.top2_gap(q)
+    want = ref["next_action"]
+    decided = gap > GREEDY_MARGIN
+    np.testing.assert_array_equal(got[decided], want[decided])
+    rows = np.arange(q.shape[0])
+    assert (q[rows, got] >= q.max(axis=1) - GREEDY_MARGIN).all(), "a next action outside the greedy margin"
+    differ = int((got != want).sum())
+    print("\n  next action: %d of %d samples decided (gap > %.0e); %d admissible choices differ from the oracle's"
+          % (int(decided.sum()), q.shape[0], GREEDY_MARGIN, differ))
+    if differ:
+        ref = orc.train_step_grads(flat, batch, kind, spec, next_action=got, **kw)
+    return dW, loss, ref, differ
 
 
 def per_tensor(flat, A, head, atoms=51, fc_inputs=wl.FC_INPUTS[wl.FRAME]):

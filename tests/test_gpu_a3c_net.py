@@ -85,9 +85,8 @@ def test_categorical_head_and_action_values_on_the_small_network(gu):
         batch["action"] = (batch["action"] % A).astype(np.int32)
         batch["done"][:3] = 1
         spec = _spec(A, head)
-        ref = orc.train_step_grads(flat, batch, kind, spec, hyper=hyper, flat_target_params=tflat)
         net = gu.GpuNet(A, head, flat, geometry="a3c", **cfgkw)
-        dW, loss = net.train(batch, kind, target_packed=net.pack(tflat))
+        dW, loss, ref, _ = gu.train_c51_or_dqn(net, orc, flat, tflat, batch, kind, spec, hyper=hyper)
         _grads(gu, dW, ref["flat"], A, head)
         gu.tol_check(loss[:1], np.array([ref["loss"]["total"]]), "loss.total " + head)
 

@@ -4,7 +4,7 @@ import pytest
 
 import workloads as wl
 from oracle import nature_cnn as orc
-from tests.gpu_util import GpuNet, check_grads, per_tensor, tol_check
+from tests.gpu_util import GpuNet, check_grads, per_tensor, tol_check, train_c51_or_dqn
 
 pytestmark = pytest.mark.gpu
 
@@ -37,17 +37,14 @@ def test_dqn_gradients(head, double_q, B):
     tflat = wl.he_normal_params(A, head, seed=3600, bias_std=0.02)
     batch = _dqn_batch(B, A)
     spec = orc.NetSpec(A, head)
-    ref = orc.train_step_grads(flat, batch, "dqn", spec, orc.Hyper(double_q=bool(double_q)), flat_target_params=tflat)
     net = GpuNet(A, head, flat, double_q=double_q)
-    dW, loss = net.train(batch, "dqn", target_packed=net.pack(tflat))
+    dW, loss, ref, _ = train_c51_or_dqn(net, orc, flat, tflat, batch, "dqn", spec, hyper=orc.Hyper(double_q=bool(double_q)))
     got, want = per_tensor(dW, A, head), per_tensor(ref["flat"], A, head)
     check_grads(got, want, "dqn %s double=%d B=%d" % (head, double_q, B))
     assert abs(loss[0] - ref["loss"]["total"]) <= 1e-2 * abs(ref["loss"]["total"]) + 1e-3
     assert loss[1] == pytest.approx(loss[0]) and loss[2] == 0 and loss[3] == 0
-    # the bootstrapped action is a discrete choice: where the selecting network's top-2 gap is below the bar a
-    # different choice is legitimate, so make sure this batch was not decided by such ties
-    sel = orc.forward(orc.unflatten(flat if double_q else tflat, spec), batch["next_obs"], spec)["q"]
-    assert (orc.top2_gap(sel) > 1e-2).mean() > 0.9
+    # most of this batch is decided by clear margins, so the equality part of the greedy rule is exercised
+    assert (orc.top2_gap(ref["select_q"]) > 1e-2).mean() > 0.9
 
 
 def test_categorical_draw_matches_the_oracle():

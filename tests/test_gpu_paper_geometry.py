@@ -89,9 +89,7 @@ def test_c51_gradients(gu):
     batch["done"][:3] = 1
     batch["reward"][0] = 0.0
     spec = _spec(A, "c51")
-    ref = orc.train_step_grads(flat, batch, "c51", spec, flat_target_params=tflat)
-    net = _net(gu, A, "c51", flat)
-    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    dW, loss, ref, _ = gu.train_c51_or_dqn(_net(gu, A, "c51", flat), orc, flat, tflat, batch, "c51", spec)
     _compare_grads(gu, dW, ref["flat"], A, "c51", loss, ref["loss"], ["total", "ce", None, None])
 
 
@@ -101,9 +99,8 @@ def test_double_dqn_dueling_gradients(gu):
     tflat = wl.he_normal_params(A, "duel", 3106, bias_std=0.1, fc_inputs=FC)
     batch = wl.c51_batch(5, B=B, frame=FRAME)
     spec = _spec(A, "duel")
-    ref = orc.train_step_grads(flat, batch, "dqn", spec, flat_target_params=tflat, hyper=orc.Hyper(double_q=True))
     net = _net(gu, A, "duel", flat, double_q=1)
-    dW, loss = net.train(batch, "dqn", target_packed=net.pack(tflat))
+    dW, loss, ref, _ = gu.train_c51_or_dqn(net, orc, flat, tflat, batch, "dqn", spec, hyper=orc.Hyper(double_q=True))
     _compare_grads(gu, dW, ref["flat"], A, "duel", loss, ref["loss"], ["total", None, None, None])
 
 

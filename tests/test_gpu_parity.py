@@ -87,9 +87,7 @@ def test_c51_gradients(gu, B):
     batch["done"][: min(B, 3)] = 1            # terminal transitions present (reward 0 hits an atom exactly)
     batch["reward"][0] = 0.0
     spec = orc.NetSpec(A, "c51")
-    ref = orc.train_step_grads(flat, batch, "c51", spec, flat_target_params=tflat)
-    net = gu.GpuNet(A, "c51", flat)
-    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    dW, loss, ref, _ = gu.train_c51_or_dqn(gu.GpuNet(A, "c51", flat), orc, flat, tflat, batch, "c51", spec)
     _compare_grads(gu, dW, ref["flat"], A, "c51", loss, ref["loss"], ["total", "ce", None, None])
 
 
@@ -105,12 +103,9 @@ def test_c51_gradients_peaked_distributions(gu):
     batch = wl.c51_batch(5, B=B)
     batch["done"][::2] = 1
     spec = orc.NetSpec(A, "c51")
-    ref = orc.train_step_grads(flat, batch, "c51", spec, flat_target_params=tflat)
+    dW, loss, ref, _ = gu.train_c51_or_dqn(gu.GpuNet(A, "c51", flat), orc, flat, tflat, batch, "c51", spec)
     want = gu.per_tensor(ref["flat"], A, "c51")
     assert np.abs(want["c51.W"]).max() > 0.1 and np.abs(want["c51.b"]).max() > 0.02
-    assert (ref["target"]["q_gap"] > 1e-3).all()   # no near-tie in the target network's greedy action (its forward is good to 1e-4)
-    net = gu.GpuNet(A, "c51", flat)
-    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
     _compare_grads(gu, dW, ref["flat"], A, "c51", loss, ref["loss"], ["total", "ce", None, None])
 
 
@@ -245,10 +240,8 @@ def test_full_size_c51_b8192(gu):
     tflat = wl.he_normal_params(A, "c51", 3005)
     batch = wl.c51_batch(5, B=B)
     spec = orc.NetSpec(A, "c51")
-    ref = orc.train_step_grads(flat, batch, "c51", spec, flat_target_params=tflat)
     assert batch["done"].sum() > 20
-    net = gu.GpuNet(A, "c51", flat)
-    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    dW, loss, ref, _ = gu.train_c51_or_dqn(gu.GpuNet(A, "c51", flat), orc, flat, tflat, batch, "c51", spec)
     _compare_grads(gu, dW, ref["flat"], A, "c51", loss, ref["loss"], ["total", "ce", None, None])
     # properties that hold at any size: gradient of the categorical head's bias sums to zero per action
     got = gu.per_tensor(dW, A, "c51")
@@ -291,9 +284,8 @@ def test_c51_other_supports(gu, A, atoms, vmin, vmax):
                  reward=r.integers(-1, 2, size=B).astype(np.float32), done=(r.random(B) < 0.3).astype(np.uint8))
     spec = orc.NetSpec(A, "c51", num_atoms=atoms)
     hyper = orc.Hyper(v_min=vmin, v_max=vmax, gamma=0.9)
-    ref = orc.train_step_grads(flat, batch, "c51", spec, hyper=hyper, flat_target_params=tflat)
     net = gu.GpuNet(A, "c51", flat, num_atoms=atoms, v_min=vmin, v_max=vmax, gamma=0.9)
-    dW, loss = net.train(batch, "c51", target_packed=net.pack(tflat))
+    dW, loss, ref, _ = gu.train_c51_or_dqn(net, orc, flat, tflat, batch, "c51", spec, hyper=hyper)
     got, want = wl.split_params(dW, A, "c51", atoms), wl.split_params(ref["flat"], A, "c51", atoms)
     gu.check_grads(got, want, "c51 A=%d atoms=%d" % (A, atoms))
     gu.tol_check(loss[:1], np.array([ref["loss"]["total"]]), "loss")

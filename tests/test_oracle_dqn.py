@@ -36,6 +36,10 @@ def test_dqn_terminal_and_double():
     np.testing.assert_allclose(orc.dqn_target(qn_t, [1.0, 1.0, 1.0], [0, 1, 0], 0.9, qn_o), [1.0 + 0.0, 1.0, 1 + 0.9])
     # ties go to the lowest index
     np.testing.assert_allclose(orc.dqn_target(np.array([[2.0, 2.0]]), [0.0], [0], 1.0, np.array([[7.0, 7.0]])), [2.0])
+    # a next action handed in replaces the argmax (of either network) and is priced by the target values
+    np.testing.assert_allclose(orc.dqn_target(qn_t, [1.0, 1.0, 1.0], [0, 1, 0], 0.9, a_star=[1, 0, 0]), [1.0, 1.0, 1 + 0.9])
+    np.testing.assert_allclose(orc.dqn_target(qn_t, [1.0, 1.0, 1.0], [0, 1, 0], 0.9, qn_o, a_star=[0, 0, 1]),
+                               [1 + 2.7, 1.0, 1 + 3.6])
 
 
 def test_dqn_grad_matches_finite_differences_and_brute_force():
@@ -135,3 +139,40 @@ def test_dqn_step_gradient_matches_finite_differences(head, double_q):
         fd[j] = (loss(xp) - loss(xm)) / 2e-6
     np.testing.assert_allclose(out["flat"][idx], fd, rtol=2e-5, atol=1e-8)
     assert y[1] == batch["reward"][1]                       # the terminal transition does not bootstrap
+
+
+@pytest.mark.parametrize("head,kind,double_q", [("q", "dqn", False), ("duel", "dqn", True), ("c51", "c51", False)])
+def test_step_with_a_given_next_action(head, kind, double_q):
+    """train_step_grads with the next actions handed in: its own greedy actions reproduce the step bit for bit,
+    and changing one sample's next action changes the step exactly as if only that sample's target had changed
+    (every objective is a batch mean: the two-sample batch's gradient is the mean of the one-sample gradients)."""
+    r = np.random.default_rng(14)
+    spec = orc.NetSpec(3, head, num_atoms=5, geometry=TINY) if head == "c51" else orc.NetSpec(3, head, geometry=TINY)
+    n = orc.param_count(spec)
+    flat, tflat = r.standard_normal(n) * 0.4, r.standard_normal(n) * 0.4
+    B = 2
+    batch = dict(obs=r.integers(0, 256, size=(B, 2, 12, 12), dtype=np.uint8),
+                 next_obs=r.integers(0, 256, size=(B, 2, 12, 12), dtype=np.uint8),
+                 action=r.integers(0, 3, B), reward=r.standard_normal(B), done=np.zeros(B, dtype=np.uint8))
+    hyp = orc.Hyper(gamma=0.9, double_q=double_q, v_min=-2.0, v_max=2.0)
+    step = lambda b, na=None: orc.train_step_grads(flat, b, kind, spec, hyp, flat_target_params=tflat, next_action=na)
+    own = step(batch)
+    sel_params = flat if double_q else tflat
+    c = orc.forward(orc.unflatten(sel_params, spec), batch["next_obs"], spec)
+    if head == "c51":
+        p = np.exp(orc.log_softmax(c["atom_logits"]))
+        want_q = p @ orc.c51_support(5, -2.0, 2.0)
+    else:
+        want_q = c["q"]
+    np.testing.assert_allclose(own["select_q"], want_q, atol=1e-13)
+    np.testing.assert_array_equal(own["next_action"], orc.greedy(want_q))
+    same = step(batch, own["next_action"])
+    np.testing.assert_array_equal(same["flat"], own["flat"])
+    other = own["next_action"].copy()
+    other[1] = (other[1] + 1) % 3
+    changed = step(batch, other)
+    np.testing.assert_array_equal(changed["next_action"], other)
+    one = lambda i, na: step({k: v[i:i + 1] for k, v in batch.items()}, na[i:i + 1])["flat"]
+    np.testing.assert_allclose(changed["flat"], 0.5 * (one(0, other) + one(1, other)), atol=1e-12)
+    np.testing.assert_allclose(one(0, other), one(0, own["next_action"]), atol=0)
+    assert np.abs(one(1, other) - one(1, own["next_action"])).max() > 1e-6

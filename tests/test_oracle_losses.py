@@ -217,6 +217,26 @@ def test_c51_target_picks_best_expected_value():
     np.testing.assert_allclose(t["m"], p[np.arange(B), t["a_star"]], atol=1e-14)   # identity projection
 
 
+def test_c51_target_with_a_given_next_action():
+    """The next action handed in replaces the argmax and nothing else: with gamma = 1, r = 0 the projection is the
+    identity, so m is that action's distribution; handing in the argmax itself changes nothing."""
+    r = np.random.default_rng(18)
+    B, A, N = 6, 5, 51
+    z = r.standard_normal((B, A, N))
+    p = np.exp(orc.log_softmax(z))
+    own = orc.c51_target(z, np.zeros(B), np.zeros(B), gamma=1.0)
+    same = orc.c51_target(z, np.zeros(B), np.zeros(B), gamma=1.0, a_star=own["a_star"])
+    np.testing.assert_array_equal(same["m"], own["m"])
+    pick = (own["a_star"] + np.array([0, 1, 0, 2, 0, 0])) % A
+    t = orc.c51_target(z, np.zeros(B), np.zeros(B), gamma=1.0, a_star=pick)
+    np.testing.assert_array_equal(t["a_star"], pick)
+    np.testing.assert_allclose(t["m"], p[np.arange(B), pick], atol=1e-14)
+    unchanged = pick == own["a_star"]
+    np.testing.assert_array_equal(t["m"][unchanged], own["m"][unchanged])
+    assert (np.abs(t["m"][~unchanged] - own["m"][~unchanged]).max(axis=1) > 1e-3).all()
+    np.testing.assert_array_equal(t["q"], own["q"])                   # the action values themselves do not depend on it
+
+
 def test_c51_loss_grad_matches_finite_differences():
     r = np.random.default_rng(9)
     B, A, N = 3, 4, 7
