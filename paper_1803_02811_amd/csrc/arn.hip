@@ -394,9 +394,10 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
         p.obs = obs; p.dp2 = dp2; p.w2d = w.w2d; p.mask1 = (const uint8_t *)(ws + o.m1); p.part1 = part1;
         p.a1 = a1; p.a2 = a2; p.dp3 = dp3; p.part2 = part2; p.part3 = part3;
         p.B = B; p.n1 = sp.c1; p.n2 = sp.c2;
+        constexpr int geom = std::is_same<G, Geo84>::value ? ARN_GEOM_84 : ARN_GEOM_PAPER;
         p.spw1 = resident_spw(B, 256);
-        p.spw2 = resident_spw((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS) * CONV2_WG_G;
-        p.spw3 = resident_spw((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS) * CONV3_WG_G;
+        p.spw2 = resident_spw((B + CONV2_WG_G - 1) / CONV2_WG_G, wgrad_wgs2(geom)) * CONV2_WG_G;
+        p.spw3 = resident_spw((B + CONV3_WG_G - 1) / CONV3_WG_G, wgrad_wgs3(geom)) * CONV3_WG_G;
         hipLaunchKernelGGL((conv_backward_kernel<G, typename Cfg::Dgrad2>), dim3(sp.c1 + sp.c2 + sp.c3),
                            dim3(ConvBackward<G, typename Cfg::Dgrad2>::THREADS), 0, s, p);
     }

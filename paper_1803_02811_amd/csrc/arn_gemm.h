@@ -409,7 +409,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
     constexpr int BN1 = P::BN1, BK2 = P::BK2, WX = P::WAVES_X, WY = 4 / WX;
     constexpr int TY = BN1 / (32 * WY), TX = BK2 / (32 * WX);
     constexpr int YC = BN1 / 8, XC = BK2 / 8;          // 16-byte chunks per staged row
-    constexpr int YROW = YC + 1, XROW = XC + 1;        // padded LDS row, in u32x4
+    constexpr int TN_PAD = 1;
+    constexpr int YROW = YC + TN_PAD, XROW = XC + TN_PAD;        // padded LDS row, in u32x4
     constexpr int Y_CH = 64 * YC / 256, X_CH = 64 * XC / 256;
     static_assert(TY >= 1 && TX >= 1 && Y_CH >= 1 && X_CH >= 1, "tile shape");
     constexpr int BIAS_SCRATCH = (256 / YC) * BN1 * 4;   // bytes: one partial bias sum per thread and column

@@ -233,8 +233,11 @@ inline int pick_split(long rows, int tiles, int target_wgs) {
 }
 // workgroups of the conv2 / conv3 weight gradients: each writes a full fp32 partial of dW, so fewer workgroups
 // mean less partial traffic (and a cheaper reduction).  The two are ranges of one grid (conv_backward_kernel) and
-// run side by side, so 128 + 128 workgroups of one per CU fill the 256 CUs.
-constexpr int WGRAD_WGS = 128;
+// run side by side, one per CU, so together they fill the 256 CUs; the split follows the measured time per sample
+// of the two (84x84 network: conv2's 81 positions x 512 columns against conv3's 49 x 576), so that both ranges
+// finish together.
+inline int wgrad_wgs2(int geom) { return geom == ARN_GEOM_84 ? 148 : 128; }
+inline int wgrad_wgs3(int geom) { return 256 - wgrad_wgs2(geom); }
 constexpr int CONV2_WG_G = 2, CONV3_WG_G = 4;   // samples staged per iteration by the conv2 / conv3 weight-gradient kernels
 // sample-resident weight-gradient kernels: samples per workgroup and number of workgroups
 inline int resident_spw(int B, int target_wgs) { return (B + target_wgs - 1) / target_wgs; }
@@ -248,15 +251,15 @@ inline Splits make_splits(const Dims &d, int B) {
         // the dense layers' weight-gradient GEMMs are cut along the batch so that about 512 workgroups exist;
         // the convolutions use the sample-resident kernels, as below
         s.c1 = resident_groups(B, 256);
-        s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS);   // sample-resident kernels, as below
-        s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS);
+        s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, wgrad_wgs2(d.geom));   // sample-resident kernels, as below
+        s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, wgrad_wgs3(d.geom));
         s.fc = pick_split(B, (d.feat / 64) * 4, 512);
         s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
         return s;
     }
     s.c1 = resident_groups(B, 256);
-    s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, WGRAD_WGS);
-    s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, WGRAD_WGS);
+    s.c2 = resident_groups((B + CONV2_WG_G - 1) / CONV2_WG_G, wgrad_wgs2(d.geom));
+    s.c3 = resident_groups((B + CONV3_WG_G - 1) / CONV3_WG_G, wgrad_wgs3(d.geom));
     s.fc = pick_split(B, 49 * 4, 392);
     s.hd = pick_split(B, 4 * (d.NHP / 64), 256);
     return s;
