@@ -327,6 +327,7 @@ __global__ void epsilon_greedy_kernel(int32_t *__restrict__ action, const float 
 }
 
 // ------------------------- Categorical DQN target ---------------------------
+constexpr int C51_MAX_A = 18;     // most actions the categorical head supports
 // One wavefront per sample, lane j = atom j.  From atom logits [A][atoms] of
 // one network (rows of `zstride` floats): per-action softmax, expected values Q, lowest-index argmax.
 // With `m_out`, also the projection of the greedy action's distribution onto
@@ -343,9 +344,16 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
     const bool on = lane < atoms;
     float best_q = -INFINITY, best_p = 0.f;
     int best_a = 0;
-    for (int a = 0; a < A; ++a) {
+    // every action's row is fetched before the first is used: one memory latency per sample instead of one per action
+    float xs[C51_MAX_A];
+#pragma unroll
+    for (int a = 0; a < C51_MAX_A; ++a)
+        xs[a] = (on && a < A) ? zin[(size_t)n * zstride + (a < A ? a : 0) * atoms + lane] : -INFINITY;
+#pragma unroll
+    for (int a = 0; a < C51_MAX_A; ++a) {
+        if (a >= A) break;
         const size_t at = ((size_t)n * A + a) * atoms + lane;   // dense outputs; the logits row has `zstride` floats
-        const float x = on ? zin[(size_t)n * zstride + a * atoms + lane] : -INFINITY;
+        const float x = xs[a];
         const float mx = wave_max(x);
         const float e = on ? expf(x - mx) : 0.f;
         const float p = e / wave_sum(e);
@@ -385,17 +393,29 @@ __global__ __launch_bounds__(64 * C51_WAVES) void c51_loss_kernel(
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     for (int c = lane; c < NHP; c += 64) sb[wv][c] = 0.f;
     float ce = 0.f;
+    const bool on = lane < atoms;
+    const int n0 = (blockIdx.x * C51_WAVES + wv) * spw;           // wavefront-uniform
+    // the operands of sample i + 1 are fetched while sample i is worked on
+    int a_next = 0;
+    float x_next = -INFINITY, m_next = 0.f;
+    auto fetch = [&](int n) __attribute__((always_inline)) {
+        if (n < B) {
+            a_next = min(max(action[n], 0), A - 1);   // an out-of-range action must not become an out-of-range read
+            x_next = on ? z[(size_t)n * zstride + a_next * atoms + lane] : -INFINITY;
+            m_next = on ? m_in[(size_t)n * atoms + lane] : 0.f;
+        }
+    };
+    fetch(n0);
     for (int i = 0; i < spw; ++i) {
-        const int n = (blockIdx.x * C51_WAVES + wv) * spw + i;    // wavefront-uniform
+        const int n = n0 + i;
         if (n >= B) break;
-        const int a = min(max(action[n], 0), A - 1);   // an out-of-range action must not become an out-of-range read
-        const bool on = lane < atoms;
-        const float x = on ? z[(size_t)n * zstride + a * atoms + lane] : -INFINITY;
+        const int a = a_next;
+        const float x = x_next, m = m_next;
+        if (i + 1 < spw) fetch(n + 1);
         const float mx = wave_max(x);
         const float e = on ? expf(x - mx) : 0.f;
         const float s = wave_sum(e);
         const float lp = x - mx - logf(s);
-        const float m = on ? m_in[(size_t)n * atoms + lane] : 0.f;
         ce += -wave_sum(on ? m * lp : 0.f);
         const float msum = wave_sum(m);
         const float g = on ? (e / s * msum - m) / (float)B : 0.f;
