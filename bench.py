@@ -377,6 +377,14 @@ def workload_report(args, arn, wl, np, torch):
         out["cold_cache_call_ms"] = stats_ms(np, cold)
         out["hbm_frac_cold"] = round((bytes_alg * B + bytes_launch) / (float(np.median(cold)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
         del junk
+        # the same call captured once into a HIP graph and replayed (what a sampler loop that cannot afford the
+        # launch gaps of three kernels does; arn_policy_forward_static exists for callers under capture)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(args.warmup):
+            g.replay()
+        out["graph_replay_ms_per_call"] = round(wall_ms(torch, g.replay, args.steps), 4)
     else:
         # forward-only (action-selection inference, the fp16 single-product path) on the same frames, for the report
         lg = torch.empty(B, A * (51 if head == "c51" else 1), dtype=torch.float32, device=dev)

@@ -224,11 +224,33 @@ __global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p)
     constexpr int A_CH = BM / RS, W_CH = BN / RS;     // 16-byte chunks staged per thread and k-tile
     static_assert(BM % RS == 0 && BN % RS == 0, "staging passes");
     constexpr bool ALO = ActLo<P, SPLIT>::value;
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
     int kt_begin = 0, KT = p.K / 64;
     if constexpr (HasKSplit<P>::value) {
+        // Split-k launches: workgroups go to the eight XCDs round robin in linear order (x fastest), and each XCD has
+        // an L2 of its own.  With the plain mapping an XCD sees every k range of its position tiles and all of W;
+        // remapped, an XCD works on one k range (or a few) of a band of position tiles, so what its L2 fetches from
+        // memory is halved (measured: 77.2 -> 38.6 MB per launch of the fc layer at 2048 samples; the launch itself
+        // 26.9 -> 26.5 us, 17.0 -> 15.2 us at 1024 samples).  Only for grids that split evenly; otherwise the plain
+        // mapping.
+        const int gx = gridDim.x, gy = gridDim.y, gz = gridDim.z;
+        const bool pow2 = (gz & (gz - 1)) == 0;
+        if (pow2 && gz >= 8) {
+            const int L = bx + gx * (by + gy * bz), c = L & 7, zpc = gz >> 3;
+            int r = L >> 3;
+            bz = c * zpc + r % zpc;
+            r /= zpc;
+            bx = r % gx;
+            by = r / gx;
+        } else if (pow2 && gz > 1 && gx % (8 / gz) == 0) {
+            const int L = bx + gx * (by + gy * bz), c = L & 7, g = 8 / gz, xs = gx / g, r = L >> 3;
+            bz = c / g;
+            bx = (c % g) * xs + r % xs;
+            by = r / xs;
+        }
         const int total = KT;
-        kt_begin = (int)blockIdx.z * total / p.ksplit;
-        KT = ((int)blockIdx.z + 1) * total / p.ksplit;
+        kt_begin = bz * total / p.ksplit;
+        KT = (bz + 1) * total / p.ksplit;
     }
     static_assert(TN >= 1 && TM >= 1, "tile shape");
 
@@ -242,7 +264,7 @@ __global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave % WN, wm = wave / WN;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN, z = blockIdx.z;
+    const int m0 = bx * BM, n0 = by * BN, z = bz;
     const int kc = tid & 7;      // which 16-byte chunk of the 128-byte k-tile row
     const int r0 = tid >> 3;     // first staged row; this thread also stages r0+RS, r0+2RS, ...
 
