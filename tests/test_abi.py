@@ -134,6 +134,10 @@ def test_action_value_heads_and_act_argument_errors(lib):
     nonext = arn.binding._Batch(*([0x1000] * 5 + [None] * 4))
     assert lib.arn_train_step_grads(cq, fake, ctypes.byref(nonext), 4, arn.ARN_LOSS_DQN, fake, fake, fake, big,
                                     None) == EINVAL
+    # the optional next-action output must be 16-byte aligned when given (checked before anything is launched)
+    badnext = arn.binding._Batch(*([0x1000] * 9 + [0x1004]))
+    assert lib.arn_train_step_grads(cq, fake, ctypes.byref(badnext), 4, arn.ARN_LOSS_DQN, fake, fake, fake, big,
+                                    None) == EINVAL
     # arn_policy_act
     assert lib.arn_policy_act(cp, fake, fake, 4, None, fake, 0.0, fake, None, fake, big, None) == EINVAL      # u
     assert lib.arn_policy_act(cp, fake, fake, 4, fake, None, 0.0, None, None, fake, big, None) == EINVAL      # action
