@@ -198,6 +198,9 @@ def main():
                          "padded conv2/conv3, per-kernel times included")
     ap.add_argument("--a3c-net", action="store_true",
                     help="secondary report: the same on the 2-convolution policy-gradient network (104x80 frames)")
+    ap.add_argument("--library-baseline", action="store_true",
+                    help="time the same network written with PyTorch's own layers (MIOpen / hipBLASLt) on this GPU: "
+                         "context for the A2C step and the forward pass, not part of the product path")
     ap.add_argument("--update-rules", action="store_true",
                     help="report the parameter-update kernels instead (secondary line)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5],
@@ -247,6 +250,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": n, "copies": 5}))
+        return
+    if args.library_baseline:
+        library_baseline_report(args, wl, np, torch)
         return
     if args.update_rules:
         update_rules_report(args, arn, wl, np, torch)
@@ -579,6 +585,59 @@ def summarise_counters(root, tag, sq):
         json.dump({"workload": tag, "fetch_scale": round(fs, 4), "write_scale": round(ws, 4),
                    "hbm_bytes_per_launch": {n: int(b) for n, _, _, b in rows}}, f, indent=1)
     print("wrote profiles/%s_traffic.json and .md" % tag)
+
+
+def library_baseline_report(args, wl, np, torch):
+    """Context line: the Nature CNN with torch.nn layers (the vendor libraries' convolutions and GEMMs, channels-last),
+    forward and A2C forward + backward on the workload's frames, in bf16 and fp32.  Nothing of the library under test
+    runs here; the figures stand beside bench.py's own lines the way the CPU oracle's do."""
+    import torch.nn as nn
+    import torch.nn.functional as F
+    dev = "cuda:0"
+    B = args.batch or 2048
+    A = 18
+
+    class Net(nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.c1, self.c2, self.c3 = nn.Conv2d(4, 32, 8, 4), nn.Conv2d(32, 64, 4, 2), nn.Conv2d(64, 64, 3, 1)
+            self.fc, self.pi, self.v = nn.Linear(3136, 512), nn.Linear(512, A), nn.Linear(512, 1)
+
+        def forward(self, x):
+            x = F.relu(self.c3(F.relu(self.c2(F.relu(self.c1(x))))))
+            h = F.relu(self.fc(x.flatten(1)))
+            return self.pi(h), self.v(h)
+
+    batch = wl.actor_critic_batch(3, B=B)
+    x8 = torch.from_numpy(batch["obs"]).to(dev)
+    act = torch.from_numpy(batch["action"].astype(np.int64)).to(dev)
+    out = {"metric": "Nature-CNN with PyTorch's own layers on the same GPU (context, not the product path)", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "data": "synthetic",
+           "config": {"workload": "a2c_b%d, torch.nn, channels-last" % B, "global_batch": B}}
+    for name, dt in (("bf16", torch.bfloat16), ("fp32", torch.float32)):
+        net = Net().to(dev).to(dt).to(memory_format=torch.channels_last)
+        adv = torch.from_numpy(batch["adv"]).to(dev).float()
+        ret = torch.from_numpy(batch["ret"]).to(dev).float()
+
+        def fwd():
+            with torch.no_grad():
+                return net((x8.to(dt) / 255).contiguous(memory_format=torch.channels_last))
+
+        def step():
+            z, v = net((x8.to(dt) / 255).contiguous(memory_format=torch.channels_last))
+            lp = F.log_softmax(z.float(), 1)
+            loss = (-(lp.gather(1, act[:, None])[:, 0] * adv).mean() + 0.5 * ((v[:, 0].float() - ret) ** 2).mean()
+                    + 0.01 * (lp.exp() * lp).sum(1).mean())
+            net.zero_grad(set_to_none=True)
+            loss.backward()
+
+        for fn in (fwd, step):
+            for _ in range(args.warmup):
+                fn()
+        f_ms, s_ms = wall_ms(torch, fwd, args.steps), wall_ms(torch, step, args.steps)
+        out[name] = {"forward_ms": round(f_ms, 4), "fwd_bwd_ms": round(s_ms, 4),
+                     "fwd_bwd_samples_per_s": round(B / (s_ms * 1e-3), 1)}
+    print(json.dumps(out))
 
 
 UPDATE_BYTES = {"rmsprop": 20, "adam": 28, "adam_local": 52, "adam_merge": 60}   # fp32 arrays read + written per parameter
