@@ -281,7 +281,7 @@ inline int loss_block(int B) { return B >= 4096 ? 16 : B <= 512 ? 4 : 8; }
 constexpr int C51_WAVES = 4;      // wavefronts per block in the C51 kernels (one sample per wavefront at a time)
 // Samples each wavefront of c51_loss_kernel takes one after the other: a block also writes one fp32 partial of the
 // head's bias gradient, so large batches use fewer, longer blocks.
-inline int c51_loss_spw(int B) { return B <= 2048 ? 1 : 8; }
+inline int c51_loss_spw(int B) { return B <= 2048 ? 1 : 4; }
 
 // byte offsets into the workspace
 struct Workspace {

@@ -328,51 +328,117 @@ __global__ void epsilon_greedy_kernel(int32_t *__restrict__ action, const float 
 
 // ------------------------- Categorical DQN target ---------------------------
 constexpr int C51_MAX_A = 18;     // most actions the categorical head supports
-// One wavefront per sample, lane j = atom j.  From atom logits [A][atoms] of
-// one network (rows of `zstride` floats): per-action softmax, expected values Q, lowest-index argmax.
-// With `m_out`, also the projection of the greedy action's distribution onto
-// the support after the shift T_j = clip(r + gamma (1-done) z_j):
+constexpr int C51_MAX_ATOMS = 64;
+constexpr int C51_LANES = 3;      // lanes that share one action's row (3 * 18 <= 64)
+constexpr int C51_PER = (C51_MAX_ATOMS + C51_LANES - 1) / C51_LANES;   // most atoms one lane holds
+// One wavefront per sample.  From atom logits [A][atoms] of one network (rows of `zstride` floats): per-action
+// softmax, expected values Q, lowest-index argmax.  With `m_out`, also the projection of the greedy action's
+// distribution onto the support after the shift T_j = clip(r + gamma (1-done) z_j):
 //     m_i = sum_j p_j max(0, 1 - |T_j - z_i| / delta).
+// The sample's logits go through LDS (coalesced reads); then three neighbouring lanes share one action, each
+// holding a third of its atoms in registers, so that the softmax of all actions is one serial pass over at most
+// C51_PER values per lane and three cross-lane exchanges, instead of three wavefront reductions per action.
+// The partial sums of the three lanes are added in lane order: the same association on every run.  The
+// projection runs with lane i = atom i over (p_j, b_j = (T_j - v_min) / delta) pairs broadcast from LDS.
 __global__ __launch_bounds__(64 * C51_WAVES) void c51_dist_kernel(
     const float *__restrict__ zin, int zstride, int B, int A, int atoms, float v_min, float v_max, float gamma,
     const float *__restrict__ reward, const uint8_t *__restrict__ done, float *__restrict__ probs,
     float *__restrict__ q_out, int32_t *__restrict__ greedy, float *__restrict__ m_out) {
-    const int lane = threadIdx.x & 63, n = blockIdx.x * C51_WAVES + (threadIdx.x >> 6);
-    if (n >= B) return;
-    const float delta = (v_max - v_min) / (float)(atoms - 1);
-    const float zj = v_min + delta * (float)lane;
-    const bool on = lane < atoms;
-    float best_q = -INFINITY, best_p = 0.f;
-    int best_a = 0;
-    // every action's row is fetched before the first is used: one memory latency per sample instead of one per action
-    float xs[C51_MAX_A];
+    __shared__ float s_x[C51_WAVES][C51_MAX_A * C51_MAX_ATOMS];
+    __shared__ float2 s_pb[C51_WAVES][C51_MAX_ATOMS];
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = blockIdx.x * C51_WAVES + wv;
+    if (n >= B) return;                       // whole wavefronts leave; the kernel has no block-wide barrier
+    float *sx = s_x[wv];
+    const int ZW = A * atoms;
+    const float delta = (v_max - v_min) / (float)(atoms - 1), inv_delta = 1.f / delta;
+    // every row of the sample is fetched before the first is used: one memory latency per sample
+    {
+        float v[C51_MAX_A];
+        const float *src = zin + (size_t)n * zstride;
 #pragma unroll
-    for (int a = 0; a < C51_MAX_A; ++a)
-        xs[a] = (on && a < A) ? zin[(size_t)n * zstride + (a < A ? a : 0) * atoms + lane] : -INFINITY;
-#pragma unroll
-    for (int a = 0; a < C51_MAX_A; ++a) {
-        if (a >= A) break;
-        const size_t at = ((size_t)n * A + a) * atoms + lane;   // dense outputs; the logits row has `zstride` floats
-        const float x = xs[a];
-        const float mx = wave_max(x);
-        const float e = on ? expf(x - mx) : 0.f;
-        const float p = e / wave_sum(e);
-        const float q = wave_sum(p * (on ? zj : 0.f));
-        if (probs && on) probs[at] = p;
-        if (q_out && lane == 0) q_out[(size_t)n * A + a] = q;
-        if (q > best_q) { best_q = q; best_a = a; best_p = p; }
-    }
-    if (greedy && lane == 0) greedy[n] = best_a;
-    if (m_out) {
-        const float shrink = done[n] ? 0.f : gamma;
-        const float T = fminf(fmaxf(reward[n] + shrink * zj, v_min), v_max);
-        const float inv_delta = 1.f / delta;
-        float m = 0.f;
-        for (int j = 0; j < atoms; ++j) {
-            const float pj = lane_value(best_p, j), Tj = lane_value(T, j);
-            m += pj * fmaxf(0.f, 1.f - fabsf(Tj - zj) * inv_delta);
+        for (int t = 0; t < C51_MAX_A; ++t) {
+            const int c = t * 64 + lane;
+            v[t] = c < ZW ? src[c] : 0.f;
         }
-        if (on) m_out[(size_t)n * atoms + lane] = m;
+#pragma unroll
+        for (int t = 0; t < C51_MAX_A; ++t) sx[t * 64 + lane] = v[t];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    const int a = lane / C51_LANES, part = lane - a * C51_LANES;
+    const int per = (atoms + C51_LANES - 1) / C51_LANES;          // wavefront-uniform
+    const int j0 = part * per;
+    const bool live = a < A;
+    const int cnt = live ? max(0, min(per, atoms - j0)) : 0;
+    const int at = (live ? a : 0) * atoms + j0;
+    float x[C51_PER];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < C51_PER; ++k) {
+        if (k < per) {
+            x[k] = k < cnt ? sx[at + k] : -INFINITY;
+            mx = fmaxf(mx, x[k]);
+        }
+    }
+    const int base = lane - part;
+    mx = fmaxf(fmaxf(__shfl(mx, base, 64), __shfl(mx, base + 1, 64)), __shfl(mx, base + 2, 64));
+    float s = 0.f, w = 0.f;
+#pragma unroll
+    for (int k = 0; k < C51_PER; ++k) {
+        if (k < per) {
+            const float e = k < cnt ? expf(x[k] - mx) : 0.f;
+            x[k] = e;
+            s += e;
+            w += e * (v_min + delta * (float)(j0 + k));
+        }
+    }
+    s = (__shfl(s, base, 64) + __shfl(s, base + 1, 64)) + __shfl(s, base + 2, 64);
+    w = (__shfl(w, base, 64) + __shfl(w, base + 1, 64)) + __shfl(w, base + 2, 64);
+    const float inv_s = 1.f / s;
+    const float q = live ? w * inv_s : -INFINITY;
+    // lowest-index argmax over the actions (a NaN anywhere gives action 0)
+    const float qmax = wave_max(q);
+    int best_a = (int)-wave_max((live && q == qmax) ? -(float)a : -64.f);
+    if (best_a >= A) best_a = 0;
+    if (q_out && live && part == 0) q_out[(size_t)n * A + a] = q;
+    if (greedy && lane == 0) greedy[n] = best_a;
+    if (probs) {
+#pragma unroll
+        for (int k = 0; k < C51_PER; ++k)
+            if (k < per && k < cnt) sx[at + k] = x[k] * inv_s;      // in place of this lane's own logits
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        float *dst = probs + (size_t)n * ZW;
+#pragma unroll
+        for (int t = 0; t < C51_MAX_A; ++t) {
+            const int c = t * 64 + lane;
+            if (c < ZW) dst[c] = sx[c];
+        }
+    }
+    if (m_out) {
+        float2 *pb = s_pb[wv];
+        if (live && a == best_a) {
+#pragma unroll
+            for (int k = 0; k < C51_PER; ++k)
+                if (k < per && k < cnt) pb[j0 + k].x = x[k] * inv_s;
+        }
+        if (lane < atoms) {
+            const float shrink = done[n] ? 0.f : gamma;
+            const float T = fminf(fmaxf(reward[n] + shrink * (v_min + delta * (float)lane), v_min), v_max);
+            pb[lane].y = (T - v_min) * inv_delta;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const float fi = (float)lane;
+        float m = 0.f;
+#pragma unroll 4
+        for (int j = 0; j < atoms; ++j) {
+            const float2 v = pb[j];
+            m += v.x * fmaxf(0.f, 1.f - fabsf(v.y - fi));
+        }
+        if (lane < atoms) m_out[(size_t)n * atoms + lane] = m;
     }
 }
 
