@@ -37,23 +37,29 @@ ROUNDERS = {"bf16": round_bf16, "f16": round_f16, "bf16x2": round_bf16x2, "exact
 
 
 def forward_with_rounded_operands(params, obs_u8, spec, fmt):
-    """The oracle's forward pass with every weight matrix and every stored activation rounded to `fmt`
+    """The oracle's forward pass with every weight matrix and every stored activation rounded to `fmt`: one format
+    name for the whole network, or {"conv1" | "conv2" | "conv3" | "fc" | "head": (weight format, format of the
+    activation the layer stores)} for a mixture
     (pixels are exact in all formats; biases and the 1/255 scale are applied in full precision, as the
     kernels' fp32 epilogues do).  Returns the same cache layout as oracle.forward for the policy/value head."""
-    q = ROUNDERS[fmt]
+    if isinstance(fmt, str):
+        fmt = {layer: (fmt, fmt) for layer in ("conv1", "conv2", "conv3", "fc", "head")}
+    qw = {layer: ROUNDERS[f[0]] for layer, f in fmt.items()}      # the layer's weights
+    qa = {layer: ROUNDERS[f[1]] for layer, f in fmt.items()}      # the activation it stores
+    q = qw["head"]
     assert spec.head == "pv"
     cache = {"x": obs_u8.astype(np.float64) / 255.0}
     a = obs_u8.astype(np.float64)
     for i, (co, k, s, p) in enumerate(spec.geometry.convs, start=1):
-        pre = orc.conv2d(a, q(params[f"conv{i}.W"]), None, s, p)
+        pre = orc.conv2d(a, qw[f"conv{i}"](params[f"conv{i}.W"]), None, s, p)
         if i == 1:
             pre = pre / 255.0
         pre = pre + params[f"conv{i}.b"][None, :, None, None]
-        a = q(np.maximum(pre, 0.0))
+        a = qa[f"conv{i}"](np.maximum(pre, 0.0))
         cache[f"pre{i}"], cache[f"act{i}"] = pre, a
     B = obs_u8.shape[0]
-    pre_fc = a.reshape(B, -1) @ q(params["fc.W"]).T + params["fc.b"]
-    h = q(np.maximum(pre_fc, 0.0))
+    pre_fc = a.reshape(B, -1) @ qw["fc"](params["fc.W"]).T + params["fc.b"]
+    h = qa["fc"](np.maximum(pre_fc, 0.0))
     cache["pre_fc"], cache["h"] = pre_fc, h
     cache["logits"] = h @ q(params["pi.W"]).T + params["pi.b"]
     cache["value"] = (h @ q(params["v.W"]).T + params["v.b"])[:, 0]
