@@ -436,7 +436,7 @@ def workload_report(args, arn, wl, np, torch):
 # rocprofv3 counter CSVs -> committed summaries (no GPU needed)
 # ---------------------------------------------------------------------------
 KERNEL_NAME_PATTERNS = [   # first match wins: mangled or demangled rocprofv3 kernel name -> instrumented launch name
-    (r"conv123_fwd_kernel", "conv123_fwd"), (r"conv23_fwd_fused", "conv23_fwd"), (r"infer_conv_kernel", "conv_infer"),
+    (r"conv123_fwd_kernel", "conv123_fwd"), (r"conv23_fwd_fused", "conv23_fwd"), (r"infer_conv_(pipelined_)?kernel", "conv_infer"),
     (r"conv_backward_kernel", "conv_bwd"), (r"conv1_fwd_resident", "conv1_fwd"), (r"ResConv2Fwd", "conv2_fwd"),
     (r"ResConv3Fwd", "conv3_fwd"), (r"ResConv3Dgrad", "conv3_dgrad"), (r"FcFwd", "fc_fwd"), (r"FcDgrad", "fc_dgrad"),
     (r"pv_head_kernel<true>|pv_head_kernelILb1", "pv_head"), (r"pv_head_kernel<false>|pv_head_kernelILb0", "pv_head_infer"),

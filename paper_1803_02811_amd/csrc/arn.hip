@@ -317,8 +317,13 @@ void infer_trunk(const Dims &d, const Packed &w, const uint8_t *obs, int B, char
         p.obs = obs; p.w1 = w.w1h; p.w2 = w.w2h; p.w3 = w.w3h; p.b1 = w.b1; p.b2 = w.b2; p.b3 = w.b3;
         p.a3 = (_Float16 *)(ws + o.a3);
         const int spw = resident_spw(B, 256);
-        hipLaunchKernelGGL((infer_conv_kernel<G, typename Cfg::Fwd2, typename Cfg::Fwd3>), dim3(cdiv(B, spw)),
-                           dim3(INF_THREADS), 0, s, p, B, spw);
+        // the software-pipelined variant where its 17 KB of weights and biases fit beside the LDS images (84x84)
+        if constexpr (infer_pipelined_fits<G, typename Cfg::Fwd2, typename Cfg::Fwd3>())
+            hipLaunchKernelGGL((infer_conv_pipelined_kernel<G, typename Cfg::Fwd2, typename Cfg::Fwd3>), dim3(cdiv(B, spw)),
+                               dim3(INF_THREADS), 0, s, p, B, spw);
+        else
+            hipLaunchKernelGGL((infer_conv_kernel<G, typename Cfg::Fwd2, typename Cfg::Fwd3>), dim3(cdiv(B, spw)),
+                               dim3(INF_THREADS), 0, s, p, B, spw);
     }
     fc_and_head_launches<G::FEAT, true>(d, w, B, ws, o, z_out, zstride, s);
 }
