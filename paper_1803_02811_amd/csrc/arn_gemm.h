@@ -115,7 +115,10 @@ __device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt
 // v if keep else 0, through a mask the optimiser cannot see through: a gather
 // written as `ok ? *p : 0` is compiled to a branch around the load with a wait
 // right behind it, which serialises the loads of one k-tile.  With the mask the
-// (always in-bounds, clamped) loads are issued back to back.
+// (always in-bounds, clamped) loads are issued back to back.  The mask is applied where
+// the registers are written to LDS, not where they are loaded: applied at the load it sits
+// in the same basic block as the prefetch, and the wavefront waits for the next tile's
+// loads before it starts the MFMAs of the current one.
 __device__ __forceinline__ u32x4 keep_or_zero(u32x4 v, bool keep) {
     uint32_t mask = keep ? 0xffffffffu : 0u;
     asm volatile("" : "+v"(mask));
@@ -304,9 +307,9 @@ __global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p)
 
     auto stage = [&](int st) __attribute__((always_inline)) {   // registers -> LDS stage st
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            sA[st * SA + (r0 + RS * i) * LDS_ROW + kc] = ra[i];
-            if constexpr (ALO) sA2[st * SA + (r0 + RS * i) * LDS_ROW + kc] = ra2[i];
+        for (int i = 0; i < A_CH; ++i) {       // rows past M were read from row 0: zeroed here
+            sA[st * SA + (r0 + RS * i) * LDS_ROW + kc] = keep_or_zero(ra[i], rows[i].ok);
+            if constexpr (ALO) sA2[st * SA + (r0 + RS * i) * LDS_ROW + kc] = keep_or_zero(ra2[i], rows[i].ok);
         }
 #pragma unroll
         for (int i = 0; i < W_CH; ++i) {
@@ -459,15 +462,13 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
         for (int i = 0; i < Y_CH; ++i) {
             const int c = tid + 256 * i, r = c / YC, cc = c % YC;
             const long m = mt + r;
-            const u32x4 v = p.loady(m < m_end ? m : m_begin, y0 + cc * 8);   // clamp, load, then zero
-            ry[i] = keep_or_zero(v, m < m_end);
+            ry[i] = p.loady(m < m_end ? m : m_begin, y0 + cc * 8);   // clamped; zeroed when staged
         }
 #pragma unroll
         for (int i = 0; i < X_CH; ++i) {
             const int c = tid + 256 * i, r = c / XC, cc = c % XC;
             const long m = mt + r;
-            const u32x4 v = p.loadx(p.xrow(m < m_end ? m : m_begin), x0 + cc * 8);
-            rx[i] = keep_or_zero(v, m < m_end);
+            rx[i] = p.loadx(p.xrow(m < m_end ? m : m_begin), x0 + cc * 8);
         }
     };
 
@@ -489,9 +490,10 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
 #pragma unroll
         for (int i = 0; i < Y_CH; ++i) {
             const int c = tid + 256 * i;
-            sY[(c / YC) * YROW + c % YC] = ry[i];
+            const u32x4 v = keep_or_zero(ry[i], mt + c / YC < m_end);   // rows past the end of the range: zero
+            sY[(c / YC) * YROW + c % YC] = v;
             if (keeps_bias) {
-                const bf16x8 f = as_bf16x8(ry[i]);
+                const bf16x8 f = as_bf16x8(v);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bs[e] += (float)f[e];
             }
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const P p, float *__restri
 #pragma unroll
         for (int i = 0; i < X_CH; ++i) {
             const int c = tid + 256 * i;
-            sX[(c / XC) * XROW + c % XC] = rx[i];
+            sX[(c / XC) * XROW + c % XC] = keep_or_zero(rx[i], mt + c / XC < m_end);
         }
         __syncthreads();
         if (mt + 64 < m_end) gload(mt + 64);

@@ -31,13 +31,12 @@ struct DenseGather {
         r.base = in + (size_t)(r.ok ? m : 0) * K_;
         return r;
     }
+    // rows past M read row 0 (in bounds); the kernels zero them when they stage the registers into LDS
     __device__ __forceinline__ u32x4 load_at(const Row &r, int k) const {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + k);
-        return keep_or_zero(v, r.ok);
+        return *reinterpret_cast<const u32x4 *>(r.base + k);
     }
     __device__ __forceinline__ u32x4 load_lo_at(const Row &r, int k) const {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + lo_off + k);
-        return keep_or_zero(v, r.ok);
+        return *reinterpret_cast<const u32x4 *>(r.base + lo_off + k);
     }
 };
 // dense rows with a run-time row length (head gradients: K = padded head width)
@@ -55,8 +54,7 @@ struct DenseGatherRt {
         return r;
     }
     __device__ __forceinline__ u32x4 load_at(const Row &r, int k) const {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(r.base + k);
-        return keep_or_zero(v, r.ok);
+        return *reinterpret_cast<const u32x4 *>(r.base + k);
     }
 };
 
