@@ -163,10 +163,7 @@ __global__ __launch_bounds__(INF_THREADS) void infer_conv_kernel(const InferConv
         }
         if constexpr (decltype(first)::value) wait_global_loads();
         __syncthreads();          // act1 complete; every read of the frame image done
-        if (s + 1 < s_end) {
-            stage();              // the next frame, prefetched during conv1
-            if (s + 2 < s_end) gload(s + 2);
-        }
+        if (s + 1 < s_end) stage();   // the next frame, prefetched earlier
 
         // ---- conv2: act1 image -> act2 image ----
 #pragma unroll 1
@@ -201,6 +198,7 @@ __global__ __launch_bounds__(INF_THREADS) void infer_conv_kernel(const InferConv
         }
         __syncthreads();          // act2 complete; every read of the act1 image done; the next frame image staged
         if (s + 1 < s_end) load_w1();   // conv1's weights for the next sample arrive while conv3 runs
+        if (s + 2 < s_end) gload(s + 2);   // the frame after the next: not in registers while conv2 runs
 
         // ---- conv3: act2 image -> act3 in global memory ----
 #pragma unroll 1
