@@ -381,9 +381,13 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
                            (long)po.bfc, sp.fc);
     }
     {
-        FcDgradT<G::FEAT> p;
-        p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
-        launch_nt("fc_dgrad", p, B, G::FEAT / 64, 1, s);
+        // 128 x 128 tiles from 1024 samples up (fewer operand bytes from the L2 per flop), 128 x 64 below (more workgroups)
+        auto launch = [&](auto p) {
+            p.in = dph; p.M = B; p.w = w.wfcd; p.maskbits = (const uint8_t *)(ws + o.m3); p.out = dp3;
+            launch_nt("fc_dgrad", p, B, (G::FEAT + p.BN - 1) / p.BN, 1, s);
+        };
+        if (B >= 1024) launch(FcDgradT<G::FEAT, 128>());
+        else launch(FcDgradT<G::FEAT, 64>());
     }
     {
         typename Cfg::Dgrad3::Args p;

@@ -219,6 +219,17 @@ struct HasPrefetch<P, decltype((void)&P::prefetch)> {
     static constexpr bool value = true;
 };
 
+// Problems whose number of weight rows N_ROWS is not a multiple of BN: the last tile's rows past the end are read from
+// the last row (and the problem's epilogue drops their columns).
+template <class P, class = void>
+struct WeightRows {
+    static constexpr int value = 1 << 30;
+};
+template <class P>
+struct WeightRows<P, decltype((void)P::N_ROWS)> {
+    static constexpr int value = P::N_ROWS;
+};
+
 template <class P, bool SPLIT = false>
 __global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p) {
     constexpr int NT = ThreadsOf<P>::value, NW = NT / 64, RS = NT / 8;   // threads, wavefronts, rows staged per pass
@@ -278,7 +289,8 @@ __global__ __launch_bounds__(ThreadsOf<P>::value) void gemm_nt_kernel(const P p)
     const u32x4 *wsrc2[W_CH];
 #pragma unroll
     for (int i = 0; i < W_CH; ++i) {
-        const size_t at = (size_t)(n0 + r0 + RS * i) * p.K;
+        const int nrow = n0 + r0 + RS * i;
+        const size_t at = (size_t)(nrow < WeightRows<P>::value ? nrow : WeightRows<P>::value - 1) * p.K;
         wsrc[i] = reinterpret_cast<const u32x4 *>(p.weights(z) + at) + kc;
         if constexpr (SPLIT) wsrc2[i] = reinterpret_cast<const u32x4 *>(p.weights_lo(z) + at) + kc;
     }

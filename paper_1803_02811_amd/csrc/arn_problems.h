@@ -152,10 +152,11 @@ struct HeadDgrad : DenseGatherRt {
     }
 };
 
-// d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][FEAT], NHWC index
-template <int FEAT_>
+// d(pre3) = (d(pre_fc) W_fc) * [act3 > 0]      [B][FEAT], NHWC index.  BN_ = 64, or 128 for large batches (a third
+// less operand traffic from the L2 per flop; FEAT need not be a multiple of it: N_ROWS).
+template <int FEAT_, int BN_ = 64>
 struct FcDgradT : DenseGather<HID> {
-    static constexpr int BM = 128, BN = 64, WAVES_N = 2, K = HID, STAGES = 1, FEAT = FEAT_;
+    static constexpr int BM = 128, BN = BN_, WAVES_N = 2, K = HID, STAGES = 1, FEAT = FEAT_, N_ROWS = FEAT_;
     const __bf16 *w;          // [FEAT][512]
     const uint8_t *maskbits;  // sign bits of act3, bit e&7 of byte e>>3 for element e = m*FEAT + n
     __bf16 *out;
@@ -164,11 +165,11 @@ struct FcDgradT : DenseGather<HID> {
     __device__ __forceinline__ const __bf16 *weights(int) const { return w; }
     // the four ReLU-derivative bits of output quad (m, n..n+3), fetched before the k loop
     __device__ __forceinline__ uint32_t prefetch(int m, int n) const {
-        const size_t at = (size_t)(m < M ? m : 0) * FEAT + n;
+        const size_t at = (size_t)(m < M ? m : 0) * FEAT + (n < FEAT ? n : 0);
         return (uint32_t)maskbits[at >> 3] >> (at & 7);
     }
     __device__ __forceinline__ void store(int m, int n, f32x4 v, int, uint32_t mb) const {
-        if (m >= M) return;
+        if (m >= M || n >= FEAT) return;
         const size_t at = (size_t)m * FEAT + n;
         *reinterpret_cast<u32x2 *>(out + at) =
             pack_bf16x4(mb & 1 ? v[0] : 0.f, mb & 2 ? v[1] : 0.f, mb & 4 ? v[2] : 0.f, mb & 8 ? v[3] : 0.f);
