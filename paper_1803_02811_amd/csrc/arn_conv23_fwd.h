@@ -31,7 +31,8 @@ constexpr int conv23_fwd_lds_bytes() { return 2 * P2::IMG + 4 * P3::IMG; }
 
 // The work of workgroup `block` (of C23_THREADS threads) in the caller's LDS buffer.
 // P2, P3: the LDS image descriptions of conv2 forward (one sample per iteration) and conv3 forward.
-template <class P2, class P3>
+// FULL: act2, act3's lo part and all sign bits are written unconditionally (see conv1_fwd_resident_body).
+template <class P2, class P3, bool FULL = false>
 __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, const Conv23Args &a, int B, int spw) {
     // conv2 (producers)
     constexpr int CI2 = P2::CI, NCH2 = CI2 / 8, IMG2 = P2::IMG, KS2 = P2::K / 32;
@@ -162,9 +163,9 @@ __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, con
                 if (valid) {
                     *reinterpret_cast<u32x2 *>(dst + t_dst[t]) = hi;
                     *reinterpret_cast<u32x2 *>(dst + IMG3 + t_dst[t]) = lo;
-                    if (a.a2) *reinterpret_cast<u32x2 *>(a.a2 + at) = hi;
+                    if (FULL || a.a2) *reinterpret_cast<u32x2 *>(a.a2 + at) = hi;
                 }
-                if (a.m2) {
+                if (FULL || a.m2) {
                     const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);     // all lanes take part
                     if (lg == 0 && valid) *reinterpret_cast<uint16_t *>(a.m2 + (at >> 3)) = (uint16_t)bits;
                 }
@@ -251,8 +252,8 @@ __device__ __forceinline__ void conv23_fwd_fused_body(u32x4 *lds, int block, con
                 const int pos = t * 16 + li;
                 const bool valid = pos < R3;
                 const size_t at = ((size_t)s * R3 + pos) * P3::CO + n0;
-                if (valid) store_bf16x4_split(a.a3, a.a3_lo, at, r0, r1, r2, r3);
-                if (a.m3) {
+                if (valid) store_bf16x4_split(a.a3, a.a3_lo, at, r0, r1, r2, r3, std::integral_constant<bool, FULL>());
+                if (FULL || a.m3) {
                     const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);     // all lanes take part
                     if (lg == 0 && valid) *reinterpret_cast<uint16_t *>(a.m3 + (at >> 3)) = (uint16_t)bits;
                 }
@@ -280,13 +281,13 @@ __global__ __launch_bounds__(C23_THREADS) void conv123_fwd_kernel(const uint8_t 
     static_assert(RES_THREADS == C23_THREADS, "one block size for both bodies");
     constexpr int L1 = conv1_fwd_lds_bytes<Geo>(), L23 = conv23_fwd_lds_bytes<P2, P3>();
     __shared__ u32x4 lds[(L1 > L23 ? L1 : L23) / 16];
-    conv1_fwd_resident_body<Geo>(lds, blockIdx.x, 0, 1, obs, w1, w1_lo, b1, const_cast<__bf16 *>(a.a1), const_cast<__bf16 *>(a.a1_lo),
+    conv1_fwd_resident_body<Geo, true>(lds, blockIdx.x, 0, 1, obs, w1, w1_lo, b1, const_cast<__bf16 *>(a.a1), const_cast<__bf16 *>(a.a1_lo),
                                  m1, B, spw);
     // The barrier orders this workgroup's act1 stores before its own reads (a workgroup's wavefronts share the CU's
     // vector cache).  A device-wide fence here is ruinous: it writes back and invalidates the whole L2 of the XCD,
     // once per workgroup (measured: 186 instead of 97 us).
     __syncthreads();
-    conv23_fwd_fused_body<P2, P3>(lds, blockIdx.x, a, B, spw);
+    conv23_fwd_fused_body<P2, P3, true>(lds, blockIdx.x, a, B, spw);
 }
 
 }  // namespace arn

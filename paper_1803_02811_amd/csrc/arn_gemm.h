@@ -49,11 +49,12 @@ __device__ __forceinline__ u32x2 pack_bf16x4(float a, float b, float c, float d)
 }
 
 // v -> (hi, lo) with hi = bf16(v), lo = bf16(v - hi)
+template <bool ALWAYS_LO = false>
 __device__ __forceinline__ void store_bf16x4_split(__bf16 *hi, __bf16 *lo, size_t at, float a, float b, float c,
-                                                   float d) {
+                                                   float d, std::integral_constant<bool, ALWAYS_LO> = {}) {
     const bf16x4 h = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
     *reinterpret_cast<u32x2 *>(hi + at) = __builtin_bit_cast(u32x2, h);
-    if (lo) {
+    if (ALWAYS_LO || lo) {
         const bf16x4 l = {(__bf16)(a - (float)h[0]), (__bf16)(b - (float)h[1]), (__bf16)(c - (float)h[2]),
                           (__bf16)(d - (float)h[3])};
         *reinterpret_cast<u32x2 *>(lo + at) = __builtin_bit_cast(u32x2, l);

@@ -310,7 +310,11 @@ __global__ __launch_bounds__(64 * ResWaves<C>::value, ResWaves<C>::value == 4 ? 
 template <class Geo>
 constexpr int conv1_fwd_lds_bytes() { return 4 * Geo::OBS_BYTES; }   // two bf16 images
 
-template <class Geo>
+// FULL: the lo part and the sign bits are always written (the gradient step's forward).  As a compile-time fact the
+// stores are unconditional, and the compiler's count of memory operations behind the frame prefetch -- which sets how
+// many of them may still be in flight when the prefetched frame is needed (s_waitcnt vmcnt counts in order) -- is the
+// real one instead of the fewest over all branches.
+template <class Geo, bool FULL = false>
 __device__ __forceinline__ void conv1_fwd_resident_body(
     u32x4 *lds, int block_x, int block_y, int grid_y, const uint8_t *__restrict__ obs, const __bf16 *__restrict__ w,
     const __bf16 *__restrict__ w_lo, const float *__restrict__ bias, __bf16 *__restrict__ out,
@@ -337,12 +341,20 @@ __device__ __forceinline__ void conv1_fwd_resident_body(
     const float4 bs = *reinterpret_cast<const float4 *>(bias + ct * 16 + 4 * lg);
 
     u32x4 rimg[NL];
-    auto gload = [&](int s) __attribute__((always_inline)) {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(obs + (size_t)s * OBS_BYTES);
+    // One persistent pointer per load, advanced by a sample after each use: with addresses computed per sample the
+    // temporaries were allocated in registers that the previous prefetch had filled, and the wait that protects them
+    // (s_waitcnt vmcnt, in order) also waited for most of the stores of the sample before.
+    const u32x4 *pimg[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int idx = tid + RES_THREADS * i;
+        pimg[i] = reinterpret_cast<const u32x4 *>(obs + (size_t)s_begin * OBS_BYTES) + (idx < IMG_U4 ? idx : IMG_U4 - 1);
+    }
+    auto gload = [&](int) __attribute__((always_inline)) {      // samples in order, starting at s_begin
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int idx = tid + RES_THREADS * i;
-            rimg[i] = src[idx < IMG_U4 ? idx : IMG_U4 - 1];
+            rimg[i] = *pimg[i];
+            pimg[i] += IMG_U4;
         }
     };
 
@@ -373,8 +385,8 @@ __device__ __forceinline__ void conv1_fwd_resident_body(
         const float r2 = fmaxf(acc[2] * sc + bs.z, 0.f), r3 = fmaxf(acc[3] * sc + bs.w, 0.f);
         const size_t at = ((size_t)s * P1 + pos) * C1 + ct * 16;
         const bool live = !RAGGED || pos < P1;
-        if (live) store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3);
-        if (mask_out) {
+        if (live) store_bf16x4_split(out, out_lo, at + 4 * lg, r0, r1, r2, r3, std::integral_constant<bool, FULL>());
+        if (FULL || mask_out) {
             const uint32_t bits = sign_bits16(r0, r1, r2, r3, lg);     // all lanes take part
             if (lg == 0 && live) *reinterpret_cast<uint16_t *>(mask_out + (at >> 3)) = (uint16_t)bits;
         }
