@@ -208,7 +208,7 @@ void fc_and_head_launches(const Dims &d, const Packed &w, int B, char *ws, const
         typedef typename std::conditional<F16, FcFwdF16T<FEAT_>, FcFwdT<FEAT_>>::type Fc;
         Fc p;
         p.in = a3; p.lo_off = a3l - a3; p.M = B; p.w = F16 ? (const __bf16 *)w.wfch : w.wfc; p.w_lo = w.wfcl; p.bias = w.bfc;
-        p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B); p.partial = (float *)(ws + o.fcp);
+        p.out = h; p.out_lo = hl; p.ksplit = fc_ksplit(B, F16); p.partial = (float *)(ws + o.fcp);
         p.to_partial = p.ksplit > 1 || d.small;
         if constexpr (F16) launch_nt("fc_fwd", p, B, HID / Fc::BN, p.ksplit, s);
         else launch_nt_split("fc_fwd", p, B, HID / Fc::BN, p.ksplit, s);
@@ -433,9 +433,10 @@ void backward_trunk(const Packed &w, const uint8_t *obs, int B, char *ws, const 
 inline int infer_rows_per_block(int B) { return B <= 512 ? 4 : B <= 4096 ? 8 : PVH_ROWS; }
 
 // Arguments of the fused policy/value head kernel that both entry points share.
-PvHeadArgs pv_head_args(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o) {
+// f16: the fc partial sums come from the no-gradient forward (its own number of k ranges)
+PvHeadArgs pv_head_args(const Dims &d, const Packed &w, int B, char *ws, const Workspace &o, bool f16) {
     PvHeadArgs p = {};
-    p.partial = (const float *)(ws + o.fcp); p.ks = fc_ksplit(B); p.bfc = w.bfc;
+    p.partial = (const float *)(ws + o.fcp); p.ks = fc_ksplit(B, f16); p.bfc = w.bfc;
     p.wh = w.wh; p.whl = w.whl; p.bh = w.bh; p.B = B; p.A = d.A;
     p.qmode = d.head == ARN_HEAD_Q ? 1 : d.head == ARN_HEAD_DUEL ? 2 : 0;
     return p;
@@ -547,7 +548,7 @@ int policy_forward_launches(const arn_config *cfg, const Dims &d, const Workspac
     infer_launches(d, w, obs, B, ws, o, logits, d.NH, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
-        PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+        PvHeadArgs p = pv_head_args(d, w, B, ws, o, true);
         p.logits = logits; p.value = value; p.probs = probs; p.greedy = greedy;
         p.rpb = infer_rows_per_block(B);
         hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
@@ -610,7 +611,7 @@ int arn_policy_act(const arn_config *cfg, const void *w_packed, const uint8_t *o
     infer_launches(d, w, obs, B, ws, o, z, d.NHP, s);
     if (d.small) {
         ProfScope ps("pv_head", s);
-        PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+        PvHeadArgs p = pv_head_args(d, w, B, ws, o, true);
         p.u = u; p.u2 = u2; p.epsilon = epsilon; p.act_out = action; p.logp_out = logp;
         p.rpb = infer_rows_per_block(B);
         hipLaunchKernelGGL(pv_head_kernel<false>, dim3(cdiv(B, p.rpb)), dim3(PVH_THREADS), 0, s, p);
@@ -694,7 +695,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             infer_launches(d, *wt, batch->next_obs, B, ws, o, nullptr, 0, s);
             {
                 ProfScope ps("q_target", s);
-                PvHeadArgs p = pv_head_args(d, *wt, B, ws, o);
+                PvHeadArgs p = pv_head_args(d, *wt, B, ws, o, true);
                 p.logits = (float *)(ws + o.qt);
                 if (!cfg->double_q) p.greedy = batch->next_action;
                 p.rpb = loss_block(B);
@@ -703,7 +704,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
             if (cfg->double_q) {
                 infer_launches(d, w, batch->next_obs, B, ws, o, nullptr, 0, s);
                 ProfScope ps("q_select", s);
-                PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+                PvHeadArgs p = pv_head_args(d, w, B, ws, o, true);
                 p.greedy = astar;
                 p.rpb = loss_block(B);
                 hipLaunchKernelGGL(pv_head_kernel<false>, dim3(lblocks), dim3(PVH_THREADS), 0, s, p);
@@ -712,7 +713,7 @@ int arn_train_step_grads(const arn_config *cfg, const void *w_packed, const arn_
         forward_launches(d, w, batch->obs, B, ws, o, nullptr, 0, true, s);
         // fc finish, head, objective, dz and the head's input gradient d(pre_fc) in one kernel
         ProfScope ps("pv_head", s);
-        PvHeadArgs p = pv_head_args(d, w, B, ws, o);
+        PvHeadArgs p = pv_head_args(d, w, B, ws, o, false);
         p.action = batch->action; p.adv = batch->adv; p.ret = batch->ret; p.old_logp = batch->old_logp;
         p.objective = loss_kind == ARN_LOSS_PPO ? 1 : loss_kind == ARN_LOSS_DQN ? 2 : 0;
         p.clip_eps = cfg->clip_eps; p.value_coef = cfg->value_coef; p.entropy_coef = cfg->entropy_coef;
